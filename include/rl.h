@@ -1,0 +1,240 @@
+/*
+ * rl.h -- C boundary of the rollout-generation library for MI355X (gfx950).
+ *
+ * What the calls compute.  In each RL iteration the policy pi_theta_old
+ * generates, for every prompt q_i, a group of G sampled responses o_{i,j}
+ * (workflow paragraph of Section 2.3; subscript of the expectation in the
+ * objective J(theta); Appendix C), each up to 16384 tokens after a prompt of
+ * up to 2048 (Appendix D).  The optimiser later needs, per generated token,
+ * pi_theta_old(o_{i,j,t} | q_i, o_{i,j,<t}) -- the denominator of the ratios
+ * s^plan, s^code of the HRD objective.  This library is that generator: a
+ * decoder-only policy (the 8B model named in Section 3.1) run autoregressively
+ * over a paged KV cache, returning sampled token ids and their log-probabilities
+ * under the sampling distribution.
+ *
+ * General conventions
+ *   - Every function returns rl_status; on any error other than RL_ERR_DEVICE
+ *     no sequence state has changed (after RL_ERR_DEVICE the model should be
+ *     destroyed).  rl_last_error() gives a message for the last failing call
+ *     on the calling thread.
+ *   - "host" / "device" on a pointer says where the memory lives.  The library
+ *     allocates no device memory: weights, KV pool, workspace and outputs are
+ *     caller-owned device buffers that must outlive the model.
+ *   - `stream` is a hipStream_t passed as void*.  Calls enqueue work on it and
+ *     return; outputs are valid once the stream has been synchronised.  Host
+ *     arrays passed to a call may be reused as soon as the call returns.
+ *   - A sequence is named by a caller-chosen id in [0, max_seqs).  The id is
+ *     also the stream id of the sampler's random numbers.  Group member j of
+ *     prompt i is simply a distinct id (e.g. i*G + j).
+ *   - Results for a sequence depend only on the weights, its own tokens, the
+ *     seed and its id -- not on which other sequences share the batch nor on
+ *     which physical pages it was given.
+ *
+ * Tensor layouts (row-major, "rows x cols"; element type = rl_model_config.dtype)
+ *   embed, lm_head  vocab x hidden               (not tied)
+ *   wqkv            (n_q+2*n_kv)*head_dim x hidden, rows ordered q heads, k heads, v heads
+ *   wo              hidden x n_q*head_dim
+ *   w_gate_up       2*ffn x hidden, the ffn gate rows followed by the ffn up rows
+ *   w_down          hidden x ffn
+ *   *_norm          RMSNorm gains: hidden (attn_norm, mlp_norm, final_norm), head_dim (q_norm, k_norm)
+ *   kv_pool         opaque; n_pages = kv_pool_bytes / rl_kv_page_bytes(cfg); one page holds
+ *                   kv_block tokens of K and V for all layers and kv heads
+ * For RL_BF16 the five projection matrices (wqkv, wo, w_gate_up, w_down, lm_head) are handed over in the
+ * library's tiled order, produced from the row-major form by rl_pack_weight(); embed and the gains stay
+ * row-major.  For RL_F32 everything is row-major (rl_pack_weight is then a copy).
+ *
+ * The decoder: pre-norm blocks  x += Wo * attn(rope(norm_q(Wq h)), ...),  x += Wd (silu(Wg h') * Wu h'),
+ * h = rmsnorm(x).  Rotary pairing is (i, i + head_dim/2) with angle pos * rope_base^(-2i/head_dim);
+ * positions count from 0 at the first prompt token.  No biases.
+ *
+ * Sampler (bit-exact contract): for vocabulary index i of the token generated at absolute
+ * position pos of sequence seq, a 32-bit word r is word (i & 3) of Philox4x32-10 with counter
+ * (i >> 2, pos, seq, 0) and key (seed low, seed high); u = (2 (r >> 9) + 1) 2^-24;
+ * g = -flog(-flog(u)) with the fp32 log fixed in the library's design notes;
+ * y_i = fma(z_i, 1/T, g) in fp32; token = argmax_i y_i, lowest index on ties.  The reported
+ * log-probability is log softmax(z / T)[token].  temperature == 0 means greedy (argmax z_i) and the
+ * log-probability is then taken at T = 1.
+ */
+#ifndef RL_ROLLOUT_H_
+#define RL_ROLLOUT_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rl_model rl_model; /* opaque, owned by the library (host memory only) */
+
+typedef enum {
+  RL_OK = 0,
+  RL_ERR_INVALID_ARG = -1,  /* null pointer, size out of range, duplicate id in one call */
+  RL_ERR_KV_FULL = -2,      /* not enough free pages for the whole call; nothing was allocated */
+  RL_ERR_BAD_SEQ = -3,      /* id out of range, not active (decode/free) or already active (prefill) */
+  RL_ERR_CTX_OVERFLOW = -4, /* a sequence would exceed max_ctx */
+  RL_ERR_DEVICE = -5,       /* a HIP call failed */
+  RL_ERR_UNSUPPORTED = -6   /* dimensions the kernels of the chosen dtype do not cover */
+} rl_status;
+
+typedef enum { RL_F32 = 0, RL_BF16 = 1 } rl_dtype;
+
+typedef struct {
+  uint32_t struct_size; /* sizeof(rl_model_config), checked */
+  uint32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+  float rms_eps, rope_base;
+  uint32_t qk_norm;  /* 1: per-head RMSNorm of q and k before the rotation */
+  uint32_t dtype;    /* rl_dtype of weights and KV; RL_BF16 needs head_dim 128 and 8B-like multiples */
+  uint32_t kv_block; /* tokens per page; must be 16 */
+  uint32_t max_seqs; /* ids are in [0, max_seqs) */
+  uint32_t max_ctx;  /* longest prompt + response, multiple of kv_block */
+  uint32_t max_rows; /* most sequences per decode call (<= 256); prefill is chunked to this internally */
+  uint64_t kv_pool_bytes;   /* size of rl_weights.kv_pool */
+  uint64_t workspace_bytes; /* size of rl_weights.workspace, >= rl_query_workspace() */
+} rl_model_config;
+
+typedef struct {
+  /* device pointers */
+  const void* embed;
+  const void* lm_head;
+  const void* final_norm;
+  /* host arrays of n_layers device pointers */
+  const void* const* attn_norm;
+  const void* const* wqkv;
+  const void* const* q_norm; /* may be NULL when qk_norm == 0 */
+  const void* const* k_norm;
+  const void* const* wo;
+  const void* const* mlp_norm;
+  const void* const* w_gate_up;
+  const void* const* w_down;
+  /* device buffers the library manages the contents of */
+  void* kv_pool;
+  void* workspace;
+} rl_weights;
+
+typedef struct {
+  float temperature; /* 0 => greedy */
+  uint32_t reserved;
+  uint64_t seed;
+} rl_sampling;
+
+/* Bytes of one KV page (kv_block tokens, all layers, K and V) for this configuration; 0 on bad config. */
+uint64_t rl_kv_page_bytes(const rl_model_config* cfg);
+
+/* Smallest workspace_bytes rl_init_model accepts for this configuration (ignores cfg->workspace_bytes). */
+rl_status rl_query_workspace(const rl_model_config* cfg, uint64_t* bytes_out);
+
+/*
+ * Build a model over caller-owned device buffers on the current HIP device.  Validates the
+ * configuration, zero-fills the KV pool, builds the rotary table in the workspace (synchronous).
+ * *out is set only on RL_OK.  Errors: INVALID_ARG, UNSUPPORTED, DEVICE.
+ */
+rl_status rl_init_model(const rl_model_config* cfg, const rl_weights* w, rl_model** out);
+
+/* Releases host state.  Sequences and pages die with the model; device buffers stay the caller's. */
+void rl_destroy_model(rl_model* m);
+
+/*
+ * Prefill: run the whole prompt of each new sequence through the decoder, fill its KV pages, and
+ * sample the first response token from the logits at the last prompt position (its RNG position is
+ * the prompt length).
+ *   seq_ids        host  [n_seqs]       fresh ids (not active)
+ *   prompt_tokens  host  [sum lens]     concatenated prompts, ids in [0, vocab)
+ *   prompt_lens    host  [n_seqs]       each in [1, max_ctx - 1]
+ *   out_tokens     device[n_seqs] int32 sampled first tokens
+ *   out_logprobs   device[n_seqs] fp32  their log-probabilities
+ * Errors: INVALID_ARG, BAD_SEQ, KV_FULL, CTX_OVERFLOW, DEVICE.
+ */
+rl_status rl_prefill(rl_model* m, void* stream, int32_t n_seqs, const int32_t* seq_ids,
+                     const int32_t* prompt_tokens, const int32_t* prompt_lens, const rl_sampling* sp,
+                     int32_t* out_tokens, float* out_logprobs);
+
+/*
+ * One decode step for n_seqs active sequences (1 <= n_seqs <= max_rows): feed in_tokens[b] at the
+ * sequence's next position, append its K/V, and sample the following token.
+ *   seq_ids       host  [n_seqs]
+ *   in_tokens     device[n_seqs] int32   (normally the previous call's out_tokens)
+ *   forced_next   device[n_seqs] int32 or NULL; entries >= 0 replace the sampled token (teacher
+ *                 forcing) and the log-probability reported is that of the forced token
+ *   out_tokens    device[n_seqs] int32;  out_logprobs device[n_seqs] fp32
+ *   debug_logits  device[n_seqs x vocab] fp32 or NULL: a copy of the logits z
+ * No host synchronisation happens inside.  Errors: INVALID_ARG, BAD_SEQ, KV_FULL, CTX_OVERFLOW, DEVICE.
+ */
+rl_status rl_decode_step(rl_model* m, void* stream, int32_t n_seqs, const int32_t* seq_ids,
+                         const int32_t* in_tokens, const int32_t* forced_next, const rl_sampling* sp,
+                         int32_t* out_tokens, float* out_logprobs, float* debug_logits);
+
+/* Retire sequences and return their pages to the pool.  Errors: INVALID_ARG, BAD_SEQ. */
+rl_status rl_free_seqs(rl_model* m, int32_t n_seqs, const int32_t* seq_ids);
+
+/* ---- helpers ------------------------------------------------------------------------------- */
+
+/* Message of the last failing call on this thread (never NULL). */
+const char* rl_last_error(void);
+
+rl_status rl_kv_stats(const rl_model* m, uint64_t* free_pages, uint64_t* total_pages);
+
+/* Tokens currently cached for a sequence; BAD_SEQ if not active. */
+rl_status rl_seq_len(const rl_model* m, int32_t seq_id, int32_t* len_out);
+
+/*
+ * Sampler alone, on logits the caller supplies (used to check the bit-exact sampling contract).
+ *   logits  device[n x vocab] fp32;  seq_ids, positions  host[n];  forced device[n] or NULL.
+ */
+rl_status rl_sample_logits(rl_model* m, void* stream, int32_t n, const float* logits,
+                           const int32_t* seq_ids, const int32_t* positions, const int32_t* forced,
+                           const rl_sampling* sp, int32_t* out_tokens, float* out_logprobs);
+
+/*
+ * Create a sequence whose first n_tokens positions of KV are given instead of computed.
+ *   k_layers, v_layers  host arrays of n_layers device pointers, each [n_tokens][n_kv][head_dim] in
+ *   the model dtype (keys as they are stored, i.e. after norm and rotation).
+ * Errors as rl_prefill.
+ */
+rl_status rl_seq_import_kv(rl_model* m, void* stream, int32_t seq_id, int32_t n_tokens,
+                           const void* const* k_layers, const void* const* v_layers);
+
+/*
+ * Decoder layers alone: like rl_decode_step but the residual stream entering layer 0 is given
+ * (hidden_in, device [n_seqs x hidden] fp32) instead of looked up from a token, and the residual
+ * stream leaving the last layer is returned (hidden_out, same shape) instead of being normalised,
+ * projected and sampled.  K/V are appended and the sequences advance by one position.
+ */
+rl_status rl_decode_hidden(rl_model* m, void* stream, int32_t n_seqs, const int32_t* seq_ids,
+                           const float* hidden_in, float* hidden_out);
+
+/*
+ * While `buf` (device, (n_layers+1) x max_rows x hidden fp32) is non-NULL, every decode call also
+ * stores the residual stream entering each layer (slot l) and leaving the last one (slot n_layers),
+ * row b at buf[(l*max_rows + b)*hidden].  NULL switches it off.
+ */
+rl_status rl_set_capture(rl_model* m, float* buf);
+
+/*
+ * Reorder a row-major [rows x cols] matrix (device) into the order the projection kernels stream
+ * (device, same size, must not overlap src).  RL_BF16: 32-row x 64-column tiles, each stored so that a
+ * wavefront reads it as four contiguous 1 KiB pieces in matrix-core operand order; needs rows % 32 == 0
+ * and cols % 64 == 0.  RL_F32: plain copy.  No model is needed.
+ */
+rl_status rl_pack_weight(void* stream, uint32_t dtype, const void* src, void* dst, int64_t rows, int64_t cols);
+
+/*
+ * Test aid: permute the free-page list with a seeded shuffle, so that later allocations scatter over
+ * the pool.  Results of every other call must not change.
+ */
+rl_status rl_debug_shuffle_free_pages(rl_model* m, uint64_t seed);
+
+/*
+ * Per-kernel timing.  While enabled, every kernel launch of decode/prefill calls is bracketed by
+ * HIP events on the caller's stream.  rl_profile_read synchronises those events, returns per kernel
+ * class the number of launches and their total milliseconds since the last read, and clears them.
+ *   names_out  host[n_max] pointers to static strings;  ms_out host[n_max];  counts_out host[n_max]
+ *   *n_out     number of classes written
+ */
+rl_status rl_profile_enable(rl_model* m, int32_t on);
+rl_status rl_profile_read(rl_model* m, int32_t n_max, const char** names_out, double* ms_out,
+                          int64_t* counts_out, int32_t* n_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RL_ROLLOUT_H_ */

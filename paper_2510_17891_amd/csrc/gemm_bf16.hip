@@ -1,0 +1,183 @@
+// Weight-streaming bf16 GEMM for decode-sized batches:  Y[M x N] = X[M x K] * W[N x K]^T.
+//
+// At M <= 256 the projection is bound by reading W once from HBM (M flop per weight byte), so the kernel is
+// organised around that stream: both operands are stored fragment-major (see frag_offset), which makes every
+// global load a fully coalesced 1 KiB wave access that lands directly in MFMA 32x32x16 operand registers -- no
+// LDS staging, no shuffles.  A wave owns a 64 x (32*MB) output tile over a slice of K; the four waves of a
+// block take four K slices and add their accumulators through LDS in a fixed order; further K splits across
+// blocks (to put >= 256 blocks on the chip for the small matrices) leave fp32 partials that the consumer sums.
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace rl {
+
+namespace {
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+template <int MB>
+struct Frags {
+  u32x4_t a[2][4];
+  u32x4_t b[MB][4];
+};
+
+template <int MB>
+__device__ __forceinline__ void load_frags(Frags<MB>& f, const u32x4_t* __restrict__ w0, const u32x4_t* __restrict__ w1,
+                                           const u32x4_t* const* __restrict__ xb, int kb, int lane) {
+  // block (rb, kb) = 256 uint4; sub-load t is [t*64 + lane]
+  const int o = kb * 256 + lane;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    f.a[0][t] = __builtin_nontemporal_load(w0 + o + t * 64);
+    f.a[1][t] = __builtin_nontemporal_load(w1 + o + t * 64);
+  }
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) f.b[mb][t] = xb[mb][o + t * 64];
+}
+
+template <int MB>
+__device__ __forceinline__ void mma_frags(const Frags<MB>& f, f32x16_t (&acc)[2][MB]) {
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+        acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, f.a[nb][t]),
+                                                              __builtin_bit_cast(bf16x8_t, f.b[mb][t]), acc[nb][mb], 0,
+                                                              0, 0);
+}
+
+// grid: x = N tile, y = K split, z = M tile of 32*MB rows.
+//   EPI == kEpiPartial: tile = 64 output columns (row blocks 2x, 2x+1 of W); out fp32 [S][M][N].
+//   EPI == kEpiSwiGLU : tile = 32 output columns (gate block x, up block x + N/32); out bf16 fragment-major [M x N].
+template <int MB, int EPI>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ W,
+                                                        void* __restrict__ out, int M, int N, int K, int kb_per_wave) {
+  __shared__ float red[4][16][64];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int KB = K >> 6;
+  const int m_blk0 = blockIdx.z * MB;
+  const int n_blocks_m = (M + 31) >> 5;
+
+  int rb0, rb1;
+  if (EPI == kEpiSwiGLU) { rb0 = blockIdx.x; rb1 = blockIdx.x + (N >> 5); }
+  else                   { rb0 = blockIdx.x * 2; rb1 = rb0 + 1; }
+  const u32x4_t* w0 = W + (size_t)rb0 * KB * 256;
+  const u32x4_t* w1 = W + (size_t)rb1 * KB * 256;
+  const u32x4_t* xb[MB];
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) {
+    int b = m_blk0 + mb;
+    if (b >= n_blocks_m) b = n_blocks_m - 1;  // clamp: surplus column blocks are computed but never stored
+    xb[mb] = X + (size_t)b * KB * 256;
+  }
+
+  f32x16_t acc[2][MB];
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[nb][mb][r] = 0.f;
+
+  const int kb_begin = (blockIdx.y * 4 + wave) * kb_per_wave;
+  const int kb_end = kb_begin + kb_per_wave;
+  Frags<MB> cur, nxt;
+  load_frags<MB>(cur, w0, w1, xb, kb_begin, lane);
+  for (int kb = kb_begin + 1; kb < kb_end; ++kb) {
+    load_frags<MB>(nxt, w0, w1, xb, kb, lane);
+    mma_frags<MB>(cur, acc);
+    cur = nxt;
+  }
+  mma_frags<MB>(cur, acc);
+
+  // ---- add the four waves' accumulators (fixed order) and write --------------------------------
+  // Output block mb is finished by wave mb % 4, which takes both row blocks (needed by SwiGLU).
+  const int col = lane & 31, hb = lane >> 5;
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) {
+    float sum[2][16];
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+      __syncthreads();
+#pragma unroll
+      for (int r = 0; r < 16; ++r) red[wave][r][lane] = acc[nb][mb][r];
+      __syncthreads();
+      if (wave == (mb & 3)) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          sum[nb][r] = (red[0][r][lane] + red[1][r][lane]) + (red[2][r][lane] + red[3][r][lane]);
+      }
+    }
+    if (wave != (mb & 3)) continue;
+    const int m = (m_blk0 + mb) * 32 + col;
+    if (m >= M) continue;
+    if (EPI == kEpiPartial) {
+      float* o = (float*)out + ((size_t)blockIdx.y * M + m) * N;
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int n = (nb ? rb1 : rb0) * 32 + 8 * q + 4 * hb;
+          *(float4*)(o + n) = make_float4(sum[nb][4 * q], sum[nb][4 * q + 1], sum[nb][4 * q + 2], sum[nb][4 * q + 3]);
+        }
+    } else {
+      uint16_t* o = (uint16_t*)out;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float a[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float gte = sum[0][4 * q + e], up = sum[1][4 * q + e];
+          a[e] = gte / (1.0f + __expf(-gte)) * up;
+        }
+        const int n = rb0 * 32 + 8 * q + 4 * hb;
+        *(uint2*)(o + frag_offset(m, n, N >> 6)) = make_uint2(pack2bf(a[0], a[1]), pack2bf(a[2], a[3]));
+      }
+    }
+  }
+}
+
+struct Plan {
+  int splits;       // K splits across blocks
+  int kb_per_wave;  // 64-wide k blocks per wave
+};
+
+Plan make_plan(int N, int K, int epi, bool allow_split) {
+  const int KB = K >> 6;
+  const int tiles = epi == kEpiSwiGLU ? (N >> 5) : (N >> 6);
+  int S = 1;
+  // Split K across blocks until about one block per CU exists; each wave keeps >= 2 k blocks.
+  while (tiles * S < 256 && (KB % (S * 2 * 4) == 0) && KB / (S * 2 * 4) >= 2 && epi != kEpiSwiGLU && allow_split) S *= 2;
+  return Plan{S, KB / (S * 4)};
+}
+
+template <int MB>
+void launch_mb(hipStream_t s, const void* X, const void* W, void* out, int M, int N, int K, int epi, bool allow_split) {
+  Plan p = make_plan(N, K, epi, allow_split);
+  const int m_tiles = (M + 32 * MB - 1) / (32 * MB);
+  if (epi == kEpiSwiGLU) {
+    dim3 grid(N >> 5, 1, m_tiles);
+    gemm_bf16_kernel<MB, kEpiSwiGLU><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave);
+  } else {
+    dim3 grid(N >> 6, p.splits, m_tiles);
+    gemm_bf16_kernel<MB, kEpiPartial><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave);
+  }
+}
+
+}  // namespace
+
+int gemm_bf16_splits(int N, int K, int epi) { return make_plan(N, K, epi, true).splits; }
+
+// Requirements (checked at model init): K % 256 == 0, N % 64 == 0 (N % 32 for SwiGLU).
+void launch_gemm_bf16(hipStream_t s, const void* X, const void* W, void* out, int M, int N, int K, int epi,
+                      bool allow_split) {
+  if (M <= 32) launch_mb<1>(s, X, W, out, M, N, K, epi, allow_split);
+  else if (M <= 64) launch_mb<2>(s, X, W, out, M, N, K, epi, allow_split);
+  else launch_mb<4>(s, X, W, out, M, N, K, epi, allow_split);
+}
+
+}  // namespace rl

@@ -1,0 +1,97 @@
+// Launchers of the gfx950 kernels.  Host orchestration (model.hip) calls these; each enqueues on the
+// given stream and returns.  Shapes are validated by the caller against what each kernel assumes.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rl {
+
+// One batch row = one (sequence, position) pair being pushed through the decoder.
+struct RowMeta {
+  int32_t seq;  // sequence id (row of the block table, RNG stream)
+  int32_t pos;  // absolute position of the token fed in this row
+};
+
+enum Dtype : int { kF32 = 0, kBF16 = 1 };
+
+// Geometry of the decoder, fixed at init and passed by value to launchers.
+struct Geometry {
+  int n_layers, hidden, n_q, n_kv, head_dim, ffn, vocab;
+  int qk_norm;
+  float rms_eps;
+  int dtype;
+  int max_blocks;   // block-table row length = max_ctx / 16
+  int64_t n_pages;  // pages in the pool
+};
+
+// "Fragment-major" order of a [rows x K] bf16 operand of the MFMA GEMM: 32-row blocks, 64-wide k
+// blocks, inside a block [t(4)][hb(2)][row(32)][e(8)] with k = 64 kb + 32 hb + 8 t + e.  A wave reads
+// block (rb, kb) as four fully coalesced 1 KiB loads, each already in MFMA 32x32x16 operand order.
+__host__ __device__ inline size_t frag_offset(int r, int k, int k_blocks) {
+  int rb = r >> 5, row = r & 31, kb = k >> 6, hb = (k >> 5) & 1, t = (k >> 3) & 3, e = k & 7;
+  return ((((size_t)(rb * (size_t)k_blocks + kb) * 4 + t) * 2 + hb) * 32 + row) * 8 + e;
+}
+
+// ---- elementwise / small kernels (both dtypes) -------------------------------------------------
+// x[r][:] = E[tok[r]][:] widened to fp32 (ids clamped to [0, V)).
+void launch_embed(hipStream_t s, int dtype, const void* embed, const int32_t* tokens, float* x, int M, int H, int V);
+
+// x[r] += sum_{s<S} part[s][r][:] (part may be null);  capture (may be null) gets x;  if gain != null,
+// h = x * rsqrt(mean(x^2)+eps) * gain written as fp32 row-major (kF32) or bf16 fragment-major (kBF16).
+void launch_residual_norm(hipStream_t s, int dtype, float* x, const float* part, int S, const void* gain,
+                          void* h_out, float* capture, int M, int H, float eps);
+
+// Sum the split partials of the QKV projection, apply per-head RMSNorm (q,k) and the rotation (q,k) at
+// each row's position, write q as fp32 [M][n_q][d] and append k,v to the row's KV page.
+void launch_qk_rope_append(hipStream_t s, const Geometry& g, const float* qkv_part, int S, const void* q_gain,
+                           const void* k_gain, const float2* rope_table, const RowMeta* rows,
+                           const int32_t* block_table, void* k_pool_layer, void* v_pool_layer, float* q_out, int M);
+
+// Scatter contiguous [n_tokens][n_kv][d] K and V (model dtype) into the pages of one sequence.
+void launch_kv_import(hipStream_t s, const Geometry& g, const void* k_src, const void* v_src, int n_tokens,
+                      const int32_t* block_table_row, void* k_pool_layer, void* v_pool_layer);
+
+// ---- attention -----------------------------------------------------------------------------------
+constexpr int kAttnChunk = 256;  // keys per split of the context (bf16 path)
+
+// bf16, head_dim 128: split-K decode attention over paged KV (MFMA), then the deterministic merge that
+// writes bf16 fragment-major [M x n_q*d].  part: fp32 [M][n_q][max_chunks][d+2].
+void launch_attn_decode_bf16(hipStream_t s, const Geometry& g, const float* q, const RowMeta* rows,
+                             const int32_t* block_table, const void* k_pool_layer, const void* v_pool_layer,
+                             float* part, int max_chunks_alloc, int grid_chunks, int M);
+void launch_attn_merge_bf16(hipStream_t s, const Geometry& g, const float* part, const RowMeta* rows,
+                            int max_chunks_alloc, void* o_out, int M);
+// fp32, any head_dim <= 256: one wave per (row, q head), whole context, output fp32 row-major [M][n_q*d].
+void launch_attn_f32(hipStream_t s, const Geometry& g, const float* q, const RowMeta* rows,
+                     const int32_t* block_table, const void* k_pool_layer, const void* v_pool_layer,
+                     float* o_out, int M);
+
+// ---- projections ---------------------------------------------------------------------------------
+enum Epilogue : int { kEpiPartial = 0, kEpiSwiGLU = 1 };
+
+// Number of K splits the bf16 GEMM uses for (N, K); partial outputs are [S][M][N] fp32.
+int gemm_bf16_splits(int N, int K, int epi);
+// bf16 MFMA GEMM: X fragment-major [M x K], W fragment-major [N x K] (2N rows for SwiGLU: gate then up).
+// kEpiPartial: out = fp32 [S][M][N];  kEpiSwiGLU: out = bf16 fragment-major [M x N] = silu(gate)*up.
+// allow_split = false forces S = 1 (the output is then the finished [M][N] product).
+void launch_gemm_bf16(hipStream_t s, const void* X, const void* W, void* out, int M, int N, int K, int epi,
+                      bool allow_split = true);
+// fp32 GEMM on vector ALUs, row-major everything; kEpiPartial writes [M][N] (one split).
+void launch_gemm_f32(hipStream_t s, const float* X, const float* W, float* out, int M, int N, int K, int epi);
+
+// Row-major [N x K] bf16 -> fragment-major (N % 32 == 0, K % 64 == 0).
+void launch_pack_weight_bf16(hipStream_t s, const void* src, void* dst, int N, int K);
+
+// ---- sampler ---------------------------------------------------------------------------------------
+constexpr int kSampleTile = 2048;  // vocabulary entries per first-stage block
+// Stage 1+2 of Gumbel-max sampling with log-probabilities from fp32 logits [M][V].
+// part: [M][n_tiles] of 4 floats.  forced may be null.
+// The RNG position of row r is rows[r].pos + pos_offset.
+void launch_sample(hipStream_t s, const float* logits, int M, int V, const RowMeta* rows, int pos_offset,
+                   const int32_t* forced, float temperature, uint64_t seed, float* part, int32_t* out_tokens,
+                   float* out_logprobs);
+
+// block_table[upd[3i]][upd[3i+1]] = upd[3i+2] for i < n (device-side mirror update of newly granted pages).
+void launch_table_update(hipStream_t s, int32_t* block_table, int max_blocks, const int32_t* upd, int n);
+
+}  // namespace rl

@@ -1,0 +1,690 @@
+// Host side of the rollout library: C boundary, sequence table, per-call metadata, kernel sequencing.
+//
+// A "row" is one (sequence, position) pair pushed through the decoder.  A decode step is one row per
+// sequence; prefill pushes every prompt token as a row, in chunks of max_rows, so both share one code path
+// (the KV append of a layer runs for all rows of a chunk before that layer's attention, and a row only
+// attends to keys at or before its own position).
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <cmath>
+#include <string>
+#include <vector>
+
+#include "../../include/rl.h"
+#include "kernels.h"
+#include "seq_table.h"
+
+using namespace rl;
+
+namespace {
+
+thread_local std::string g_err = "";
+
+rl_status fail(rl_status st, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return st;
+}
+
+#define HIP_TRY(expr)                                                                   \
+  do {                                                                                  \
+    hipError_t e_ = (expr);                                                             \
+    if (e_ != hipSuccess) return fail(RL_ERR_DEVICE, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+constexpr int kRing = 64;  // per-call metadata slots in flight
+
+size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+struct Layout {
+  size_t block_table, rope, ring, x, x_last, h, part, q, attn_part, o, a, logits, samp_part, total;
+  size_t slot_bytes, slot_upd, slot_tok;
+  int max_chunks, n_tiles;
+};
+
+size_t elem_size(uint32_t dtype) { return dtype == RL_BF16 ? 2 : 4; }
+
+rl_status check_config(const rl_model_config* c) {
+  if (!c) return fail(RL_ERR_INVALID_ARG, "config is NULL");
+  if (c->struct_size != sizeof(rl_model_config)) return fail(RL_ERR_INVALID_ARG, "struct_size mismatch");
+  if (c->dtype != RL_F32 && c->dtype != RL_BF16) return fail(RL_ERR_INVALID_ARG, "unknown dtype");
+  if (c->kv_block != 16) return fail(RL_ERR_UNSUPPORTED, "kv_block must be 16");
+  if (!c->n_layers || !c->hidden || !c->n_q_heads || !c->n_kv_heads || !c->head_dim || !c->ffn)
+    return fail(RL_ERR_INVALID_ARG, "zero dimension");
+  if (c->n_q_heads % c->n_kv_heads) return fail(RL_ERR_INVALID_ARG, "n_q_heads %% n_kv_heads != 0");
+  if (c->max_seqs == 0 || c->max_rows == 0 || c->max_rows > 256) return fail(RL_ERR_INVALID_ARG, "max_rows must be in [1,256]");
+  if (c->max_ctx == 0 || c->max_ctx % 16) return fail(RL_ERR_INVALID_ARG, "max_ctx must be a positive multiple of 16");
+  if (c->hidden % 8 || c->hidden > 8192 || c->head_dim % 2 || c->head_dim > 128 || c->ffn % 8 || c->vocab % 4)
+    return fail(RL_ERR_UNSUPPORTED, "need hidden %% 8 == 0, hidden <= 8192, even head_dim <= 128, ffn %% 8 == 0, vocab %% 4 == 0");
+  if (c->dtype == RL_BF16) {
+    const uint32_t qd = c->n_q_heads * c->head_dim, nqkv = (c->n_q_heads + 2 * c->n_kv_heads) * c->head_dim;
+    if (c->head_dim != 128 || c->n_q_heads / c->n_kv_heads > 8) return fail(RL_ERR_UNSUPPORTED, "bf16 needs head_dim 128 and group <= 8");
+    if (c->hidden % 256 || qd % 256 || c->ffn % 256) return fail(RL_ERR_UNSUPPORTED, "bf16 needs hidden, n_q*head_dim, ffn multiples of 256");
+    if (nqkv % 64 || c->hidden % 64 || c->ffn % 64 || c->vocab % 64) return fail(RL_ERR_UNSUPPORTED, "bf16 needs projection widths multiples of 64");
+  }
+  return RL_OK;
+}
+
+void compute_layout(const rl_model_config& c, Layout* L) {
+  const size_t R = c.max_rows, Rp = (R + 31) / 32 * 32, H = c.hidden, d = c.head_dim;
+  const size_t nq = c.n_q_heads, nkv = c.n_kv_heads, F = c.ffn, V = c.vocab;
+  const size_t act = elem_size(c.dtype);
+  const size_t nqkv = (nq + 2 * nkv) * d;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  L->max_chunks = (int)((c.max_ctx + kAttnChunk - 1) / kAttnChunk);
+  L->n_tiles = (int)((V + kSampleTile - 1) / kSampleTile);
+  L->slot_upd = align_up(R * sizeof(RowMeta));
+  L->slot_tok = L->slot_upd + align_up(R * 3 * sizeof(int32_t));
+  L->slot_bytes = L->slot_tok + align_up(R * sizeof(int32_t));
+  L->block_table = take((size_t)c.max_seqs * (c.max_ctx / 16) * 4);
+  L->rope = take((size_t)c.max_ctx * (d / 2) * sizeof(float2));
+  L->ring = take(kRing * L->slot_bytes);
+  L->x = take(R * H * 4);
+  L->x_last = take(R * H * 4);
+  L->h = take(Rp * H * act);
+  size_t part_elems;
+  if (c.dtype == RL_BF16) {
+    size_t a1 = (size_t)gemm_bf16_splits((int)nqkv, (int)H, kEpiPartial) * R * nqkv;
+    size_t a2 = (size_t)gemm_bf16_splits((int)H, (int)(nq * d), kEpiPartial) * R * H;
+    size_t a3 = (size_t)gemm_bf16_splits((int)H, (int)F, kEpiPartial) * R * H;
+    part_elems = a1 > a2 ? a1 : a2;
+    if (a3 > part_elems) part_elems = a3;
+  } else {
+    part_elems = R * (nqkv > H ? nqkv : H);
+  }
+  L->part = take(part_elems * 4);
+  L->q = take(R * nq * d * 4);
+  L->attn_part = take(c.dtype == RL_BF16 ? R * nq * (size_t)L->max_chunks * (d + 2) * 4 : 256);
+  L->o = take(Rp * nq * d * act);
+  L->a = take(Rp * F * act);
+  L->logits = take(V ? R * V * 4 : 256);
+  L->samp_part = take(V ? R * (size_t)L->n_tiles * 16 : 256);
+  L->total = off;
+}
+
+enum Kind { K_META, K_EMBED, K_NORM, K_QKV, K_ROPE_APPEND, K_ATTN, K_ATTN_MERGE, K_OPROJ, K_GATEUP, K_DOWN, K_LMHEAD, K_SAMPLE, K_COUNT };
+const char* const kKindNames[K_COUNT] = {"meta", "embed", "residual_norm", "gemm_qkv", "qk_rope_append", "attn_decode",
+                                        "attn_merge", "gemm_o", "gemm_gate_up_swiglu", "gemm_down", "gemm_lm_head", "sample"};
+
+}  // namespace
+
+struct rl_model {
+  rl_model_config cfg;
+  Geometry geo;
+  Layout lay;
+  SeqTable* table = nullptr;
+  // weights (device pointers)
+  const void *embed, *lm_head, *final_norm;
+  std::vector<const void*> attn_norm, wqkv, q_norm, k_norm, wo, mlp_norm, w_gate_up, w_down;
+  char* kv_pool;
+  char* ws;
+  size_t layer_kv_bytes, kv_half_bytes;
+  // pinned host ring for per-call metadata
+  char* host_ring = nullptr;
+  hipEvent_t ring_ev[kRing];
+  bool ring_used[kRing];
+  int ring_next = 0;
+  float* capture = nullptr;
+  // profiling
+  bool prof_on = false;
+  std::vector<hipEvent_t> ev_pool;
+  struct Pending { int kind; hipEvent_t a, b; };
+  std::vector<Pending> pending;
+  double prof_ms[K_COUNT];
+  int64_t prof_n[K_COUNT];
+
+  template <typename T> T* wsp(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+  void* k_pool(int l) const { return kv_pool + (size_t)l * layer_kv_bytes; }
+  void* v_pool(int l) const { return kv_pool + (size_t)l * layer_kv_bytes + kv_half_bytes; }
+};
+
+namespace {
+
+struct Timer {
+  rl_model* m;
+  hipStream_t st;
+  hipEvent_t b = nullptr;
+  int kind;
+  Timer(rl_model* m_, hipStream_t st_, int kind_) : m(m_), st(st_), kind(kind_) {
+    if (!m->prof_on) return;
+    hipEvent_t a = take();
+    b = take();
+    if (a && b) {
+      (void)hipEventRecord(a, st);
+      m->pending.push_back({kind, a, b});
+    } else {
+      b = nullptr;
+    }
+  }
+  ~Timer() {
+    if (b) (void)hipEventRecord(b, st);
+  }
+  hipEvent_t take() {
+    if (!m->ev_pool.empty()) { hipEvent_t e = m->ev_pool.back(); m->ev_pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+};
+
+// Reserve a metadata slot: wait (practically never) until its previous upload has been consumed.
+rl_status ring_acquire(rl_model* m, int* slot_out) {
+  int s = m->ring_next;
+  m->ring_next = (s + 1) % kRing;
+  if (m->ring_used[s]) HIP_TRY(hipEventSynchronize(m->ring_ev[s]));
+  *slot_out = s;
+  return RL_OK;
+}
+
+// Run all decoder layers on the M rows whose residual stream sits in ws.x.  Leaves the last down-projection's
+// split partials pending; returns their count so that the caller's final residual_norm adds them.
+int run_layers(rl_model* m, hipStream_t st, int M, const RowMeta* rows, int grid_chunks) {
+  const Geometry& g = m->geo;
+  const bool bf = g.dtype == kBF16;
+  const int H = g.hidden, nqd = g.n_q * g.head_dim, nqkv = (g.n_q + 2 * g.n_kv) * g.head_dim, F = g.ffn;
+  float* x = m->wsp<float>(m->lay.x);
+  void* h = m->wsp<void>(m->lay.h);
+  float* part = m->wsp<float>(m->lay.part);
+  float* q = m->wsp<float>(m->lay.q);
+  float* apart = m->wsp<float>(m->lay.attn_part);
+  void* o = m->wsp<void>(m->lay.o);
+  void* a = m->wsp<void>(m->lay.a);
+  const float2* rope = m->wsp<float2>(m->lay.rope);
+  const int32_t* bt = m->wsp<int32_t>(m->lay.block_table);
+  int pend = 0;
+  for (int l = 0; l < g.n_layers; ++l) {
+    float* cap = m->capture ? m->capture + (size_t)l * m->cfg.max_rows * H : nullptr;
+    { Timer t(m, st, K_NORM);
+      launch_residual_norm(st, g.dtype, x, pend ? part : nullptr, pend, m->attn_norm[l], h, cap, M, H, g.rms_eps); }
+    int s_qkv = 1;
+    { Timer t(m, st, K_QKV);
+      if (bf) { launch_gemm_bf16(st, h, m->wqkv[l], part, M, nqkv, H, kEpiPartial); s_qkv = gemm_bf16_splits(nqkv, H, kEpiPartial); }
+      else launch_gemm_f32(st, (const float*)h, (const float*)m->wqkv[l], part, M, nqkv, H, kEpiPartial); }
+    { Timer t(m, st, K_ROPE_APPEND);
+      launch_qk_rope_append(st, g, part, s_qkv, g.qk_norm ? m->q_norm[l] : nullptr, g.qk_norm ? m->k_norm[l] : nullptr, rope,
+                            rows, bt, m->k_pool(l), m->v_pool(l), q, M); }
+    if (bf) {
+      { Timer t(m, st, K_ATTN);
+        launch_attn_decode_bf16(st, g, q, rows, bt, m->k_pool(l), m->v_pool(l), apart, m->lay.max_chunks, grid_chunks, M); }
+      { Timer t(m, st, K_ATTN_MERGE);
+        launch_attn_merge_bf16(st, g, apart, rows, m->lay.max_chunks, o, M); }
+    } else {
+      Timer t(m, st, K_ATTN);
+      launch_attn_f32(st, g, q, rows, bt, m->k_pool(l), m->v_pool(l), (float*)o, M);
+    }
+    int s_o = 1;
+    { Timer t(m, st, K_OPROJ);
+      if (bf) { launch_gemm_bf16(st, o, m->wo[l], part, M, H, nqd, kEpiPartial); s_o = gemm_bf16_splits(H, nqd, kEpiPartial); }
+      else launch_gemm_f32(st, (const float*)o, (const float*)m->wo[l], part, M, H, nqd, kEpiPartial); }
+    { Timer t(m, st, K_NORM);
+      launch_residual_norm(st, g.dtype, x, part, s_o, m->mlp_norm[l], h, nullptr, M, H, g.rms_eps); }
+    { Timer t(m, st, K_GATEUP);
+      if (bf) launch_gemm_bf16(st, h, m->w_gate_up[l], a, M, F, H, kEpiSwiGLU);
+      else launch_gemm_f32(st, (const float*)h, (const float*)m->w_gate_up[l], (float*)a, M, F, H, kEpiSwiGLU); }
+    { Timer t(m, st, K_DOWN);
+      if (bf) { launch_gemm_bf16(st, a, m->w_down[l], part, M, H, F, kEpiPartial); pend = gemm_bf16_splits(H, F, kEpiPartial); }
+      else { launch_gemm_f32(st, (const float*)a, (const float*)m->w_down[l], part, M, H, F, kEpiPartial); pend = 1; } }
+  }
+  return pend;
+}
+
+// Final norm, output projection and sampling for M rows whose residual is in `xbuf` (pending partials added).
+void run_head(rl_model* m, hipStream_t st, int M, float* xbuf, int pend, const RowMeta* rows, int pos_offset,
+              const int32_t* forced, const rl_sampling* sp, int32_t* out_tokens, float* out_lp, float* debug_logits) {
+  const Geometry& g = m->geo;
+  void* h = m->wsp<void>(m->lay.h);
+  float* part = m->wsp<float>(m->lay.part);
+  float* logits = m->wsp<float>(m->lay.logits);
+  float* cap = m->capture ? m->capture + (size_t)g.n_layers * m->cfg.max_rows * g.hidden : nullptr;
+  { Timer t(m, st, K_NORM);
+    launch_residual_norm(st, g.dtype, xbuf, pend ? part : nullptr, pend, m->final_norm, h, cap, M, g.hidden, g.rms_eps); }
+  { Timer t(m, st, K_LMHEAD);
+    if (g.dtype == kBF16) launch_gemm_bf16(st, h, m->lm_head, logits, M, g.vocab, g.hidden, kEpiPartial, false);
+    else launch_gemm_f32(st, (const float*)h, (const float*)m->lm_head, logits, M, g.vocab, g.hidden, kEpiPartial); }
+  { Timer t(m, st, K_SAMPLE);
+    launch_sample(st, logits, M, g.vocab, rows, pos_offset, forced, sp->temperature, sp->seed,
+                  m->wsp<float>(m->lay.samp_part), out_tokens, out_lp); }
+  if (debug_logits)
+    (void)hipMemcpyAsync(debug_logits, logits, (size_t)M * g.vocab * 4, hipMemcpyDeviceToDevice, st);
+}
+
+// Checks shared by decode calls; on success `grants` holds the pages handed out and lens are NOT yet advanced.
+rl_status admit_decode(rl_model* m, int32_t n, const int32_t* seq_ids, std::vector<PageGrant>* grants) {
+  if (n < 1 || n > (int32_t)m->cfg.max_rows) return fail(RL_ERR_INVALID_ARG, "n_seqs %d outside [1, max_rows=%u]", n, m->cfg.max_rows);
+  if (!seq_ids) return fail(RL_ERR_INVALID_ARG, "seq_ids is NULL");
+  SeqTable& T = *m->table;
+  std::vector<char> seen(T.max_seqs(), 0);
+  int64_t need = 0;
+  for (int i = 0; i < n; ++i) {
+    int32_t s = seq_ids[i];
+    if (!T.active(s)) return fail(RL_ERR_BAD_SEQ, "sequence %d is not active", s);
+    if (seen[s]) return fail(RL_ERR_INVALID_ARG, "sequence %d appears twice", s);
+    seen[s] = 1;
+    if (T.len(s) + 1 > T.max_ctx()) return fail(RL_ERR_CTX_OVERFLOW, "sequence %d would exceed max_ctx %d", s, T.max_ctx());
+    need += T.pages_missing(s, T.len(s) + 1);
+  }
+  if (need > T.free_pages()) return fail(RL_ERR_KV_FULL, "need %lld pages, %lld free", (long long)need, (long long)T.free_pages());
+  for (int i = 0; i < n; ++i) T.reserve(seq_ids[i], T.len(seq_ids[i]) + 1, grants);
+  return RL_OK;
+}
+
+// Build and upload the rows (and page grants) of one decode call; returns device pointers into the slot.
+rl_status upload_decode_meta(rl_model* m, hipStream_t st, int32_t n, const int32_t* seq_ids,
+                             const std::vector<PageGrant>& grants, const RowMeta** rows_dev, int* grid_chunks) {
+  int slot;
+  rl_status rs = ring_acquire(m, &slot);
+  if (rs != RL_OK) return rs;
+  char* hs = m->host_ring + (size_t)slot * m->lay.slot_bytes;
+  char* ds = m->ws + m->lay.ring + (size_t)slot * m->lay.slot_bytes;
+  RowMeta* hr = (RowMeta*)hs;
+  int max_ctx = 0;
+  for (int i = 0; i < n; ++i) {
+    hr[i].seq = seq_ids[i];
+    hr[i].pos = m->table->len(seq_ids[i]);
+    if (hr[i].pos + 1 > max_ctx) max_ctx = hr[i].pos + 1;
+  }
+  int32_t* hu = (int32_t*)(hs + m->lay.slot_upd);
+  for (size_t i = 0; i < grants.size(); ++i) { hu[3 * i] = grants[i].seq; hu[3 * i + 1] = grants[i].block; hu[3 * i + 2] = grants[i].page; }
+  Timer t(m, st, K_META);
+  HIP_TRY(hipMemcpyAsync(ds, hs, (size_t)n * sizeof(RowMeta), hipMemcpyHostToDevice, st));
+  if (!grants.empty()) {
+    HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_upd, hu, grants.size() * 12, hipMemcpyHostToDevice, st));
+    launch_table_update(st, m->wsp<int32_t>(m->lay.block_table), m->geo.max_blocks, (const int32_t*)(ds + m->lay.slot_upd), (int)grants.size());
+  }
+  HIP_TRY(hipEventRecord(m->ring_ev[slot], st));
+  m->ring_used[slot] = true;
+  *rows_dev = (const RowMeta*)ds;
+  *grid_chunks = (max_ctx + kAttnChunk - 1) / kAttnChunk;
+  return RL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* rl_last_error(void) { return g_err.c_str(); }
+
+uint64_t rl_kv_page_bytes(const rl_model_config* c) {
+  if (check_config(c) != RL_OK) return 0;
+  return (uint64_t)c->n_layers * 2 * c->n_kv_heads * 16 * c->head_dim * elem_size(c->dtype);
+}
+
+rl_status rl_query_workspace(const rl_model_config* c, uint64_t* bytes_out) {
+  rl_status rs = check_config(c);
+  if (rs != RL_OK) return rs;
+  if (!bytes_out) return fail(RL_ERR_INVALID_ARG, "bytes_out is NULL");
+  Layout L;
+  compute_layout(*c, &L);
+  *bytes_out = L.total;
+  return RL_OK;
+}
+
+rl_status rl_init_model(const rl_model_config* c, const rl_weights* w, rl_model** out) {
+  rl_status rs = check_config(c);
+  if (rs != RL_OK) return rs;
+  if (!w || !out) return fail(RL_ERR_INVALID_ARG, "weights or out is NULL");
+  if (!w->final_norm || !w->attn_norm || !w->wqkv || !w->wo || !w->mlp_norm || !w->w_gate_up || !w->w_down || !w->kv_pool || !w->workspace)
+    return fail(RL_ERR_INVALID_ARG, "a required weight pointer is NULL");
+  if (c->vocab && (!w->embed || !w->lm_head)) return fail(RL_ERR_INVALID_ARG, "embed/lm_head is NULL with vocab > 0");
+  if (c->qk_norm && (!w->q_norm || !w->k_norm)) return fail(RL_ERR_INVALID_ARG, "q_norm/k_norm is NULL with qk_norm = 1");
+  Layout L;
+  compute_layout(*c, &L);
+  if (c->workspace_bytes < L.total) return fail(RL_ERR_INVALID_ARG, "workspace_bytes %llu < required %llu", (unsigned long long)c->workspace_bytes, (unsigned long long)L.total);
+  const uint64_t page_bytes = rl_kv_page_bytes(c);
+  const int64_t n_pages = (int64_t)(c->kv_pool_bytes / page_bytes);
+  if (n_pages < 1 || n_pages > 0x7fffffff) return fail(RL_ERR_INVALID_ARG, "kv_pool_bytes gives %lld pages", (long long)n_pages);
+
+  rl_model* m = new rl_model();
+  m->cfg = *c;
+  m->lay = L;
+  m->geo = Geometry{(int)c->n_layers, (int)c->hidden, (int)c->n_q_heads, (int)c->n_kv_heads, (int)c->head_dim, (int)c->ffn,
+                    (int)c->vocab, (int)c->qk_norm, c->rms_eps, (int)c->dtype, (int)(c->max_ctx / 16), n_pages};
+  m->embed = w->embed; m->lm_head = w->lm_head; m->final_norm = w->final_norm;
+  auto copy = [&](std::vector<const void*>& dst, const void* const* src) {
+    dst.assign(c->n_layers, nullptr);
+    if (src) for (uint32_t l = 0; l < c->n_layers; ++l) dst[l] = src[l];
+  };
+  copy(m->attn_norm, w->attn_norm); copy(m->wqkv, w->wqkv); copy(m->q_norm, w->q_norm); copy(m->k_norm, w->k_norm);
+  copy(m->wo, w->wo); copy(m->mlp_norm, w->mlp_norm); copy(m->w_gate_up, w->w_gate_up); copy(m->w_down, w->w_down);
+  for (uint32_t l = 0; l < c->n_layers; ++l)
+    if (!m->attn_norm[l] || !m->wqkv[l] || !m->wo[l] || !m->mlp_norm[l] || !m->w_gate_up[l] || !m->w_down[l] ||
+        (c->qk_norm && (!m->q_norm[l] || !m->k_norm[l]))) {
+      delete m;
+      return fail(RL_ERR_INVALID_ARG, "layer %u has a NULL weight pointer", l);
+    }
+  m->kv_pool = (char*)w->kv_pool;
+  m->ws = (char*)w->workspace;
+  m->kv_half_bytes = (size_t)n_pages * c->n_kv_heads * 16 * c->head_dim * elem_size(c->dtype);
+  m->layer_kv_bytes = 2 * m->kv_half_bytes;
+  m->table = new SeqTable((int)c->max_seqs, (int)c->max_ctx, n_pages);
+  for (int i = 0; i < K_COUNT; ++i) { m->prof_ms[i] = 0; m->prof_n[i] = 0; }
+  for (int i = 0; i < kRing; ++i) { m->ring_ev[i] = nullptr; m->ring_used[i] = false; }
+
+  auto bail = [&](hipError_t e, const char* what) {
+    rl_status r = fail(RL_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+    rl_destroy_model(m);
+    return r;
+  };
+  hipError_t e;
+  if ((e = hipHostMalloc((void**)&m->host_ring, kRing * L.slot_bytes, hipHostMallocDefault)) != hipSuccess) return bail(e, "hipHostMalloc");
+  for (int i = 0; i < kRing; ++i)
+    if ((e = hipEventCreateWithFlags(&m->ring_ev[i], hipEventDisableTiming)) != hipSuccess) return bail(e, "hipEventCreate");
+  // Stale slots of recycled pages are multiplied by zero weights, so the pool must never hold NaN/Inf patterns.
+  if ((e = hipMemset(m->kv_pool, 0, (size_t)n_pages * page_bytes)) != hipSuccess) return bail(e, "hipMemset(kv_pool)");
+  if ((e = hipMemset(m->ws + L.block_table, 0, (size_t)c->max_seqs * (c->max_ctx / 16) * 4)) != hipSuccess) return bail(e, "hipMemset(block_table)");
+  {
+    const int half = (int)c->head_dim / 2;
+    std::vector<float2> tab((size_t)c->max_ctx * half);
+    for (int i = 0; i < half; ++i) {
+      const double freq = std::pow((double)c->rope_base, -2.0 * i / (double)c->head_dim);
+      for (uint32_t p = 0; p < c->max_ctx; ++p) {
+        const double ang = (double)p * freq;
+        tab[(size_t)p * half + i] = make_float2((float)std::cos(ang), (float)std::sin(ang));
+      }
+    }
+    if ((e = hipMemcpy(m->ws + L.rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice)) != hipSuccess) return bail(e, "hipMemcpy(rope)");
+  }
+  if ((e = hipDeviceSynchronize()) != hipSuccess) return bail(e, "hipDeviceSynchronize");
+  *out = m;
+  return RL_OK;
+}
+
+void rl_destroy_model(rl_model* m) {
+  if (!m) return;
+  for (auto& p : m->pending) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+  for (auto ev : m->ev_pool) (void)hipEventDestroy(ev);
+  for (int i = 0; i < kRing; ++i) if (m->ring_ev[i]) (void)hipEventDestroy(m->ring_ev[i]);
+  if (m->host_ring) (void)hipHostFree(m->host_ring);
+  delete m->table;
+  delete m;
+}
+
+rl_status rl_kv_stats(const rl_model* m, uint64_t* free_pages, uint64_t* total_pages) {
+  if (!m) return fail(RL_ERR_INVALID_ARG, "model is NULL");
+  if (free_pages) *free_pages = (uint64_t)m->table->free_pages();
+  if (total_pages) *total_pages = (uint64_t)m->table->n_pages();
+  return RL_OK;
+}
+
+rl_status rl_seq_len(const rl_model* m, int32_t seq_id, int32_t* len_out) {
+  if (!m || !len_out) return fail(RL_ERR_INVALID_ARG, "NULL argument");
+  if (!m->table->active(seq_id)) return fail(RL_ERR_BAD_SEQ, "sequence %d is not active", seq_id);
+  *len_out = m->table->len(seq_id);
+  return RL_OK;
+}
+
+rl_status rl_free_seqs(rl_model* m, int32_t n, const int32_t* seq_ids) {
+  if (!m || (n > 0 && !seq_ids) || n < 0) return fail(RL_ERR_INVALID_ARG, "bad arguments");
+  SeqTable& T = *m->table;
+  std::vector<char> seen(T.max_seqs(), 0);
+  for (int i = 0; i < n; ++i) {
+    if (!T.active(seq_ids[i])) return fail(RL_ERR_BAD_SEQ, "sequence %d is not active", seq_ids[i]);
+    if (seen[seq_ids[i]]) return fail(RL_ERR_INVALID_ARG, "sequence %d appears twice", seq_ids[i]);
+    seen[seq_ids[i]] = 1;
+  }
+  for (int i = 0; i < n; ++i) T.release(seq_ids[i]);
+  return RL_OK;
+}
+
+rl_status rl_debug_shuffle_free_pages(rl_model* m, uint64_t seed) {
+  if (!m) return fail(RL_ERR_INVALID_ARG, "model is NULL");
+  m->table->shuffle_free(seed);
+  return RL_OK;
+}
+
+rl_status rl_set_capture(rl_model* m, float* buf) {
+  if (!m) return fail(RL_ERR_INVALID_ARG, "model is NULL");
+  m->capture = buf;
+  return RL_OK;
+}
+
+rl_status rl_decode_step(rl_model* m, void* stream, int32_t n, const int32_t* seq_ids, const int32_t* in_tokens,
+                         const int32_t* forced_next, const rl_sampling* sp, int32_t* out_tokens, float* out_logprobs,
+                         float* debug_logits) {
+  if (!m || !in_tokens || !sp || !out_tokens || !out_logprobs) return fail(RL_ERR_INVALID_ARG, "NULL argument");
+  if (m->geo.vocab == 0) return fail(RL_ERR_UNSUPPORTED, "model has no vocabulary");
+  hipStream_t st = (hipStream_t)stream;
+  std::vector<PageGrant> grants;
+  rl_status rs = admit_decode(m, n, seq_ids, &grants);
+  if (rs != RL_OK) return rs;
+  const RowMeta* rows;
+  int grid_chunks;
+  rs = upload_decode_meta(m, st, n, seq_ids, grants, &rows, &grid_chunks);
+  if (rs != RL_OK) return rs;
+  float* x = m->wsp<float>(m->lay.x);
+  { Timer t(m, st, K_EMBED);
+    launch_embed(st, m->geo.dtype, m->embed, in_tokens, x, n, m->geo.hidden, m->geo.vocab); }
+  int pend = run_layers(m, st, n, rows, grid_chunks);
+  run_head(m, st, n, x, pend, rows, 1, forced_next, sp, out_tokens, out_logprobs, debug_logits);
+  HIP_TRY(hipGetLastError());
+  for (int i = 0; i < n; ++i) m->table->set_len(seq_ids[i], m->table->len(seq_ids[i]) + 1);
+  return RL_OK;
+}
+
+rl_status rl_decode_hidden(rl_model* m, void* stream, int32_t n, const int32_t* seq_ids, const float* hidden_in,
+                           float* hidden_out) {
+  if (!m || !hidden_in || !hidden_out) return fail(RL_ERR_INVALID_ARG, "NULL argument");
+  hipStream_t st = (hipStream_t)stream;
+  std::vector<PageGrant> grants;
+  rl_status rs = admit_decode(m, n, seq_ids, &grants);
+  if (rs != RL_OK) return rs;
+  const RowMeta* rows;
+  int grid_chunks;
+  rs = upload_decode_meta(m, st, n, seq_ids, grants, &rows, &grid_chunks);
+  if (rs != RL_OK) return rs;
+  float* x = m->wsp<float>(m->lay.x);
+  const size_t bytes = (size_t)n * m->geo.hidden * 4;
+  HIP_TRY(hipMemcpyAsync(x, hidden_in, bytes, hipMemcpyDeviceToDevice, st));
+  int pend = run_layers(m, st, n, rows, grid_chunks);
+  float* cap = m->capture ? m->capture + (size_t)m->geo.n_layers * m->cfg.max_rows * m->geo.hidden : nullptr;
+  { Timer t(m, st, K_NORM);
+    launch_residual_norm(st, m->geo.dtype, x, m->wsp<float>(m->lay.part), pend, nullptr, nullptr, cap, n, m->geo.hidden, m->geo.rms_eps); }
+  HIP_TRY(hipMemcpyAsync(hidden_out, x, bytes, hipMemcpyDeviceToDevice, st));
+  HIP_TRY(hipGetLastError());
+  for (int i = 0; i < n; ++i) m->table->set_len(seq_ids[i], m->table->len(seq_ids[i]) + 1);
+  return RL_OK;
+}
+
+rl_status rl_prefill(rl_model* m, void* stream, int32_t n, const int32_t* seq_ids, const int32_t* prompt_tokens,
+                     const int32_t* prompt_lens, const rl_sampling* sp, int32_t* out_tokens, float* out_logprobs) {
+  if (!m || !seq_ids || !prompt_tokens || !prompt_lens || !sp || !out_tokens || !out_logprobs)
+    return fail(RL_ERR_INVALID_ARG, "NULL argument");
+  if (m->geo.vocab == 0) return fail(RL_ERR_UNSUPPORTED, "model has no vocabulary");
+  if (n < 1 || n > (int32_t)m->cfg.max_rows) return fail(RL_ERR_INVALID_ARG, "n_seqs %d outside [1, max_rows=%u]", n, m->cfg.max_rows);
+  hipStream_t st = (hipStream_t)stream;
+  SeqTable& T = *m->table;
+  const int R = (int)m->cfg.max_rows, H = m->geo.hidden;
+  std::vector<char> seen(T.max_seqs(), 0);
+  int64_t need = 0, total = 0;
+  for (int i = 0; i < n; ++i) {
+    const int32_t s = seq_ids[i];
+    if (!T.valid_id(s)) return fail(RL_ERR_BAD_SEQ, "sequence id %d out of range", s);
+    if (T.active(s)) return fail(RL_ERR_BAD_SEQ, "sequence %d is already active", s);
+    if (seen[s]) return fail(RL_ERR_INVALID_ARG, "sequence %d appears twice", s);
+    seen[s] = 1;
+    if (prompt_lens[i] < 1) return fail(RL_ERR_INVALID_ARG, "prompt %d is empty", i);
+    if (prompt_lens[i] > T.max_ctx() - 1) return fail(RL_ERR_CTX_OVERFLOW, "prompt %d has %d tokens, max_ctx is %d", i, prompt_lens[i], T.max_ctx());
+    need += SeqTable::blocks_for(prompt_lens[i]);
+    total += prompt_lens[i];
+  }
+  for (int64_t i = 0; i < total; ++i)
+    if (prompt_tokens[i] < 0 || prompt_tokens[i] >= m->geo.vocab) return fail(RL_ERR_INVALID_ARG, "token %d at %lld outside the vocabulary", prompt_tokens[i], (long long)i);
+  if (need > T.free_pages()) return fail(RL_ERR_KV_FULL, "need %lld pages, %lld free", (long long)need, (long long)T.free_pages());
+
+  int32_t* bt = m->wsp<int32_t>(m->lay.block_table);
+  for (int i = 0; i < n; ++i) {
+    const int32_t s = seq_ids[i];
+    T.activate(s);
+    T.reserve(s, prompt_lens[i], nullptr);
+    // pageable source: the runtime stages it before returning, so the vector may change afterwards
+    HIP_TRY(hipMemcpyAsync(bt + (size_t)s * m->geo.max_blocks, T.pages(s).data(), T.pages(s).size() * 4, hipMemcpyHostToDevice, st));
+  }
+
+  float* x = m->wsp<float>(m->lay.x);
+  float* x_last = m->wsp<float>(m->lay.x_last);
+  // rows in (sequence, position) order, cut into chunks of R
+  int seq_i = 0, pos = 0;
+  int64_t done = 0, tok_off = 0;
+  std::vector<int64_t> tok_base(n);
+  for (int i = 0; i < n; ++i) { tok_base[i] = tok_off; tok_off += prompt_lens[i]; }
+  while (done < total) {
+    const int M = (int)std::min<int64_t>(R, total - done);
+    int slot;
+    rl_status rs = ring_acquire(m, &slot);
+    if (rs != RL_OK) return rs;
+    char* hs = m->host_ring + (size_t)slot * m->lay.slot_bytes;
+    char* ds = m->ws + m->lay.ring + (size_t)slot * m->lay.slot_bytes;
+    RowMeta* hr = (RowMeta*)hs;
+    int32_t* ht = (int32_t*)(hs + m->lay.slot_tok);
+    int max_ctx = 0;
+    struct Last { int row, seq_index; };
+    std::vector<Last> lasts;
+    for (int r = 0; r < M; ++r) {
+      hr[r].seq = seq_ids[seq_i];
+      hr[r].pos = pos;
+      ht[r] = prompt_tokens[tok_base[seq_i] + pos];
+      if (pos + 1 > max_ctx) max_ctx = pos + 1;
+      if (pos + 1 == prompt_lens[seq_i]) { lasts.push_back({r, seq_i}); ++seq_i; pos = 0; }
+      else ++pos;
+    }
+    { Timer t(m, st, K_META);
+      HIP_TRY(hipMemcpyAsync(ds, hs, (size_t)M * sizeof(RowMeta), hipMemcpyHostToDevice, st));
+      HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_tok, ht, (size_t)M * 4, hipMemcpyHostToDevice, st));
+      HIP_TRY(hipEventRecord(m->ring_ev[slot], st));
+      m->ring_used[slot] = true; }
+    const RowMeta* rows = (const RowMeta*)ds;
+    { Timer t(m, st, K_EMBED);
+      launch_embed(st, m->geo.dtype, m->embed, (const int32_t*)(ds + m->lay.slot_tok), x, M, H, m->geo.vocab); }
+    int pend = run_layers(m, st, M, rows, (max_ctx + kAttnChunk - 1) / kAttnChunk);
+    // fold the pending partials into x, then keep the rows that end a prompt
+    float* cap = m->capture ? m->capture + (size_t)m->geo.n_layers * m->cfg.max_rows * H : nullptr;
+    { Timer t(m, st, K_NORM);
+      launch_residual_norm(st, m->geo.dtype, x, m->wsp<float>(m->lay.part), pend, nullptr, nullptr, cap, M, H, m->geo.rms_eps); }
+    for (const Last& l : lasts)
+      HIP_TRY(hipMemcpyAsync(x_last + (size_t)l.seq_index * H, x + (size_t)l.row * H, (size_t)H * 4, hipMemcpyDeviceToDevice, st));
+    done += M;
+  }
+  // logits at the last prompt position of every sequence; the sampled token sits at position prompt_len
+  {
+    int slot;
+    rl_status rs = ring_acquire(m, &slot);
+    if (rs != RL_OK) return rs;
+    char* hs = m->host_ring + (size_t)slot * m->lay.slot_bytes;
+    char* ds = m->ws + m->lay.ring + (size_t)slot * m->lay.slot_bytes;
+    RowMeta* hr = (RowMeta*)hs;
+    for (int i = 0; i < n; ++i) { hr[i].seq = seq_ids[i]; hr[i].pos = prompt_lens[i]; }
+    HIP_TRY(hipMemcpyAsync(ds, hs, (size_t)n * sizeof(RowMeta), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipEventRecord(m->ring_ev[slot], st));
+    m->ring_used[slot] = true;
+    float* keep = m->capture;
+    m->capture = nullptr;  // slot n_layers was already written per chunk
+    run_head(m, st, n, x_last, 0, (const RowMeta*)ds, 0, nullptr, sp, out_tokens, out_logprobs, nullptr);
+    m->capture = keep;
+  }
+  HIP_TRY(hipGetLastError());
+  for (int i = 0; i < n; ++i) T.set_len(seq_ids[i], prompt_lens[i]);
+  return RL_OK;
+}
+
+rl_status rl_seq_import_kv(rl_model* m, void* stream, int32_t seq_id, int32_t n_tokens, const void* const* k_layers,
+                           const void* const* v_layers) {
+  if (!m || !k_layers || !v_layers) return fail(RL_ERR_INVALID_ARG, "NULL argument");
+  SeqTable& T = *m->table;
+  if (!T.valid_id(seq_id)) return fail(RL_ERR_BAD_SEQ, "sequence id %d out of range", seq_id);
+  if (T.active(seq_id)) return fail(RL_ERR_BAD_SEQ, "sequence %d is already active", seq_id);
+  if (n_tokens < 0 || n_tokens > T.max_ctx() - 1) return fail(RL_ERR_CTX_OVERFLOW, "n_tokens %d outside [0, max_ctx)", n_tokens);
+  for (int l = 0; l < m->geo.n_layers; ++l)
+    if (n_tokens > 0 && (!k_layers[l] || !v_layers[l])) return fail(RL_ERR_INVALID_ARG, "layer %d KV pointer is NULL", l);
+  if (SeqTable::blocks_for(n_tokens) > T.free_pages()) return fail(RL_ERR_KV_FULL, "need %d pages, %lld free", SeqTable::blocks_for(n_tokens), (long long)T.free_pages());
+  hipStream_t st = (hipStream_t)stream;
+  T.activate(seq_id);
+  T.reserve(seq_id, n_tokens, nullptr);
+  int32_t* bt_row = m->wsp<int32_t>(m->lay.block_table) + (size_t)seq_id * m->geo.max_blocks;
+  if (n_tokens > 0) {
+    HIP_TRY(hipMemcpyAsync(bt_row, T.pages(seq_id).data(), T.pages(seq_id).size() * 4, hipMemcpyHostToDevice, st));
+    for (int l = 0; l < m->geo.n_layers; ++l)
+      launch_kv_import(st, m->geo, k_layers[l], v_layers[l], n_tokens, bt_row, m->k_pool(l), m->v_pool(l));
+  }
+  HIP_TRY(hipGetLastError());
+  T.set_len(seq_id, n_tokens);
+  return RL_OK;
+}
+
+rl_status rl_sample_logits(rl_model* m, void* stream, int32_t n, const float* logits, const int32_t* seq_ids,
+                           const int32_t* positions, const int32_t* forced, const rl_sampling* sp, int32_t* out_tokens,
+                           float* out_logprobs) {
+  if (!m || !logits || !seq_ids || !positions || !sp || !out_tokens || !out_logprobs) return fail(RL_ERR_INVALID_ARG, "NULL argument");
+  if (m->geo.vocab == 0) return fail(RL_ERR_UNSUPPORTED, "model has no vocabulary");
+  if (n < 1 || n > (int32_t)m->cfg.max_rows) return fail(RL_ERR_INVALID_ARG, "n %d outside [1, max_rows]", n);
+  hipStream_t st = (hipStream_t)stream;
+  int slot;
+  rl_status rs = ring_acquire(m, &slot);
+  if (rs != RL_OK) return rs;
+  char* hs = m->host_ring + (size_t)slot * m->lay.slot_bytes;
+  char* ds = m->ws + m->lay.ring + (size_t)slot * m->lay.slot_bytes;
+  RowMeta* hr = (RowMeta*)hs;
+  for (int i = 0; i < n; ++i) { hr[i].seq = seq_ids[i]; hr[i].pos = positions[i]; }
+  HIP_TRY(hipMemcpyAsync(ds, hs, (size_t)n * sizeof(RowMeta), hipMemcpyHostToDevice, st));
+  HIP_TRY(hipEventRecord(m->ring_ev[slot], st));
+  m->ring_used[slot] = true;
+  launch_sample(st, logits, n, m->geo.vocab, (const RowMeta*)ds, 0, forced, sp->temperature, sp->seed,
+                m->wsp<float>(m->lay.samp_part), out_tokens, out_logprobs);
+  HIP_TRY(hipGetLastError());
+  return RL_OK;
+}
+
+rl_status rl_pack_weight(void* stream, uint32_t dtype, const void* src, void* dst, int64_t rows, int64_t cols) {
+  if (!src || !dst || rows < 1 || cols < 1) return fail(RL_ERR_INVALID_ARG, "bad arguments");
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == RL_F32) {
+    HIP_TRY(hipMemcpyAsync(dst, src, (size_t)rows * cols * 4, hipMemcpyDeviceToDevice, st));
+    return RL_OK;
+  }
+  if (dtype != RL_BF16) return fail(RL_ERR_INVALID_ARG, "unknown dtype");
+  if (rows % 32 || cols % 64 || rows > 0x7fffffff || cols > 0x7fffffff) return fail(RL_ERR_UNSUPPORTED, "bf16 packing needs rows %% 32 == 0 and cols %% 64 == 0");
+  launch_pack_weight_bf16(st, src, dst, (int)rows, (int)cols);
+  HIP_TRY(hipGetLastError());
+  return RL_OK;
+}
+
+rl_status rl_profile_enable(rl_model* m, int32_t on) {
+  if (!m) return fail(RL_ERR_INVALID_ARG, "model is NULL");
+  m->prof_on = on != 0;
+  return RL_OK;
+}
+
+rl_status rl_profile_read(rl_model* m, int32_t n_max, const char** names_out, double* ms_out, int64_t* counts_out,
+                          int32_t* n_out) {
+  if (!m || !names_out || !ms_out || !counts_out || !n_out) return fail(RL_ERR_INVALID_ARG, "NULL argument");
+  for (auto& p : m->pending) {
+    HIP_TRY(hipEventSynchronize(p.b));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, p.a, p.b));
+    m->prof_ms[p.kind] += ms;
+    m->prof_n[p.kind] += 1;
+    m->ev_pool.push_back(p.a);
+    m->ev_pool.push_back(p.b);
+  }
+  m->pending.clear();
+  int k = 0;
+  for (int i = 0; i < K_COUNT && k < n_max; ++i) {
+    names_out[k] = kKindNames[i];
+    ms_out[k] = m->prof_ms[i];
+    counts_out[k] = m->prof_n[i];
+    m->prof_ms[i] = 0;
+    m->prof_n[i] = 0;
+    ++k;
+  }
+  *n_out = k;
+  return RL_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,89 @@
+// Host-side sequence table and KV page allocator (no GPU calls; unit-tested on the CPU).
+//
+// A page holds 16 tokens of K and V for every layer.  Pages are handed out from a LIFO free list; a call
+// that needs several pages first checks that all of them exist, so a failing call changes nothing.
+#pragma once
+#include <stdint.h>
+
+#include <algorithm>
+#include <vector>
+
+namespace rl {
+
+struct PageGrant {
+  int32_t seq, block, page;
+};
+
+class SeqTable {
+ public:
+  static constexpr int kBlock = 16;
+
+  SeqTable(int max_seqs, int max_ctx, int64_t n_pages)
+      : max_seqs_(max_seqs), max_ctx_(max_ctx), max_blocks_(max_ctx / kBlock), n_pages_(n_pages),
+        len_(max_seqs, -1), pages_(max_seqs) {
+    free_.reserve(n_pages);
+    for (int64_t p = n_pages - 1; p >= 0; --p) free_.push_back((int32_t)p);  // page 0 is handed out first
+  }
+
+  int max_seqs() const { return max_seqs_; }
+  int max_ctx() const { return max_ctx_; }
+  int max_blocks() const { return max_blocks_; }
+  int64_t n_pages() const { return n_pages_; }
+  int64_t free_pages() const { return (int64_t)free_.size(); }
+
+  bool valid_id(int32_t s) const { return s >= 0 && s < max_seqs_; }
+  bool active(int32_t s) const { return valid_id(s) && len_[s] >= 0; }
+  int32_t len(int32_t s) const { return len_[s]; }
+  const std::vector<int32_t>& pages(int32_t s) const { return pages_[s]; }
+
+  static int blocks_for(int tokens) { return (tokens + kBlock - 1) / kBlock; }
+
+  // Pages still missing for `s` to hold `tokens` tokens (s may be inactive: then all of them).
+  int pages_missing(int32_t s, int tokens) const {
+    int have = len_[s] >= 0 ? (int)pages_[s].size() : 0;
+    return std::max(0, blocks_for(tokens) - have);
+  }
+
+  // Activate a fresh sequence with length 0.
+  void activate(int32_t s) {
+    len_[s] = 0;
+    pages_[s].clear();
+  }
+
+  // Grow the page list of `s` to cover `tokens` tokens; the caller has checked free_pages().
+  void reserve(int32_t s, int tokens, std::vector<PageGrant>* grants) {
+    int need = blocks_for(tokens);
+    while ((int)pages_[s].size() < need) {
+      int32_t p = free_.back();
+      free_.pop_back();
+      if (grants) grants->push_back(PageGrant{s, (int32_t)pages_[s].size(), p});
+      pages_[s].push_back(p);
+    }
+  }
+
+  void set_len(int32_t s, int32_t n) { len_[s] = n; }
+
+  void release(int32_t s) {
+    for (auto it = pages_[s].rbegin(); it != pages_[s].rend(); ++it) free_.push_back(*it);
+    pages_[s].clear();
+    len_[s] = -1;
+  }
+
+  // Deterministic shuffle of the free list (test aid: results must not depend on page placement).
+  void shuffle_free(uint64_t seed) {
+    uint64_t x = seed * 0x9E3779B97F4A7C15ull + 0x7F4A7C15ull;
+    for (size_t i = free_.size(); i > 1; --i) {
+      x ^= x << 13; x ^= x >> 7; x ^= x << 17;
+      std::swap(free_[i - 1], free_[x % i]);
+    }
+  }
+
+ private:
+  int max_seqs_, max_ctx_, max_blocks_;
+  int64_t n_pages_;
+  std::vector<int32_t> len_;  // -1 = inactive
+  std::vector<std::vector<int32_t>> pages_;
+  std::vector<int32_t> free_;
+};
+
+}  // namespace rl

@@ -1,0 +1,32 @@
+// C wrappers around the host sequence table so that its logic can be exercised without a GPU.
+// Built with g++ into its own small library by the CPU tests; not part of the product library.
+#include "seq_table.h"
+
+extern "C" {
+
+void* st_create(int max_seqs, int max_ctx, long long n_pages) { return new rl::SeqTable(max_seqs, max_ctx, n_pages); }
+void st_destroy(void* t) { delete (rl::SeqTable*)t; }
+long long st_free_pages(void* t) { return ((rl::SeqTable*)t)->free_pages(); }
+int st_active(void* t, int s) { return ((rl::SeqTable*)t)->active(s) ? 1 : 0; }
+int st_len(void* t, int s) { return ((rl::SeqTable*)t)->len(s); }
+int st_pages_missing(void* t, int s, int tokens) { return ((rl::SeqTable*)t)->pages_missing(s, tokens); }
+void st_activate(void* t, int s) { ((rl::SeqTable*)t)->activate(s); }
+void st_set_len(void* t, int s, int n) { ((rl::SeqTable*)t)->set_len(s, n); }
+void st_release(void* t, int s) { ((rl::SeqTable*)t)->release(s); }
+void st_shuffle(void* t, unsigned long long seed) { ((rl::SeqTable*)t)->shuffle_free(seed); }
+int st_n_seq_pages(void* t, int s) { return (int)((rl::SeqTable*)t)->pages(s).size(); }
+int st_seq_page(void* t, int s, int i) { return ((rl::SeqTable*)t)->pages(s)[i]; }
+// returns the number of grants written (seq, block, page triples)
+int st_reserve(void* t, int s, int tokens, int* grants_out, int max_grants) {
+  std::vector<rl::PageGrant> g;
+  ((rl::SeqTable*)t)->reserve(s, tokens, &g);
+  int n = 0;
+  for (auto& x : g) {
+    if (n >= max_grants) break;
+    grants_out[3 * n] = x.seq; grants_out[3 * n + 1] = x.block; grants_out[3 * n + 2] = x.page;
+    ++n;
+  }
+  return (int)g.size();
+}
+
+}  // extern "C"

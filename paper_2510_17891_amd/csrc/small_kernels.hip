@@ -1,0 +1,260 @@
+// Embedding gather, residual + RMSNorm, per-head norm + rotary + KV append, KV import, weight packing.
+// These move little data per step; they are written for few launches and simple indexing.
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace rl {
+
+// ------------------------------------------------------------------------------------------------
+// Embedding gather (rollout step "x = E[token]").
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ tok,
+                                                    float* __restrict__ x, int H, int V) {
+  const int r = blockIdx.x;
+  const int t = min(max(tok[r], 0), V - 1);  // ids come from device memory the host cannot inspect
+  const size_t base = (size_t)t * H;
+  for (int i = threadIdx.x; i < H; i += 256) x[(size_t)r * H + i] = load_as_float(E, base + i);
+}
+
+void launch_embed(hipStream_t s, int dtype, const void* embed, const int32_t* tokens, float* x, int M, int H, int V) {
+  if (dtype == kBF16)
+    embed_kernel<uint16_t><<<M, 256, 0, s>>>((const uint16_t*)embed, tokens, x, H, V);
+  else
+    embed_kernel<float><<<M, 256, 0, s>>>((const float*)embed, tokens, x, H, V);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Residual update + RMSNorm.  One block per row.  The split partials of the preceding projection are
+// summed in a fixed order, so results do not depend on the batch.
+// ------------------------------------------------------------------------------------------------
+template <bool BF16>
+__global__ __launch_bounds__(256) void residual_norm_kernel(float* __restrict__ x, const float* __restrict__ part,
+                                                            int S, size_t split_stride, const void* __restrict__ gain,
+                                                            void* __restrict__ h_out, float* __restrict__ capture,
+                                                            int H, float eps) {
+  __shared__ float red[4];
+  const int r = blockIdx.x;
+  float* xr = x + (size_t)r * H;
+  float ss = 0.f;
+  // H <= 256 * 8 * 4 is checked by the host; each thread owns groups of 8 consecutive elements.
+  for (int i0 = threadIdx.x * 8; i0 < H; i0 += 256 * 8) {
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = xr[i0 + e];
+    for (int sp = 0; sp < S; ++sp) {
+      const float* p = part + sp * split_stride + (size_t)r * H + i0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] += p[e];
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      if (S > 0) xr[i0 + e] = v[e];
+      if (capture) capture[(size_t)r * H + i0 + e] = v[e];
+      ss += v[e] * v[e];
+    }
+  }
+  if (gain == nullptr) return;
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  ss = (red[0] + red[1]) + (red[2] + red[3]);
+  const float inv = 1.0f / sqrtf(ss / (float)H + eps);
+  for (int i0 = threadIdx.x * 8; i0 < H; i0 += 256 * 8) {
+    if (BF16) {
+      const uint16_t* g = (const uint16_t*)gain;
+      uint32_t w[4];
+#pragma unroll
+      for (int e = 0; e < 8; e += 2)
+        w[e >> 1] = pack2bf(xr[i0 + e] * inv * bf2f(g[i0 + e]), xr[i0 + e + 1] * inv * bf2f(g[i0 + e + 1]));
+      uint4 o = make_uint4(w[0], w[1], w[2], w[3]);
+      *(uint4*)((uint16_t*)h_out + frag_offset(r, i0, H >> 6)) = o;
+    } else {
+      const float* g = (const float*)gain;
+      float* h = (float*)h_out + (size_t)r * H;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) h[i0 + e] = xr[i0 + e] * inv * g[i0 + e];
+    }
+  }
+}
+
+void launch_residual_norm(hipStream_t s, int dtype, float* x, const float* part, int S, const void* gain,
+                          void* h_out, float* capture, int M, int H, float eps) {
+  size_t stride = (size_t)M * H;
+  if (dtype == kBF16)
+    residual_norm_kernel<true><<<M, 256, 0, s>>>(x, part, S, stride, gain, h_out, capture, H, eps);
+  else
+    residual_norm_kernel<false><<<M, 256, 0, s>>>(x, part, S, stride, gain, h_out, capture, H, eps);
+}
+
+// ------------------------------------------------------------------------------------------------
+// KV page element offsets.
+//   fp32 pages: plain [16 tokens][d].
+//   bf16 pages (d = 128): K as [d/8][16 tokens][8] so that the 16 keys x 32 dims an MFMA step needs are
+//   one coalesced 1 KiB read; V as [d/32][4 key groups][16 dims][2 x 4 keys] so that a lane's 16 bytes
+//   are four keys of two dims -- the transposed operand of the P*V product with no shuffle.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ int k_page_offset_bf16(int t, int dd) { return ((dd >> 3) * 16 + t) * 8 + (dd & 7); }
+__device__ __forceinline__ int v_page_offset_bf16(int t, int dd) {
+  int dblk = dd >> 4, dl = dd & 15, jj = dblk >> 1, par = dblk & 1, g = t >> 2;
+  return ((jj * 64 + g * 16 + dl) * 8) + par * 4 + (t & 3);
+}
+
+template <bool BF16>
+__device__ __forceinline__ void kv_store(void* pool_layer, int64_t page, int hk, int n_kv, int d, int t, int dd,
+                                         float val, bool is_v) {
+  const size_t page_elems = (size_t)kPageTokens * d;
+  const size_t base = ((size_t)page * n_kv + hk) * page_elems;
+  if (BF16) {
+    int off = is_v ? v_page_offset_bf16(t, dd) : k_page_offset_bf16(t, dd);
+    ((uint16_t*)pool_layer)[base + off] = (uint16_t)f2bf(val);
+  } else {
+    ((float*)pool_layer)[base + (size_t)t * d + dd] = val;
+  }
+}
+
+// One wave per (row, head).  Lane i < d/2 owns the rotary pair (i, i + d/2).
+template <bool BF16>
+__global__ __launch_bounds__(64) void qk_rope_append_kernel(const float* __restrict__ part, int S, size_t split_stride,
+                                                            const void* __restrict__ q_gain,
+                                                            const void* __restrict__ k_gain,
+                                                            const float2* __restrict__ rope, const RowMeta* __restrict__ rows,
+                                                            const int32_t* __restrict__ block_table, int max_blocks,
+                                                            void* __restrict__ k_pool, void* __restrict__ v_pool,
+                                                            float* __restrict__ q_out, int n_q, int n_kv, int d,
+                                                            int qk_norm, float eps) {
+  const int hh = blockIdx.x, r = blockIdx.y, lane = threadIdx.x;
+  const int half = d >> 1;
+  const int n_tot = (n_q + 2 * n_kv) * d;
+  const RowMeta rm = rows[r];
+  // lanes may own more than one pair when d/2 > 64
+  for (int i = lane; i < ((half + 63) & ~63); i += 64) {
+    const bool live = i < half;
+    float v0 = 0.f, v1 = 0.f;
+    if (live) {
+      for (int sp = 0; sp < S; ++sp) {
+        const float* p = part + sp * split_stride + (size_t)r * n_tot + (size_t)hh * d;
+        v0 += p[i];
+        v1 += p[i + half];
+      }
+    }
+    const bool is_q = hh < n_q, is_k = !is_q && hh < n_q + n_kv;
+    if (is_q || is_k) {
+      if (qk_norm) {
+        // d <= 128 here (one pass); wider heads are rejected by the host for this kernel
+        float ss = wave_sum(v0 * v0 + v1 * v1);
+        float inv = 1.0f / sqrtf(ss / (float)d + eps);
+        if (live) {
+          float g0, g1;
+          if (BF16) {
+            const uint16_t* g = (const uint16_t*)(is_q ? q_gain : k_gain);
+            g0 = bf2f(g[i]); g1 = bf2f(g[i + half]);
+          } else {
+            const float* g = (const float*)(is_q ? q_gain : k_gain);
+            g0 = g[i]; g1 = g[i + half];
+          }
+          v0 = v0 * inv * g0;
+          v1 = v1 * inv * g1;
+        }
+      }
+      if (live) {
+        float2 cs = rope[(size_t)rm.pos * half + i];
+        float r0 = v0 * cs.x - v1 * cs.y;
+        float r1 = v1 * cs.x + v0 * cs.y;
+        v0 = r0; v1 = r1;
+      }
+    }
+    if (!live) continue;
+    if (is_q) {
+      float* q = q_out + ((size_t)r * n_q + hh) * d;
+      q[i] = v0;
+      q[i + half] = v1;
+    } else {
+      const int hk = is_k ? hh - n_q : hh - n_q - n_kv;
+      const int64_t page = block_table[(size_t)rm.seq * max_blocks + (rm.pos >> 4)];
+      const int t = rm.pos & 15;
+      kv_store<BF16>(is_k ? k_pool : v_pool, page, hk, n_kv, d, t, i, v0, !is_k);
+      kv_store<BF16>(is_k ? k_pool : v_pool, page, hk, n_kv, d, t, i + half, v1, !is_k);
+    }
+  }
+}
+
+void launch_qk_rope_append(hipStream_t s, const Geometry& g, const float* qkv_part, int S, const void* q_gain,
+                           const void* k_gain, const float2* rope_table, const RowMeta* rows,
+                           const int32_t* block_table, void* k_pool_layer, void* v_pool_layer, float* q_out, int M) {
+  dim3 grid(g.n_q + 2 * g.n_kv, M);
+  size_t stride = (size_t)M * (g.n_q + 2 * g.n_kv) * g.head_dim;
+  if (g.dtype == kBF16)
+    qk_rope_append_kernel<true><<<grid, 64, 0, s>>>(qkv_part, S, stride, q_gain, k_gain, rope_table, rows, block_table,
+                                                    g.max_blocks, k_pool_layer, v_pool_layer, q_out, g.n_q, g.n_kv,
+                                                    g.head_dim, g.qk_norm, g.rms_eps);
+  else
+    qk_rope_append_kernel<false><<<grid, 64, 0, s>>>(qkv_part, S, stride, q_gain, k_gain, rope_table, rows, block_table,
+                                                     g.max_blocks, k_pool_layer, v_pool_layer, q_out, g.n_q, g.n_kv,
+                                                     g.head_dim, g.qk_norm, g.rms_eps);
+}
+
+// ------------------------------------------------------------------------------------------------
+// KV import: contiguous [n_tokens][n_kv][d] -> pages of one sequence.
+// ------------------------------------------------------------------------------------------------
+template <typename T, bool BF16>
+__global__ __launch_bounds__(256) void kv_import_kernel(const T* __restrict__ k_src, const T* __restrict__ v_src,
+                                                        int n_tokens, const int32_t* __restrict__ bt_row,
+                                                        void* __restrict__ k_pool, void* __restrict__ v_pool, int n_kv,
+                                                        int d) {
+  const int tok = blockIdx.x;
+  const int64_t page = bt_row[tok >> 4];
+  const int t = tok & 15;
+  for (int i = threadIdx.x; i < n_kv * d; i += 256) {
+    int hk = i / d, dd = i - hk * d;
+    size_t src = (size_t)tok * n_kv * d + i;
+    kv_store<BF16>(k_pool, page, hk, n_kv, d, t, dd, load_as_float(k_src, src), false);
+    kv_store<BF16>(v_pool, page, hk, n_kv, d, t, dd, load_as_float(v_src, src), true);
+  }
+}
+
+void launch_kv_import(hipStream_t s, const Geometry& g, const void* k_src, const void* v_src, int n_tokens,
+                      const int32_t* block_table_row, void* k_pool_layer, void* v_pool_layer) {
+  if (n_tokens <= 0) return;
+  if (g.dtype == kBF16)
+    kv_import_kernel<uint16_t, true><<<n_tokens, 256, 0, s>>>((const uint16_t*)k_src, (const uint16_t*)v_src, n_tokens,
+                                                              block_table_row, k_pool_layer, v_pool_layer, g.n_kv,
+                                                              g.head_dim);
+  else
+    kv_import_kernel<float, false><<<n_tokens, 256, 0, s>>>((const float*)k_src, (const float*)v_src, n_tokens,
+                                                            block_table_row, k_pool_layer, v_pool_layer, g.n_kv,
+                                                            g.head_dim);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Weight packing: row-major [N][K] bf16 -> fragment-major.  One thread per 8 consecutive k.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void pack_weight_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int N,
+                                                          int K) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;  // over N * K/8
+  const int kg = K >> 3;
+  if (idx >= (size_t)N * kg) return;
+  const int n = (int)(idx / kg), k = (int)(idx - (size_t)n * kg) * 8;
+  dst[frag_offset(n, k, K >> 6) >> 3] = src[idx];
+}
+
+void launch_pack_weight_bf16(hipStream_t s, const void* src, void* dst, int N, int K) {
+  size_t total = (size_t)N * (K >> 3);
+  pack_weight_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const uint4*)src, (uint4*)dst, N, K);
+}
+
+}  // namespace rl
+
+namespace rl {
+
+__global__ void table_update_kernel(int32_t* __restrict__ bt, int max_blocks, const int32_t* __restrict__ upd, int n) {
+  const int i = blockIdx.x * 64 + threadIdx.x;
+  if (i < n) bt[(size_t)upd[3 * i] * max_blocks + upd[3 * i + 1]] = upd[3 * i + 2];
+}
+
+void launch_table_update(hipStream_t s, int32_t* block_table, int max_blocks, const int32_t* upd, int n) {
+  if (n <= 0) return;
+  table_update_kernel<<<(n + 63) / 64, 64, 0, s>>>(block_table, max_blocks, upd, n);
+}
+
+}  // namespace rl

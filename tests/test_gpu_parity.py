@@ -1,0 +1,286 @@
+"""GPU parity: the HIP path, called through the C boundary, against the CPU oracle on the same seeded inputs.
+
+Bars: sampled ids bit-exact given the same logits and RNG counters; fp32 logits within 1e-4 (max |diff| over
+max |ref| per row); bf16 logits / layer outputs within 3e-2 on the same bf16-rounded weights with >= 99 %
+argmax agreement; log-probabilities within 1e-5 (fp32 logits).
+"""
+import numpy as np
+import pytest
+import torch
+
+import rollout_inputs as ri
+from helpers import dims_of, make_both, rel_inf, to_device
+from oracle import oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def amd():
+    import paper_2510_17891_amd as pkg
+    pkg.lib()
+    return pkg
+
+
+# ------------------------------------------------------------------------------------------------ sampler
+def _sampler_model(amd, vocab, bf16):
+    if bf16:
+        shape = dict(ri.SHAPES["layer8b"], n_layers=1, hidden=256, n_q=2, n_kv=1, ffn=256, vocab=vocab)
+    else:
+        shape = dict(ri.SHAPES["tiny"], n_layers=1, vocab=vocab)
+    w, _ = make_both(shape, 11)
+    return amd.Rollout(shape, to_device(w), max_seqs=64, max_ctx=64, max_rows=16, kv_pages=8)
+
+
+@pytest.mark.parametrize("vocab,bf16", [(4096, False), (151936, True), (1000, False)])
+def test_sampler_bit_exact_and_logprob(amd, vocab, bf16):
+    ro = _sampler_model(amd, vocab, bf16)
+    n = 6
+    z = ri.normal((n, vocab), 1.3, 5, 70)
+    z[1, 17] = z[1, 900] = 9.0           # an exact tie far above the rest (greedy must take the lower index)
+    z[2, :] = 0.25                       # all equal: only the noise decides
+    z[3, 5] = float("-inf")
+    zd = z.to(DEV)
+    seqs, poss = [3, 0, 7, 63, 1, 2], [0, 1, 65535, 77, 2048, 16383]
+    for T, seed in [(1.0, 1234), (0.7, 99), (0.0, 5), (1.0, 2 ** 63 + 12345)]:
+        tok, lp = ro.rl_sample_logits(zd, seqs, poss, T, seed)
+        torch.cuda.synchronize()
+        for r in range(n):
+            t_ref, lp_ref = orc.sample(z[r].numpy(), T, seed, seqs[r], poss[r])
+            assert int(tok[r]) == t_ref, (T, seed, r)
+            assert abs(float(lp[r]) - lp_ref) < 1e-5 * max(1.0, abs(lp_ref)), (T, r, float(lp[r]), lp_ref)
+    forced = torch.tensor([5, -1, 0, vocab - 1, -1, 3], dtype=torch.int32, device=DEV)
+    tok, lp = ro.rl_sample_logits(zd, seqs, poss, 1.0, 1234, forced=forced)
+    torch.cuda.synchronize()
+    for r in range(n):
+        t_ref, lp_ref = orc.sample(z[r].numpy(), 1.0, 1234, seqs[r], poss[r], forced=int(forced[r]))
+        assert int(tok[r]) == t_ref
+        if np.isfinite(lp_ref):
+            assert abs(float(lp[r]) - lp_ref) < 1e-5 * max(1.0, abs(lp_ref))
+        else:
+            assert float(lp[r]) == lp_ref
+    ro.close()
+
+
+# ------------------------------------------------------------------------------- fp32 tiny model, end to end
+def test_tiny_fp32_greedy_rollout_matches_oracle(amd):
+    """4 prompts x 64 tokens, greedy decode of 32 tokens: every token identical, logits within 1e-4."""
+    shape = ri.SHAPES["tiny"]
+    w, wn = make_both(shape, ri.BASE_SEED + 1)
+    ro = amd.Rollout(shape, to_device(w), max_seqs=8, max_ctx=128, max_rows=64, kv_pages=40)
+    ro.rl_debug_shuffle_free_pages(3)
+    om = orc.OracleModel(dims_of(shape), wn, max_ctx=128)
+    prompts = ri.tokens((4, 64), shape["vocab"], ri.BASE_SEED + 1, 900).tolist()
+    seqs = [5, 0, 2, 7]
+    tok, lp = ro.rl_prefill(seqs, prompts, 0.0, 0)        # prefill is chunked: 256 rows > max_rows = 64
+    torch.cuda.synchronize()
+    z0 = [om.prefill(s, p) for s, p in zip(seqs, prompts)]
+    for i, s in enumerate(seqs):
+        t_ref, lp_ref = orc.sample(z0[i], 0.0, 0, s, 64)
+        assert int(tok[i]) == t_ref and abs(float(lp[i]) - lp_ref) < 2e-5
+    logits = torch.empty(4, shape["vocab"], device=DEV)
+    worst = 0.0
+    for step in range(32):
+        cur = tok
+        tok, lp = ro.rl_decode_step(seqs, cur, 0.0, 0, debug_logits=logits)
+        torch.cuda.synchronize()
+        zg = logits.cpu().numpy()
+        for i, s in enumerate(seqs):
+            z = om.forward_token(s, int(cur[i]))
+            worst = max(worst, float(rel_inf(zg[i], z)))
+            t_ref, lp_ref = orc.sample(z, 0.0, 0, s, 65 + step)
+            assert int(tok[i]) == t_ref, (step, i)
+            assert abs(float(lp[i]) - lp_ref) < 2e-5
+    assert worst < 1e-4, worst
+    assert ro.rl_seq_len(5) == 96
+    ro.rl_free_seqs(seqs)
+    assert ro.rl_kv_stats() == (40, 40)
+    ro.close()
+
+
+def test_tiny_fp32_sampled_rollout_ids_bit_exact_given_logits(amd):
+    """T = 1 sampling: with the GPU's own logits the oracle sampler reproduces every id; ragged prompts."""
+    shape = dict(ri.SHAPES["tiny"], qk_norm=0)
+    w, wn = make_both(shape, ri.BASE_SEED + 2)
+    ro = amd.Rollout(shape, to_device(w), max_seqs=4, max_ctx=64, max_rows=4, kv_pages=12)
+    om = orc.OracleModel(dims_of(shape), wn, max_ctx=64)
+    lens = [1, 17, 16]
+    prompts = [ri.tokens((n,), shape["vocab"], 3, 910 + i).tolist() for i, n in enumerate(lens)]
+    seqs = [0, 1, 3]
+    seed = 20251017
+    tok, lp = ro.rl_prefill(seqs, prompts, 1.0, seed)
+    torch.cuda.synchronize()
+    for i, s in enumerate(seqs):
+        z = om.prefill(s, prompts[i])
+        t_ref, lp_ref = orc.sample(z, 1.0, seed, s, lens[i])
+        assert int(tok[i]) == t_ref and abs(float(lp[i]) - lp_ref) < 2e-5
+    logits = torch.empty(3, shape["vocab"], device=DEV)
+    for step in range(20):
+        cur = tok
+        tok, lp = ro.rl_decode_step(seqs, cur, 1.0, seed, debug_logits=logits)
+        torch.cuda.synchronize()
+        zg = logits.cpu().numpy()
+        for i, s in enumerate(seqs):
+            z = om.forward_token(s, int(cur[i]))
+            assert rel_inf(zg[i], z) < 1e-4
+            t_ref, lp_ref = orc.sample(zg[i], 1.0, seed, s, lens[i] + step + 1)
+            assert int(tok[i]) == t_ref
+            assert abs(float(lp[i]) - lp_ref) < 1e-5
+    ro.close()
+
+
+# ------------------------------------------------------------------------- bf16, one layer at 8B dimensions
+def _layer_case(amd, ctxs, seed, max_rows=None, shuffle=None):
+    """Import random N(0,1) bf16 KV of the given lengths, run one decode step on N(0,1) hidden rows."""
+    shape = ri.SHAPES["layer8b"]
+    w, wn = make_both(shape, seed)
+    B = len(ctxs)
+    max_ctx = (max(ctxs) + 1 + 15) // 16 * 16 + 16
+    pages = sum((c + 1 + 15) // 16 for c in ctxs) + 4
+    ro = amd.Rollout(shape, to_device(w), max_seqs=B, max_ctx=max_ctx, max_rows=max_rows or B, kv_pages=pages)
+    if shuffle is not None:
+        ro.rl_debug_shuffle_free_pages(shuffle)
+    nkv, d, H = shape["n_kv"], shape["head_dim"], shape["hidden"]
+    ks, vs = [], []
+    for b, c in enumerate(ctxs):
+        k = ri.normal((c, nkv, d), 1.0, seed, 2000 + 2 * b, dtype=torch.bfloat16)
+        v = ri.normal((c, nkv, d), 1.0, seed, 2001 + 2 * b, dtype=torch.bfloat16)
+        ks.append(k)
+        vs.append(v)
+        ro.rl_seq_import_kv(b, [k.to(DEV)], [v.to(DEV)])
+    x = ri.normal((B, H), 1.0, seed, 1999).to(torch.bfloat16).float()
+    return shape, wn, ro, ks, vs, x
+
+
+def _oracle_layer_row(shape, wn, k, v, x_row, ctx):
+    kc = np.zeros((ctx + 1, shape["n_kv"], shape["head_dim"]), np.float32)
+    vc = np.zeros_like(kc)
+    kc[:ctx] = k.float().numpy()
+    vc[:ctx] = v.float().numpy()
+    xo = np.ascontiguousarray(x_row.numpy().copy())
+    orc.layer_forward(dims_of(shape), wn["layers"][0], xo, ctx, kc, vc)
+    return xo
+
+
+@pytest.mark.parametrize("ctxs", [
+    [0, 1, 15, 16, 17, 255, 256, 257, 700],            # page and chunk boundaries, empty history
+    [300 + 7 * i for i in range(37)],                  # 37 rows: two column blocks with a ragged tail
+    [33],                                              # a single row
+])
+def test_bf16_layer_decode_matches_oracle(amd, ctxs):
+    shape, wn, ro, ks, vs, x = _layer_case(amd, ctxs, seed=31, shuffle=9)
+    out = ro.rl_decode_hidden(list(range(len(ctxs))), x.to(DEV))
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    assert np.isfinite(out).all()
+    for b, c in enumerate(ctxs):
+        ref = _oracle_layer_row(shape, wn, ks[b], vs[b], x[b], c)
+        err = rel_inf(out[b] - x[b].numpy(), ref - x[b].numpy())
+        assert err < 3e-2, (b, c, err)
+        assert ro.rl_seq_len(b) == c + 1
+    ro.close()
+
+
+def test_bf16_layer_batch_and_page_placement_invariance(amd):
+    ctxs = [40, 513, 100, 257, 31]
+    shape, wn, ro, ks, vs, x = _layer_case(amd, ctxs, seed=32)
+    full = ro.rl_decode_hidden(list(range(5)), x.to(DEV)).cpu()
+    ro.close()
+    # same sequences, other pages, decoded alone or in another order
+    shape, wn, ro, ks, vs, x = _layer_case(amd, ctxs, seed=32, shuffle=1234)
+    alone = ro.rl_decode_hidden([3], x[3:4].to(DEV)).cpu()
+    rest = ro.rl_decode_hidden([4, 0, 2, 1], x[[4, 0, 2, 1]].to(DEV)).cpu()
+    torch.cuda.synchronize()
+    assert torch.equal(alone[0], full[3])
+    assert torch.equal(rest, full[[4, 0, 2, 1]])
+    ro.close()
+
+
+# --------------------------------------------------------------------------- bf16 small full model, logits
+def test_bf16_small_model_teacher_forced_logits(amd):
+    """2-layer bf16 decoder (8B head geometry, narrow): prefill + teacher-forced decode; logits within 3e-2,
+    argmax agreement >= 99 %, sampled ids reproduced by the oracle sampler from the GPU's logits."""
+    shape = dict(ri.SHAPES["layer8b"], n_layers=2, hidden=512, n_q=4, n_kv=1, ffn=768, vocab=8192)
+    w, wn = make_both(shape, 41, std=0.05)
+    ro = amd.Rollout(shape, to_device(w), max_seqs=4, max_ctx=320, max_rows=40, kv_pages=64)
+    om = orc.OracleModel(dims_of(shape), wn, max_ctx=320)
+    lens = [270, 3, 33]
+    prompts = [ri.tokens((n,), shape["vocab"], 41, 920 + i).tolist() for i, n in enumerate(lens)]
+    seqs = [2, 0, 1]
+    seed = 77
+    tok, lp = ro.rl_prefill(seqs, prompts, 1.0, seed)
+    torch.cuda.synchronize()
+    for i, s in enumerate(seqs):
+        om.prefill(s, prompts[i])
+    steps = 24
+    forced_all = ri.tokens((steps, 3), shape["vocab"], 41, 930)
+    logits = torch.empty(3, shape["vocab"], device=DEV)
+    cur = ri.tokens((3,), shape["vocab"], 41, 929).to(DEV)
+    agree, total, worst = 0, 0, 0.0
+    for step in range(steps):
+        forced = forced_all[step].clone()
+        forced[step % 3] = -1                         # leave one row sampled each step
+        tok, lp = ro.rl_decode_step(seqs, cur, 1.0, seed, forced_next=forced.to(DEV), debug_logits=logits)
+        torch.cuda.synchronize()
+        zg = logits.cpu().numpy()
+        for i, s in enumerate(seqs):
+            z = om.forward_token(s, int(cur[i]))
+            worst = max(worst, float(rel_inf(zg[i], z)))
+            agree += int(np.argmax(zg[i]) == np.argmax(z))
+            total += 1
+            t_ref, lp_ref = orc.sample(zg[i], 1.0, seed, s, lens[i] + step + 1, forced=int(forced[i]))
+            assert int(tok[i]) == t_ref
+            assert abs(float(lp[i]) - lp_ref) < 1e-4
+            _, lp_orc = orc.sample(z, 1.0, seed, s, lens[i] + step + 1, forced=t_ref)
+            assert abs(float(lp[i]) - lp_orc) < 5e-2
+        cur = tok
+    assert worst < 3e-2, worst
+    assert agree >= 0.99 * total, (agree, total)
+    ro.close()
+
+
+# ------------------------------------------------------------------------------------------- error handling
+def test_error_paths_leave_state_untouched(amd):
+    B = amd.binding
+    shape = ri.SHAPES["tiny"]
+    w, _ = make_both(shape, 51)
+    ro = amd.Rollout(shape, to_device(w), max_seqs=4, max_ctx=32, max_rows=4, kv_pages=3)
+    p = ri.tokens((20,), shape["vocab"], 51, 940).tolist()
+    with pytest.raises(B.RLError) as e:
+        ro.rl_prefill([0, 1], [p, p], 0.0, 0)         # 2 x 2 pages > 3
+    assert e.value.status == B.RL_ERR_KV_FULL and ro.rl_kv_stats() == (3, 3)
+    with pytest.raises(B.RLError) as e:
+        ro.rl_prefill([4], [p], 0.0, 0)
+    assert e.value.status == B.RL_ERR_BAD_SEQ
+    with pytest.raises(B.RLError) as e:
+        ro.rl_prefill([0], [p + p], 0.0, 0)
+    assert e.value.status == B.RL_ERR_CTX_OVERFLOW
+    with pytest.raises(B.RLError) as e:
+        ro.rl_prefill([0], [[shape["vocab"]]], 0.0, 0)
+    assert e.value.status == B.RL_ERR_INVALID_ARG
+    tok, _ = ro.rl_prefill([0], [p], 0.0, 0)
+    assert ro.rl_kv_stats() == (1, 3)
+    with pytest.raises(B.RLError) as e:
+        ro.rl_prefill([0], [p], 0.0, 0)               # already active
+    assert e.value.status == B.RL_ERR_BAD_SEQ
+    with pytest.raises(B.RLError) as e:
+        ro.rl_decode_step([1], tok, 0.0, 0)           # not active
+    assert e.value.status == B.RL_ERR_BAD_SEQ
+    with pytest.raises(B.RLError) as e:
+        ro.rl_decode_step([0, 0], torch.cat([tok, tok]), 0.0, 0)
+    assert e.value.status == B.RL_ERR_INVALID_ARG
+    for _ in range(12):                               # 20 -> 32 tokens = max_ctx
+        tok, _ = ro.rl_decode_step([0], tok, 0.0, 0)
+    assert ro.rl_seq_len(0) == 32
+    with pytest.raises(B.RLError) as e:
+        ro.rl_decode_step([0], tok, 0.0, 0)
+    assert e.value.status == B.RL_ERR_CTX_OVERFLOW and ro.rl_seq_len(0) == 32
+    ro.rl_free_seqs([0])
+    with pytest.raises(B.RLError) as e:
+        ro.rl_free_seqs([0])
+    assert e.value.status == B.RL_ERR_BAD_SEQ
+    assert ro.rl_kv_stats() == (3, 3)
+    torch.cuda.synchronize()
+    ro.close()

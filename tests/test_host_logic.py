@@ -1,0 +1,108 @@
+"""CPU tests of the library's host side: exported symbols of the C boundary and the page allocator."""
+import ctypes as C
+import os
+import re
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CSRC = os.path.join(ROOT, "paper_2510_17891_amd", "csrc")
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2510_17891_amd import binding
+    L = binding.lib()                       # loads without a GPU; no compute call is made here
+    header = open(os.path.join(ROOT, "include", "rl.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(rl_[a-z_0-9]+)\s*\(", header)))
+    assert len(declared) >= 18
+    for name in declared:
+        assert hasattr(L, name), name
+    assert sorted(binding.EXPORTS) == declared
+    assert L.rl_last_error() is not None
+
+
+def test_config_validation_needs_no_gpu():
+    from paper_2510_17891_amd import binding as B
+    import rollout_inputs as ri
+    L = B.lib()
+    need = C.c_uint64()
+    cfg = B.make_config(ri.SHAPES["full8b"], B.RL_BF16, 256, 16384, 256)
+    assert L.rl_query_workspace(C.byref(cfg), C.byref(need)) == B.RL_OK
+    assert 100e6 < need.value < 2e9
+    assert L.rl_kv_page_bytes(C.byref(cfg)) == 36 * 2 * 8 * 16 * 128 * 2      # 147456 B per token
+    bad = B.make_config(dict(ri.SHAPES["full8b"], head_dim=64), B.RL_BF16, 4, 64, 4)
+    assert L.rl_query_workspace(C.byref(bad), C.byref(need)) == B.RL_ERR_UNSUPPORTED
+    assert b"head_dim" in L.rl_last_error()
+    bad = B.make_config(ri.SHAPES["tiny"], B.RL_F32, 4, 60, 4)                 # max_ctx not a multiple of 16
+    assert L.rl_query_workspace(C.byref(bad), C.byref(need)) == B.RL_ERR_INVALID_ARG
+    bad = B.make_config(ri.SHAPES["tiny"], B.RL_F32, 4, 64, 300)
+    assert L.rl_query_workspace(C.byref(bad), C.byref(need)) == B.RL_ERR_INVALID_ARG
+    cfg = B.make_config(ri.SHAPES["tiny"], B.RL_F32, 4, 64, 4)
+    cfg.struct_size = 8
+    assert L.rl_query_workspace(C.byref(cfg), C.byref(need)) == B.RL_ERR_INVALID_ARG
+    assert L.rl_init_model(None, None, None) == B.RL_ERR_INVALID_ARG
+
+
+@pytest.fixture(scope="module")
+def st(tmp_path_factory):
+    out = str(tmp_path_factory.mktemp("st") / "libseqtable.so")
+    subprocess.run(["g++", "-O1", "-std=c++17", "-fPIC", "-shared", "-fsanitize=undefined", "-fno-sanitize-recover",
+                    "-o", out, os.path.join(CSRC, "seq_table_capi.cpp")], check=True)
+    L = C.CDLL(out)
+    L.st_create.restype = C.c_void_p
+    L.st_create.argtypes = [C.c_int, C.c_int, C.c_longlong]
+    L.st_free_pages.restype = C.c_longlong
+    for f in ("st_destroy", "st_free_pages"):
+        getattr(L, f).argtypes = [C.c_void_p]
+    for f in ("st_active", "st_len", "st_activate", "st_release", "st_n_seq_pages"):
+        getattr(L, f).argtypes = [C.c_void_p, C.c_int]
+    for f in ("st_pages_missing", "st_set_len", "st_seq_page"):
+        getattr(L, f).argtypes = [C.c_void_p, C.c_int, C.c_int]
+    L.st_shuffle.argtypes = [C.c_void_p, C.c_ulonglong]
+    L.st_reserve.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_int), C.c_int]
+    return L
+
+
+def _reserve(L, t, s, tokens):
+    buf = (C.c_int * 3000)()
+    n = L.st_reserve(t, s, tokens, buf, 1000)
+    return [(buf[3 * i], buf[3 * i + 1], buf[3 * i + 2]) for i in range(n)]
+
+
+def test_page_allocator_growth_free_reuse(st):
+    t = st.st_create(4, 64, 6)
+    assert st.st_free_pages(t) == 6 and not st.st_active(t, 0)
+    assert st.st_pages_missing(t, 0, 17) == 2
+    st.st_activate(t, 0)
+    g = _reserve(st, t, 0, 17)
+    assert [(s, b) for s, b, _ in g] == [(0, 0), (0, 1)] and st.st_free_pages(t) == 4
+    st.st_set_len(t, 0, 17)
+    assert st.st_pages_missing(t, 0, 32) == 0 and st.st_pages_missing(t, 0, 33) == 1
+    assert _reserve(st, t, 0, 32) == []                       # ragged growth: no page until the boundary
+    g2 = _reserve(st, t, 0, 33)
+    assert len(g2) == 1 and g2[0][1] == 2
+    st.st_activate(t, 1)
+    g3 = _reserve(st, t, 1, 48)
+    assert st.st_free_pages(t) == 0
+    pages = [p for _, _, p in g + g2 + g3]
+    assert sorted(pages) == list(range(6))                    # every page handed out exactly once
+    assert st.st_pages_missing(t, 2, 1) == 1                  # an inactive sequence needs all its pages
+    st.st_release(t, 0)
+    assert st.st_free_pages(t) == 3 and not st.st_active(t, 0) and st.st_len(t, 0) == -1
+    st.st_activate(t, 2)
+    g4 = _reserve(st, t, 2, 40)
+    assert sorted(p for _, _, p in g4) == sorted(p for _, _, p in g + g2)   # freed pages are reused
+    assert st.st_n_seq_pages(t, 2) == 3 and st.st_seq_page(t, 2, 0) == g4[0][2]
+    st.st_destroy(t)
+
+
+def test_page_allocator_shuffle_is_a_permutation(st):
+    t = st.st_create(2, 16 * 100, 100)
+    st.st_shuffle(t, 42)
+    st.st_activate(t, 0)
+    g = _reserve(st, t, 0, 1600)
+    pages = [p for _, _, p in g]
+    assert sorted(pages) == list(range(100)) and pages != list(range(100))
+    st.st_destroy(t)
