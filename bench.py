@@ -1,0 +1,232 @@
+"""Benchmark of the rollout hot path on one MI355X.
+
+Workload "full8b_32x1024+N" (default): the 36-layer 8B-shaped bf16 policy, 4 prompts x group 8 = 32 sequences
+with 1024-token prompts (uniform-random ids stand in for the paper's prompts, N(0,0.02) weights for the
+checkpoint).  The prompts are prefilled (timed separately), then EXACTLY --steps decode steps are timed; one
+step = embed, 36 layers (norm, QKV, rotary+append, paged attention, O, norm, gate/up+SwiGLU, down), final
+norm, lm_head, Gumbel-max sampling with log-probs, for all 32 sequences.  Everything is resident in HBM when the
+timed region starts.  Prints one JSON line.
+
+Workload "layer8b_b64_ctx2048" (--workload layer): one decoder layer at the same dimensions, batch 64 over
+2048 cached tokens per sequence, one decode step per "step".
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=512)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", choices=["full", "layer"], default="full")
+    ap.add_argument("--profile-steps", type=int, default=8, help="extra steps run with per-kernel events")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true")
+    return ap.parse_args()
+
+
+def kernel_bytes(shape, M, ctx_sum, bf=2):
+    """Algorithmic HBM bytes of one launch of each kernel class at batch M (sum of contexts ctx_sum)."""
+    H, d, F, V = shape["hidden"], shape["head_dim"], shape["ffn"], shape["vocab"]
+    nq, nkv = shape["n_q"], shape["n_kv"]
+    nqkv, nqd = (nq + 2 * nkv) * d, nq * d
+    return {
+        "gemm_qkv": nqkv * H * bf + M * H * bf + M * nqkv * 4,
+        "gemm_o": H * nqd * bf + M * nqd * bf + M * H * 4,
+        "gemm_gate_up_swiglu": 2 * F * H * bf + M * H * bf + M * F * bf,
+        "gemm_down": H * F * bf + M * F * bf + M * H * 4,
+        "gemm_lm_head": V * H * bf + M * H * bf + M * V * 4,
+        "attn_decode": ctx_sum * nkv * 2 * d * bf + M * nqd * 4 * 2,
+    }
+
+
+def cpu_baseline_full(shape, ctx, n_seq=2):
+    """Time the oracle on a bounded sample: one decoder layer for n_seq sequences at context `ctx`, plus 1/16 of
+    the output projection; scale to the 36-layer model.  Returns tokens/s of the oracle for one sequence."""
+    import numpy as np
+    import torch
+    import rollout_inputs as ri
+    from oracle import oracle as orc
+    dims = {k: shape[k] for k in ("hidden", "n_q", "n_kv", "head_dim", "ffn", "qk_norm", "rms_eps", "rope_base")}
+    lw = {k: np.ascontiguousarray(v.to(torch.bfloat16).float().numpy())
+          for k, v in ri.make_layer(shape, ri.BASE_SEED, 0).items()}
+    rows = shape["vocab"] // 16
+    lm = np.ascontiguousarray(ri.normal((rows, shape["hidden"]), 0.02, ri.BASE_SEED, 2).to(torch.bfloat16).float().numpy())
+    kc = np.ascontiguousarray(ri.normal((ctx + 1, shape["n_kv"], shape["head_dim"]), 1.0, ri.BASE_SEED, 7).numpy())
+    vc = kc.copy()
+    x = ri.normal((n_seq, shape["hidden"]), 1.0, ri.BASE_SEED, 8).numpy()
+    orc.matvec(lm[:64], x[0])  # load the library, spin up threads
+    t0 = time.perf_counter()
+    for s in range(n_seq):
+        xs = np.ascontiguousarray(x[s].copy())
+        orc.layer_forward(dims, lw, xs, ctx, kc, vc)
+    t_layer = (time.perf_counter() - t0) / n_seq
+    t0 = time.perf_counter()
+    for s in range(n_seq):
+        orc.matvec(lm, x[s])
+    t_head = (time.perf_counter() - t0) / n_seq * 16
+    t_tok = shape["n_layers"] * t_layer + t_head
+    return {"value": 1.0 / t_tok, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"oracle timed on 1 decoder layer x {n_seq} sequences at context {ctx} and 1/16 of the lm_head rows, "
+                      f"scaled to {shape['n_layers']} layers + full lm_head for one sequence (sampler excluded)"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (rollouts shard by whole sequences with no per-step "
+              "communication; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import rollout_inputs as ri
+    from paper_2510_17891_amd import Rollout
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    seed = ri.BASE_SEED + 2
+
+    if args.workload == "full":
+        shape = ri.SHAPES["full8b"]
+        n_prompts, G, P = 4, 8, 1024
+        B = n_prompts * G
+        total_steps = args.warmup + args.steps + (0 if args.no_profile else args.profile_steps)
+        max_ctx = (P + total_steps + 1 + 15) // 16 * 16
+        pages = B * (max_ctx // 16)
+        w = ri.make_weights(shape, seed, device=dev, dtype=torch.bfloat16)
+        ro = Rollout(shape, w, max_seqs=B, max_ctx=max_ctx, max_rows=256, kv_pages=pages)
+        del w
+        torch.cuda.empty_cache()
+        prompts = ri.tokens((n_prompts, P), shape["vocab"], seed, 900)
+        prompt_list = [prompts[i // G].tolist() for i in range(B)]
+        seq_ids = list(range(B))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        tok, lp = ro.rl_prefill(seq_ids, prompt_list, 1.0, seed)
+        torch.cuda.synchronize()
+        prefill_s = time.perf_counter() - t0
+        workload = f"full8b_36L_bf16_{B}seq_prompt{P}_T1.0"
+        ctx0 = P
+    else:
+        shape = ri.SHAPES["layer8b"]
+        B, ctx0 = 64, 2048
+        total_steps = args.warmup + args.steps + (0 if args.no_profile else args.profile_steps)
+        max_ctx = (ctx0 + total_steps + 1 + 15) // 16 * 16
+        pages = B * (max_ctx // 16)
+        w = ri.make_weights(shape, seed, device=dev, dtype=torch.bfloat16)
+        ro = Rollout(shape, w, max_seqs=B, max_ctx=max_ctx, max_rows=B, kv_pages=pages)
+        ro.rl_debug_shuffle_free_pages(seed)  # block tables are a random permutation of the pool
+        for b in range(B):
+            k = ri.normal((ctx0, shape["n_kv"], shape["head_dim"]), 1.0, seed, 2000 + 2 * b, device=dev, dtype=torch.bfloat16)
+            v = ri.normal((ctx0, shape["n_kv"], shape["head_dim"]), 1.0, seed, 2001 + 2 * b, device=dev, dtype=torch.bfloat16)
+            ro.rl_seq_import_kv(b, [k], [v])
+        seq_ids = list(range(B))
+        x_in = ri.normal((B, shape["hidden"]), 1.0, seed, 1999, device=dev)
+        x_out = torch.empty_like(x_in)
+        prefill_s = None
+        workload = f"layer8b_1L_bf16_b{B}_ctx{ctx0}"
+
+    from paper_2510_17891_amd.binding import _i32
+    ids = _i32(seq_ids)
+    if args.workload == "full":
+        bufs = [(torch.empty(B, dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.float32, device=dev))
+                for _ in range(2)]
+        state = {"cur": tok, "i": 0}
+
+        def step():
+            ot, ol = bufs[state["i"] & 1]
+            ro.rl_decode_step(ids, state["cur"], 1.0, seed, out_tokens=ot, out_logprobs=ol)
+            state["cur"] = ot
+            state["i"] += 1
+    else:
+        def step():
+            ro.rl_decode_hidden(ids, x_in, x_out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    ctx_begin = ctx0 + args.warmup
+    ctx_end = ctx_begin + args.steps  # context of the last timed step is ctx_end - 1 (+1 for the fed token)
+    ctx_avg = 0.5 * (ctx_begin + ctx_end - 1) + 1
+    n_layers = shape["n_layers"]
+    kb_mid = kernel_bytes(shape, B, int(B * ctx_avg)) if shape["vocab"] else None
+    step_bytes = None
+    if args.workload == "full":
+        kbm = kernel_bytes(shape, B, int(B * ctx_avg))
+        step_bytes = n_layers * (kbm["gemm_qkv"] + kbm["gemm_o"] + kbm["gemm_gate_up_swiglu"] + kbm["gemm_down"]
+                                 + kbm["attn_decode"]) + kbm["gemm_lm_head"]
+    else:
+        shp = dict(shape, vocab=4)
+        kbm = kernel_bytes(shp, B, int(B * ctx_avg))
+        step_bytes = kbm["gemm_qkv"] + kbm["gemm_o"] + kbm["gemm_gate_up_swiglu"] + kbm["gemm_down"] + kbm["attn_decode"]
+
+    out = {
+        "metric": "generated tokens/s (8B-shaped bf16 decode) + % peak HBM GB/s, 1 MI355X",
+        "value": B * args.steps / elapsed,
+        "unit": "tokens/s" if args.workload == "full" else "layer-tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": workload, "batch": B, "context_first_timed_step": ctx_begin + 1,
+                   "context_last_timed_step": ctx_end, "kv_block": 16, "temperature": 1.0},
+        "step_hbm_fraction": step_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9),
+        "step_algorithmic_GB": step_bytes / 1e9,
+    }
+    if prefill_s is not None:
+        out["prefill_s"] = prefill_s
+        out["prefill_tokens_per_s"] = B * 1024 / prefill_s
+
+    # ---- per-kernel durations from HIP events on the launch stream, same steps, same state --------------
+    if not args.no_profile:
+        ro.rl_profile_enable(True)
+        for _ in range(args.profile_steps):
+            step()
+        torch.cuda.synchronize()
+        prof = ro.rl_profile_read()
+        ro.rl_profile_enable(False)
+        ctx_p = ctx_end + 0.5 * (args.profile_steps - 1) + 1
+        shp = shape if shape["vocab"] else dict(shape, vocab=4)
+        kb = kernel_bytes(shp, B, int(B * ctx_p))
+        kernels = {}
+        for name, (cnt, ms) in prof.items():
+            if cnt == 0:
+                continue
+            avg_us = ms / cnt * 1e3
+            entry = {"launches": cnt, "avg_us": avg_us, "share": None}
+            if name in kb:
+                entry["achieved_GBs"] = kb[name] / (avg_us * 1e-6) / 1e9
+                entry["bytes"] = kb[name]
+            kernels[name] = entry
+        tot = sum(e["avg_us"] * e["launches"] for e in kernels.values())
+        for e in kernels.values():
+            e["share"] = e["avg_us"] * e["launches"] / tot
+        out["kernels"] = kernels
+        dom = max((n for n in kernels if n in kb), key=lambda n: kernels[n]["avg_us"] * kernels[n]["launches"])
+        out["roofline"] = {"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["achieved_GBs"], "peak": HBM_PEAK_GBS,
+                           "unit": "GB/s", "frac": kernels[dom]["achieved_GBs"] / HBM_PEAK_GBS, "traffic": None}
+    if not args.no_cpu_baseline:
+        if args.workload == "full":
+            out["cpu_baseline"] = cpu_baseline_full(shape, int(ctx_avg))
+        else:
+            cb = cpu_baseline_full(dict(shape, vocab=16 * 64), ctx0, n_seq=2)
+            cb["unit"] = "layer-tokens/s"
+            out["cpu_baseline"] = cb
+    ro.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

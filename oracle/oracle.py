@@ -35,6 +35,7 @@ def lib():
     if _lib is None:
         path = _build.build()
         L = C.CDLL(path)
+        L.orc_num_threads.restype = C.c_int32
         L.orc_bf16_round.restype = C.c_float
         L.orc_bf16_round.argtypes = [C.c_float]
         L.orc_bf16_round_array.argtypes = [_f32p, C.c_int64]
@@ -73,6 +74,10 @@ def _p(a):
 
 def f32(a):
     return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def num_threads():
+    return int(lib().orc_num_threads())
 
 
 def bf16_round(a):

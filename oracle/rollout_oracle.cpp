@@ -29,6 +29,9 @@
 #include <cstdint>
 #include <cstring>
 #include <vector>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 extern "C" {
 
@@ -61,6 +64,15 @@ struct orc_layer {
   const float* w_up;       // [F][H]
   const float* w_down;     // [H][F]
 };
+
+// Threads the row-parallel matvec uses (reported next to timings of this oracle).
+int32_t orc_num_threads() {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
 
 // Round-to-nearest-even of an fp32 value to bfloat16, widened back to fp32.
 // Used by tests to put weights / KV on the bf16 grid before both sides see them.
