@@ -28,7 +28,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=512)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", choices=["full", "layer"], default="full")
+    ap.add_argument("--workload", choices=["full", "layer", "copy"], default="full")
     ap.add_argument("--profile-steps", type=int, default=8, help="extra steps run with per-kernel events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
@@ -93,6 +93,30 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     seed = ri.BASE_SEED + 2
+
+    if args.workload == "copy":
+        # Plain device copy of known size: the reference against which HBM byte counters are scaled, and the
+        # on-box streaming ceiling (reads 1 GiB and writes 1 GiB per launch).
+        n = 1 << 30
+        src = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        red = torch.empty(n // 4, dtype=torch.float32, device=dev).normal_()
+        for _ in range(max(1, args.warmup)):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / args.steps
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            red.sum()
+        torch.cuda.synchronize()
+        dr = (time.perf_counter() - t0) / args.steps
+        print(json.dumps({"workload": "copy_1GiB", "bytes_read": n, "bytes_written": n, "us_per_copy": dt * 1e6,
+                          "copy_GBs_read_plus_write": 2 * n / dt / 1e9, "read_only_sum_GBs": n / dr / 1e9}))
+        return
 
     if args.workload == "full":
         shape = ri.SHAPES["full8b"]

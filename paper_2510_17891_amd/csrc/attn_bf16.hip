@@ -10,8 +10,12 @@
 //   O^T[d][head]          += V^T[d][key] P[key][head]    MFMA 16x16x32 over two pages (32 keys); the P operand is
 //                                                        exactly the registers the score MFMA produced
 //
-// One wave handles one (row, kv head, 256-key chunk) and leaves (max, sum, unnormalised O) per head; a second
-// small kernel merges the chunks of a row in index order, which makes the result independent of the batch.
+// One block of four waves handles one (row, kv head).  The context is cut into segments whose number and
+// bounds depend on the context length alone (4*ceil(ctx/1024) equal runs of 32-key steps); each wave streams a
+// contiguous quarter of them, leaving (max, sum, unnormalised O) per head and segment, and after a block barrier
+// the four waves merge the segments of one head each, flat and in index order.  Nothing crosses blocks, so no
+// device-scope fence (an L2 write-back on this multi-die part) is needed, and the bits of a row's result do not
+// depend on the batch.
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -48,19 +52,25 @@ __device__ __forceinline__ void load_pair(PagePair& pp, const u32x4_t* __restric
   }
 }
 
-// grid: x = chunk, y = kv head, z = row.  block = one wave.
-__global__ __launch_bounds__(64) void attn_decode_bf16_kernel(const float* __restrict__ q, const RowMeta* __restrict__ rows,
-                                                              const int32_t* __restrict__ block_table, int max_blocks,
-                                                              const u32x4_t* __restrict__ k_pool,
-                                                              const u32x4_t* __restrict__ v_pool, float* __restrict__ part,
-                                                              int max_chunks, int n_q, int n_kv, float scale) {
-  const int chunk = blockIdx.x, hk = blockIdx.y, r = blockIdx.z, lane = threadIdx.x;
+__host__ __device__ inline int attn_num_segments(int ctx) { return 4 * ((ctx + 1023) / 1024); }
+
+// grid: x = kv head, y = row.  block = four waves.
+__global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* __restrict__ q, const RowMeta* __restrict__ rows,
+                                                               const int32_t* __restrict__ block_table, int max_blocks,
+                                                               const u32x4_t* __restrict__ k_pool,
+                                                               const u32x4_t* __restrict__ v_pool, float* __restrict__ part,
+                                                               int max_segs, int n_q, int n_kv, float scale,
+                                                               uint16_t* __restrict__ o_out) {
+  extern __shared__ int32_t pages[];  // block-table slice of this row: ceil(ctx/16) entries (+1 pad)
+  const int hk = blockIdx.x, r = blockIdx.y;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const RowMeta rm = rows[r];
   const int ctx = rm.pos + 1;  // keys 0..pos (the row's own key was appended before this kernel)
-  const int key0 = chunk * kAttnChunk;
-  if (key0 >= ctx) return;
   const int group = n_q / n_kv;  // <= 8
   const int j = lane & 15, g = lane >> 4;
+  const int n_blk = (ctx + 15) >> 4;
+  for (int i = threadIdx.x; i <= n_blk; i += 256)  // entry n_blk duplicates the last page (odd page counts)
+    pages[i] = block_table[(size_t)rm.seq * max_blocks + (i < n_blk ? i : n_blk - 1)];
 
   // ---- q operand: column j < group holds head hk*group + j; hi/lo bf16 split ---------------------
   u32x4_t q_hi[4], q_lo[4];
@@ -81,41 +91,42 @@ __global__ __launch_bounds__(64) void attn_decode_bf16_kernel(const float* __res
       q_lo[s] = (u32x4_t){lo[0], lo[1], lo[2], lo[3]};
     }
   }
-
-  // ---- page ids of this chunk (16 pages), lane i < 16 holds page i -------------------------------
-  const int last_blk = (ctx - 1) >> 4;
-  int my_blk = (key0 >> 4) + (lane & 15);
-  if (my_blk > last_blk) my_blk = last_blk;  // never dereference unallocated entries
-  const int32_t my_page = block_table[(size_t)rm.seq * max_blocks + my_blk];
+  __syncthreads();
 
   const u32x4_t* kb = k_pool + (size_t)hk * (kPageElems / 8);
   const u32x4_t* vb = v_pool + (size_t)hk * (kPageElems / 8);
+  const int n_it = (ctx + 31) >> 5;  // 32-key steps
+  const int n_seg = attn_num_segments(ctx);
+  const int seg_per_wave = n_seg >> 2;
+  auto seg_begin = [&](int sgm) { return (int)(((long long)sgm * n_it) / n_seg); };
 
   f32x4_t o_acc[8];
+  float m_run, l_run;
+  auto reset = [&]() {
 #pragma unroll
-  for (int b = 0; b < 8; ++b) o_acc[b] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-  float m_run = -INFINITY, l_run = 0.f;
+    for (int b = 0; b < 8; ++b) o_acc[b] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+    m_run = -INFINITY;
+    l_run = 0.f;
+  };
+  reset();
+  int seg = wave * seg_per_wave;
+  const int seg_end = seg + seg_per_wave;
+  const int it_begin = seg_begin(seg), it_end = seg_begin(seg_end);
+  while (seg < seg_end && seg_begin(seg + 1) == seg_begin(seg)) ++seg;  // skip leading empty segments
+  int boundary = seg < seg_end ? seg_begin(seg + 1) : it_end;
 
-  const int keys_here = min(kAttnChunk, ctx - key0);
-  const int n_iter = (keys_here + 31) >> 5;
-
-  PagePair cur, nxt;
-  load_pair(cur, kb, vb, __shfl(my_page, 0, kWave), __shfl(my_page, 1, kWave), n_kv, lane);
-  for (int it = 0; it < n_iter; ++it) {
-    if (it + 1 < n_iter)
-      load_pair(nxt, kb, vb, __shfl(my_page, 2 * it + 2, kWave), __shfl(my_page, 2 * it + 3, kWave), n_kv, lane);
-
-    // scores for 32 keys: lane (g, j) gets keys 4g..4g+3 of page a (sa) and of page b (sb) for column j
+  // One step = 32 keys (two pages): scores, online softmax, P*V; at a segment end the partial is written.
+  auto step = [&](const PagePair& pp, int it) __attribute__((always_inline)) {
     f32x4_t sa = (f32x4_t){0.f, 0.f, 0.f, 0.f}, sb = sa;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       const bf16x8_t qa = __builtin_bit_cast(bf16x8_t, q_hi[s]), ql = __builtin_bit_cast(bf16x8_t, q_lo[s]);
-      sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, cur.k[0][s]), qa, sa, 0, 0, 0);
-      sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, cur.k[0][s]), ql, sa, 0, 0, 0);
-      sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, cur.k[1][s]), qa, sb, 0, 0, 0);
-      sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, cur.k[1][s]), ql, sb, 0, 0, 0);
+      sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pp.k[0][s]), qa, sa, 0, 0, 0);
+      sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pp.k[0][s]), ql, sa, 0, 0, 0);
+      sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pp.k[1][s]), qa, sb, 0, 0, 0);
+      sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pp.k[1][s]), ql, sb, 0, 0, 0);
     }
-    const int kbase = key0 + it * 32 + 4 * g;
+    const int kbase = it * 32 + 4 * g;
     float sc[8];
     float mx = -INFINITY;
 #pragma unroll
@@ -126,7 +137,7 @@ __global__ __launch_bounds__(64) void attn_decode_bf16_kernel(const float* __res
     }
     mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
     mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-    const float m_new = fmaxf(m_run, mx);  // finite: key0 + it*32 < ctx always holds for lane group 0
+    const float m_new = fmaxf(m_run, mx);  // finite: key it*32 < ctx always holds for lane group 0
     const float alpha = __expf(m_run - m_new);
     m_run = m_new;
     uint32_t pw[4];
@@ -143,66 +154,95 @@ __global__ __launch_bounds__(64) void attn_decode_bf16_kernel(const float* __res
     for (int b = 0; b < 8; ++b) {
       const int jj = b >> 1, par = b & 1;
       u32x4_t vop;
-      vop[0] = cur.v[0][jj][2 * par];
-      vop[1] = cur.v[0][jj][2 * par + 1];
-      vop[2] = cur.v[1][jj][2 * par];
-      vop[3] = cur.v[1][jj][2 * par + 1];
+      vop[0] = pp.v[0][jj][2 * par];
+      vop[1] = pp.v[0][jj][2 * par + 1];
+      vop[2] = pp.v[1][jj][2 * par];
+      vop[3] = pp.v[1][jj][2 * par + 1];
       o_acc[b] *= alpha;
       o_acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vop), p_op, o_acc[b], 0, 0, 0);
     }
-    cur = nxt;
-  }
-
-  // ---- write the chunk's partial: lanes with j < group hold head hk*group + j --------------------
-  l_run += __shfl_xor(l_run, 16, kWave);
-  l_run += __shfl_xor(l_run, 32, kWave);
-  if (j < group) {
-    float* p = part + (((size_t)r * n_q + (size_t)hk * group + j) * max_chunks + chunk) * kPartStride;
+    if (it + 1 == boundary) {  // wave-uniform
+      float l_tot = l_run + __shfl_xor(l_run, 16, kWave);
+      l_tot += __shfl_xor(l_tot, 32, kWave);
+      if (j < group) {
+        float* p = part + (((size_t)r * n_q + (size_t)hk * group + j) * max_segs + seg) * kPartStride;
 #pragma unroll
-    for (int b = 0; b < 8; ++b)
-      *(float4*)(p + 16 * b + 4 * g) = make_float4(o_acc[b][0], o_acc[b][1], o_acc[b][2], o_acc[b][3]);
-    if (g == 0) { p[kD] = m_run; p[kD + 1] = l_run; }
-  }
-}
+        for (int b = 0; b < 8; ++b)
+          *(float4*)(p + 16 * b + 4 * g) = make_float4(o_acc[b][0], o_acc[b][1], o_acc[b][2], o_acc[b][3]);
+        if (g == 0) { p[kD] = m_run; p[kD + 1] = l_tot; }
+      }
+      reset();
+      ++seg;
+      while (seg < seg_end && seg_begin(seg + 1) == seg_begin(seg)) ++seg;
+      boundary = seg < seg_end ? seg_begin(seg + 1) : it_end;
+    }
+  };
+  auto fetch = [&](PagePair& pp, int it) __attribute__((always_inline)) {
+    load_pair(pp, kb, vb, pages[2 * it], pages[2 * it + 1], n_kv, lane);
+  };
 
-// One wave per (row, head): combine chunks in index order; lane owns dims 2*lane, 2*lane+1.
-__global__ __launch_bounds__(64) void attn_merge_bf16_kernel(const float* __restrict__ part, const RowMeta* __restrict__ rows,
-                                                             int max_chunks, uint16_t* __restrict__ o_out, int n_q) {
-  const int h = blockIdx.x, r = blockIdx.y, lane = threadIdx.x;
-  const int ctx = rows[r].pos + 1;
-  const int n_chunks = (ctx + kAttnChunk - 1) / kAttnChunk;
-  const float* p = part + ((size_t)r * n_q + h) * max_chunks * kPartStride;
-  float M = -INFINITY;
-  for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, p[(size_t)c * kPartStride + kD]);
-  float o0 = 0.f, o1 = 0.f, den = 0.f;
-  for (int c = 0; c < n_chunks; ++c) {
-    const float* pc = p + (size_t)c * kPartStride;
-    const float w = __expf(pc[kD] - M);
-    den += w * pc[kD + 1];
-    const float2 v = *(const float2*)(pc + 2 * lane);
-    o0 += w * v.x;
-    o1 += w * v.y;
+  // Two register buffers, refilled unconditionally inside the loop so that the compiler's wait counts let the
+  // other buffer's 16 loads stay in flight while one is consumed; the ragged end is peeled off below.
+  if (it_begin < it_end) {
+    PagePair pa, pb;
+    fetch(pa, it_begin);
+    int it = it_begin;
+    for (; it + 2 < it_end; it += 2) {
+      fetch(pb, it + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      step(pa, it);
+      __builtin_amdgcn_sched_barrier(0);
+      fetch(pa, it + 2);
+      __builtin_amdgcn_sched_barrier(0);
+      step(pb, it + 1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (it + 1 < it_end) {  // two steps left
+      fetch(pb, it + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      step(pa, it);
+      step(pb, it + 1);
+    } else {  // one step left
+      step(pa, it);
+    }
   }
-  const float inv = 1.0f / den;
-  const int k = h * kD + 2 * lane;
-  *(uint32_t*)(o_out + frag_offset(r, k, (n_q * kD) >> 6)) = pack2bf(o0 * inv, o1 * inv);
+
+  // ---- merge: wave w takes heads w, w+4 of the group; lane owns dims 2*lane, 2*lane+1 ------------
+  __threadfence_block();
+  __syncthreads();
+  for (int hh = wave; hh < group; hh += 4) {
+    const int head = hk * group + hh;
+    const float* p = part + ((size_t)r * n_q + head) * max_segs * kPartStride;
+    float M = -INFINITY;
+    for (int c = 0; c < n_seg; ++c)
+      if (seg_begin(c + 1) != seg_begin(c)) M = fmaxf(M, p[(size_t)c * kPartStride + kD]);
+    float o0 = 0.f, o1 = 0.f, den = 0.f;
+    for (int c = 0; c < n_seg; ++c) {
+      if (seg_begin(c + 1) == seg_begin(c)) continue;  // empty segment: nothing was written
+      const float* pc = p + (size_t)c * kPartStride;
+      const float w = __expf(pc[kD] - M);
+      den += w * pc[kD + 1];
+      const float2 v = *(const float2*)(pc + 2 * lane);
+      o0 += w * v.x;
+      o1 += w * v.y;
+    }
+    const float inv = 1.0f / den;
+    *(uint32_t*)(o_out + frag_offset(r, head * kD + 2 * lane, (n_q * kD) >> 6)) = pack2bf(o0 * inv, o1 * inv);
+  }
 }
 
 }  // namespace
 
+int attn_bf16_max_segments(int max_ctx) { return attn_num_segments(max_ctx); }
+
 void launch_attn_decode_bf16(hipStream_t s, const Geometry& g, const float* q, const RowMeta* rows,
                              const int32_t* block_table, const void* k_pool_layer, const void* v_pool_layer,
-                             float* part, int max_chunks_alloc, int grid_chunks, int M) {
-  dim3 grid(grid_chunks, g.n_kv, M);
-  attn_decode_bf16_kernel<<<grid, 64, 0, s>>>(q, rows, block_table, g.max_blocks, (const u32x4_t*)k_pool_layer,
-                                              (const u32x4_t*)v_pool_layer, part, max_chunks_alloc, g.n_q, g.n_kv,
-                                              1.0f / sqrtf((float)g.head_dim));
-}
-
-void launch_attn_merge_bf16(hipStream_t s, const Geometry& g, const float* part, const RowMeta* rows,
-                            int max_chunks_alloc, void* o_out, int M) {
-  dim3 grid(g.n_q, M);
-  attn_merge_bf16_kernel<<<grid, 64, 0, s>>>(part, rows, max_chunks_alloc, (uint16_t*)o_out, g.n_q);
+                             float* part, int max_segs_alloc, int max_ctx_in_batch, void* o_out, int M) {
+  dim3 grid(g.n_kv, M);
+  const size_t lds = ((size_t)(max_ctx_in_batch + 15) / 16 + 1) * sizeof(int32_t);
+  attn_decode_bf16_kernel<<<grid, 256, lds, s>>>(q, rows, block_table, g.max_blocks, (const u32x4_t*)k_pool_layer,
+                                                 (const u32x4_t*)v_pool_layer, part, max_segs_alloc, g.n_q, g.n_kv,
+                                                 1.0f / sqrtf((float)g.head_dim), (uint16_t*)o_out);
 }
 
 }  // namespace rl

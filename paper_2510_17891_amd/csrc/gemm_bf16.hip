@@ -6,6 +6,8 @@
 // LDS staging, no shuffles.  A wave owns a 64 x (32*MB) output tile over a slice of K; the four waves of a
 // block take four K slices and add their accumulators through LDS in a fixed order; further K splits across
 // blocks (to put >= 256 blocks on the chip for the small matrices) leave fp32 partials that the consumer sums.
+#include <stdlib.h>
+
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -53,7 +55,10 @@ __device__ __forceinline__ void mma_frags(const Frags<MB>& f, f32x16_t (&acc)[2]
 // grid: x = N tile, y = K split, z = M tile of 32*MB rows.
 //   EPI == kEpiPartial: tile = 64 output columns (row blocks 2x, 2x+1 of W); out fp32 [S][M][N].
 //   EPI == kEpiSwiGLU : tile = 32 output columns (gate block x, up block x + N/32); out bf16 fragment-major [M x N].
-template <int MB, int EPI>
+// ST = k blocks a wave keeps in flight.  HBM latency is ~10x the MFMA time of a block, so the loop is a ring of
+// ST register buffers: compute block i, immediately re-issue its buffer for block i + ST.  The scheduling
+// barriers keep the compiler from sinking the loads below the next block's MFMAs.
+template <int MB, int EPI, int ST>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ W,
                                                         void* __restrict__ out, int M, int N, int K, int kb_per_wave) {
   __shared__ float red[4][16][64];
@@ -83,16 +88,35 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const u32x4_t* __restric
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[nb][mb][r] = 0.f;
 
-  const int kb_begin = (blockIdx.y * 4 + wave) * kb_per_wave;
-  const int kb_end = kb_begin + kb_per_wave;
-  Frags<MB> cur, nxt;
-  load_frags<MB>(cur, w0, w1, xb, kb_begin, lane);
-  for (int kb = kb_begin + 1; kb < kb_end; ++kb) {
-    load_frags<MB>(nxt, w0, w1, xb, kb, lane);
-    mma_frags<MB>(cur, acc);
-    cur = nxt;
+  const int kb0 = (blockIdx.y * 4 + wave) * kb_per_wave;
+  const int n = kb_per_wave;
+  Frags<MB> f[ST];
+#pragma unroll
+  for (int s = 0; s < ST; ++s) load_frags<MB>(f[s], w0, w1, xb, kb0 + s, lane);  // the launcher guarantees ST <= n
+  const int full = n / ST, rem = n - full * ST;
+  int b = 0;
+  for (int r = 0; r + 1 < full; ++r) {  // steady state: every buffer is refilled
+#pragma unroll
+    for (int s = 0; s < ST; ++s) {
+      mma_frags<MB>(f[s], acc);
+      __builtin_amdgcn_sched_barrier(0);
+      load_frags<MB>(f[s], w0, w1, xb, kb0 + b + s + ST, lane);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    b += ST;
   }
-  mma_frags<MB>(cur, acc);
+  if (full > 0) {  // last full round: refill only what the remainder round will use
+#pragma unroll
+    for (int s = 0; s < ST; ++s) {
+      mma_frags<MB>(f[s], acc);
+      __builtin_amdgcn_sched_barrier(0);
+      if (s < rem) load_frags<MB>(f[s], w0, w1, xb, kb0 + b + s + ST, lane);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+#pragma unroll
+  for (int s = 0; s < ST; ++s)
+    if (s < rem) mma_frags<MB>(f[s], acc);
 
   // ---- add the four waves' accumulators (fixed order) and write --------------------------------
   // Output block mb is finished by wave mb % 4, which takes both row blocks (needed by SwiGLU).
@@ -155,16 +179,16 @@ Plan make_plan(int N, int K, int epi, bool allow_split) {
   return Plan{S, KB / (S * 4)};
 }
 
-template <int MB>
+template <int MB, int ST>
 void launch_mb(hipStream_t s, const void* X, const void* W, void* out, int M, int N, int K, int epi, bool allow_split) {
   Plan p = make_plan(N, K, epi, allow_split);
   const int m_tiles = (M + 32 * MB - 1) / (32 * MB);
   if (epi == kEpiSwiGLU) {
     dim3 grid(N >> 5, 1, m_tiles);
-    gemm_bf16_kernel<MB, kEpiSwiGLU><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave);
+    gemm_bf16_kernel<MB, kEpiSwiGLU, ST><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave);
   } else {
     dim3 grid(N >> 6, p.splits, m_tiles);
-    gemm_bf16_kernel<MB, kEpiPartial><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave);
+    gemm_bf16_kernel<MB, kEpiPartial, ST><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave);
   }
 }
 
@@ -172,12 +196,27 @@ void launch_mb(hipStream_t s, const void* X, const void* W, void* out, int M, in
 
 int gemm_bf16_splits(int N, int K, int epi) { return make_plan(N, K, epi, true).splits; }
 
+template <int MB>
+void launch_st(hipStream_t s, const void* X, const void* W, void* out, int M, int N, int K, int epi, bool allow_split,
+               int stages) {
+  const int n = make_plan(N, K, epi, allow_split).kb_per_wave;
+  if (stages > n) stages = n;  // the kernel's prologue fills all of its buffers unconditionally
+  switch (stages) {
+    case 1: launch_mb<MB, 1>(s, X, W, out, M, N, K, epi, allow_split); break;
+    case 2: launch_mb<MB, 2>(s, X, W, out, M, N, K, epi, allow_split); break;
+    case 3: launch_mb<MB, 3>(s, X, W, out, M, N, K, epi, allow_split); break;
+    default: launch_mb<MB, 4>(s, X, W, out, M, N, K, epi, allow_split); break;
+  }
+}
+
 // Requirements (checked at model init): K % 256 == 0, N % 64 == 0 (N % 32 for SwiGLU).
 void launch_gemm_bf16(hipStream_t s, const void* X, const void* W, void* out, int M, int N, int K, int epi,
                       bool allow_split) {
-  if (M <= 32) launch_mb<1>(s, X, W, out, M, N, K, epi, allow_split);
-  else if (M <= 64) launch_mb<2>(s, X, W, out, M, N, K, epi, allow_split);
-  else launch_mb<4>(s, X, W, out, M, N, K, epi, allow_split);
+  static const int tune = getenv("RL_GEMM_ST") ? atoi(getenv("RL_GEMM_ST")) : 0;
+  static const int force_mb = getenv("RL_GEMM_MB") ? atoi(getenv("RL_GEMM_MB")) : 0;
+  if (M <= 32 || force_mb == 1) launch_st<1>(s, X, W, out, M, N, K, epi, allow_split, tune ? tune : 4);
+  else if (M <= 64) launch_st<2>(s, X, W, out, M, N, K, epi, allow_split, tune ? tune : 2);
+  else launch_st<4>(s, X, W, out, M, N, K, epi, allow_split, tune ? tune : 2);
 }
 
 }  // namespace rl

@@ -52,15 +52,13 @@ void launch_kv_import(hipStream_t s, const Geometry& g, const void* k_src, const
                       const int32_t* block_table_row, void* k_pool_layer, void* v_pool_layer);
 
 // ---- attention -----------------------------------------------------------------------------------
-constexpr int kAttnChunk = 256;  // keys per split of the context (bf16 path)
-
-// bf16, head_dim 128: split-K decode attention over paged KV (MFMA), then the deterministic merge that
-// writes bf16 fragment-major [M x n_q*d].  part: fp32 [M][n_q][max_chunks][d+2].
+// bf16, head_dim 128: decode attention over paged KV (MFMA), one block per (row, kv head), context cut into
+// segments that depend on the context length only and merged in index order; writes bf16 fragment-major
+// [M x n_q*d].  part: fp32 [M][n_q][max_segs][d+2] with max_segs = attn_bf16_max_segments(max_ctx).
+int attn_bf16_max_segments(int max_ctx);
 void launch_attn_decode_bf16(hipStream_t s, const Geometry& g, const float* q, const RowMeta* rows,
                              const int32_t* block_table, const void* k_pool_layer, const void* v_pool_layer,
-                             float* part, int max_chunks_alloc, int grid_chunks, int M);
-void launch_attn_merge_bf16(hipStream_t s, const Geometry& g, const float* part, const RowMeta* rows,
-                            int max_chunks_alloc, void* o_out, int M);
+                             float* part, int max_segs_alloc, int max_ctx_in_batch, void* o_out, int M);
 // fp32, any head_dim <= 256: one wave per (row, q head), whole context, output fp32 row-major [M][n_q*d].
 void launch_attn_f32(hipStream_t s, const Geometry& g, const float* q, const RowMeta* rows,
                      const int32_t* block_table, const void* k_pool_layer, const void* v_pool_layer,

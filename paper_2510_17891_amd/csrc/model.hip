@@ -46,7 +46,7 @@ size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 struct Layout {
   size_t block_table, rope, ring, x, x_last, h, part, q, attn_part, o, a, logits, samp_part, total;
   size_t slot_bytes, slot_upd, slot_tok;
-  int max_chunks, n_tiles;
+  int max_segs, n_tiles;
 };
 
 size_t elem_size(uint32_t dtype) { return dtype == RL_BF16 ? 2 : 4; }
@@ -79,7 +79,7 @@ void compute_layout(const rl_model_config& c, Layout* L) {
   const size_t nqkv = (nq + 2 * nkv) * d;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
-  L->max_chunks = (int)((c.max_ctx + kAttnChunk - 1) / kAttnChunk);
+  L->max_segs = attn_bf16_max_segments((int)c.max_ctx);
   L->n_tiles = (int)((V + kSampleTile - 1) / kSampleTile);
   L->slot_upd = align_up(R * sizeof(RowMeta));
   L->slot_tok = L->slot_upd + align_up(R * 3 * sizeof(int32_t));
@@ -102,7 +102,7 @@ void compute_layout(const rl_model_config& c, Layout* L) {
   }
   L->part = take(part_elems * 4);
   L->q = take(R * nq * d * 4);
-  L->attn_part = take(c.dtype == RL_BF16 ? R * nq * (size_t)L->max_chunks * (d + 2) * 4 : 256);
+  L->attn_part = take(c.dtype == RL_BF16 ? R * nq * (size_t)L->max_segs * (d + 2) * 4 : 256);
   L->o = take(Rp * nq * d * act);
   L->a = take(Rp * F * act);
   L->logits = take(V ? R * V * 4 : 256);
@@ -110,9 +110,9 @@ void compute_layout(const rl_model_config& c, Layout* L) {
   L->total = off;
 }
 
-enum Kind { K_META, K_EMBED, K_NORM, K_QKV, K_ROPE_APPEND, K_ATTN, K_ATTN_MERGE, K_OPROJ, K_GATEUP, K_DOWN, K_LMHEAD, K_SAMPLE, K_COUNT };
+enum Kind { K_META, K_EMBED, K_NORM, K_QKV, K_ROPE_APPEND, K_ATTN, K_OPROJ, K_GATEUP, K_DOWN, K_LMHEAD, K_SAMPLE, K_COUNT };
 const char* const kKindNames[K_COUNT] = {"meta", "embed", "residual_norm", "gemm_qkv", "qk_rope_append", "attn_decode",
-                                        "attn_merge", "gemm_o", "gemm_gate_up_swiglu", "gemm_down", "gemm_lm_head", "sample"};
+                                        "gemm_o", "gemm_gate_up_swiglu", "gemm_down", "gemm_lm_head", "sample"};
 
 }  // namespace
 
@@ -186,7 +186,7 @@ rl_status ring_acquire(rl_model* m, int* slot_out) {
 
 // Run all decoder layers on the M rows whose residual stream sits in ws.x.  Leaves the last down-projection's
 // split partials pending; returns their count so that the caller's final residual_norm adds them.
-int run_layers(rl_model* m, hipStream_t st, int M, const RowMeta* rows, int grid_chunks) {
+int run_layers(rl_model* m, hipStream_t st, int M, const RowMeta* rows, int max_ctx_in_batch) {
   const Geometry& g = m->geo;
   const bool bf = g.dtype == kBF16;
   const int H = g.hidden, nqd = g.n_q * g.head_dim, nqkv = (g.n_q + 2 * g.n_kv) * g.head_dim, F = g.ffn;
@@ -212,10 +212,8 @@ int run_layers(rl_model* m, hipStream_t st, int M, const RowMeta* rows, int grid
       launch_qk_rope_append(st, g, part, s_qkv, g.qk_norm ? m->q_norm[l] : nullptr, g.qk_norm ? m->k_norm[l] : nullptr, rope,
                             rows, bt, m->k_pool(l), m->v_pool(l), q, M); }
     if (bf) {
-      { Timer t(m, st, K_ATTN);
-        launch_attn_decode_bf16(st, g, q, rows, bt, m->k_pool(l), m->v_pool(l), apart, m->lay.max_chunks, grid_chunks, M); }
-      { Timer t(m, st, K_ATTN_MERGE);
-        launch_attn_merge_bf16(st, g, apart, rows, m->lay.max_chunks, o, M); }
+      Timer t(m, st, K_ATTN);
+      launch_attn_decode_bf16(st, g, q, rows, bt, m->k_pool(l), m->v_pool(l), apart, m->lay.max_segs, max_ctx_in_batch, o, M);
     } else {
       Timer t(m, st, K_ATTN);
       launch_attn_f32(st, g, q, rows, bt, m->k_pool(l), m->v_pool(l), (float*)o, M);
@@ -278,7 +276,7 @@ rl_status admit_decode(rl_model* m, int32_t n, const int32_t* seq_ids, std::vect
 
 // Build and upload the rows (and page grants) of one decode call; returns device pointers into the slot.
 rl_status upload_decode_meta(rl_model* m, hipStream_t st, int32_t n, const int32_t* seq_ids,
-                             const std::vector<PageGrant>& grants, const RowMeta** rows_dev, int* grid_chunks) {
+                             const std::vector<PageGrant>& grants, const RowMeta** rows_dev, int* max_ctx_out) {
   int slot;
   rl_status rs = ring_acquire(m, &slot);
   if (rs != RL_OK) return rs;
@@ -302,7 +300,7 @@ rl_status upload_decode_meta(rl_model* m, hipStream_t st, int32_t n, const int32
   HIP_TRY(hipEventRecord(m->ring_ev[slot], st));
   m->ring_used[slot] = true;
   *rows_dev = (const RowMeta*)ds;
-  *grid_chunks = (max_ctx + kAttnChunk - 1) / kAttnChunk;
+  *max_ctx_out = max_ctx;
   return RL_OK;
 }
 
@@ -456,13 +454,13 @@ rl_status rl_decode_step(rl_model* m, void* stream, int32_t n, const int32_t* se
   rl_status rs = admit_decode(m, n, seq_ids, &grants);
   if (rs != RL_OK) return rs;
   const RowMeta* rows;
-  int grid_chunks;
-  rs = upload_decode_meta(m, st, n, seq_ids, grants, &rows, &grid_chunks);
+  int max_ctx_in_batch;
+  rs = upload_decode_meta(m, st, n, seq_ids, grants, &rows, &max_ctx_in_batch);
   if (rs != RL_OK) return rs;
   float* x = m->wsp<float>(m->lay.x);
   { Timer t(m, st, K_EMBED);
     launch_embed(st, m->geo.dtype, m->embed, in_tokens, x, n, m->geo.hidden, m->geo.vocab); }
-  int pend = run_layers(m, st, n, rows, grid_chunks);
+  int pend = run_layers(m, st, n, rows, max_ctx_in_batch);
   run_head(m, st, n, x, pend, rows, 1, forced_next, sp, out_tokens, out_logprobs, debug_logits);
   HIP_TRY(hipGetLastError());
   for (int i = 0; i < n; ++i) m->table->set_len(seq_ids[i], m->table->len(seq_ids[i]) + 1);
@@ -477,13 +475,13 @@ rl_status rl_decode_hidden(rl_model* m, void* stream, int32_t n, const int32_t* 
   rl_status rs = admit_decode(m, n, seq_ids, &grants);
   if (rs != RL_OK) return rs;
   const RowMeta* rows;
-  int grid_chunks;
-  rs = upload_decode_meta(m, st, n, seq_ids, grants, &rows, &grid_chunks);
+  int max_ctx_in_batch;
+  rs = upload_decode_meta(m, st, n, seq_ids, grants, &rows, &max_ctx_in_batch);
   if (rs != RL_OK) return rs;
   float* x = m->wsp<float>(m->lay.x);
   const size_t bytes = (size_t)n * m->geo.hidden * 4;
   HIP_TRY(hipMemcpyAsync(x, hidden_in, bytes, hipMemcpyDeviceToDevice, st));
-  int pend = run_layers(m, st, n, rows, grid_chunks);
+  int pend = run_layers(m, st, n, rows, max_ctx_in_batch);
   float* cap = m->capture ? m->capture + (size_t)m->geo.n_layers * m->cfg.max_rows * m->geo.hidden : nullptr;
   { Timer t(m, st, K_NORM);
     launch_residual_norm(st, m->geo.dtype, x, m->wsp<float>(m->lay.part), pend, nullptr, nullptr, cap, n, m->geo.hidden, m->geo.rms_eps); }
@@ -563,7 +561,7 @@ rl_status rl_prefill(rl_model* m, void* stream, int32_t n, const int32_t* seq_id
     const RowMeta* rows = (const RowMeta*)ds;
     { Timer t(m, st, K_EMBED);
       launch_embed(st, m->geo.dtype, m->embed, (const int32_t*)(ds + m->lay.slot_tok), x, M, H, m->geo.vocab); }
-    int pend = run_layers(m, st, M, rows, (max_ctx + kAttnChunk - 1) / kAttnChunk);
+    int pend = run_layers(m, st, M, rows, max_ctx);
     // fold the pending partials into x, then keep the rows that end a prompt
     float* cap = m->capture ? m->capture + (size_t)m->geo.n_layers * m->cfg.max_rows * H : nullptr;
     { Timer t(m, st, K_NORM);

@@ -25,55 +25,58 @@ void launch_embed(hipStream_t s, int dtype, const void* embed, const int32_t* to
 }
 
 // ------------------------------------------------------------------------------------------------
-// Residual update + RMSNorm.  One block per row.  The split partials of the preceding projection are
-// summed in a fixed order, so results do not depend on the batch.
+// Residual update + RMSNorm.  One block per row, one float4 per thread and pass (H/4 threads, at most 1024), so
+// that the few dependent memory round trips of this latency-bound step are as short as possible.  The split
+// partials of the preceding projection are summed in a fixed order, so results do not depend on the batch.
 // ------------------------------------------------------------------------------------------------
 template <bool BF16>
-__global__ __launch_bounds__(256) void residual_norm_kernel(float* __restrict__ x, const float* __restrict__ part,
-                                                            int S, size_t split_stride, const void* __restrict__ gain,
-                                                            void* __restrict__ h_out, float* __restrict__ capture,
-                                                            int H, float eps) {
-  __shared__ float red[4];
-  const int r = blockIdx.x;
+__global__ __launch_bounds__(1024) void residual_norm_kernel(float* __restrict__ x, const float* __restrict__ part,
+                                                             int S, size_t split_stride, const void* __restrict__ gain,
+                                                             void* __restrict__ h_out, float* __restrict__ capture,
+                                                             int H, float eps) {
+  __shared__ float red[16];
+  const int r = blockIdx.x, nthr = blockDim.x;
   float* xr = x + (size_t)r * H;
   float ss = 0.f;
-  // H <= 256 * 8 * 4 is checked by the host; each thread owns groups of 8 consecutive elements.
-  for (int i0 = threadIdx.x * 8; i0 < H; i0 += 256 * 8) {
-    float v[8];
+  constexpr int kMaxPass = 2;  // H <= 1024 threads * 4 * kMaxPass, checked by the host
+  float4 keep[kMaxPass];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = xr[i0 + e];
-    for (int sp = 0; sp < S; ++sp) {
-      const float* p = part + sp * split_stride + (size_t)r * H + i0;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] += p[e];
+  for (int pass = 0; pass < kMaxPass; ++pass) {
+    const int i0 = (pass * nthr + threadIdx.x) * 4;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i0 < H) {
+      v = *(const float4*)(xr + i0);
+#pragma unroll 4
+      for (int sp = 0; sp < S; ++sp) {
+        const float4 p = *(const float4*)(part + sp * split_stride + (size_t)r * H + i0);
+        v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+      }
+      if (S > 0) *(float4*)(xr + i0) = v;
+      if (capture) *(float4*)(capture + (size_t)r * H + i0) = v;
     }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      if (S > 0) xr[i0 + e] = v[e];
-      if (capture) capture[(size_t)r * H + i0 + e] = v[e];
-      ss += v[e] * v[e];
-    }
+    keep[pass] = v;
+    ss += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
   }
   if (gain == nullptr) return;
   ss = wave_sum(ss);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
   __syncthreads();
-  ss = (red[0] + red[1]) + (red[2] + red[3]);
+  ss = 0.f;
+  for (int w = 0; w < (nthr >> 6); ++w) ss += red[w];
   const float inv = 1.0f / sqrtf(ss / (float)H + eps);
-  for (int i0 = threadIdx.x * 8; i0 < H; i0 += 256 * 8) {
+#pragma unroll
+  for (int pass = 0; pass < kMaxPass; ++pass) {
+    const int i0 = (pass * nthr + threadIdx.x) * 4;
+    if (i0 >= H) continue;
+    const float4 v = keep[pass];
     if (BF16) {
-      const uint16_t* g = (const uint16_t*)gain;
-      uint32_t w[4];
-#pragma unroll
-      for (int e = 0; e < 8; e += 2)
-        w[e >> 1] = pack2bf(xr[i0 + e] * inv * bf2f(g[i0 + e]), xr[i0 + e + 1] * inv * bf2f(g[i0 + e + 1]));
-      uint4 o = make_uint4(w[0], w[1], w[2], w[3]);
-      *(uint4*)((uint16_t*)h_out + frag_offset(r, i0, H >> 6)) = o;
+      const uint2 gb = *(const uint2*)((const uint16_t*)gain + i0);
+      const uint32_t w0 = pack2bf(v.x * inv * bf2f(gb.x & 0xffffu), v.y * inv * bf2f(gb.x >> 16));
+      const uint32_t w1 = pack2bf(v.z * inv * bf2f(gb.y & 0xffffu), v.w * inv * bf2f(gb.y >> 16));
+      *(uint2*)((uint16_t*)h_out + frag_offset(r, i0, H >> 6)) = make_uint2(w0, w1);
     } else {
-      const float* g = (const float*)gain;
-      float* h = (float*)h_out + (size_t)r * H;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) h[i0 + e] = xr[i0 + e] * inv * g[i0 + e];
+      const float4 g = *(const float4*)((const float*)gain + i0);
+      *(float4*)((float*)h_out + (size_t)r * H + i0) = make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w);
     }
   }
 }
@@ -81,10 +84,12 @@ __global__ __launch_bounds__(256) void residual_norm_kernel(float* __restrict__ 
 void launch_residual_norm(hipStream_t s, int dtype, float* x, const float* part, int S, const void* gain,
                           void* h_out, float* capture, int M, int H, float eps) {
   size_t stride = (size_t)M * H;
+  int threads = ((H / 4 + 63) / 64) * 64;
+  if (threads > 1024) threads = 1024;
   if (dtype == kBF16)
-    residual_norm_kernel<true><<<M, 256, 0, s>>>(x, part, S, stride, gain, h_out, capture, H, eps);
+    residual_norm_kernel<true><<<M, threads, 0, s>>>(x, part, S, stride, gain, h_out, capture, H, eps);
   else
-    residual_norm_kernel<false><<<M, 256, 0, s>>>(x, part, S, stride, gain, h_out, capture, H, eps);
+    residual_norm_kernel<false><<<M, threads, 0, s>>>(x, part, S, stride, gain, h_out, capture, H, eps);
 }
 
 // ------------------------------------------------------------------------------------------------
