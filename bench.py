@@ -22,6 +22,31 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM traffic of the dominant kernels from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/hbm_traffic_counters.md),
+# stored as measured bytes / algorithmic bytes of the same launches, each counter scaled by what it reads for a plain
+# 1 GiB device copy (FETCH_SIZE x 2.0000, WRITE_SIZE x 1.0000).  An entry is used only while the kernel's source
+# file still has the hash it had when the counters were taken; otherwise "traffic" is null.
+TRAFFIC_RATIO = {
+    ("layer", "attn_decode"): (1.053, "attn_bf16.hip", "4cb295c31eea2fa0"),
+    ("layer", "gemm_gate_up_swiglu"): (1.019, "gemm_bf16.hip", "27ea55bc8599fdc6"),
+    ("full", "attn_decode"): (1.077, "attn_bf16.hip", "4cb295c31eea2fa0"),
+    ("full", "gemm_gate_up_swiglu"): (1.010, "gemm_bf16.hip", "27ea55bc8599fdc6"),
+}
+
+
+def measured_traffic(workload, kernel, algorithmic_bytes):
+    import hashlib
+    ent = TRAFFIC_RATIO.get((workload, kernel))
+    if ent is None:
+        return None
+    ratio, src, sha = ent
+    path = os.path.join(ROOT, "paper_2510_17891_amd", "csrc", src)
+    try:
+        cur = hashlib.sha256(open(path, "rb").read()).hexdigest()[:16]
+    except OSError:
+        return None
+    return ratio * algorithmic_bytes if cur == sha else None
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -32,6 +57,9 @@ def parse():
     ap.add_argument("--profile-steps", type=int, default=8, help="extra steps run with per-kernel events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--prefill", choices=["real", "import"], default="real",
+                    help="import: fill the prompt KV with random N(0,1) pages instead of running the prefill "
+                         "(for counter runs that should only see decode steps)")
     return ap.parse_args()
 
 
@@ -133,10 +161,19 @@ def main():
         prompt_list = [prompts[i // G].tolist() for i in range(B)]
         seq_ids = list(range(B))
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        tok, lp = ro.rl_prefill(seq_ids, prompt_list, 1.0, seed)
-        torch.cuda.synchronize()
-        prefill_s = time.perf_counter() - t0
+        if args.prefill == "real":
+            t0 = time.perf_counter()
+            tok, lp = ro.rl_prefill(seq_ids, prompt_list, 1.0, seed)
+            torch.cuda.synchronize()
+            prefill_s = time.perf_counter() - t0
+        else:
+            kv = [ri.normal((P, shape["n_kv"], shape["head_dim"]), 1.0, seed, 3000 + l, device=dev, dtype=torch.bfloat16)
+                  for l in range(shape["n_layers"])]
+            for b in seq_ids:
+                ro.rl_seq_import_kv(b, kv, kv)
+            tok = prompts[0, :B].to(dev).contiguous()
+            torch.cuda.synchronize()
+            prefill_s = None
         workload = f"full8b_36L_bf16_{B}seq_prompt{P}_T1.0"
         ctx0 = P
     else:
@@ -212,6 +249,8 @@ def main():
     if prefill_s is not None:
         out["prefill_s"] = prefill_s
         out["prefill_tokens_per_s"] = B * 1024 / prefill_s
+    elif args.workload == "full":
+        out["config"]["prompt_kv"] = "imported N(0,1)"
 
     # ---- per-kernel durations from HIP events on the launch stream, same steps, same state --------------
     if not args.no_profile:
@@ -240,7 +279,8 @@ def main():
         out["kernels"] = kernels
         dom = max((n for n in kernels if n in kb), key=lambda n: kernels[n]["avg_us"] * kernels[n]["launches"])
         out["roofline"] = {"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["achieved_GBs"], "peak": HBM_PEAK_GBS,
-                           "unit": "GB/s", "frac": kernels[dom]["achieved_GBs"] / HBM_PEAK_GBS, "traffic": None}
+                           "unit": "GB/s", "frac": kernels[dom]["achieved_GBs"] / HBM_PEAK_GBS,
+                           "traffic": measured_traffic(args.workload, dom, kb[dom])}
     if not args.no_cpu_baseline:
         if args.workload == "full":
             out["cpu_baseline"] = cpu_baseline_full(shape, int(ctx_avg))

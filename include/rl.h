@@ -153,10 +153,12 @@ rl_status rl_prefill(rl_model* m, void* stream, int32_t n_seqs, const int32_t* s
  * sequence's next position, append its K/V, and sample the following token.
  *   seq_ids       host  [n_seqs]
  *   in_tokens     device[n_seqs] int32   (normally the previous call's out_tokens)
- *   forced_next   device[n_seqs] int32 or NULL; entries >= 0 replace the sampled token (teacher
- *                 forcing) and the log-probability reported is that of the forced token
+ *   forced_next   device[n_seqs] int32 or NULL; entries in [0, vocab) replace the sampled token (teacher
+ *                 forcing) and the log-probability reported is that of the forced token; any other
+ *                 value leaves that row sampled
  *   out_tokens    device[n_seqs] int32;  out_logprobs device[n_seqs] fp32
- *   debug_logits  device[n_seqs x vocab] fp32 or NULL: a copy of the logits z
+ *   debug_logits  device[n_seqs x vocab] fp32 or NULL: a copy of the logits z (otherwise the bf16
+ *                 path never writes logits to memory: sampling runs in the output projection)
  * No host synchronisation happens inside.  Errors: INVALID_ARG, BAD_SEQ, KV_FULL, CTX_OVERFLOW, DEVICE.
  */
 rl_status rl_decode_step(rl_model* m, void* stream, int32_t n_seqs, const int32_t* seq_ids,

@@ -65,15 +65,28 @@ void launch_attn_f32(hipStream_t s, const Geometry& g, const float* q, const Row
                      float* o_out, int M);
 
 // ---- projections ---------------------------------------------------------------------------------
-enum Epilogue : int { kEpiPartial = 0, kEpiSwiGLU = 1 };
+enum Epilogue : int { kEpiPartial = 0, kEpiSwiGLU = 1, kEpiSample = 2 };
+
+// Arguments of the sampling epilogue of the output projection (ignored by the other epilogues).
+struct SampleEpilogue {
+  const RowMeta* rows = nullptr;  // RNG stream (seq) and position (pos + pos_offset) per row
+  int pos_offset = 0;
+  float inv_t = 1.f;
+  int greedy = 1;
+  uint32_t seed_lo = 0, seed_hi = 0;
+  const int32_t* forced = nullptr;  // per row, or null
+  float* forced_z = nullptr;        // [M] logit of the forced token
+  float* part = nullptr;            // [M][N/64][8] per-tile partials for launch_sample_merge
+  float* logits_out = nullptr;      // optional [M][N] copy of the logits
+};
 
 // Number of K splits the bf16 GEMM uses for (N, K); partial outputs are [S][M][N] fp32.
 int gemm_bf16_splits(int N, int K, int epi);
 // bf16 MFMA GEMM: X fragment-major [M x K], W fragment-major [N x K] (2N rows for SwiGLU: gate then up).
-// kEpiPartial: out = fp32 [S][M][N];  kEpiSwiGLU: out = bf16 fragment-major [M x N] = silu(gate)*up.
-// allow_split = false forces S = 1 (the output is then the finished [M][N] product).
+// kEpiPartial: out = fp32 [S][M][N];  kEpiSwiGLU: out = bf16 fragment-major [M x N] = silu(gate)*up;
+// kEpiSample: out unused, results go through *se.  allow_split = false forces S = 1 (finished [M][N] product).
 void launch_gemm_bf16(hipStream_t s, const void* X, const void* W, void* out, int M, int N, int K, int epi,
-                      bool allow_split = true);
+                      bool allow_split = true, const SampleEpilogue* se = nullptr);
 // fp32 GEMM on vector ALUs, row-major everything; kEpiPartial writes [M][N] (one split).
 void launch_gemm_f32(hipStream_t s, const float* X, const float* W, float* out, int M, int N, int K, int epi);
 
@@ -81,13 +94,16 @@ void launch_gemm_f32(hipStream_t s, const float* X, const float* W, float* out, 
 void launch_pack_weight_bf16(hipStream_t s, const void* src, void* dst, int N, int K);
 
 // ---- sampler ---------------------------------------------------------------------------------------
-constexpr int kSampleTile = 2048;  // vocabulary entries per first-stage block
-// Stage 1+2 of Gumbel-max sampling with log-probabilities from fp32 logits [M][V].
-// part: [M][n_tiles] of 4 floats.  forced may be null.
+constexpr int kSampleTile = 2048;  // vocabulary entries per first-stage block of the stand-alone sampler
+// Gumbel-max sampling with log-probabilities from fp32 logits [M][V] in memory (two stages).
+// part: [M][ceil(V/2048)][8] floats; forced may be null; forced_z: [M] floats.
 // The RNG position of row r is rows[r].pos + pos_offset.
 void launch_sample(hipStream_t s, const float* logits, int M, int V, const RowMeta* rows, int pos_offset,
-                   const int32_t* forced, float temperature, uint64_t seed, float* part, int32_t* out_tokens,
-                   float* out_logprobs);
+                   const int32_t* forced, float temperature, uint64_t seed, float* part, float* forced_z,
+                   int32_t* out_tokens, float* out_logprobs);
+// Second stage alone, over the [M][n_tiles][8] partials the sampling epilogue of the bf16 projection left.
+void launch_sample_merge(hipStream_t s, const float* part, int n_tiles, int M, int V, const int32_t* forced,
+                         const float* forced_z, float temperature, int32_t* out_tokens, float* out_logprobs);
 
 // block_table[upd[3i]][upd[3i+1]] = upd[3i+2] for i < n (device-side mirror update of newly granted pages).
 void launch_table_update(hipStream_t s, int32_t* block_table, int max_blocks, const int32_t* upd, int n);

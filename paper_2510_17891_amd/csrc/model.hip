@@ -44,7 +44,7 @@ constexpr int kRing = 64;  // per-call metadata slots in flight
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 struct Layout {
-  size_t block_table, rope, ring, x, x_last, h, part, q, attn_part, o, a, logits, samp_part, total;
+  size_t block_table, rope, ring, x, x_last, h, part, q, attn_part, o, a, logits, samp_part, forced_z, total;
   size_t slot_bytes, slot_upd, slot_tok;
   int max_segs, n_tiles;
 };
@@ -105,8 +105,13 @@ void compute_layout(const rl_model_config& c, Layout* L) {
   L->attn_part = take(c.dtype == RL_BF16 ? R * nq * (size_t)L->max_segs * (d + 2) * 4 : 256);
   L->o = take(Rp * nq * d * act);
   L->a = take(Rp * F * act);
-  L->logits = take(V ? R * V * 4 : 256);
-  L->samp_part = take(V ? R * (size_t)L->n_tiles * 16 : 256);
+  // bf16: logits never reach memory (sampling happens in the projection's epilogue, 64 entries per partial);
+  // fp32: logits are written and scanned by the stand-alone sampler (2048 entries per partial).  rl_sample_logits
+  // uses the stand-alone sampler in both cases.
+  L->logits = take(V && c.dtype == RL_F32 ? R * V * 4 : 256);
+  const size_t tiles_fused = V / 64 + 1;
+  L->samp_part = take(V ? R * (tiles_fused > (size_t)L->n_tiles ? tiles_fused : (size_t)L->n_tiles) * 32 : 256);
+  L->forced_z = take(R * 4);
   L->total = off;
 }
 
@@ -244,14 +249,27 @@ void run_head(rl_model* m, hipStream_t st, int M, float* xbuf, int pend, const R
   float* cap = m->capture ? m->capture + (size_t)g.n_layers * m->cfg.max_rows * g.hidden : nullptr;
   { Timer t(m, st, K_NORM);
     launch_residual_norm(st, g.dtype, xbuf, pend ? part : nullptr, pend, m->final_norm, h, cap, M, g.hidden, g.rms_eps); }
-  { Timer t(m, st, K_LMHEAD);
-    if (g.dtype == kBF16) launch_gemm_bf16(st, h, m->lm_head, logits, M, g.vocab, g.hidden, kEpiPartial, false);
-    else launch_gemm_f32(st, (const float*)h, (const float*)m->lm_head, logits, M, g.vocab, g.hidden, kEpiPartial); }
-  { Timer t(m, st, K_SAMPLE);
-    launch_sample(st, logits, M, g.vocab, rows, pos_offset, forced, sp->temperature, sp->seed,
-                  m->wsp<float>(m->lay.samp_part), out_tokens, out_lp); }
-  if (debug_logits)
-    (void)hipMemcpyAsync(debug_logits, logits, (size_t)M * g.vocab * 4, hipMemcpyDeviceToDevice, st);
+  float* spart = m->wsp<float>(m->lay.samp_part);
+  float* fz = m->wsp<float>(m->lay.forced_z);
+  if (g.dtype == kBF16) {
+    SampleEpilogue se;
+    se.rows = rows; se.pos_offset = pos_offset;
+    se.greedy = !(sp->temperature > 0.f);
+    se.inv_t = se.greedy ? 1.0f : 1.0f / sp->temperature;
+    se.seed_lo = (uint32_t)(sp->seed & 0xffffffffu); se.seed_hi = (uint32_t)(sp->seed >> 32);
+    se.forced = forced; se.forced_z = fz; se.part = spart; se.logits_out = debug_logits;
+    { Timer t(m, st, K_LMHEAD);
+      launch_gemm_bf16(st, h, m->lm_head, nullptr, M, g.vocab, g.hidden, kEpiSample, false, &se); }
+    { Timer t(m, st, K_SAMPLE);
+      launch_sample_merge(st, spart, g.vocab >> 6, M, g.vocab, forced, fz, sp->temperature, out_tokens, out_lp); }
+  } else {
+    { Timer t(m, st, K_LMHEAD);
+      launch_gemm_f32(st, (const float*)h, (const float*)m->lm_head, logits, M, g.vocab, g.hidden, kEpiPartial); }
+    { Timer t(m, st, K_SAMPLE);
+      launch_sample(st, logits, M, g.vocab, rows, pos_offset, forced, sp->temperature, sp->seed, spart, fz, out_tokens, out_lp); }
+    if (debug_logits)
+      (void)hipMemcpyAsync(debug_logits, logits, (size_t)M * g.vocab * 4, hipMemcpyDeviceToDevice, st);
+  }
 }
 
 // Checks shared by decode calls; on success `grants` holds the pages handed out and lens are NOT yet advanced.
@@ -634,7 +652,7 @@ rl_status rl_sample_logits(rl_model* m, void* stream, int32_t n, const float* lo
   HIP_TRY(hipEventRecord(m->ring_ev[slot], st));
   m->ring_used[slot] = true;
   launch_sample(st, logits, n, m->geo.vocab, (const RowMeta*)ds, 0, forced, sp->temperature, sp->seed,
-                m->wsp<float>(m->lay.samp_part), out_tokens, out_logprobs);
+                m->wsp<float>(m->lay.samp_part), m->wsp<float>(m->lay.forced_z), out_tokens, out_logprobs);
   HIP_TRY(hipGetLastError());
   return RL_OK;
 }
