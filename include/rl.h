@@ -149,6 +149,22 @@ rl_status rl_prefill(rl_model* m, void* stream, int32_t n_seqs, const int32_t* s
                      int32_t* out_tokens, float* out_logprobs);
 
 /*
+ * Prefill for grouped sampling: prompt i is followed by group_size sequences seq_ids[i*group_size + j], the G
+ * samples that the RL loop draws from the same prompt (Section 2.3).  The prompt is run once; the members share
+ * every KV page the prompt fills completely (those pages are never written again) and own a private copy of the
+ * partial last page, so later calls treat them as ordinary independent sequences.  Each member's first token is
+ * sampled from the same logits with its own random stream.  Results are identical to rl_prefill of the prompt
+ * repeated group_size times.
+ *   seq_ids        host  [n_prompts * group_size]   fresh ids;  n_prompts * group_size <= max_rows
+ *   prompt_tokens  host  [sum lens], prompt_lens host [n_prompts]
+ *   out_tokens / out_logprobs  device [n_prompts * group_size]
+ * Errors as rl_prefill.
+ */
+rl_status rl_prefill_groups(rl_model* m, void* stream, int32_t n_prompts, int32_t group_size, const int32_t* seq_ids,
+                            const int32_t* prompt_tokens, const int32_t* prompt_lens, const rl_sampling* sp,
+                            int32_t* out_tokens, float* out_logprobs);
+
+/*
  * One decode step for n_seqs active sequences (1 <= n_seqs <= max_rows): feed in_tokens[b] at the
  * sequence's next position, append its K/V, and sample the following token.
  *   seq_ids       host  [n_seqs]

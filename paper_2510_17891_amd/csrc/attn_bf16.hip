@@ -28,7 +28,8 @@ typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
 constexpr int kD = 128;
 constexpr int kPageElems = kPageTokens * kD;  // 2048 bf16 = 4 KiB per (page, kv head), K or V
-constexpr int kPartStride = kD + 2;           // floats per (row, head, chunk): O[128], max, sum
+constexpr int kPartStride = kD + 2;           // floats per (row, head, segment): O[128], max, sum
+constexpr int kLdsSegs = 16;                  // contexts up to 4096 keep their segment partials in LDS
 
 struct PagePair {
   u32x4_t k[2][4];  // [page a|b][mfma step s]: keys x dims 32s..32s+31
@@ -60,8 +61,8 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
                                                                const u32x4_t* __restrict__ k_pool,
                                                                const u32x4_t* __restrict__ v_pool, float* __restrict__ part,
                                                                int max_segs, int n_q, int n_kv, float scale,
-                                                               uint16_t* __restrict__ o_out) {
-  extern __shared__ int32_t pages[];  // block-table slice of this row: ceil(ctx/16) entries (+1 pad)
+                                                               uint16_t* __restrict__ o_out, int lds_part_offset) {
+  extern __shared__ int32_t pages[];  // block-table slice of this row: ceil(ctx/16) entries (+1 pad), then partials
   const int hk = blockIdx.x, r = blockIdx.y;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const RowMeta rm = rows[r];
@@ -97,6 +98,11 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
   const u32x4_t* vb = v_pool + (size_t)hk * (kPageElems / 8);
   const int n_it = (ctx + 31) >> 5;  // 32-key steps
   const int n_seg = attn_num_segments(ctx);
+  // Segment partials of short contexts (<= kLdsSegs segments) stay in LDS; longer ones go through the workspace.
+  const bool in_lds = n_seg <= kLdsSegs;
+  float* pbase = in_lds ? (float*)(pages + lds_part_offset) : part + (size_t)r * n_q * max_segs * kPartStride;
+  const int seg_stride = in_lds ? n_seg : max_segs;          // segments per head in the chosen buffer
+  const int head0 = in_lds ? 0 : hk * group;                 // LDS holds this block's heads only
   const int seg_per_wave = n_seg >> 2;
   auto seg_begin = [&](int sgm) { return (int)(((long long)sgm * n_it) / n_seg); };
 
@@ -165,10 +171,12 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
       float l_tot = l_run + __shfl_xor(l_run, 16, kWave);
       l_tot += __shfl_xor(l_tot, 32, kWave);
       if (j < group) {
-        float* p = part + (((size_t)r * n_q + (size_t)hk * group + j) * max_segs + seg) * kPartStride;
+        float* p = pbase + ((size_t)(head0 + j) * seg_stride + seg) * kPartStride;
 #pragma unroll
-        for (int b = 0; b < 8; ++b)
-          *(float4*)(p + 16 * b + 4 * g) = make_float4(o_acc[b][0], o_acc[b][1], o_acc[b][2], o_acc[b][3]);
+        for (int b = 0; b < 8; ++b) {
+          p[16 * b + 4 * g] = o_acc[b][0]; p[16 * b + 4 * g + 1] = o_acc[b][1];
+          p[16 * b + 4 * g + 2] = o_acc[b][2]; p[16 * b + 4 * g + 3] = o_acc[b][3];
+        }
         if (g == 0) { p[kD] = m_run; p[kD + 1] = l_tot; }
       }
       reset();
@@ -212,7 +220,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
   __syncthreads();
   for (int hh = wave; hh < group; hh += 4) {
     const int head = hk * group + hh;
-    const float* p = part + ((size_t)r * n_q + head) * max_segs * kPartStride;
+    const float* p = pbase + (size_t)(head0 + hh) * seg_stride * kPartStride;
     float M = -INFINITY;
     for (int c = 0; c < n_seg; ++c)
       if (seg_begin(c + 1) != seg_begin(c)) M = fmaxf(M, p[(size_t)c * kPartStride + kD]);
@@ -222,9 +230,8 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
       const float* pc = p + (size_t)c * kPartStride;
       const float w = __expf(pc[kD] - M);
       den += w * pc[kD + 1];
-      const float2 v = *(const float2*)(pc + 2 * lane);
-      o0 += w * v.x;
-      o1 += w * v.y;
+      o0 += w * pc[2 * lane];
+      o1 += w * pc[2 * lane + 1];
     }
     const float inv = 1.0f / den;
     *(uint32_t*)(o_out + frag_offset(r, head * kD + 2 * lane, (n_q * kD) >> 6)) = pack2bf(o0 * inv, o1 * inv);
@@ -239,10 +246,13 @@ void launch_attn_decode_bf16(hipStream_t s, const Geometry& g, const float* q, c
                              const int32_t* block_table, const void* k_pool_layer, const void* v_pool_layer,
                              float* part, int max_segs_alloc, int max_ctx_in_batch, void* o_out, int M) {
   dim3 grid(g.n_kv, M);
-  const size_t lds = ((size_t)(max_ctx_in_batch + 15) / 16 + 1) * sizeof(int32_t);
+  const int page_ints = ((max_ctx_in_batch + 15) / 16 + 1 + 3) & ~3;  // keeps the partials 16-byte aligned
+  int segs = attn_num_segments(max_ctx_in_batch);
+  if (segs > kLdsSegs) segs = kLdsSegs;
+  const size_t lds = (size_t)page_ints * 4 + (size_t)(g.n_q / g.n_kv) * segs * kPartStride * sizeof(float);
   attn_decode_bf16_kernel<<<grid, 256, lds, s>>>(q, rows, block_table, g.max_blocks, (const u32x4_t*)k_pool_layer,
                                                  (const u32x4_t*)v_pool_layer, part, max_segs_alloc, g.n_q, g.n_kv,
-                                                 1.0f / sqrtf((float)g.head_dim), (uint16_t*)o_out);
+                                                 1.0f / sqrtf((float)g.head_dim), (uint16_t*)o_out, page_ints);
 }
 
 }  // namespace rl

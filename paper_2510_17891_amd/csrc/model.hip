@@ -509,26 +509,31 @@ rl_status rl_decode_hidden(rl_model* m, void* stream, int32_t n, const int32_t* 
   return RL_OK;
 }
 
-rl_status rl_prefill(rl_model* m, void* stream, int32_t n, const int32_t* seq_ids, const int32_t* prompt_tokens,
-                     const int32_t* prompt_lens, const rl_sampling* sp, int32_t* out_tokens, float* out_logprobs) {
-  if (!m || !seq_ids || !prompt_tokens || !prompt_lens || !sp || !out_tokens || !out_logprobs)
-    return fail(RL_ERR_INVALID_ARG, "NULL argument");
+// Prefill of n_prompts prompts, each followed by `group` sequences (seq_ids[i*group + j]).  Member 0 of a group
+// runs the prompt; the others share every page the prompt fills completely and get a private copy of the partial
+// last page, so the prompt's KV is computed and stored once per group.
+static rl_status prefill_impl(rl_model* m, hipStream_t st, int32_t n_prompts, int32_t group, const int32_t* seq_ids,
+                              const int32_t* prompt_tokens, const int32_t* prompt_lens, const rl_sampling* sp,
+                              int32_t* out_tokens, float* out_logprobs) {
   if (m->geo.vocab == 0) return fail(RL_ERR_UNSUPPORTED, "model has no vocabulary");
-  if (n < 1 || n > (int32_t)m->cfg.max_rows) return fail(RL_ERR_INVALID_ARG, "n_seqs %d outside [1, max_rows=%u]", n, m->cfg.max_rows);
-  hipStream_t st = (hipStream_t)stream;
+  if (n_prompts < 1 || group < 1 || (int64_t)n_prompts * group > (int64_t)m->cfg.max_rows)
+    return fail(RL_ERR_INVALID_ARG, "n_prompts %d x group %d outside [1, max_rows=%u]", n_prompts, group, m->cfg.max_rows);
   SeqTable& T = *m->table;
+  const int n_all = n_prompts * group;
   const int R = (int)m->cfg.max_rows, H = m->geo.hidden;
   std::vector<char> seen(T.max_seqs(), 0);
   int64_t need = 0, total = 0;
-  for (int i = 0; i < n; ++i) {
+  for (int i = 0; i < n_all; ++i) {
     const int32_t s = seq_ids[i];
     if (!T.valid_id(s)) return fail(RL_ERR_BAD_SEQ, "sequence id %d out of range", s);
     if (T.active(s)) return fail(RL_ERR_BAD_SEQ, "sequence %d is already active", s);
     if (seen[s]) return fail(RL_ERR_INVALID_ARG, "sequence %d appears twice", s);
     seen[s] = 1;
+  }
+  for (int i = 0; i < n_prompts; ++i) {
     if (prompt_lens[i] < 1) return fail(RL_ERR_INVALID_ARG, "prompt %d is empty", i);
     if (prompt_lens[i] > T.max_ctx() - 1) return fail(RL_ERR_CTX_OVERFLOW, "prompt %d has %d tokens, max_ctx is %d", i, prompt_lens[i], T.max_ctx());
-    need += SeqTable::blocks_for(prompt_lens[i]);
+    need += SeqTable::blocks_for(prompt_lens[i]) + (int64_t)(group - 1) * ((prompt_lens[i] % SeqTable::kBlock) ? 1 : 0);
     total += prompt_lens[i];
   }
   for (int64_t i = 0; i < total; ++i)
@@ -536,8 +541,8 @@ rl_status rl_prefill(rl_model* m, void* stream, int32_t n, const int32_t* seq_id
   if (need > T.free_pages()) return fail(RL_ERR_KV_FULL, "need %lld pages, %lld free", (long long)need, (long long)T.free_pages());
 
   int32_t* bt = m->wsp<int32_t>(m->lay.block_table);
-  for (int i = 0; i < n; ++i) {
-    const int32_t s = seq_ids[i];
+  for (int i = 0; i < n_prompts; ++i) {
+    const int32_t s = seq_ids[i * group];
     T.activate(s);
     T.reserve(s, prompt_lens[i], nullptr);
     // pageable source: the runtime stages it before returning, so the vector may change afterwards
@@ -546,11 +551,11 @@ rl_status rl_prefill(rl_model* m, void* stream, int32_t n, const int32_t* seq_id
 
   float* x = m->wsp<float>(m->lay.x);
   float* x_last = m->wsp<float>(m->lay.x_last);
-  // rows in (sequence, position) order, cut into chunks of R
-  int seq_i = 0, pos = 0;
+  // rows in (prompt, position) order, cut into chunks of R
+  int pi = 0, pos = 0;
   int64_t done = 0, tok_off = 0;
-  std::vector<int64_t> tok_base(n);
-  for (int i = 0; i < n; ++i) { tok_base[i] = tok_off; tok_off += prompt_lens[i]; }
+  std::vector<int64_t> tok_base(n_prompts);
+  for (int i = 0; i < n_prompts; ++i) { tok_base[i] = tok_off; tok_off += prompt_lens[i]; }
   while (done < total) {
     const int M = (int)std::min<int64_t>(R, total - done);
     int slot;
@@ -561,14 +566,14 @@ rl_status rl_prefill(rl_model* m, void* stream, int32_t n, const int32_t* seq_id
     RowMeta* hr = (RowMeta*)hs;
     int32_t* ht = (int32_t*)(hs + m->lay.slot_tok);
     int max_ctx = 0;
-    struct Last { int row, seq_index; };
+    struct Last { int row, prompt; };
     std::vector<Last> lasts;
     for (int r = 0; r < M; ++r) {
-      hr[r].seq = seq_ids[seq_i];
+      hr[r].seq = seq_ids[pi * group];
       hr[r].pos = pos;
-      ht[r] = prompt_tokens[tok_base[seq_i] + pos];
+      ht[r] = prompt_tokens[tok_base[pi] + pos];
       if (pos + 1 > max_ctx) max_ctx = pos + 1;
-      if (pos + 1 == prompt_lens[seq_i]) { lasts.push_back({r, seq_i}); ++seq_i; pos = 0; }
+      if (pos + 1 == prompt_lens[pi]) { lasts.push_back({r, pi}); ++pi; pos = 0; }
       else ++pos;
     }
     { Timer t(m, st, K_META);
@@ -580,14 +585,51 @@ rl_status rl_prefill(rl_model* m, void* stream, int32_t n, const int32_t* seq_id
     { Timer t(m, st, K_EMBED);
       launch_embed(st, m->geo.dtype, m->embed, (const int32_t*)(ds + m->lay.slot_tok), x, M, H, m->geo.vocab); }
     int pend = run_layers(m, st, M, rows, max_ctx);
-    // fold the pending partials into x, then keep the rows that end a prompt
+    // fold the pending partials into x, then keep the rows that end a prompt (one copy per group member)
     float* cap = m->capture ? m->capture + (size_t)m->geo.n_layers * m->cfg.max_rows * H : nullptr;
     { Timer t(m, st, K_NORM);
       launch_residual_norm(st, m->geo.dtype, x, m->wsp<float>(m->lay.part), pend, nullptr, nullptr, cap, M, H, m->geo.rms_eps); }
     for (const Last& l : lasts)
-      HIP_TRY(hipMemcpyAsync(x_last + (size_t)l.seq_index * H, x + (size_t)l.row * H, (size_t)H * 4, hipMemcpyDeviceToDevice, st));
+      for (int j = 0; j < group; ++j)
+        HIP_TRY(hipMemcpyAsync(x_last + (size_t)(l.prompt * group + j) * H, x + (size_t)l.row * H, (size_t)H * 4, hipMemcpyDeviceToDevice, st));
     done += M;
   }
+
+  // ---- the other members of each group: shared full pages, private copy of the partial page ---------------
+  if (group > 1) {
+    std::vector<int32_t> pairs;  // (src page, dst page)
+    for (int i = 0; i < n_prompts; ++i) {
+      const int32_t lead = seq_ids[i * group];
+      const int full = prompt_lens[i] / SeqTable::kBlock;
+      const bool partial = prompt_lens[i] % SeqTable::kBlock;
+      for (int j = 1; j < group; ++j) {
+        const int32_t s = seq_ids[i * group + j];
+        T.activate(s);
+        T.share_prefix(s, lead, full);
+        if (partial) {
+          T.reserve(s, prompt_lens[i], nullptr);
+          pairs.push_back(T.pages(lead)[full]);
+          pairs.push_back(T.pages(s)[full]);
+        }
+        HIP_TRY(hipMemcpyAsync(bt + (size_t)s * m->geo.max_blocks, T.pages(s).data(), T.pages(s).size() * 4, hipMemcpyHostToDevice, st));
+      }
+    }
+    if (!pairs.empty()) {
+      int slot;
+      rl_status rs = ring_acquire(m, &slot);
+      if (rs != RL_OK) return rs;
+      char* hs = m->host_ring + (size_t)slot * m->lay.slot_bytes;
+      char* ds = m->ws + m->lay.ring + (size_t)slot * m->lay.slot_bytes;
+      memcpy(hs + m->lay.slot_upd, pairs.data(), pairs.size() * 4);  // at most 2 * max_rows ints
+      HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_upd, hs + m->lay.slot_upd, pairs.size() * 4, hipMemcpyHostToDevice, st));
+      HIP_TRY(hipEventRecord(m->ring_ev[slot], st));
+      m->ring_used[slot] = true;
+      launch_page_copy(st, m->kv_pool, m->layer_kv_bytes, m->kv_half_bytes,
+                       (size_t)m->geo.n_kv * 16 * m->geo.head_dim * elem_size(m->cfg.dtype), m->geo.n_layers,
+                       (const int32_t*)(ds + m->lay.slot_upd), (int)(pairs.size() / 2));
+    }
+  }
+
   // logits at the last prompt position of every sequence; the sampled token sits at position prompt_len
   {
     int slot;
@@ -596,18 +638,34 @@ rl_status rl_prefill(rl_model* m, void* stream, int32_t n, const int32_t* seq_id
     char* hs = m->host_ring + (size_t)slot * m->lay.slot_bytes;
     char* ds = m->ws + m->lay.ring + (size_t)slot * m->lay.slot_bytes;
     RowMeta* hr = (RowMeta*)hs;
-    for (int i = 0; i < n; ++i) { hr[i].seq = seq_ids[i]; hr[i].pos = prompt_lens[i]; }
-    HIP_TRY(hipMemcpyAsync(ds, hs, (size_t)n * sizeof(RowMeta), hipMemcpyHostToDevice, st));
+    for (int i = 0; i < n_all; ++i) { hr[i].seq = seq_ids[i]; hr[i].pos = prompt_lens[i / group]; }
+    HIP_TRY(hipMemcpyAsync(ds, hs, (size_t)n_all * sizeof(RowMeta), hipMemcpyHostToDevice, st));
     HIP_TRY(hipEventRecord(m->ring_ev[slot], st));
     m->ring_used[slot] = true;
     float* keep = m->capture;
     m->capture = nullptr;  // slot n_layers was already written per chunk
-    run_head(m, st, n, x_last, 0, (const RowMeta*)ds, 0, nullptr, sp, out_tokens, out_logprobs, nullptr);
+    run_head(m, st, n_all, x_last, 0, (const RowMeta*)ds, 0, nullptr, sp, out_tokens, out_logprobs, nullptr);
     m->capture = keep;
   }
   HIP_TRY(hipGetLastError());
-  for (int i = 0; i < n; ++i) T.set_len(seq_ids[i], prompt_lens[i]);
+  for (int i = 0; i < n_all; ++i) T.set_len(seq_ids[i], prompt_lens[i / group]);
   return RL_OK;
+}
+
+rl_status rl_prefill(rl_model* m, void* stream, int32_t n, const int32_t* seq_ids, const int32_t* prompt_tokens,
+                     const int32_t* prompt_lens, const rl_sampling* sp, int32_t* out_tokens, float* out_logprobs) {
+  if (!m || !seq_ids || !prompt_tokens || !prompt_lens || !sp || !out_tokens || !out_logprobs)
+    return fail(RL_ERR_INVALID_ARG, "NULL argument");
+  return prefill_impl(m, (hipStream_t)stream, n, 1, seq_ids, prompt_tokens, prompt_lens, sp, out_tokens, out_logprobs);
+}
+
+rl_status rl_prefill_groups(rl_model* m, void* stream, int32_t n_prompts, int32_t group_size, const int32_t* seq_ids,
+                            const int32_t* prompt_tokens, const int32_t* prompt_lens, const rl_sampling* sp,
+                            int32_t* out_tokens, float* out_logprobs) {
+  if (!m || !seq_ids || !prompt_tokens || !prompt_lens || !sp || !out_tokens || !out_logprobs)
+    return fail(RL_ERR_INVALID_ARG, "NULL argument");
+  return prefill_impl(m, (hipStream_t)stream, n_prompts, group_size, seq_ids, prompt_tokens, prompt_lens, sp, out_tokens,
+                      out_logprobs);
 }
 
 rl_status rl_seq_import_kv(rl_model* m, void* stream, int32_t seq_id, int32_t n_tokens, const void* const* k_layers,

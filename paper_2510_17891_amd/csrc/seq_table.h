@@ -2,6 +2,8 @@
 //
 // A page holds 16 tokens of K and V for every layer.  Pages are handed out from a LIFO free list; a call
 // that needs several pages first checks that all of them exist, so a failing call changes nothing.
+// Pages are reference counted: the samples of one prompt share the pages that the prompt fills completely
+// (they are never written again), and a page returns to the free list when its last holder is released.
 #pragma once
 #include <stdint.h>
 
@@ -20,7 +22,7 @@ class SeqTable {
 
   SeqTable(int max_seqs, int max_ctx, int64_t n_pages)
       : max_seqs_(max_seqs), max_ctx_(max_ctx), max_blocks_(max_ctx / kBlock), n_pages_(n_pages),
-        len_(max_seqs, -1), pages_(max_seqs) {
+        len_(max_seqs, -1), pages_(max_seqs), ref_(n_pages, 0) {
     free_.reserve(n_pages);
     for (int64_t p = n_pages - 1; p >= 0; --p) free_.push_back((int32_t)p);  // page 0 is handed out first
   }
@@ -56,6 +58,7 @@ class SeqTable {
     while ((int)pages_[s].size() < need) {
       int32_t p = free_.back();
       free_.pop_back();
+      ref_[p] = 1;
       if (grants) grants->push_back(PageGrant{s, (int32_t)pages_[s].size(), p});
       pages_[s].push_back(p);
     }
@@ -64,10 +67,21 @@ class SeqTable {
   void set_len(int32_t s, int32_t n) { len_[s] = n; }
 
   void release(int32_t s) {
-    for (auto it = pages_[s].rbegin(); it != pages_[s].rend(); ++it) free_.push_back(*it);
+    for (auto it = pages_[s].rbegin(); it != pages_[s].rend(); ++it)
+      if (--ref_[*it] == 0) free_.push_back(*it);
     pages_[s].clear();
     len_[s] = -1;
   }
+
+  // Make the (freshly activated, page-less) sequence `dst` share the first `n_blocks` pages of `src`.
+  void share_prefix(int32_t dst, int32_t src, int n_blocks) {
+    for (int b = 0; b < n_blocks; ++b) {
+      const int32_t p = pages_[src][b];
+      ++ref_[p];
+      pages_[dst].push_back(p);
+    }
+  }
+  int32_t refcount(int32_t page) const { return ref_[page]; }
 
   // Deterministic shuffle of the free list (test aid: results must not depend on page placement).
   void shuffle_free(uint64_t seed) {
@@ -84,6 +98,7 @@ class SeqTable {
   std::vector<int32_t> len_;  // -1 = inactive
   std::vector<std::vector<int32_t>> pages_;
   std::vector<int32_t> free_;
+  std::vector<int32_t> ref_;  // holders per page
 };
 
 }  // namespace rl

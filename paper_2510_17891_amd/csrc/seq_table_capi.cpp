@@ -14,6 +14,8 @@ void st_activate(void* t, int s) { ((rl::SeqTable*)t)->activate(s); }
 void st_set_len(void* t, int s, int n) { ((rl::SeqTable*)t)->set_len(s, n); }
 void st_release(void* t, int s) { ((rl::SeqTable*)t)->release(s); }
 void st_shuffle(void* t, unsigned long long seed) { ((rl::SeqTable*)t)->shuffle_free(seed); }
+void st_share_prefix(void* t, int dst, int src, int n_blocks) { ((rl::SeqTable*)t)->share_prefix(dst, src, n_blocks); }
+int st_refcount(void* t, int page) { return ((rl::SeqTable*)t)->refcount(page); }
 int st_n_seq_pages(void* t, int s) { return (int)((rl::SeqTable*)t)->pages(s).size(); }
 int st_seq_page(void* t, int s, int i) { return ((rl::SeqTable*)t)->pages(s)[i]; }
 // returns the number of grants written (seq, block, page triples)

@@ -40,6 +40,20 @@ __global__ __launch_bounds__(1024) void residual_norm_kernel(float* __restrict__
   float ss = 0.f;
   constexpr int kMaxPass = 2;  // H <= 1024 threads * 4 * kMaxPass, checked by the host
   float4 keep[kMaxPass];
+  float4 gv[kMaxPass];  // gains, fetched together with the data so that only one memory round trip precedes the sum
+#pragma unroll
+  for (int pass = 0; pass < kMaxPass; ++pass) {
+    const int i0 = (pass * nthr + threadIdx.x) * 4;
+    gv[pass] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (gain != nullptr && i0 < H) {
+      if (BF16) {
+        const uint2 gb = *(const uint2*)((const uint16_t*)gain + i0);
+        gv[pass] = make_float4(bf2f(gb.x & 0xffffu), bf2f(gb.x >> 16), bf2f(gb.y & 0xffffu), bf2f(gb.y >> 16));
+      } else {
+        gv[pass] = *(const float4*)((const float*)gain + i0);
+      }
+    }
+  }
 #pragma unroll
   for (int pass = 0; pass < kMaxPass; ++pass) {
     const int i0 = (pass * nthr + threadIdx.x) * 4;
@@ -68,14 +82,11 @@ __global__ __launch_bounds__(1024) void residual_norm_kernel(float* __restrict__
   for (int pass = 0; pass < kMaxPass; ++pass) {
     const int i0 = (pass * nthr + threadIdx.x) * 4;
     if (i0 >= H) continue;
-    const float4 v = keep[pass];
+    const float4 v = keep[pass], g = gv[pass];
     if (BF16) {
-      const uint2 gb = *(const uint2*)((const uint16_t*)gain + i0);
-      const uint32_t w0 = pack2bf(v.x * inv * bf2f(gb.x & 0xffffu), v.y * inv * bf2f(gb.x >> 16));
-      const uint32_t w1 = pack2bf(v.z * inv * bf2f(gb.y & 0xffffu), v.w * inv * bf2f(gb.y >> 16));
-      *(uint2*)((uint16_t*)h_out + frag_offset(r, i0, H >> 6)) = make_uint2(w0, w1);
+      *(uint2*)((uint16_t*)h_out + frag_offset(r, i0, H >> 6)) =
+          make_uint2(pack2bf(v.x * inv * g.x, v.y * inv * g.y), pack2bf(v.z * inv * g.z, v.w * inv * g.w));
     } else {
-      const float4 g = *(const float4*)((const float*)gain + i0);
       *(float4*)((float*)h_out + (size_t)r * H + i0) = make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w);
     }
   }
@@ -132,42 +143,48 @@ __global__ __launch_bounds__(64) void qk_rope_append_kernel(const float* __restr
   const int half = d >> 1;
   const int n_tot = (n_q + 2 * n_kv) * d;
   const RowMeta rm = rows[r];
+  const bool is_q = hh < n_q, is_k = !is_q && hh < n_q + n_kv;
+  // Everything that depends only on the row's (seq, pos) is requested first, so that it travels together with the
+  // partial sums instead of after them.
+  int64_t page = 0;
+  if (!is_q) page = block_table[(size_t)rm.seq * max_blocks + (rm.pos >> 4)];
   // lanes may own more than one pair when d/2 > 64
   for (int i = lane; i < ((half + 63) & ~63); i += 64) {
     const bool live = i < half;
+    float2 cs = make_float2(1.f, 0.f);
+    float g0 = 1.f, g1 = 1.f;
+    if (live && (is_q || is_k)) {
+      cs = rope[(size_t)rm.pos * half + i];
+      if (qk_norm) {
+        if (BF16) {
+          const uint16_t* g = (const uint16_t*)(is_q ? q_gain : k_gain);
+          g0 = bf2f(g[i]); g1 = bf2f(g[i + half]);
+        } else {
+          const float* g = (const float*)(is_q ? q_gain : k_gain);
+          g0 = g[i]; g1 = g[i + half];
+        }
+      }
+    }
     float v0 = 0.f, v1 = 0.f;
     if (live) {
+#pragma unroll 4
       for (int sp = 0; sp < S; ++sp) {
         const float* p = part + sp * split_stride + (size_t)r * n_tot + (size_t)hh * d;
         v0 += p[i];
         v1 += p[i + half];
       }
     }
-    const bool is_q = hh < n_q, is_k = !is_q && hh < n_q + n_kv;
     if (is_q || is_k) {
       if (qk_norm) {
         // d <= 128 here (one pass); wider heads are rejected by the host for this kernel
-        float ss = wave_sum(v0 * v0 + v1 * v1);
-        float inv = 1.0f / sqrtf(ss / (float)d + eps);
-        if (live) {
-          float g0, g1;
-          if (BF16) {
-            const uint16_t* g = (const uint16_t*)(is_q ? q_gain : k_gain);
-            g0 = bf2f(g[i]); g1 = bf2f(g[i + half]);
-          } else {
-            const float* g = (const float*)(is_q ? q_gain : k_gain);
-            g0 = g[i]; g1 = g[i + half];
-          }
-          v0 = v0 * inv * g0;
-          v1 = v1 * inv * g1;
-        }
+        const float ss = wave_sum(v0 * v0 + v1 * v1);
+        const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+        v0 = v0 * inv * g0;
+        v1 = v1 * inv * g1;
       }
-      if (live) {
-        float2 cs = rope[(size_t)rm.pos * half + i];
-        float r0 = v0 * cs.x - v1 * cs.y;
-        float r1 = v1 * cs.x + v0 * cs.y;
-        v0 = r0; v1 = r1;
-      }
+      const float r0 = v0 * cs.x - v1 * cs.y;
+      const float r1 = v1 * cs.x + v0 * cs.y;
+      v0 = r0; v1 = r1;
     }
     if (!live) continue;
     if (is_q) {
@@ -176,7 +193,6 @@ __global__ __launch_bounds__(64) void qk_rope_append_kernel(const float* __restr
       q[i + half] = v1;
     } else {
       const int hk = is_k ? hh - n_q : hh - n_q - n_kv;
-      const int64_t page = block_table[(size_t)rm.seq * max_blocks + (rm.pos >> 4)];
       const int t = rm.pos & 15;
       kv_store<BF16>(is_k ? k_pool : v_pool, page, hk, n_kv, d, t, i, v0, !is_k);
       kv_store<BF16>(is_k ? k_pool : v_pool, page, hk, n_kv, d, t, i + half, v1, !is_k);
@@ -260,6 +276,28 @@ __global__ void table_update_kernel(int32_t* __restrict__ bt, int max_blocks, co
 void launch_table_update(hipStream_t s, int32_t* block_table, int max_blocks, const int32_t* upd, int n) {
   if (n <= 0) return;
   table_update_kernel<<<(n + 63) / 64, 64, 0, s>>>(block_table, max_blocks, upd, n);
+}
+
+}  // namespace rl
+
+namespace rl {
+
+// grid: x = layer * 2 + (K|V), y = pair.  Copies one page of one pool half with 16-byte accesses.
+__global__ __launch_bounds__(256) void page_copy_kernel(char* __restrict__ pool, size_t layer_bytes, size_t half_bytes,
+                                                        size_t page_bytes_half, const int32_t* __restrict__ pairs) {
+  const int layer = blockIdx.x >> 1, half = blockIdx.x & 1;
+  const int32_t src = pairs[2 * blockIdx.y], dst = pairs[2 * blockIdx.y + 1];
+  char* base = pool + (size_t)layer * layer_bytes + (size_t)half * half_bytes;
+  const uint4* s = (const uint4*)(base + (size_t)src * page_bytes_half);
+  uint4* d = (uint4*)(base + (size_t)dst * page_bytes_half);
+  for (size_t i = threadIdx.x; i < page_bytes_half / 16; i += 256) d[i] = s[i];
+}
+
+void launch_page_copy(hipStream_t s, void* kv_pool, size_t layer_bytes, size_t half_bytes, size_t page_bytes_half,
+                      int n_layers, const int32_t* pairs, int n_pairs) {
+  if (n_pairs <= 0) return;
+  dim3 grid(n_layers * 2, n_pairs);
+  page_copy_kernel<<<grid, 256, 0, s>>>((char*)kv_pool, layer_bytes, half_bytes, page_bytes_half, pairs);
 }
 
 }  // namespace rl

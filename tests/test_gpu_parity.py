@@ -446,3 +446,54 @@ def test_tiny_fp32_ragged_continuous_batch(amd):
             t_ref, lp_ref = orc.sample(zg, 1.0, seed, slot, pos)
             assert t_ref == a["toks"][t] and abs(lp_ref - a["lps"][t]) < 1e-5, (idx, t)
     ro.close()
+
+
+# ------------------------------------------------------------------ grouped sampling with shared prompt pages
+@pytest.mark.parametrize("kind", ["tiny_f32", "small_bf16"])
+def test_prefill_groups_equals_independent_prefill(amd, kind):
+    """G samples per prompt: the prompt runs once, full pages are shared, the partial page is copied.  Tokens,
+    log-probs and every later decode step are bit-identical to prefilling the prompt G times; the oracle confirms
+    the first tokens; the pool accounting shows the sharing."""
+    if kind == "tiny_f32":
+        shape = ri.SHAPES["tiny"]
+        w, wn = make_both(shape, 61)
+    else:
+        shape = dict(ri.SHAPES["layer8b"], n_layers=2, hidden=512, n_q=4, n_kv=1, ffn=768, vocab=8192)
+        w, wn = make_both(shape, 61, std=0.05)
+    G, seed = 4, 99
+    lens = [37, 32, 5]                                 # partial page, exactly two pages, less than a page
+    prompts = [ri.tokens((n,), shape["vocab"], 61, 980 + i).tolist() for i, n in enumerate(lens)]
+    ids = list(range(len(lens) * G))
+    wd = to_device(w)
+    ra = amd.Rollout(shape, wd, max_seqs=16, max_ctx=96, max_rows=16, kv_pages=80)
+    rb = amd.Rollout(shape, wd, max_seqs=16, max_ctx=96, max_rows=16, kv_pages=80)
+    rb.rl_debug_shuffle_free_pages(17)
+    ta, la = ra.rl_prefill(ids, [prompts[i // G] for i in ids], 1.0, seed)
+    tb, lb = rb.rl_prefill_groups(ids, G, prompts, 1.0, seed)
+    torch.cuda.synchronize()
+    assert torch.equal(ta, tb) and torch.equal(la, lb)
+    # independent: 3+2+1 pages per member; grouped: shared full pages + one private partial page per member
+    assert ra.rl_kv_stats()[0] == 80 - G * (3 + 2 + 1)
+    assert rb.rl_kv_stats()[0] == 80 - ((2 + G) + 2 + G)
+    if kind == "tiny_f32":
+        om = orc.OracleModel(dims_of(shape), wn, max_ctx=96)
+        for i, p in enumerate(prompts):
+            z = om.prefill(i, p)
+            for j in range(G):
+                t_ref, lp_ref = orc.sample(z, 1.0, seed, i * G + j, lens[i])
+                assert int(tb[i * G + j]) == t_ref and abs(float(lb[i * G + j]) - lp_ref) < 2e-5
+    assert len(set(tb.tolist())) > 3                   # members draw different first tokens
+    za = torch.empty(len(ids), shape["vocab"], device=DEV)
+    zb = torch.empty_like(za)
+    for step in range(20):                             # crosses page boundaries of every member
+        ta, la = ra.rl_decode_step(ids, ta, 1.0, seed, debug_logits=za)
+        tb, lb = rb.rl_decode_step(ids, tb, 1.0, seed, debug_logits=zb)
+        torch.cuda.synchronize()
+        assert torch.equal(za, zb) and torch.equal(ta, tb) and torch.equal(la, lb), step
+    # retiring members one by one returns shared pages only with their last holder
+    rb.rl_free_seqs(ids[:G - 1] + ids[G:2 * G])
+    free_mid = rb.rl_kv_stats()[0]
+    rb.rl_free_seqs([ids[G - 1]] + ids[2 * G:])
+    assert rb.rl_kv_stats() == (80, 80) and free_mid < 80
+    ra.close()
+    rb.close()

@@ -60,6 +60,8 @@ def st(tmp_path_factory):
         getattr(L, f).argtypes = [C.c_void_p, C.c_int]
     for f in ("st_pages_missing", "st_set_len", "st_seq_page"):
         getattr(L, f).argtypes = [C.c_void_p, C.c_int, C.c_int]
+    L.st_share_prefix.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int]
+    L.st_refcount.argtypes = [C.c_void_p, C.c_int]
     L.st_shuffle.argtypes = [C.c_void_p, C.c_ulonglong]
     L.st_reserve.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_int), C.c_int]
     return L
@@ -105,4 +107,26 @@ def test_page_allocator_shuffle_is_a_permutation(st):
     g = _reserve(st, t, 0, 1600)
     pages = [p for _, _, p in g]
     assert sorted(pages) == list(range(100)) and pages != list(range(100))
+    st.st_destroy(t)
+
+
+def test_page_sharing_reference_counts(st):
+    t = st.st_create(4, 64, 8)
+    st.st_activate(t, 0)
+    g = _reserve(st, t, 0, 40)                                # 3 pages, the last one partial
+    pages = [p for _, _, p in g]
+    for s in (1, 2):
+        st.st_activate(t, s)
+        st.st_share_prefix(t, s, 0, 2)                        # share the two full pages
+        own = _reserve(st, t, s, 40)                          # private copy target for the partial page
+        assert len(own) == 1 and own[0][1] == 2 and own[0][2] not in pages
+        assert [st.st_seq_page(t, s, i) for i in range(2)] == pages[:2]
+    assert st.st_refcount(t, pages[0]) == 3 and st.st_refcount(t, pages[2]) == 1
+    assert st.st_free_pages(t) == 8 - 5
+    st.st_release(t, 0)                                       # shared pages survive their first holder
+    assert st.st_free_pages(t) == 8 - 4 and st.st_refcount(t, pages[0]) == 2
+    st.st_release(t, 1)
+    assert st.st_free_pages(t) == 8 - 3
+    st.st_release(t, 2)
+    assert st.st_free_pages(t) == 8 and st.st_refcount(t, pages[0]) == 0
     st.st_destroy(t)
