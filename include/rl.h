@@ -165,6 +165,20 @@ rl_status rl_prefill_groups(rl_model* m, void* stream, int32_t n_prompts, int32_
                             int32_t* out_tokens, float* out_logprobs);
 
 /*
+ * Teacher-forced scoring: log pi_theta(tok[t+1] | tok[0..t]) under softmax(z / T) for t = 0 .. len-2 of every
+ * sequence -- the numerator of the ratios s^plan, s^code of the HRD objective (Section 2.3) and, with the rollout
+ * weights, a recomputation of their denominator.  The sequences are scratch: seq_ids must be fresh ids, their
+ * pages are taken for the duration of the call and given back before it returns (work enqueued later on the
+ * same stream is ordered after this call's kernels).
+ *   seq_ids host [n_seqs];  tokens host [sum lens];  lens host [n_seqs], each in [2, max_ctx]
+ *   temperature   T > 0; T = 0 is read as T = 1
+ *   out_logprobs  device [sum (len_i - 1)] fp32, sequence after sequence
+ * Errors: INVALID_ARG, BAD_SEQ, KV_FULL, CTX_OVERFLOW, DEVICE.
+ */
+rl_status rl_score(rl_model* m, void* stream, int32_t n_seqs, const int32_t* seq_ids, const int32_t* tokens,
+                   const int32_t* lens, float temperature, float* out_logprobs);
+
+/*
  * One decode step for n_seqs active sequences (1 <= n_seqs <= max_rows): feed in_tokens[b] at the
  * sequence's next position, append its K/V, and sample the following token.
  *   seq_ids       host  [n_seqs]

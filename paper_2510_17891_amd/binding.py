@@ -18,7 +18,7 @@ RL_ERR_CTX_OVERFLOW, RL_ERR_DEVICE, RL_ERR_UNSUPPORTED = -4, -5, -6
 RL_F32, RL_BF16 = 0, 1
 
 EXPORTS = [
-    "rl_kv_page_bytes", "rl_query_workspace", "rl_init_model", "rl_destroy_model", "rl_prefill", "rl_prefill_groups",
+    "rl_kv_page_bytes", "rl_query_workspace", "rl_init_model", "rl_destroy_model", "rl_prefill", "rl_prefill_groups", "rl_score",
     "rl_decode_step", "rl_free_seqs", "rl_last_error", "rl_kv_stats", "rl_seq_len", "rl_sample_logits",
     "rl_seq_import_kv", "rl_decode_hidden", "rl_set_capture", "rl_pack_weight",
     "rl_debug_shuffle_free_pages", "rl_profile_enable", "rl_profile_read",
@@ -76,6 +76,7 @@ def lib():
                                  C.POINTER(rl_sampling), C.c_void_p, C.c_void_p]
         L.rl_prefill_groups.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, _i32p, _i32p, _i32p,
                                         C.POINTER(rl_sampling), C.c_void_p, C.c_void_p]
+        L.rl_score.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, _i32p, _i32p, _i32p, C.c_float, C.c_void_p]
         L.rl_decode_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, _i32p, C.c_void_p, C.c_void_p,
                                      C.POINTER(rl_sampling), C.c_void_p, C.c_void_p, C.c_void_p]
         L.rl_free_seqs.argtypes = [C.c_void_p, C.c_int32, _i32p]
@@ -227,6 +228,14 @@ class Rollout:
         check(lib().rl_prefill_groups(self.h, _stream(), len(prompts), group_size, _i32(seq_ids), _i32(flat),
                                       _i32([len(p) for p in prompts]), C.byref(sp), _ptr(out_t), _ptr(out_lp)))
         return out_t, out_lp
+
+    def rl_score(self, seq_ids, sequences, temperature):
+        """Teacher-forced log-probs of tokens 1.. of each int sequence; returns one device fp32 tensor (concatenated)."""
+        flat = [int(t) for q in sequences for t in q]
+        out = torch.empty(len(flat) - len(sequences), dtype=torch.float32, device=self.device)
+        check(lib().rl_score(self.h, _stream(), len(sequences), _i32(seq_ids), _i32(flat),
+                             _i32([len(q) for q in sequences]), temperature, _ptr(out)))
+        return out
 
     def rl_decode_step(self, seq_ids, in_tokens, temperature, seed, forced_next=None, debug_logits=None,
                        out_tokens=None, out_logprobs=None):

@@ -110,6 +110,9 @@ void launch_sample(hipStream_t s, const float* logits, int M, int V, const RowMe
 void launch_sample_merge(hipStream_t s, const float* part, int n_tiles, int M, int V, const int32_t* forced,
                          const float* forced_z, float temperature, int32_t* out_tokens, float* out_logprobs);
 
+// out[idx[i]] = src[i] for idx[i] >= 0.
+void launch_scatter_f32(hipStream_t s, const float* src, const int32_t* idx, float* out, int n);
+
 // block_table[upd[3i]][upd[3i+1]] = upd[3i+2] for i < n (device-side mirror update of newly granted pages).
 void launch_table_update(hipStream_t s, int32_t* block_table, int max_blocks, const int32_t* upd, int n);
 

@@ -40,11 +40,12 @@ rl_status fail(rl_status st, const char* fmt, ...) {
   } while (0)
 
 constexpr int kRing = 64;  // per-call metadata slots in flight
+constexpr int T_MAX_SCORE = 4096;  // sequences per scoring call
 
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 struct Layout {
-  size_t block_table, rope, ring, x, x_last, h, part, q, attn_part, o, a, logits, samp_part, forced_z, total;
+  size_t block_table, rope, ring, x, x_last, h, part, q, attn_part, o, a, logits, samp_part, forced_z, tmp_tok, tmp_lp, total;
   size_t slot_bytes, slot_upd, slot_tok;
   int max_segs, n_tiles;
 };
@@ -112,6 +113,8 @@ void compute_layout(const rl_model_config& c, Layout* L) {
   const size_t tiles_fused = V / 64 + 1;
   L->samp_part = take(V ? R * (tiles_fused > (size_t)L->n_tiles ? tiles_fused : (size_t)L->n_tiles) * 32 : 256);
   L->forced_z = take(R * 4);
+  L->tmp_tok = take(R * 4);
+  L->tmp_lp = take(R * 4);
   L->total = off;
 }
 
@@ -241,7 +244,8 @@ int run_layers(rl_model* m, hipStream_t st, int M, const RowMeta* rows, int max_
 
 // Final norm, output projection and sampling for M rows whose residual is in `xbuf` (pending partials added).
 void run_head(rl_model* m, hipStream_t st, int M, float* xbuf, int pend, const RowMeta* rows, int pos_offset,
-              const int32_t* forced, const rl_sampling* sp, int32_t* out_tokens, float* out_lp, float* debug_logits) {
+              const int32_t* forced, const rl_sampling* sp, int32_t* out_tokens, float* out_lp, float* debug_logits,
+              bool score_only = false) {
   const Geometry& g = m->geo;
   void* h = m->wsp<void>(m->lay.h);
   float* part = m->wsp<float>(m->lay.part);
@@ -256,6 +260,7 @@ void run_head(rl_model* m, hipStream_t st, int M, float* xbuf, int pend, const R
     se.rows = rows; se.pos_offset = pos_offset;
     se.greedy = !(sp->temperature > 0.f);
     se.inv_t = se.greedy ? 1.0f : 1.0f / sp->temperature;
+    if (score_only) se.greedy = 1;  // every row is forced: skip the random numbers, keep the temperature
     se.seed_lo = (uint32_t)(sp->seed & 0xffffffffu); se.seed_hi = (uint32_t)(sp->seed >> 32);
     se.forced = forced; se.forced_z = fz; se.part = spart; se.logits_out = debug_logits;
     { Timer t(m, st, K_LMHEAD);
@@ -666,6 +671,87 @@ rl_status rl_prefill_groups(rl_model* m, void* stream, int32_t n_prompts, int32_
     return fail(RL_ERR_INVALID_ARG, "NULL argument");
   return prefill_impl(m, (hipStream_t)stream, n_prompts, group_size, seq_ids, prompt_tokens, prompt_lens, sp, out_tokens,
                       out_logprobs);
+}
+
+rl_status rl_score(rl_model* m, void* stream, int32_t n, const int32_t* seq_ids, const int32_t* tokens,
+                   const int32_t* lens, float temperature, float* out_logprobs) {
+  if (!m || !seq_ids || !tokens || !lens || !out_logprobs) return fail(RL_ERR_INVALID_ARG, "NULL argument");
+  if (m->geo.vocab == 0) return fail(RL_ERR_UNSUPPORTED, "model has no vocabulary");
+  if (n < 1 || n > T_MAX_SCORE) return fail(RL_ERR_INVALID_ARG, "n_seqs %d outside [1, %d]", n, T_MAX_SCORE);
+  hipStream_t st = (hipStream_t)stream;
+  SeqTable& T = *m->table;
+  const int R = (int)m->cfg.max_rows, H = m->geo.hidden;
+  std::vector<char> seen(T.max_seqs(), 0);
+  int64_t need = 0, total = 0;
+  for (int i = 0; i < n; ++i) {
+    const int32_t s = seq_ids[i];
+    if (!T.valid_id(s)) return fail(RL_ERR_BAD_SEQ, "sequence id %d out of range", s);
+    if (T.active(s)) return fail(RL_ERR_BAD_SEQ, "sequence %d is already active", s);
+    if (seen[s]) return fail(RL_ERR_INVALID_ARG, "sequence %d appears twice", s);
+    seen[s] = 1;
+    if (lens[i] < 2) return fail(RL_ERR_INVALID_ARG, "sequence %d has fewer than 2 tokens", i);
+    if (lens[i] > T.max_ctx()) return fail(RL_ERR_CTX_OVERFLOW, "sequence %d has %d tokens, max_ctx is %d", i, lens[i], T.max_ctx());
+    need += SeqTable::blocks_for(lens[i]);
+    total += lens[i];
+  }
+  for (int64_t i = 0; i < total; ++i)
+    if (tokens[i] < 0 || tokens[i] >= m->geo.vocab) return fail(RL_ERR_INVALID_ARG, "token %d at %lld outside the vocabulary", tokens[i], (long long)i);
+  if (need > T.free_pages()) return fail(RL_ERR_KV_FULL, "need %lld pages, %lld free", (long long)need, (long long)T.free_pages());
+
+  int32_t* bt = m->wsp<int32_t>(m->lay.block_table);
+  for (int i = 0; i < n; ++i) {
+    const int32_t s = seq_ids[i];
+    T.activate(s);
+    T.reserve(s, lens[i], nullptr);
+    HIP_TRY(hipMemcpyAsync(bt + (size_t)s * m->geo.max_blocks, T.pages(s).data(), T.pages(s).size() * 4, hipMemcpyHostToDevice, st));
+  }
+  float* x = m->wsp<float>(m->lay.x);
+  int32_t* tmp_tok = m->wsp<int32_t>(m->lay.tmp_tok);
+  float* tmp_lp = m->wsp<float>(m->lay.tmp_lp);
+  rl_sampling sp{temperature, 0u, 0ull};
+  int si = 0, pos = 0;
+  int64_t done = 0, tok_off = 0, out_off = 0;
+  std::vector<int64_t> tok_base(n), out_base(n);
+  for (int i = 0; i < n; ++i) { tok_base[i] = tok_off; tok_off += lens[i]; out_base[i] = out_off; out_off += lens[i] - 1; }
+  rl_status result = RL_OK;
+  while (done < total && result == RL_OK) {
+    const int M = (int)std::min<int64_t>(R, total - done);
+    int slot;
+    result = ring_acquire(m, &slot);
+    if (result != RL_OK) break;
+    char* hs = m->host_ring + (size_t)slot * m->lay.slot_bytes;
+    char* ds = m->ws + m->lay.ring + (size_t)slot * m->lay.slot_bytes;
+    RowMeta* hr = (RowMeta*)hs;
+    int32_t* ht = (int32_t*)(hs + m->lay.slot_tok);
+    int32_t* hf = (int32_t*)(hs + m->lay.slot_upd);  // [0,R): token to score, [R,2R): output index or -1
+    int max_ctx = 0;
+    for (int r = 0; r < M; ++r) {
+      hr[r].seq = seq_ids[si];
+      hr[r].pos = pos;
+      ht[r] = tokens[tok_base[si] + pos];
+      if (pos + 1 > max_ctx) max_ctx = pos + 1;
+      if (pos + 1 == lens[si]) { hf[r] = 0; hf[R + r] = -1; ++si; pos = 0; }
+      else { hf[r] = tokens[tok_base[si] + pos + 1]; hf[R + r] = (int32_t)(out_base[si] + pos); ++pos; }
+    }
+    { Timer t(m, st, K_META);
+      HIP_TRY(hipMemcpyAsync(ds, hs, (size_t)M * sizeof(RowMeta), hipMemcpyHostToDevice, st));
+      HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_tok, ht, (size_t)M * 4, hipMemcpyHostToDevice, st));
+      HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_upd, hf, (size_t)2 * R * 4, hipMemcpyHostToDevice, st));
+      HIP_TRY(hipEventRecord(m->ring_ev[slot], st));
+      m->ring_used[slot] = true; }
+    const RowMeta* rows = (const RowMeta*)ds;
+    const int32_t* forced = (const int32_t*)(ds + m->lay.slot_upd);
+    { Timer t(m, st, K_EMBED);
+      launch_embed(st, m->geo.dtype, m->embed, (const int32_t*)(ds + m->lay.slot_tok), x, M, H, m->geo.vocab); }
+    int pend = run_layers(m, st, M, rows, max_ctx);
+    run_head(m, st, M, x, pend, rows, 1, forced, &sp, tmp_tok, tmp_lp, nullptr, true);
+    launch_scatter_f32(st, tmp_lp, forced + R, out_logprobs, M);
+    done += M;
+  }
+  if (result == RL_OK && hipGetLastError() != hipSuccess) result = fail(RL_ERR_DEVICE, "kernel launch failed");
+  // the sequences were only scratch: later work on this stream is ordered after the kernels above
+  for (int i = 0; i < n; ++i) T.release(seq_ids[i]);
+  return result;
 }
 
 rl_status rl_seq_import_kv(rl_model* m, void* stream, int32_t seq_id, int32_t n_tokens, const void* const* k_layers,

@@ -301,3 +301,17 @@ void launch_page_copy(hipStream_t s, void* kv_pool, size_t layer_bytes, size_t h
 }
 
 }  // namespace rl
+
+namespace rl {
+
+__global__ void scatter_f32_kernel(const float* __restrict__ src, const int32_t* __restrict__ idx, float* __restrict__ out, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n && idx[i] >= 0) out[idx[i]] = src[i];
+}
+
+void launch_scatter_f32(hipStream_t s, const float* src, const int32_t* idx, float* out, int n) {
+  if (n <= 0) return;
+  scatter_f32_kernel<<<(n + 255) / 256, 256, 0, s>>>(src, idx, out, n);
+}
+
+}  // namespace rl

@@ -168,6 +168,7 @@ def _oracle_layer_row(shape, wn, k, v, x_row, ctx):
     [0, 1, 15, 16, 17, 255, 256, 257, 700],            # page and chunk boundaries, empty history
     [300 + 7 * i for i in range(37)],                  # 37 rows: two column blocks with a ragged tail
     [33],                                              # a single row
+    [16383, 8191, 4096, 4095, 1024, 1023],             # longest context; both sides of the LDS/workspace merge switch
 ])
 def test_bf16_layer_decode_matches_oracle(amd, ctxs):
     shape, wn, ro, ks, vs, x = _layer_case(amd, ctxs, seed=31, shuffle=9)
@@ -497,3 +498,64 @@ def test_prefill_groups_equals_independent_prefill(amd, kind):
     assert rb.rl_kv_stats() == (80, 80) and free_mid < 80
     ra.close()
     rb.close()
+
+
+# ------------------------------------------------------------------------------ teacher-forced scoring call
+def test_score_matches_oracle_log_softmax(amd):
+    shape = ri.SHAPES["tiny"]
+    w, wn = make_both(shape, 71)
+    ro = amd.Rollout(shape, to_device(w), max_seqs=8, max_ctx=64, max_rows=16, kv_pages=12)
+    lens = [40, 2, 17]
+    seqs = [ri.tokens((n,), shape["vocab"], 71, 990 + i).tolist() for i, n in enumerate(lens)]
+    for T in (1.0, 0.7):
+        out = ro.rl_score([4, 0, 7], seqs, T).cpu().numpy()
+        assert ro.rl_kv_stats() == (12, 12)             # scratch sequences are gone
+        invT = float(np.float32(1.0) / np.float32(T))
+        k = 0
+        for i, q in enumerate(seqs):
+            om = orc.OracleModel(dims_of(shape), wn, max_ctx=64)
+            for t in range(len(q) - 1):
+                ls = orc.log_softmax(om.forward_token(0, q[t]), invT)
+                assert abs(out[k] - ls[q[t + 1]]) < 2e-5, (T, i, t)
+                k += 1
+        assert k == out.size
+    B = amd.binding
+    with pytest.raises(B.RLError) as e:
+        ro.rl_score([0], [list(range(70))], 1.0)
+    assert e.value.status == B.RL_ERR_CTX_OVERFLOW and ro.rl_kv_stats() == (12, 12)
+    ro.close()
+
+
+@pytest.mark.parametrize("kind", ["tiny_f32", "small_bf16"])
+def test_rescored_rollout_gives_ratio_one(amd, kind):
+    """With theta = theta_old the probability ratio of the objective is exactly one: the log-probs returned while
+    sampling equal the log-probs of a teacher-forced pass over the finished sequences."""
+    if kind == "tiny_f32":
+        shape = ri.SHAPES["tiny"]
+        w, _ = make_both(shape, 72)
+    else:
+        shape = dict(ri.SHAPES["layer8b"], n_layers=2, hidden=512, n_q=4, n_kv=1, ffn=768, vocab=8192)
+        w, _ = make_both(shape, 72, std=0.05)
+    ro = amd.Rollout(shape, to_device(w), max_seqs=8, max_ctx=96, max_rows=24, kv_pages=40)
+    G, seed, n_new = 3, 5, 30
+    prompts = [ri.tokens((n,), shape["vocab"], 72, 995 + i).tolist() for i, n in enumerate([21, 16])]
+    ids = list(range(2 * G))
+    tok, lp = ro.rl_prefill_groups(ids, G, prompts, 1.0, seed)
+    toks, lps = [tok.cpu()], [lp.cpu()]
+    for _ in range(n_new - 1):
+        tok, lp = ro.rl_decode_step(ids, tok, 1.0, seed)
+        toks.append(tok.cpu())
+        lps.append(lp.cpu())
+    toks, lps = torch.stack(toks, 1), torch.stack(lps, 1)          # [6, n_new]
+    ro.rl_free_seqs(ids)
+    full = [prompts[i // G] + toks[i].tolist() for i in ids]
+    sc = ro.rl_score(ids, full, 1.0).cpu()
+    k = 0
+    for i in ids:
+        P = len(prompts[i // G])
+        got = sc[k + P - 1:k + P - 1 + n_new]
+        ratio = torch.exp(got - lps[i])
+        assert torch.all((ratio - 1).abs() < 1e-5), (i, (ratio - 1).abs().max())
+        k += len(full[i]) - 1
+    assert len({tuple(t.tolist()) for t in toks[:G]}) == G          # the samples of one prompt differ
+    ro.close()
