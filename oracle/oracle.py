@@ -63,6 +63,12 @@ def lib():
         L.orc_log_softmax.argtypes = [_f32p, C.c_int32, C.c_float, _f64p]
         L.orc_sample_histogram.argtypes = [_f32p, C.c_int32, C.c_float, C.c_uint64, C.c_uint32,
                                            C.c_uint32, C.c_int64, C.POINTER(C.c_int64)]
+        _i32p = C.POINTER(C.c_int32)
+        L.orc_hrd_objective.restype = C.c_double
+        L.orc_hrd_objective.argtypes = [C.c_int32, C.c_int32, _i32p, _i32p, _f32p, _f32p, _f32p, _f32p,
+                                        C.c_double, C.c_double, C.c_double, C.c_int32, _f64p]
+        L.orc_plan_length.restype = C.c_int32
+        L.orc_plan_length.argtypes = [_i32p, C.c_int32, C.c_int32]
         _lib = L
     return _lib
 
@@ -246,3 +252,25 @@ class OracleModel:
         for t in tokens:
             z = self.forward_token(seq, int(t))
         return z
+
+
+def _ip(a):
+    assert a.dtype == np.int32 and a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def hrd_objective(n_prompts, G, off, n_plan, lp_new, lp_old, r_speedup, r_correct, alpha=0.1, eps=0.2, beta=0.0,
+                  mode=0):
+    """(J, per-output terms) of the HRD objective (mode 0) or the uniform-reward GRPO objective (mode 1)."""
+    off = np.ascontiguousarray(off, np.int32)
+    n_plan = np.ascontiguousarray(n_plan, np.int32)
+    seq = np.zeros(n_prompts * G, np.float64)
+    J = lib().orc_hrd_objective(n_prompts, G, _ip(off), _ip(n_plan), _p(f32(lp_new)), _p(f32(lp_old)),
+                                _p(f32(r_speedup)), _p(f32(r_correct)), alpha, eps, beta, mode,
+                                seq.ctypes.data_as(_f64p))
+    return float(J), seq
+
+
+def plan_length(tokens, delimiter):
+    t = np.ascontiguousarray(tokens, np.int32)
+    return int(lib().orc_plan_length(_ip(t), t.size, delimiter))

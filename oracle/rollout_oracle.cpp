@@ -23,7 +23,9 @@
 // invariance, SiLU identities, brute-force matvec, prefill-vs-decode
 // consistency, zero-layer model = one matvec, published known-answer vectors
 // of the counter generator, log accuracy against libm, Gumbel-max frequencies
-// against softmax on a tiny vocabulary.  No function here is "parity unpinned".
+// against softmax on a tiny vocabulary; for the objective: ratio-one closed form, zero-sum advantages, clip
+// cases worked by hand, class weights, both printed forms of the clipped term.  No function here is
+// "parity unpinned".
 
 #include <cmath>
 #include <cstdint>
@@ -360,6 +362,68 @@ void orc_sample_histogram(const float* z, int32_t vocab, float temperature, uint
     orc_sample(z, vocab, temperature, seed, seq, pos0 + (uint32_t)t, -1, &tok, &lp);
     counts[tok] += 1;
   }
+}
+
+// ---------------------------------------------------------------------------
+// Policy objective with Hierarchical Reward Decomposition (Section 2.3) and its uniform-reward GRPO counterpart
+// (Appendix C), forward value only, for a batch of n_prompts groups of G sampled outputs.
+//
+// Output (i,j) has |o| = off[k+1]-off[k] tokens (k = i*G+j); its first n_plan[k] tokens are the plan class T^plan,
+// the rest the code class T^code.  Per token t: s_t = exp(lp_new[t] - lp_old[t]).
+//   mode 0 (HRD):     A^c = r^c - mean_j r^c with r^plan = r_speedup, r^code = r_correct;
+//                     J_i^c = 1/G sum_j 1/|o| sum_{t in T^c} min(A^c s_t, A^c clip(s_t, 1-eps, 1+eps));
+//                     J = mean_i [alpha J_i^plan + J_i^code].
+//   mode 1 (uniform): r = beta r_correct + (1-beta) r_speedup, A = r - mean_j r;
+//                     L_i = 1/G sum_j 1/|o| sum_t A min(s_t, clip(s_t, 1-eps, 1+eps));  J = mean_i L_i
+//                     (the advantage multiplies the min, as the appendix writes it).
+// seq_term[k] (optional) receives the 1/|o| sum of output k before the 1/G and 1/n_prompts factors.
+// ---------------------------------------------------------------------------
+double orc_hrd_objective(int32_t n_prompts, int32_t G, const int32_t* off, const int32_t* n_plan,
+                         const float* lp_new, const float* lp_old, const float* r_speedup, const float* r_correct,
+                         double alpha, double eps, double beta, int32_t mode, double* seq_term) {
+  double J = 0.0;
+  for (int32_t i = 0; i < n_prompts; ++i) {
+    double mean_s = 0.0, mean_c = 0.0, mean_u = 0.0;
+    for (int32_t j = 0; j < G; ++j) {
+      const int32_t k = i * G + j;
+      mean_s += r_speedup[k];
+      mean_c += r_correct[k];
+      mean_u += beta * r_correct[k] + (1.0 - beta) * r_speedup[k];
+    }
+    mean_s /= G; mean_c /= G; mean_u /= G;
+    double Ji = 0.0;
+    for (int32_t j = 0; j < G; ++j) {
+      const int32_t k = i * G + j;
+      const int32_t len = off[k + 1] - off[k];
+      double acc = 0.0;
+      for (int32_t t = 0; t < len; ++t) {
+        const double s = std::exp((double)lp_new[off[k] + t] - (double)lp_old[off[k] + t]);
+        const double sc = s < 1.0 - eps ? 1.0 - eps : (s > 1.0 + eps ? 1.0 + eps : s);
+        if (mode == 0) {
+          const bool plan = t < n_plan[k];
+          const double A = plan ? (double)r_speedup[k] - mean_s : (double)r_correct[k] - mean_c;
+          const double term = std::fmin(A * s, A * sc);
+          acc += plan ? alpha * term : term;
+        } else {
+          const double A = beta * r_correct[k] + (1.0 - beta) * r_speedup[k] - mean_u;
+          acc += A * std::fmin(s, sc);
+        }
+      }
+      const double term = len > 0 ? acc / (double)len : 0.0;
+      if (seq_term) seq_term[k] = term;
+      Ji += term;
+    }
+    J += Ji / G;
+  }
+  return J / n_prompts;
+}
+
+// Number of plan tokens of one output: everything up to and including the first occurrence of the delimiter
+// token that closes the reasoning trace; an output without it is all plan.
+int32_t orc_plan_length(const int32_t* tokens, int32_t len, int32_t delimiter) {
+  for (int32_t t = 0; t < len; ++t)
+    if (tokens[t] == delimiter) return t + 1;
+  return len;
 }
 
 }  // extern "C"
