@@ -242,6 +242,37 @@ rl_status rl_decode_hidden(rl_model* m, void* stream, int32_t n_seqs, const int3
 rl_status rl_set_capture(rl_model* m, float* buf);
 
 /*
+ * Forward value of the policy objective (no model needed; all arrays on the device).
+ *   mode 0  Hierarchical Reward Decomposition (Section 2.3): tokens of an output are split into the plan class (the
+ *           reasoning trace, up to and including the delimiter that closes it) and the code class; advantages are
+ *           group-mean-baselined per class, A^plan from r_speedup and A^code from r_correct;
+ *           J = mean_i [ alpha J_i^plan + J_i^code ],
+ *           J_i^c = 1/G sum_j 1/|o_ij| sum_{t in T^c} min(A^c s_t, A^c clip(s_t, 1-eps, 1+eps)),
+ *           s_t = exp(lp_new[t] - lp_old[t]).
+ *   mode 1  uniform-reward GRPO (Appendix C): r = beta r_correct + (1-beta) r_speedup, A = r - mean_j r,
+ *           L_i = 1/G sum_j 1/|o_ij| sum_t A min(s_t, clip(s_t, 1-eps, 1+eps)).
+ *   offsets    [n_prompts*G + 1] int32: output k (= i*G + j) owns tokens offsets[k] .. offsets[k+1]-1 of lp_new/lp_old
+ *   n_plan     [n_prompts*G] int32 plan-token counts, or NULL: then tokens (response token ids, same indexing as
+ *              lp_*) are scanned for delimiter_token (an output without it is all plan)
+ *   r_speedup, r_correct  [n_prompts*G] fp32 rewards
+ *   seq_terms  [n_prompts*G] fp32 out: the 1/|o| sum of each output (before the 1/G and 1/n_prompts factors)
+ *   n_plan_out [n_prompts*G] int32 out or NULL: the plan lengths used
+ *   out_value  [1] fp32 out: the objective
+ * Sums run in a fixed order (reproducible bits).  Errors: INVALID_ARG, DEVICE.
+ */
+typedef struct {
+  float alpha;    /* weight of the plan class, 0.1 in the paper's main runs */
+  float eps_clip; /* clip range, 0.2 */
+  float beta;     /* mode 1 only: share of the correctness reward */
+  int32_t mode;   /* 0 = HRD, 1 = uniform */
+} rl_objective_params;
+
+rl_status rl_hrd_objective(void* stream, int32_t n_prompts, int32_t group_size, const int32_t* offsets,
+                           const int32_t* n_plan, const int32_t* tokens, int32_t delimiter_token, const float* lp_new,
+                           const float* lp_old, const float* r_speedup, const float* r_correct,
+                           const rl_objective_params* p, float* seq_terms, int32_t* n_plan_out, float* out_value);
+
+/*
  * Reorder a row-major [rows x cols] matrix (device) into the order the projection kernels stream
  * (device, same size, must not overlap src).  RL_BF16: 32-row x 64-column tiles, each stored so that a
  * wavefront reads it as four contiguous 1 KiB pieces in matrix-core operand order; needs rows % 32 == 0

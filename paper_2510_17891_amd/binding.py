@@ -18,7 +18,7 @@ RL_ERR_CTX_OVERFLOW, RL_ERR_DEVICE, RL_ERR_UNSUPPORTED = -4, -5, -6
 RL_F32, RL_BF16 = 0, 1
 
 EXPORTS = [
-    "rl_kv_page_bytes", "rl_query_workspace", "rl_init_model", "rl_destroy_model", "rl_prefill", "rl_prefill_groups", "rl_score",
+    "rl_kv_page_bytes", "rl_query_workspace", "rl_init_model", "rl_destroy_model", "rl_prefill", "rl_prefill_groups", "rl_score", "rl_hrd_objective",
     "rl_decode_step", "rl_free_seqs", "rl_last_error", "rl_kv_stats", "rl_seq_len", "rl_sample_logits",
     "rl_seq_import_kv", "rl_decode_hidden", "rl_set_capture", "rl_pack_weight",
     "rl_debug_shuffle_free_pages", "rl_profile_enable", "rl_profile_read",
@@ -46,6 +46,10 @@ class rl_weights(C.Structure):
 
 class rl_sampling(C.Structure):
     _fields_ = [("temperature", C.c_float), ("reserved", C.c_uint32), ("seed", C.c_uint64)]
+
+
+class rl_objective_params(C.Structure):
+    _fields_ = [("alpha", C.c_float), ("eps_clip", C.c_float), ("beta", C.c_float), ("mode", C.c_int32)]
 
 
 class RLError(RuntimeError):
@@ -77,6 +81,8 @@ def lib():
         L.rl_prefill_groups.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, _i32p, _i32p, _i32p,
                                         C.POINTER(rl_sampling), C.c_void_p, C.c_void_p]
         L.rl_score.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, _i32p, _i32p, _i32p, C.c_float, C.c_void_p]
+        L.rl_hrd_objective.argtypes = [C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 3 + [C.c_int32] + \
+            [C.c_void_p] * 4 + [C.POINTER(rl_objective_params)] + [C.c_void_p] * 3
         L.rl_decode_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, _i32p, C.c_void_p, C.c_void_p,
                                      C.POINTER(rl_sampling), C.c_void_p, C.c_void_p, C.c_void_p]
         L.rl_free_seqs.argtypes = [C.c_void_p, C.c_int32, _i32p]
@@ -135,6 +141,23 @@ def rl_pack_weight(w):
     out = torch.empty_like(w)
     check(lib().rl_pack_weight(_stream(), dt, _ptr(w), _ptr(out), w.shape[0], w.shape[1]))
     return out
+
+
+def rl_hrd_objective(n_prompts, group_size, offsets, lp_new, lp_old, r_speedup, r_correct, alpha=0.1, eps_clip=0.2,
+                     beta=0.0, mode=0, n_plan=None, tokens=None, delimiter_token=-1):
+    """Objective value (device scalar), per-output terms and plan lengths; all inputs are device tensors."""
+    n = n_prompts * group_size
+    dev = lp_new.device
+    seq = torch.empty(n, dtype=torch.float32, device=dev)
+    npl = torch.empty(n, dtype=torch.int32, device=dev)
+    out = torch.empty(1, dtype=torch.float32, device=dev)
+    p = rl_objective_params(alpha, eps_clip, beta, mode)
+    st = lib().rl_hrd_objective(_stream(), n_prompts, group_size, _ptr(offsets), _ptr(n_plan), _ptr(tokens),
+                                delimiter_token, _ptr(lp_new), _ptr(lp_old), _ptr(r_speedup), _ptr(r_correct),
+                                C.byref(p), _ptr(seq), _ptr(npl), _ptr(out))
+    if st != RL_OK:
+        raise RLError(st, "rl_hrd_objective: bad arguments or launch failure")
+    return out, seq, npl
 
 
 class Rollout:

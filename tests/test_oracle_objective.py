@@ -50,6 +50,8 @@ def test_clip_cases_worked_by_hand():
     assert abs(J(0.5, 1.0) - 0.5 * (0.5 * 0.5 - 0.5 * 1.0)) < 1e-7     # A>0, s below: not clipped (min takes A*s)
     assert abs(J(1.0, 0.5) - 0.5 * (0.5 * 1.0 - 0.5 * 0.8)) < 1e-7     # A<0, s below the clip: capped at 1-eps
     assert abs(J(1.0, 1.5) - 0.5 * (0.5 * 1.0 - 0.5 * 1.5)) < 1e-7     # A<0, s above: not clipped
+    assert abs(J(1.1, 0.7) - 0.5 * (0.5 * 1.1 - 0.5 * 0.8)) < 1e-7     # just inside / just outside the band
+    assert abs(J(1.3, 0.9) - 0.5 * (0.5 * 1.2 - 0.5 * 0.9)) < 1e-7
 
 
 def test_class_split_weights_and_length_normalisation():
