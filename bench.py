@@ -57,6 +57,10 @@ def parse():
     ap.add_argument("--profile-steps", type=int, default=8, help="extra steps run with per-kernel events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--contiguous-pages", action="store_true",
+                    help="layer workload: give every sequence consecutive pages instead of a random permutation")
+    ap.add_argument("--batch", type=int, default=64, help="layer workload: sequences per step")
+    ap.add_argument("--ctx", type=int, default=2048, help="layer workload: cached tokens per sequence at the start")
     ap.add_argument("--prefill", choices=["real", "import"], default="real",
                     help="import: fill the prompt KV with random N(0,1) pages instead of running the prefill "
                          "(for counter runs that should only see decode steps)")
@@ -179,13 +183,14 @@ def main():
         ctx0 = P
     else:
         shape = ri.SHAPES["layer8b"]
-        B, ctx0 = 64, 2048
+        B, ctx0 = args.batch, args.ctx
         total_steps = args.warmup + args.steps + (0 if args.no_profile else args.profile_steps)
         max_ctx = (ctx0 + total_steps + 1 + 15) // 16 * 16
         pages = B * (max_ctx // 16)
         w = ri.make_weights(shape, seed, device=dev, dtype=torch.bfloat16)
         ro = Rollout(shape, w, max_seqs=B, max_ctx=max_ctx, max_rows=B, kv_pages=pages)
-        ro.rl_debug_shuffle_free_pages(seed)  # block tables are a random permutation of the pool
+        if not args.contiguous_pages:
+            ro.rl_debug_shuffle_free_pages(seed)  # block tables are a random permutation of the pool
         for b in range(B):
             k = ri.normal((ctx0, shape["n_kv"], shape["head_dim"]), 1.0, seed, 2000 + 2 * b, device=dev, dtype=torch.bfloat16)
             v = ri.normal((ctx0, shape["n_kv"], shape["head_dim"]), 1.0, seed, 2001 + 2 * b, device=dev, dtype=torch.bfloat16)

@@ -10,11 +10,16 @@
 //   O^T[d][head]          += V^T[d][key] P[key][head]    MFMA 16x16x32 over two pages (32 keys); the P operand is
 //                                                        exactly the registers the score MFMA produced
 //
-// One block of four waves handles one (row, kv head).  The context is cut into segments whose number and
-// bounds depend on the context length alone (4*ceil(ctx/1024) equal runs of 32-key steps); each wave streams a
-// contiguous quarter of them, leaving (max, sum, unnormalised O) per head and segment, and after a block barrier
-// the four waves merge the segments of one head each, flat and in index order.  Nothing crosses blocks, so no
-// device-scope fence (an L2 write-back on this multi-die part) is needed, and the bits of a row's result do not
+// The context is cut into segments whose number and bounds depend on the context length alone
+// (4*ceil(ctx/1024) equal runs of 32-key steps), each leaving (max, sum, unnormalised O) per head.  One block of
+// four waves handles up to 16 segments of one (row, kv head), each wave a contiguous quarter.
+//   ctx <= 4096: one block per (row, kv head); partials stay in LDS and after a block barrier the four waves
+//                merge the segments of one head each, flat and in index order.
+//   ctx  > 4096: ceil(segments/16) blocks per (row, kv head), so that long contexts become many short blocks
+//                that the dispatcher can balance; partials go to the workspace and a second small kernel does the
+//                same flat merge.
+// Which path runs is a function of the row's context only, and nothing synchronises across blocks inside a
+// kernel (a device-scope fence is an L2 write-back on this multi-die part), so the bits of a row's result do not
 // depend on the batch.
 #include "device_utils.h"
 #include "kernels.h"
@@ -39,8 +44,9 @@ struct PagePair {
 __device__ __forceinline__ void load_pair(PagePair& pp, const u32x4_t* __restrict__ kbase,
                                           const u32x4_t* __restrict__ vbase, int64_t page_a, int64_t page_b, int n_kv,
                                           int lane) {
-  const size_t oa = (size_t)page_a * n_kv * (kPageElems / 8) + lane;
-  const size_t ob = (size_t)page_b * n_kv * (kPageElems / 8) + lane;
+  // per layer the pool is [page][kv head][K | V]: the K and V blocks of a (page, head) are adjacent
+  const size_t oa = (size_t)page_a * n_kv * (2 * kPageElems / 8) + lane;
+  const size_t ob = (size_t)page_b * n_kv * (2 * kPageElems / 8) + lane;
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
     pp.k[0][s] = __builtin_nontemporal_load(kbase + oa + s * 64);
@@ -55,7 +61,9 @@ __device__ __forceinline__ void load_pair(PagePair& pp, const u32x4_t* __restric
 
 __host__ __device__ inline int attn_num_segments(int ctx) { return 4 * ((ctx + 1023) / 1024); }
 
-// grid: x = kv head, y = row.  block = four waves.
+__host__ __device__ inline int attn_num_splits(int n_seg) { return n_seg <= kLdsSegs ? 1 : (n_seg + kLdsSegs - 1) / kLdsSegs; }
+
+// grid: x = kv head, y = row, z = split.  block = four waves.
 __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* __restrict__ q, const RowMeta* __restrict__ rows,
                                                                const int32_t* __restrict__ block_table, int max_blocks,
                                                                const u32x4_t* __restrict__ k_pool,
@@ -67,6 +75,8 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const RowMeta rm = rows[r];
   const int ctx = rm.pos + 1;  // keys 0..pos (the row's own key was appended before this kernel)
+  const int n_seg = attn_num_segments(ctx);
+  if ((int)blockIdx.z >= attn_num_splits(n_seg)) return;  // block-uniform
   const int group = n_q / n_kv;  // <= 8
   const int j = lane & 15, g = lane >> 4;
   const int n_blk = (ctx + 15) >> 4;
@@ -94,17 +104,18 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
   }
   __syncthreads();
 
-  const u32x4_t* kb = k_pool + (size_t)hk * (kPageElems / 8);
-  const u32x4_t* vb = v_pool + (size_t)hk * (kPageElems / 8);
+  const u32x4_t* kb = k_pool + (size_t)hk * (2 * kPageElems / 8);
+  const u32x4_t* vb = v_pool + (size_t)hk * (2 * kPageElems / 8);
   const int n_it = (ctx + 31) >> 5;  // 32-key steps
-  const int n_seg = attn_num_segments(ctx);
   // Segment partials of short contexts (<= kLdsSegs segments) stay in LDS; longer ones go through the workspace.
   const bool in_lds = n_seg <= kLdsSegs;
+  const int seg0 = blockIdx.z * kLdsSegs;                       // this block's segments: [seg0, seg0 + segs_here)
+  const int segs_here = min(kLdsSegs, n_seg - seg0);            // a multiple of 4
   float* pbase = in_lds ? (float*)(pages + lds_part_offset) : part + (size_t)r * n_q * max_segs * kPartStride;
   const int seg_stride = in_lds ? n_seg : max_segs;          // segments per head in the chosen buffer
   const int head0 = in_lds ? 0 : hk * group;                 // LDS holds this block's heads only
-  const int seg_per_wave = n_seg >> 2;
-  auto seg_begin = [&](int sgm) { return (int)(((long long)sgm * n_it) / n_seg); };
+  const int seg_per_wave = segs_here >> 2;
+  auto seg_begin = [&](int sgm) { return (int)(((unsigned)sgm * (unsigned)n_it) / (unsigned)n_seg); };  // < 2^31: n_it < 2^16, sgm <= 288
 
   f32x4_t o_acc[8];
   float m_run, l_run;
@@ -115,7 +126,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
     l_run = 0.f;
   };
   reset();
-  int seg = wave * seg_per_wave;
+  int seg = seg0 + wave * seg_per_wave;
   const int seg_end = seg + seg_per_wave;
   const int it_begin = seg_begin(seg), it_end = seg_begin(seg_end);
   while (seg < seg_end && seg_begin(seg + 1) == seg_begin(seg)) ++seg;  // skip leading empty segments
@@ -215,6 +226,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
     }
   }
 
+  if (!in_lds) return;  // long context: attn_merge_bf16_kernel combines the partials of all blocks
   // ---- merge: wave w takes heads w, w+4 of the group; lane owns dims 2*lane, 2*lane+1 ------------
   __threadfence_block();
   __syncthreads();
@@ -238,6 +250,59 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
   }
 }
 
+// Merge of the long-context rows (more than kLdsSegs segments, none of them empty): one wave per (row, head).
+// The segment weights exp(m_c - M) are formed by the lanes in parallel (max and denominator by the wave's fixed
+// butterfly), then the O partials are accumulated in index order, eight loads in flight at a time.  Rows with
+// short contexts were finished by the first kernel.
+__global__ __launch_bounds__(64) void attn_merge_bf16_kernel(const float* __restrict__ part, const RowMeta* __restrict__ rows,
+                                                             int max_segs, uint16_t* __restrict__ o_out, int n_q) {
+  const int head = blockIdx.x, r = blockIdx.y, lane = threadIdx.x;
+  const int ctx = rows[r].pos + 1;
+  const int n_seg = attn_num_segments(ctx);
+  if (n_seg <= kLdsSegs) return;
+  const float* p = part + ((size_t)r * n_q + head) * max_segs * kPartStride;
+  constexpr int kMaxPerLane = 4;  // up to 256 segments = contexts up to 65536
+  float mc[kMaxPerLane], lc[kMaxPerLane];
+  float M = -INFINITY;
+#pragma unroll
+  for (int u = 0; u < kMaxPerLane; ++u) {
+    const int c = lane + 64 * u;
+    mc[u] = -INFINITY;
+    lc[u] = 0.f;
+    if (c < n_seg) { mc[u] = p[(size_t)c * kPartStride + kD]; lc[u] = p[(size_t)c * kPartStride + kD + 1]; }
+    M = fmaxf(M, mc[u]);
+  }
+  M = wave_max(M);
+  float den = 0.f;
+#pragma unroll
+  for (int u = 0; u < kMaxPerLane; ++u) {
+    mc[u] = __expf(mc[u] - M);  // weight of segment lane + 64u (0 beyond n_seg)
+    den += mc[u] * lc[u];
+  }
+  den = wave_sum(den);
+  float o0 = 0.f, o1 = 0.f;
+#pragma unroll
+  for (int u = 0; u < kMaxPerLane; ++u) {
+    const int c_end = min(64, n_seg - 64 * u);  // a multiple of 4, like n_seg
+    for (int cl = 0; cl < c_end; cl += 4) {
+      float2 v[4];
+      float w[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        v[e] = *(const float2*)(p + (size_t)(64 * u + cl + e) * kPartStride + 2 * lane);
+        w[e] = __shfl(mc[u], cl + e, kWave);
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        o0 += w[e] * v[e].x;
+        o1 += w[e] * v[e].y;
+      }
+    }
+  }
+  const float inv = 1.0f / den;
+  *(uint32_t*)(o_out + frag_offset(r, head * kD + 2 * lane, (n_q * kD) >> 6)) = pack2bf(o0 * inv, o1 * inv);
+}
+
 }  // namespace
 
 int attn_bf16_max_segments(int max_ctx) { return attn_num_segments(max_ctx); }
@@ -245,14 +310,16 @@ int attn_bf16_max_segments(int max_ctx) { return attn_num_segments(max_ctx); }
 void launch_attn_decode_bf16(hipStream_t s, const Geometry& g, const float* q, const RowMeta* rows,
                              const int32_t* block_table, const void* k_pool_layer, const void* v_pool_layer,
                              float* part, int max_segs_alloc, int max_ctx_in_batch, void* o_out, int M) {
-  dim3 grid(g.n_kv, M);
+  const int n_seg_max = attn_num_segments(max_ctx_in_batch);
+  dim3 grid(g.n_kv, M, attn_num_splits(n_seg_max));
   const int page_ints = ((max_ctx_in_batch + 15) / 16 + 1 + 3) & ~3;  // keeps the partials 16-byte aligned
-  int segs = attn_num_segments(max_ctx_in_batch);
-  if (segs > kLdsSegs) segs = kLdsSegs;
+  const int segs = n_seg_max > kLdsSegs ? kLdsSegs : n_seg_max;
   const size_t lds = (size_t)page_ints * 4 + (size_t)(g.n_q / g.n_kv) * segs * kPartStride * sizeof(float);
   attn_decode_bf16_kernel<<<grid, 256, lds, s>>>(q, rows, block_table, g.max_blocks, (const u32x4_t*)k_pool_layer,
                                                  (const u32x4_t*)v_pool_layer, part, max_segs_alloc, g.n_q, g.n_kv,
                                                  1.0f / sqrtf((float)g.head_dim), (uint16_t*)o_out, page_ints);
+  if (n_seg_max > kLdsSegs)
+    attn_merge_bf16_kernel<<<dim3(g.n_q, M), 64, 0, s>>>(part, rows, max_segs_alloc, (uint16_t*)o_out, g.n_q);
 }
 
 }  // namespace rl

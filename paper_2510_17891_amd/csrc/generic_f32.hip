@@ -77,7 +77,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const float* __restrict__ 
     const int key = kb + lane;
     float sc = -INFINITY;
     if (key < ctx) {
-      const float* kp = k_pool + ((size_t)pg[lane >> 4] * n_kv + hk) * page_elems + (size_t)(key & 15) * d;
+      const float* kp = k_pool + ((size_t)pg[lane >> 4] * n_kv + hk) * 2 * page_elems + (size_t)(key & 15) * d;
       float dot = 0.f;
       for (int i = 0; i < d; ++i) dot = fmaf(qs[i], kp[i], dot);
       sc = dot * scale;
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const float* __restrict__ 
       if (i < d) {
         float a = acc[c] * alpha;
         for (int t = 0; t < nk; ++t) {
-          const float* vp = v_pool + ((size_t)pg[t >> 4] * n_kv + hk) * page_elems + (size_t)(t & 15) * d;
+          const float* vp = v_pool + ((size_t)pg[t >> 4] * n_kv + hk) * 2 * page_elems + (size_t)(t & 15) * d;
           a = fmaf(ps[t], vp[i], a);
         }
         acc[c] = a;

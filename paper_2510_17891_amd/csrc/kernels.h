@@ -51,10 +51,10 @@ void launch_qk_rope_append(hipStream_t s, const Geometry& g, const float* qkv_pa
 void launch_kv_import(hipStream_t s, const Geometry& g, const void* k_src, const void* v_src, int n_tokens,
                       const int32_t* block_table_row, void* k_pool_layer, void* v_pool_layer);
 
-// Copy whole KV pages (all layers, K and V): pool byte layout [layer][K|V][page][page_bytes_half]; pairs = n x
-// (src page, dst page) in device memory.
-void launch_page_copy(hipStream_t s, void* kv_pool, size_t layer_bytes, size_t half_bytes, size_t page_bytes_half,
-                      int n_layers, const int32_t* pairs, int n_pairs);
+// Copy whole KV pages (all layers): pool byte layout [layer][page][page_bytes]; pairs = n x (src page, dst page)
+// in device memory.
+void launch_page_copy(hipStream_t s, void* kv_pool, size_t layer_bytes, size_t page_bytes, int n_layers,
+                      const int32_t* pairs, int n_pairs);
 
 // ---- attention -----------------------------------------------------------------------------------
 // bf16, head_dim 128: decode attention over paged KV (MFMA), one block per (row, kv head), context cut into

@@ -134,7 +134,7 @@ struct rl_model {
   std::vector<const void*> attn_norm, wqkv, q_norm, k_norm, wo, mlp_norm, w_gate_up, w_down;
   char* kv_pool;
   char* ws;
-  size_t layer_kv_bytes, kv_half_bytes;
+  size_t layer_kv_bytes, kv_block_bytes;  // one layer of the pool; one K (or V) block of a (page, kv head)
   // pinned host ring for per-call metadata
   char* host_ring = nullptr;
   hipEvent_t ring_ev[kRing];
@@ -151,7 +151,7 @@ struct rl_model {
 
   template <typename T> T* wsp(size_t off) const { return reinterpret_cast<T*>(ws + off); }
   void* k_pool(int l) const { return kv_pool + (size_t)l * layer_kv_bytes; }
-  void* v_pool(int l) const { return kv_pool + (size_t)l * layer_kv_bytes + kv_half_bytes; }
+  void* v_pool(int l) const { return kv_pool + (size_t)l * layer_kv_bytes + kv_block_bytes; }
 };
 
 namespace {
@@ -383,8 +383,8 @@ rl_status rl_init_model(const rl_model_config* c, const rl_weights* w, rl_model*
     }
   m->kv_pool = (char*)w->kv_pool;
   m->ws = (char*)w->workspace;
-  m->kv_half_bytes = (size_t)n_pages * c->n_kv_heads * 16 * c->head_dim * elem_size(c->dtype);
-  m->layer_kv_bytes = 2 * m->kv_half_bytes;
+  m->kv_block_bytes = (size_t)16 * c->head_dim * elem_size(c->dtype);
+  m->layer_kv_bytes = (size_t)n_pages * c->n_kv_heads * 2 * m->kv_block_bytes;
   m->table = new SeqTable((int)c->max_seqs, (int)c->max_ctx, n_pages);
   for (int i = 0; i < K_COUNT; ++i) { m->prof_ms[i] = 0; m->prof_n[i] = 0; }
   for (int i = 0; i < kRing; ++i) { m->ring_ev[i] = nullptr; m->ring_used[i] = false; }
@@ -629,8 +629,7 @@ static rl_status prefill_impl(rl_model* m, hipStream_t st, int32_t n_prompts, in
       HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_upd, hs + m->lay.slot_upd, pairs.size() * 4, hipMemcpyHostToDevice, st));
       HIP_TRY(hipEventRecord(m->ring_ev[slot], st));
       m->ring_used[slot] = true;
-      launch_page_copy(st, m->kv_pool, m->layer_kv_bytes, m->kv_half_bytes,
-                       (size_t)m->geo.n_kv * 16 * m->geo.head_dim * elem_size(m->cfg.dtype), m->geo.n_layers,
+      launch_page_copy(st, m->kv_pool, m->layer_kv_bytes, (size_t)m->geo.n_kv * 2 * m->kv_block_bytes, m->geo.n_layers,
                        (const int32_t*)(ds + m->lay.slot_upd), (int)(pairs.size() / 2));
     }
   }

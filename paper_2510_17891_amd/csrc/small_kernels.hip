@@ -120,7 +120,7 @@ template <bool BF16>
 __device__ __forceinline__ void kv_store(void* pool_layer, int64_t page, int hk, int n_kv, int d, int t, int dd,
                                          float val, bool is_v) {
   const size_t page_elems = (size_t)kPageTokens * d;
-  const size_t base = ((size_t)page * n_kv + hk) * page_elems;
+  const size_t base = ((size_t)page * n_kv + hk) * 2 * page_elems;  // [page][kv head][K | V]; V's base pointer is one block in
   if (BF16) {
     int off = is_v ? v_page_offset_bf16(t, dd) : k_page_offset_bf16(t, dd);
     ((uint16_t*)pool_layer)[base + off] = (uint16_t)f2bf(val);
@@ -282,22 +282,21 @@ void launch_table_update(hipStream_t s, int32_t* block_table, int max_blocks, co
 
 namespace rl {
 
-// grid: x = layer * 2 + (K|V), y = pair.  Copies one page of one pool half with 16-byte accesses.
-__global__ __launch_bounds__(256) void page_copy_kernel(char* __restrict__ pool, size_t layer_bytes, size_t half_bytes,
-                                                        size_t page_bytes_half, const int32_t* __restrict__ pairs) {
-  const int layer = blockIdx.x >> 1, half = blockIdx.x & 1;
+// grid: x = layer, y = pair.  Copies one page (all kv heads, K and V: contiguous inside a layer) with 16-byte accesses.
+__global__ __launch_bounds__(256) void page_copy_kernel(char* __restrict__ pool, size_t layer_bytes, size_t page_bytes,
+                                                        const int32_t* __restrict__ pairs) {
   const int32_t src = pairs[2 * blockIdx.y], dst = pairs[2 * blockIdx.y + 1];
-  char* base = pool + (size_t)layer * layer_bytes + (size_t)half * half_bytes;
-  const uint4* s = (const uint4*)(base + (size_t)src * page_bytes_half);
-  uint4* d = (uint4*)(base + (size_t)dst * page_bytes_half);
-  for (size_t i = threadIdx.x; i < page_bytes_half / 16; i += 256) d[i] = s[i];
+  char* base = pool + (size_t)blockIdx.x * layer_bytes;
+  const uint4* s = (const uint4*)(base + (size_t)src * page_bytes);
+  uint4* d = (uint4*)(base + (size_t)dst * page_bytes);
+  for (size_t i = threadIdx.x; i < page_bytes / 16; i += 256) d[i] = s[i];
 }
 
-void launch_page_copy(hipStream_t s, void* kv_pool, size_t layer_bytes, size_t half_bytes, size_t page_bytes_half,
-                      int n_layers, const int32_t* pairs, int n_pairs) {
+void launch_page_copy(hipStream_t s, void* kv_pool, size_t layer_bytes, size_t page_bytes, int n_layers,
+                      const int32_t* pairs, int n_pairs) {
   if (n_pairs <= 0) return;
-  dim3 grid(n_layers * 2, n_pairs);
-  page_copy_kernel<<<grid, 256, 0, s>>>((char*)kv_pool, layer_bytes, half_bytes, page_bytes_half, pairs);
+  dim3 grid(n_layers, n_pairs);
+  page_copy_kernel<<<grid, 256, 0, s>>>((char*)kv_pool, layer_bytes, page_bytes, pairs);
 }
 
 }  // namespace rl
