@@ -6,6 +6,8 @@
 // LDS staging, no shuffles.  A wave owns a 64 x (32*MB) output tile over a slice of K; the four waves of a
 // block take four K slices and add their accumulators through LDS in a fixed order; further K splits across
 // blocks (to put >= 256 blocks on the chip for the small matrices) leave fp32 partials that the consumer sums.
+#include <type_traits>
+
 #include "device_utils.h"
 #include "kernels.h"
 #include "sampler_device.h"
@@ -22,15 +24,20 @@ struct Frags {
   u32x4_t b[MB][4];
 };
 
-template <int MB>
+template <int MB, bool NT = true>
 __device__ __forceinline__ void load_frags(Frags<MB>& f, const u32x4_t* __restrict__ w0, const u32x4_t* __restrict__ w1,
                                            const u32x4_t* const* __restrict__ xb, int kb, int lane) {
   // block (rb, kb) = 256 uint4; sub-load t is [t*64 + lane]
   const int o = kb * 256 + lane;
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
-    f.a[0][t] = __builtin_nontemporal_load(w0 + o + t * 64);
-    f.a[1][t] = __builtin_nontemporal_load(w1 + o + t * 64);
+    if (NT) {  // weights pass through once
+      f.a[0][t] = __builtin_nontemporal_load(w0 + o + t * 64);
+      f.a[1][t] = __builtin_nontemporal_load(w1 + o + t * 64);
+    } else {   // the block's other waves read the same tile: let it live in L1/L2
+      f.a[0][t] = w0[o + t * 64];
+      f.a[1][t] = w1[o + t * 64];
+    }
   }
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb)
@@ -49,6 +56,70 @@ __device__ __forceinline__ void mma_frags(const Frags<MB>& f, f32x16_t (&acc)[2]
         acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, f.a[nb][t]),
                                                               __builtin_bit_cast(bf16x8_t, f.b[mb][t]), acc[nb][mb], 0,
                                                               0, 0);
+}
+
+// Write one finished 64 x 32 output block held in MFMA accumulator order: lane (col, hb) has, for both row blocks,
+// outputs n = rb*32 + 8q + 4hb + e (q, e = 0..3) of batch row m.
+template <int EPI>
+__device__ __forceinline__ void store_block(const float (&sum)[2][16], int m, int hb, int rb0, int rb1, int split, int M,
+                                          int N, void* __restrict__ out, const SampleEpilogue& se, int tile) {
+  if (EPI == kEpiPartial) {
+    float* o = (float*)out + ((size_t)split * M + m) * N;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = (nb ? rb1 : rb0) * 32 + 8 * q + 4 * hb;
+        *(float4*)(o + n) = make_float4(sum[nb][4 * q], sum[nb][4 * q + 1], sum[nb][4 * q + 2], sum[nb][4 * q + 3]);
+      }
+  } else if (EPI == kEpiSwiGLU) {
+    uint16_t* o = (uint16_t*)out;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      float a[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float gte = sum[0][4 * q + e], up = sum[1][4 * q + e];
+        a[e] = gte / (1.0f + __expf(-gte)) * up;
+      }
+      const int n = rb0 * 32 + 8 * q + 4 * hb;
+      *(uint2*)(o + frag_offset(m, n, N >> 6)) = make_uint2(pack2bf(a[0], a[1]), pack2bf(a[2], a[3]));
+    }
+  } else {
+    // lane (col, hb) holds 32 logits of row m: vocabulary ids (rb*32 + 8q + 4hb + e), in aligned groups of four,
+    // i.e. one Philox block per group.
+    const RowMeta rm = se.rows[m];
+    const uint32_t pos = (uint32_t)(rm.pos + se.pos_offset), seq = (uint32_t)rm.seq;
+    const int f = se.forced ? se.forced[m] : -1;
+    Best best{-INFINITY, -1, 0.f};
+    float lm = -INFINITY, ls = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n0 = (nb ? rb1 : rb0) * 32 + 8 * q + 4 * hb;
+        uint32_t rnd[4] = {0, 0, 0, 0};
+        if (!se.greedy) philox4x32_10((uint32_t)n0 >> 2, pos, seq, 0u, se.seed_lo, se.seed_hi, rnd);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float zi = sum[nb][4 * q + e];
+          const float y = se.greedy ? zi : __fmaf_rn(zi, se.inv_t, gumbel(rnd[e]));
+          best = better(best, Best{y, n0 + e, zi});
+          lse_merge(lm, ls, zi * se.inv_t, 1.0f);
+          if (n0 + e == f) se.forced_z[m] = zi;
+        }
+        if (se.logits_out)
+          *(float4*)(se.logits_out + (size_t)m * N + n0) =
+              make_float4(sum[nb][4 * q], sum[nb][4 * q + 1], sum[nb][4 * q + 2], sum[nb][4 * q + 3]);
+      }
+    best = better(best, shfl_xor_best(best, 32));  // the other half of this row's 64 entries
+    lse_merge(lm, ls, __shfl_xor(lm, 32, kWave), __shfl_xor(ls, 32, kWave));
+    if (hb == 0) {
+      float* p = se.part + ((size_t)m * (N >> 6) + tile) * kSamplePartFloats;
+      *(float4*)p = make_float4(best.y, __int_as_float(best.idx), best.z, 0.f);
+      *(float4*)(p + 4) = make_float4(lm, ls, 0.f, 0.f);
+    }
+  }
 }
 
 // grid: x = N tile, y = K split, z = M tile of 32*MB rows.
@@ -142,63 +213,215 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const u32x4_t* __restric
     if (wave != (mb & 3)) continue;
     const int m = (m_blk0 + mb) * 32 + col;
     if (m >= M) continue;
-    if (EPI == kEpiPartial) {
-      float* o = (float*)out + ((size_t)blockIdx.y * M + m) * N;
+    store_block<EPI>(sum, m, hb, rb0, rb1, blockIdx.y, M, N, out, se, blockIdx.x);
+  }
+}
+
+// Variant for 64 < M <= 256: the four waves take different batch-column blocks (MBW blocks of 32 each) instead of
+// different K quarters, so a wave needs only 32*MBW accumulator columns and the block still streams W once (the
+// four waves read the same weight tile at about the same time; only the first read leaves L2).  To keep a row's
+// result bit-identical to the K-split variants, every wave still forms the four K-quarter sums separately and adds
+// them as (q0 + q1) + (q2 + q3).
+template <int MBW, int EPI, int ST>
+__global__ __launch_bounds__(256) void gemm_bf16_cols_kernel(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ W,
+                                                             void* __restrict__ out, int M, int N, int K, int kb_per_quarter,
+                                                             SampleEpilogue se) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int KB = K >> 6;
+  const int m_blk0 = (blockIdx.z * 4 + wave) * MBW;
+  const int n_blocks_m = (M + 31) >> 5;
+  if (m_blk0 >= n_blocks_m) return;  // this wave has no rows (no barriers below)
+
+  int rb0, rb1;
+  if (EPI == kEpiSwiGLU) { rb0 = blockIdx.x; rb1 = blockIdx.x + (N >> 5); }
+  else                   { rb0 = blockIdx.x * 2; rb1 = rb0 + 1; }
+  const u32x4_t* w0 = W + (size_t)rb0 * KB * 256;
+  const u32x4_t* w1 = W + (size_t)rb1 * KB * 256;
+  const u32x4_t* xb[MBW];
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
+  for (int mb = 0; mb < MBW; ++mb) {
+    int b = m_blk0 + mb;
+    if (b >= n_blocks_m) b = n_blocks_m - 1;
+    xb[mb] = X + (size_t)b * KB * 256;
+  }
+  const int kb0 = blockIdx.y * 4 * kb_per_quarter;
+  const int rounds = kb_per_quarter / ST;  // the launcher picks ST so that it divides kb_per_quarter
+  Frags<MBW> f[ST];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int n = (nb ? rb1 : rb0) * 32 + 8 * q + 4 * hb;
-          *(float4*)(o + n) = make_float4(sum[nb][4 * q], sum[nb][4 * q + 1], sum[nb][4 * q + 2], sum[nb][4 * q + 3]);
-        }
-    } else if (EPI == kEpiSwiGLU) {
-      uint16_t* o = (uint16_t*)out;
+  for (int s = 0; s < ST; ++s) load_frags<MBW, false>(f[s], w0, w1, xb, kb0 + s, lane);
+  // One K quarter into a fresh accumulator.  The register ring keeps running across quarters: every block but the
+  // last ST of the whole range re-issues its buffer for the block ST ahead.
+  auto quarter = [&](f32x16_t (&a)[2][MBW], int q, bool last) __attribute__((always_inline)) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        float a[4];
+    for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float gte = sum[0][4 * q + e], up = sum[1][4 * q + e];
-          a[e] = gte / (1.0f + __expf(-gte)) * up;
-        }
-        const int n = rb0 * 32 + 8 * q + 4 * hb;
-        *(uint2*)(o + frag_offset(m, n, N >> 6)) = make_uint2(pack2bf(a[0], a[1]), pack2bf(a[2], a[3]));
-      }
-    } else {
-      // lane (col, hb) holds 32 logits of row m: vocabulary ids (rb*32 + 8q + 4hb + e), in aligned groups of four,
-      // i.e. one Philox block per group.
-      const RowMeta rm = se.rows[m];
-      const uint32_t pos = (uint32_t)(rm.pos + se.pos_offset), seq = (uint32_t)rm.seq;
-      const int f = se.forced ? se.forced[m] : -1;
-      Best best{-INFINITY, -1, 0.f};
-      float lm = -INFINITY, ls = 0.f;
+      for (int mb = 0; mb < MBW; ++mb)
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
+        for (int r = 0; r < 16; ++r) a[nb][mb][r] = 0.f;
+    const int base = kb0 + q * kb_per_quarter;
+    const int refill_rounds = last ? rounds - 1 : rounds;
+    for (int r = 0; r < refill_rounds; ++r) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int n0 = (nb ? rb1 : rb0) * 32 + 8 * q + 4 * hb;
-          uint32_t rnd[4] = {0, 0, 0, 0};
-          if (!se.greedy) philox4x32_10((uint32_t)n0 >> 2, pos, seq, 0u, se.seed_lo, se.seed_hi, rnd);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float zi = sum[nb][4 * q + e];
-            const float y = se.greedy ? zi : __fmaf_rn(zi, se.inv_t, gumbel(rnd[e]));
-            best = better(best, Best{y, n0 + e, zi});
-            lse_merge(lm, ls, zi * se.inv_t, 1.0f);
-            if (n0 + e == f) se.forced_z[m] = zi;
-          }
-          if (se.logits_out)
-            *(float4*)(se.logits_out + (size_t)m * N + n0) =
-                make_float4(sum[nb][4 * q], sum[nb][4 * q + 1], sum[nb][4 * q + 2], sum[nb][4 * q + 3]);
-        }
-      best = better(best, shfl_xor_best(best, 32));  // the other half of this row's 64 entries
-      lse_merge(lm, ls, __shfl_xor(lm, 32, kWave), __shfl_xor(ls, 32, kWave));
-      if (hb == 0) {
-        float* p = se.part + ((size_t)m * (N >> 6) + blockIdx.x) * kSamplePartFloats;
-        *(float4*)p = make_float4(best.y, __int_as_float(best.idx), best.z, 0.f);
-        *(float4*)(p + 4) = make_float4(lm, ls, 0.f, 0.f);
+      for (int s = 0; s < ST; ++s) {
+        mma_frags<MBW>(f[s], a);
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags<MBW, false>(f[s], w0, w1, xb, base + r * ST + s + ST, lane);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
+    if (last) {
+#pragma unroll
+      for (int s = 0; s < ST; ++s) mma_frags<MBW>(f[s], a);
+    }
+  };
+  f32x16_t acc[2][MBW], other[2][MBW], s01[2][MBW];
+  quarter(s01, 0, false);
+  quarter(other, 1, false);
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+    for (int mb = 0; mb < MBW; ++mb) s01[nb][mb] += other[nb][mb];
+  quarter(other, 2, false);
+  quarter(acc, 3, true);
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+    for (int mb = 0; mb < MBW; ++mb) acc[nb][mb] = s01[nb][mb] + (other[nb][mb] + acc[nb][mb]);
+
+  const int col = lane & 31, hb = lane >> 5;
+#pragma unroll
+  for (int mb = 0; mb < MBW; ++mb) {
+    const int m = (m_blk0 + mb) * 32 + col;
+    if (m >= M) continue;
+    float sum[2][16];
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sum[nb][r] = acc[nb][mb][r];
+    store_block<EPI>(sum, m, hb, rb0, rb1, blockIdx.y, M, N, out, se, blockIdx.x);
+  }
+}
+
+// Variant of the column-split kernel that fetches every weight tile from global memory once per block: the 256
+// threads copy the tile (two 32-row blocks x 64 k = 8 KiB) into one of four LDS stages, one barrier per k block
+// publishes it, and each wave reads its MFMA A fragments from LDS while its own activation fragments keep coming
+// straight from L2.  Weight registers run four k blocks ahead of the LDS stage they feed.  Needs K quarters that
+// are multiples of four k blocks (true for every 8B-shaped matrix); same quarter arithmetic, same bits.
+template <int MBW, int EPI, int XS>
+__global__ __launch_bounds__(256, MBW == 1 ? 2 : 1) void gemm_bf16_lds_kernel(const u32x4_t* __restrict__ X,
+                                                                           const u32x4_t* __restrict__ W,
+                                                                           void* __restrict__ out, int M, int N, int K,
+                                                                           int kb_per_quarter, SampleEpilogue se) {
+  __shared__ u32x4_t wlds[4][2][256];  // 32 KiB
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int KB = K >> 6;
+  const int n_blocks_m = (M + 31) >> 5;
+  int m_blk0 = (blockIdx.z * 4 + wave) * MBW;
+  const bool has_rows = m_blk0 < n_blocks_m;
+  if (!has_rows) m_blk0 = n_blocks_m - 1;  // idle waves shadow a valid block (they still carry tiles and barriers)
+
+  int rb0, rb1;
+  if (EPI == kEpiSwiGLU) { rb0 = blockIdx.x; rb1 = blockIdx.x + (N >> 5); }
+  else                   { rb0 = blockIdx.x * 2; rb1 = rb0 + 1; }
+  const u32x4_t* w0 = W + (size_t)rb0 * KB * 256 + tid;
+  const u32x4_t* w1 = W + (size_t)rb1 * KB * 256 + tid;
+  const u32x4_t* xb[MBW];
+#pragma unroll
+  for (int mb = 0; mb < MBW; ++mb) {
+    int b = m_blk0 + mb;
+    if (b >= n_blocks_m) b = n_blocks_m - 1;
+    xb[mb] = X + (size_t)b * KB * 256 + lane;
+  }
+  const int n = 4 * kb_per_quarter;
+  const int kb0 = blockIdx.y * n;
+  auto kb_of = [&](int i) { return kb0 + (i < n ? i : n - 1); };  // clamped: no conditional loads in the pipeline
+
+  u32x4_t wr[4][2];          // weight registers: slot s holds a block with index = s (mod 4)
+  u32x4_t xr[XS][MBW][4];    // activation fragments: slot s holds a block with index = s (mod XS)
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    wr[s][0] = __builtin_nontemporal_load(w0 + (size_t)kb_of(s) * 256);
+    wr[s][1] = __builtin_nontemporal_load(w1 + (size_t)kb_of(s) * 256);
+  }
+#pragma unroll
+  for (int s = 0; s < XS; ++s)
+#pragma unroll
+    for (int mb = 0; mb < MBW; ++mb)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) xr[s][mb][t] = xb[mb][(size_t)kb_of(s) * 256 + t * 64];
+  wlds[0][0][tid] = wr[0][0];
+  wlds[0][1][tid] = wr[0][1];
+  wr[0][0] = __builtin_nontemporal_load(w0 + (size_t)kb_of(4) * 256);
+  wr[0][1] = __builtin_nontemporal_load(w1 + (size_t)kb_of(4) * 256);
+
+  // One k block: publish the next tile, barrier, multiply this one.  j = i mod 4 at compile time.
+  auto iter = [&](f32x16_t (&a)[2][MBW], int i, auto jc) __attribute__((always_inline)) {
+    constexpr int j = decltype(jc)::value, jn = (j + 1) & 3, jx = j % XS;
+    wlds[jn][0][tid] = wr[jn][0];
+    wlds[jn][1][tid] = wr[jn][1];
+    wr[jn][0] = __builtin_nontemporal_load(w0 + (size_t)kb_of(i + 5) * 256);
+    wr[jn][1] = __builtin_nontemporal_load(w1 + (size_t)kb_of(i + 5) * 256);
+    // Barrier that orders LDS traffic only: __syncthreads() would also drain every global load in flight
+    // (loads and stores share one counter on this ISA), i.e. the whole prefetch pipeline, once per k block.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const bf16x8_t a0 = __builtin_bit_cast(bf16x8_t, wlds[j][0][t * 64 + lane]);
+      const bf16x8_t a1 = __builtin_bit_cast(bf16x8_t, wlds[j][1][t * 64 + lane]);
+#pragma unroll
+      for (int mb = 0; mb < MBW; ++mb) {
+        const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, xr[jx][mb][t]);
+        a[0][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bfrag, a[0][mb], 0, 0, 0);
+        a[1][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bfrag, a[1][mb], 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int mb = 0; mb < MBW; ++mb)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) xr[jx][mb][t] = xb[mb][(size_t)kb_of(i + XS) * 256 + t * 64];
+  };
+  auto quarter = [&](f32x16_t (&a)[2][MBW], int q) __attribute__((always_inline)) {
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int mb = 0; mb < MBW; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) a[nb][mb][r] = 0.f;
+    for (int i = q * kb_per_quarter; i < (q + 1) * kb_per_quarter; i += 4) {
+      iter(a, i, std::integral_constant<int, 0>{});
+      iter(a, i + 1, std::integral_constant<int, 1>{});
+      iter(a, i + 2, std::integral_constant<int, 2>{});
+      iter(a, i + 3, std::integral_constant<int, 3>{});
+    }
+  };
+  f32x16_t acc[2][MBW], other[2][MBW], s01[2][MBW];
+  quarter(s01, 0);
+  quarter(other, 1);
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+    for (int mb = 0; mb < MBW; ++mb) s01[nb][mb] += other[nb][mb];
+  quarter(other, 2);
+  quarter(acc, 3);
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+    for (int mb = 0; mb < MBW; ++mb) acc[nb][mb] = s01[nb][mb] + (other[nb][mb] + acc[nb][mb]);
+
+  if (!has_rows) return;
+  const int col = lane & 31, hb = lane >> 5;
+#pragma unroll
+  for (int mb = 0; mb < MBW; ++mb) {
+    const int m = (m_blk0 + mb) * 32 + col;
+    if (m >= M) continue;
+    float sum[2][16];
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sum[nb][r] = acc[nb][mb][r];
+    store_block<EPI>(sum, m, hb, rb0, rb1, blockIdx.y, M, N, out, se, blockIdx.x);
   }
 }
 
@@ -250,6 +473,52 @@ void launch_st(hipStream_t s, const void* X, const void* W, void* out, int M, in
   }
 }
 
+template <int MBW, int ST>
+void launch_cols_st(hipStream_t s, const void* X, const void* W, void* out, int M, int N, int K, int epi, bool allow_split,
+                    const SampleEpilogue& se) {
+  Plan p = make_plan(N, K, epi, allow_split);  // same K split as the other variants: bit-identical results
+  const int m_tiles = (M + 128 * MBW - 1) / (128 * MBW);
+  if (epi == kEpiSwiGLU) {
+    dim3 grid(N >> 5, 1, m_tiles);
+    gemm_bf16_cols_kernel<MBW, kEpiSwiGLU, ST><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
+  } else if (epi == kEpiSample) {
+    dim3 grid(N >> 6, 1, m_tiles);
+    gemm_bf16_cols_kernel<MBW, kEpiSample, ST><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
+  } else {
+    dim3 grid(N >> 6, p.splits, m_tiles);
+    gemm_bf16_cols_kernel<MBW, kEpiPartial, ST><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
+  }
+}
+
+template <int MBW, int XS>
+void launch_lds(hipStream_t s, const void* X, const void* W, void* out, int M, int N, int K, int epi, bool allow_split,
+                const SampleEpilogue& se) {
+  Plan p = make_plan(N, K, epi, allow_split);
+  const int m_tiles = (M + 128 * MBW - 1) / (128 * MBW);
+  if (epi == kEpiSwiGLU) {
+    dim3 grid(N >> 5, 1, m_tiles);
+    gemm_bf16_lds_kernel<MBW, kEpiSwiGLU, XS><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
+  } else if (epi == kEpiSample) {
+    dim3 grid(N >> 6, 1, m_tiles);
+    gemm_bf16_lds_kernel<MBW, kEpiSample, XS><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
+  } else {
+    dim3 grid(N >> 6, p.splits, m_tiles);
+    gemm_bf16_lds_kernel<MBW, kEpiPartial, XS><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
+  }
+}
+
+template <int MBW>
+void launch_cols(hipStream_t s, const void* X, const void* W, void* out, int M, int N, int K, int epi, bool allow_split,
+                 const SampleEpilogue& se) {
+  if (make_plan(N, K, epi, allow_split).kb_per_wave % 4 == 0) {  // weight tiles shared through LDS
+    launch_lds<MBW, MBW == 1 ? 4 : 2>(s, X, W, out, M, N, K, epi, allow_split, se);
+    return;
+  }
+  // two buffers in flight per wave when the quarter length allows it (it does for every 8B-shaped matrix)
+  if (make_plan(N, K, epi, allow_split).kb_per_wave % 2 == 0) launch_cols_st<MBW, 2>(s, X, W, out, M, N, K, epi, allow_split, se);
+  else launch_cols_st<MBW, 1>(s, X, W, out, M, N, K, epi, allow_split, se);
+}
+
 // Requirements (checked at model init): K % 256 == 0, N % 64 == 0 (N % 32 for SwiGLU).
 void launch_gemm_bf16(hipStream_t s, const void* X, const void* W, void* out, int M, int N, int K, int epi,
                       bool allow_split, const SampleEpilogue* se) {
@@ -258,7 +527,8 @@ void launch_gemm_bf16(hipStream_t s, const void* X, const void* W, void* out, in
   if (epi == kEpiSample) allow_split = false;
   if (M <= 32) launch_st<1>(s, X, W, out, M, N, K, epi, allow_split, 4, e);
   else if (M <= 64) launch_st<2>(s, X, W, out, M, N, K, epi, allow_split, 2, e);
-  else launch_st<4>(s, X, W, out, M, N, K, epi, allow_split, 2, e);
+  else if (M <= 128) launch_cols<1>(s, X, W, out, M, N, K, epi, allow_split, e);
+  else launch_cols<2>(s, X, W, out, M, N, K, epi, allow_split, e);
 }
 
 }  // namespace rl

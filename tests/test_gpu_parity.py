@@ -559,3 +559,17 @@ def test_rescored_rollout_gives_ratio_one(amd, kind):
         k += len(full[i]) - 1
     assert len({tuple(t.tolist()) for t in toks[:G]}) == G          # the samples of one prompt differ
     ro.close()
+
+
+def test_bf16_layer_bits_do_not_depend_on_batch_size_class(amd):
+    """The projection kernels change shape with the batch (32-, 64-, 128-, 256-column variants); a row's result must
+    keep its bits in all of them."""
+    base = [40, 513, 100, 257, 31]
+    outs = []
+    for n in (5, 40, 70, 140):
+        ctxs = base + [(11 * i) % 60 for i in range(n - 5)]
+        shape, wn, ro, ks, vs, x = _layer_case(amd, ctxs, seed=35)
+        outs.append(ro.rl_decode_hidden(list(range(n)), x.to(DEV)).cpu()[:5])
+        ro.close()
+    for o in outs[1:]:
+        assert torch.equal(o, outs[0])
