@@ -86,7 +86,7 @@ typedef struct {
   uint32_t dtype;    /* rl_dtype of weights and KV; RL_BF16 needs head_dim 128 and 8B-like multiples */
   uint32_t kv_block; /* tokens per page; must be 16 */
   uint32_t max_seqs; /* ids are in [0, max_seqs) */
-  uint32_t max_ctx;  /* longest prompt + response, multiple of kv_block */
+  uint32_t max_ctx;  /* longest prompt + response, multiple of kv_block; bf16: at most 65536 */
   uint32_t max_rows; /* most sequences per decode call (<= 256); prefill is chunked to this internally */
   uint64_t kv_pool_bytes;   /* size of rl_weights.kv_pool */
   uint64_t workspace_bytes; /* size of rl_weights.workspace, >= rl_query_workspace() */

@@ -69,6 +69,7 @@ rl_status check_config(const rl_model_config* c) {
     if (c->head_dim != 128 || c->n_q_heads / c->n_kv_heads > 8) return fail(RL_ERR_UNSUPPORTED, "bf16 needs head_dim 128 and group <= 8");
     if (c->hidden % 256 || qd % 256 || c->ffn % 256) return fail(RL_ERR_UNSUPPORTED, "bf16 needs hidden, n_q*head_dim, ffn multiples of 256");
     if (nqkv % 64 || c->hidden % 64 || c->ffn % 64 || c->vocab % 64) return fail(RL_ERR_UNSUPPORTED, "bf16 needs projection widths multiples of 64");
+    if (c->max_ctx > 65536) return fail(RL_ERR_UNSUPPORTED, "bf16 attention merges at most 256 segments: max_ctx <= 65536");
   }
   return RL_OK;
 }

@@ -4,6 +4,9 @@
 // that needs several pages first checks that all of them exist, so a failing call changes nothing.
 // Pages are reference counted: the samples of one prompt share the pages that the prompt fills completely
 // (they are never written again), and a page returns to the free list when its last holder is released.
+// Placement: a growing sequence first tries the page right after its last one (inside an aligned run of kRun
+// pages), and fresh requests are served run starts first, so that sequences growing in lock step still end up
+// with long physically contiguous stretches (fewer TLB entries and DRAM rows per streamed context).
 #pragma once
 #include <stdint.h>
 
@@ -19,19 +22,23 @@ struct PageGrant {
 class SeqTable {
  public:
   static constexpr int kBlock = 16;
+  static constexpr int kRun = 32;  // pages per placement run (512 tokens)
 
   SeqTable(int max_seqs, int max_ctx, int64_t n_pages)
       : max_seqs_(max_seqs), max_ctx_(max_ctx), max_blocks_(max_ctx / kBlock), n_pages_(n_pages),
-        len_(max_seqs, -1), pages_(max_seqs), ref_(n_pages, 0) {
-    free_.reserve(n_pages);
-    for (int64_t p = n_pages - 1; p >= 0; --p) free_.push_back((int32_t)p);  // page 0 is handed out first
+        len_(max_seqs, -1), pages_(max_seqs), ref_(n_pages, 0), is_free_(n_pages, 1), free_count_(n_pages) {
+    free_.reserve(2 * n_pages);
+    // popped from the back: run starts first (0, kRun, 2 kRun, ...), then the remaining pages in ascending order
+    for (int64_t p = n_pages - 1; p >= 0; --p)
+      if (p % kRun != 0) free_.push_back((int32_t)p);
+    for (int64_t p = (n_pages - 1) / kRun * kRun; p >= 0; p -= kRun) free_.push_back((int32_t)p);
   }
 
   int max_seqs() const { return max_seqs_; }
   int max_ctx() const { return max_ctx_; }
   int max_blocks() const { return max_blocks_; }
   int64_t n_pages() const { return n_pages_; }
-  int64_t free_pages() const { return (int64_t)free_.size(); }
+  int64_t free_pages() const { return free_count_; }
 
   bool valid_id(int32_t s) const { return s >= 0 && s < max_seqs_; }
   bool active(int32_t s) const { return valid_id(s) && len_[s] >= 0; }
@@ -56,8 +63,7 @@ class SeqTable {
   void reserve(int32_t s, int tokens, std::vector<PageGrant>* grants) {
     int need = blocks_for(tokens);
     while ((int)pages_[s].size() < need) {
-      int32_t p = free_.back();
-      free_.pop_back();
+      const int32_t p = take_page(pages_[s].empty() ? -1 : pages_[s].back());
       ref_[p] = 1;
       if (grants) grants->push_back(PageGrant{s, (int32_t)pages_[s].size(), p});
       pages_[s].push_back(p);
@@ -68,7 +74,7 @@ class SeqTable {
 
   void release(int32_t s) {
     for (auto it = pages_[s].rbegin(); it != pages_[s].rend(); ++it)
-      if (--ref_[*it] == 0) free_.push_back(*it);
+      if (--ref_[*it] == 0) give_page(*it);
     pages_[s].clear();
     len_[s] = -1;
   }
@@ -85,6 +91,8 @@ class SeqTable {
 
   // Deterministic shuffle of the free list (test aid: results must not depend on page placement).
   void shuffle_free(uint64_t seed) {
+    compact();
+    contiguous_ = false;  // scattered placement is the point of this aid
     uint64_t x = seed * 0x9E3779B97F4A7C15ull + 0x7F4A7C15ull;
     for (size_t i = free_.size(); i > 1; --i) {
       x ^= x << 13; x ^= x >> 7; x ^= x << 17;
@@ -93,12 +101,48 @@ class SeqTable {
   }
 
  private:
+  // The stack may hold entries of pages that were meanwhile taken by the "next page" rule (or twice after a
+  // take/give cycle); is_free_ is the truth and stale entries are skipped when popped.
+  int32_t take_page(int32_t last) {
+    if (contiguous_ && last >= 0 && (last + 1) % kRun != 0 && last + 1 < n_pages_ && is_free_[last + 1]) {
+      is_free_[last + 1] = 0;
+      --free_count_;
+      return last + 1;
+    }
+    for (;;) {
+      const int32_t p = free_.back();
+      free_.pop_back();
+      if (is_free_[p]) {
+        is_free_[p] = 0;
+        --free_count_;
+        return p;
+      }
+    }
+  }
+  void give_page(int32_t p) {
+    is_free_[p] = 1;
+    ++free_count_;
+    if ((int64_t)free_.size() >= 4 * n_pages_) compact();
+    free_.push_back(p);
+  }
+  void compact() {  // drop stale and duplicate entries, keeping the pop order of the survivors
+    std::vector<char> seen(n_pages_, 0);
+    std::vector<int32_t> keep;
+    keep.reserve(free_.size());
+    for (auto it = free_.rbegin(); it != free_.rend(); ++it)
+      if (is_free_[*it] && !seen[*it]) { seen[*it] = 1; keep.push_back(*it); }
+    free_.assign(keep.rbegin(), keep.rend());
+  }
+
   int max_seqs_, max_ctx_, max_blocks_;
   int64_t n_pages_;
   std::vector<int32_t> len_;  // -1 = inactive
   std::vector<std::vector<int32_t>> pages_;
   std::vector<int32_t> free_;
   std::vector<int32_t> ref_;  // holders per page
+  std::vector<char> is_free_;
+  int64_t free_count_;
+  bool contiguous_ = true;
 };
 
 }  // namespace rl

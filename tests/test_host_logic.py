@@ -130,3 +130,35 @@ def test_page_sharing_reference_counts(st):
     st.st_release(t, 2)
     assert st.st_free_pages(t) == 8 and st.st_refcount(t, pages[0]) == 0
     st.st_destroy(t)
+
+
+def test_lockstep_growth_keeps_sequences_physically_contiguous(st):
+    """Eight sequences growing one page at a time in turn: each still gets consecutive pages inside its own run,
+    the pool is used completely before anything fails, and frees/reuse keep the accounting exact."""
+    n_pages, n_seq = 8 * 32 + 5, 8
+    t = st.st_create(n_seq, 16 * 64, n_pages)
+    for s in range(n_seq):
+        st.st_activate(t, s)
+    for blk in range(1, 33):
+        for s in range(n_seq):
+            g = _reserve(st, t, s, 16 * blk)
+            assert len(g) == 1
+    for s in range(n_seq):
+        pages = [st.st_seq_page(t, s, i) for i in range(32)]
+        assert pages == list(range(pages[0], pages[0] + 32)) and pages[0] % 32 == 0
+    assert st.st_free_pages(t) == 5
+    got = _reserve(st, t, 0, 16 * 37)                        # the odd pages at the end are still usable
+    assert sorted(p for _, _, p in got) == list(range(256, 261)) and st.st_free_pages(t) == 0
+    st.st_release(t, 3)
+    assert st.st_free_pages(t) == 32
+    st.st_activate(t, 3)
+    g = _reserve(st, t, 3, 16 * 32)
+    assert len({p for _, _, p in g}) == 32 and st.st_free_pages(t) == 0
+    all_pages = [st.st_seq_page(t, s, i) for s in range(n_seq) for i in range(st.st_n_seq_pages(t, s))]
+    assert sorted(all_pages) == list(range(n_pages))         # nothing handed out twice
+    for _ in range(6):                                       # churn: stale stack entries never surface
+        st.st_release(t, 3)
+        st.st_activate(t, 3)
+        g = _reserve(st, t, 3, 16 * 32)
+        assert len({p for _, _, p in g}) == 32 and st.st_free_pages(t) == 0
+    st.st_destroy(t)
