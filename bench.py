@@ -64,6 +64,10 @@ def parse():
     ap.add_argument("--prefill", choices=["real", "import"], default="real",
                     help="import: fill the prompt KV with random N(0,1) pages instead of running the prefill "
                          "(for counter runs that should only see decode steps)")
+    ap.add_argument("--group", type=int, default=1,
+                    help="layer workload: every `group` consecutive sequences continue one cached context (shared pages)")
+    ap.add_argument("--no-share-attention", action="store_true",
+                    help="full workload: attention over the prompt pages once per row instead of once per set of samples")
     return ap.parse_args()
 
 
@@ -161,6 +165,8 @@ def main():
         ro = Rollout(shape, w, max_seqs=B, max_ctx=max_ctx, max_rows=256, kv_pages=pages)
         del w
         torch.cuda.empty_cache()
+        if args.no_share_attention:
+            ro.rl_debug_share_attention(False)
         prompts = ri.tokens((n_prompts, P), shape["vocab"], seed, 900)
         prompt_list = [prompts[i // G].tolist() for i in range(B)]
         seq_ids = list(range(B))
@@ -191,15 +197,19 @@ def main():
         ro = Rollout(shape, w, max_seqs=B, max_ctx=max_ctx, max_rows=B, kv_pages=pages)
         if not args.contiguous_pages:
             ro.rl_debug_shuffle_free_pages(seed)  # block tables are a random permutation of the pool
-        for b in range(B):
+        if args.no_share_attention:
+            ro.rl_debug_share_attention(False)
+        for b in range(0, B, args.group):
             k = ri.normal((ctx0, shape["n_kv"], shape["head_dim"]), 1.0, seed, 2000 + 2 * b, device=dev, dtype=torch.bfloat16)
             v = ri.normal((ctx0, shape["n_kv"], shape["head_dim"]), 1.0, seed, 2001 + 2 * b, device=dev, dtype=torch.bfloat16)
             ro.rl_seq_import_kv(b, [k], [v])
+            if args.group > 1:
+                ro.rl_seq_fork(b, list(range(b + 1, min(B, b + args.group))))
         seq_ids = list(range(B))
         x_in = ri.normal((B, shape["hidden"]), 1.0, seed, 1999, device=dev)
         x_out = torch.empty_like(x_in)
         prefill_s = None
-        workload = f"layer8b_1L_bf16_b{B}_ctx{ctx0}"
+        workload = f"layer8b_1L_bf16_b{B}_ctx{ctx0}" + (f"_group{args.group}" if args.group > 1 else "")
 
     from paper_2510_17891_amd.binding import _i32
     ids = _i32(seq_ids)

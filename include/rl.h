@@ -281,10 +281,29 @@ rl_status rl_hrd_objective(void* stream, int32_t n_prompts, int32_t group_size, 
 rl_status rl_pack_weight(void* stream, uint32_t dtype, const void* src, void* dst, int64_t rows, int64_t cols);
 
 /*
+ * Continue one sequence as several (the G outputs sampled for one prompt, Section 2.3, from a state that is
+ * already in the cache): each new_seq_ids[i] (host [n], inactive ids, n <= max_rows) becomes a sequence of the same
+ * length as src_seq whose KV is that of src_seq.  Pages that src_seq has filled completely are shared (never
+ * written again, returned to the pool with their last holder); a partial last page is copied, one new page per
+ * new sequence.  Later decode steps of the new sequences and of src_seq are independent and give, bit for bit,
+ * what sequences prefilled one by one give.  RL_ERR_BAD_SEQ, RL_ERR_KV_FULL, RL_ERR_INVALID_ARG leave the state
+ * untouched.  The page copy is enqueued on `stream`.
+ */
+rl_status rl_seq_fork(rl_model* m, void* stream, int32_t src_seq, int32_t n, const int32_t* new_seq_ids);
+
+/*
  * Test aid: permute the free-page list with a seeded shuffle, so that later allocations scatter over
  * the pool.  Results of every other call must not change.
  */
 rl_status rl_debug_shuffle_free_pages(rl_model* m, uint64_t seed);
+
+/*
+ * Test aid: switch off (on = 0) or on again (the default) the decode-step treatment of the samples of one
+ * prompt (Section 2.3): sequences made by rl_prefill_groups hold the prompt's full pages in common, and rows
+ * of such sequences that stand at the same position have the attention over those pages computed once per set
+ * of rows instead of once per row.  Results of every other call must not change by a single bit.
+ */
+rl_status rl_debug_share_attention(rl_model* m, int32_t on);
 
 /*
  * Per-kernel timing.  While enabled, every kernel launch of decode/prefill calls is bracketed by

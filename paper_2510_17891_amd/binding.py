@@ -21,7 +21,7 @@ EXPORTS = [
     "rl_kv_page_bytes", "rl_query_workspace", "rl_init_model", "rl_destroy_model", "rl_prefill", "rl_prefill_groups", "rl_score", "rl_hrd_objective",
     "rl_decode_step", "rl_free_seqs", "rl_last_error", "rl_kv_stats", "rl_seq_len", "rl_sample_logits",
     "rl_seq_import_kv", "rl_decode_hidden", "rl_set_capture", "rl_pack_weight",
-    "rl_debug_shuffle_free_pages", "rl_profile_enable", "rl_profile_read",
+    "rl_debug_shuffle_free_pages", "rl_debug_share_attention", "rl_seq_fork", "rl_profile_enable", "rl_profile_read",
 ]
 
 
@@ -95,6 +95,8 @@ def lib():
         L.rl_set_capture.argtypes = [C.c_void_p, C.c_void_p]
         L.rl_pack_weight.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64]
         L.rl_debug_shuffle_free_pages.argtypes = [C.c_void_p, C.c_uint64]
+        L.rl_debug_share_attention.argtypes = [C.c_void_p, C.c_int32]
+        L.rl_seq_fork.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, _i32p]
         L.rl_profile_enable.argtypes = [C.c_void_p, C.c_int32]
         L.rl_profile_read.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                       C.POINTER(C.c_int64), _i32p]
@@ -321,6 +323,12 @@ class Rollout:
 
     def rl_debug_shuffle_free_pages(self, seed):
         check(lib().rl_debug_shuffle_free_pages(self.h, seed))
+
+    def rl_seq_fork(self, src_seq, new_seq_ids):
+        check(lib().rl_seq_fork(self.h, _stream(), src_seq, len(new_seq_ids), _i32(new_seq_ids)))
+
+    def rl_debug_share_attention(self, on):
+        check(lib().rl_debug_share_attention(self.h, int(on)))
 
     def rl_profile_enable(self, on):
         check(lib().rl_profile_enable(self.h, 1 if on else 0))

@@ -21,6 +21,16 @@
 // Which path runs is a function of the row's context only, and nothing synchronises across blocks inside a
 // kernel (a device-scope fence is an L2 write-back on this multi-die part), so the bits of a row's result do not
 // depend on the batch.
+//
+// Shared prompt pages (the samples of one prompt, Section 2.3): rows of equal context length whose first pages are
+// the same physical pages form sets of up to 16 / group rows.  The same launch holds one more kind of block: a
+// "set" block computes up to four of the segments that lie inside the shared pages once for the whole set, the
+// set's (row, head) pairs side by side in the columns of the matrix operand.  The rows of a set start after those
+// segments; both kinds leave their partials in the workspace and the merge kernel combines them with the
+// arithmetic of the in-block merge.  A column of the matrix product does not depend on its neighbours and the
+// segment bounds are the same, so a row's bits equal those of the row computed alone.
+#include <algorithm>
+
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -59,47 +69,114 @@ __device__ __forceinline__ void load_pair(PagePair& pp, const u32x4_t* __restric
   }
 }
 
-__host__ __device__ inline int attn_num_segments(int ctx) { return 4 * ((ctx + 1023) / 1024); }
-
 __host__ __device__ inline int attn_num_splits(int n_seg) { return n_seg <= kLdsSegs ? 1 : (n_seg + kLdsSegs - 1) / kLdsSegs; }
 
-// grid: x = kv head, y = row, z = split.  block = four waves.
+// Flat merge of the (at most kLdsSegs) segments of one head: running maximum, weights exp(m_c - M), sums in index
+// order; the lane owns dims 2*lane, 2*lane+1.  seg_ptr(c) -> [O(128), max, sum] of segment c (LDS or workspace);
+// all loads are issued before the arithmetic.  Returns the two normalised outputs packed as bf16.
+template <typename F>
+__device__ __forceinline__ uint32_t merge_short(F seg_ptr, int n_seg, int n_it, int lane) {
+  float mx[kLdsSegs], lx[kLdsSegs];
+  float2 vx[kLdsSegs];
+#pragma unroll
+  for (int c = 0; c < kLdsSegs; ++c) {
+    mx[c] = -INFINITY;  // marks an absent or empty segment (nothing was written for it)
+    lx[c] = 0.f;
+    vx[c] = make_float2(0.f, 0.f);
+    if (c < n_seg && attn_seg_begin(c + 1, n_it, n_seg) != attn_seg_begin(c, n_it, n_seg)) {
+      const float* pc = seg_ptr(c);
+      mx[c] = pc[kD];
+      lx[c] = pc[kD + 1];
+      vx[c] = *(const float2*)(pc + 2 * lane);
+    }
+  }
+  float M = -INFINITY;
+#pragma unroll
+  for (int c = 0; c < kLdsSegs; ++c) M = fmaxf(M, mx[c]);
+  float o0 = 0.f, o1 = 0.f, den = 0.f;
+#pragma unroll
+  for (int c = 0; c < kLdsSegs; ++c) {
+    if (mx[c] != -INFINITY) {  // a segment with keys has a finite maximum
+      const float w = __expf(mx[c] - M);
+      den = fmaf(w, lx[c], den);
+      o0 = fmaf(w, vx[c].x, o0);
+      o1 = fmaf(w, vx[c].y, o1);
+    }
+  }
+  const float inv = 1.0f / den;
+  return pack2bf(o0 * inv, o1 * inv);
+}
+
+// grid: x = kv head, y = row, then set of rows (y >= n_rows), z = split.  block = four waves.
+// Row block: the row's segments from skip_segs[row] (or 0) on, up to kLdsSegs per block.  Set block: up to four of
+// the leading shared[y - n_rows].n_segs segments for all rows of the set.
 __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* __restrict__ q, const RowMeta* __restrict__ rows,
                                                                const int32_t* __restrict__ block_table, int max_blocks,
                                                                const u32x4_t* __restrict__ k_pool,
                                                                const u32x4_t* __restrict__ v_pool, float* __restrict__ part,
                                                                int max_segs, int n_q, int n_kv, float scale,
-                                                               uint16_t* __restrict__ o_out, int lds_part_offset) {
+                                                               uint16_t* __restrict__ o_out, int lds_part_offset,
+                                                               int n_rows, const int32_t* __restrict__ skip_segs,
+                                                               const AttnShared* __restrict__ shared) {
   extern __shared__ int32_t pages[];  // block-table slice of this row: ceil(ctx/16) entries (+1 pad), then partials
-  const int hk = blockIdx.x, r = blockIdx.y;
+  const int hk = blockIdx.x;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int group = n_q / n_kv;  // <= 8
+  const int j = lane & 15, g = lane >> 4;
+  const bool is_set = (int)blockIdx.y >= n_rows;  // block-uniform
+  // column j of the matrix operand: member j / group of the set (the row itself in a row block), head j % group
+  int r, n_members = 1, skip = 0, shared_segs = 0;
+  int col_row;
+  if (is_set) {
+    const AttnShared* sh = shared + (blockIdx.y - n_rows);
+    n_members = sh->n_rows;
+    shared_segs = sh->n_segs;
+    r = sh->rows[0];
+    const int mj = j / group;
+    col_row = sh->rows[mj < n_members ? mj : 0];
+  } else {
+    r = blockIdx.y;
+    col_row = r;
+    if (skip_segs) skip = skip_segs[r];
+  }
+  const bool col_valid = j < n_members * group;
+  const int col_head = hk * group + j % group;
   const RowMeta rm = rows[r];
   const int ctx = rm.pos + 1;  // keys 0..pos (the row's own key was appended before this kernel)
   const int n_seg = attn_num_segments(ctx);
-  if ((int)blockIdx.z >= attn_num_splits(n_seg)) return;  // block-uniform
-  const int group = n_q / n_kv;  // <= 8
-  const int j = lane & 15, g = lane >> 4;
+  const bool in_lds = !is_set && skip == 0 && n_seg <= kLdsSegs;  // merged by this block
+  // this block's segments [lo, hi)
+  int lo, hi;
+  if (is_set) {
+    lo = blockIdx.z * 4;
+    hi = min(lo + 4, shared_segs);
+  } else {
+    if ((int)blockIdx.z >= attn_num_splits(n_seg)) return;  // block-uniform
+    lo = max((int)blockIdx.z * kLdsSegs, skip);
+    hi = min((int)blockIdx.z * kLdsSegs + kLdsSegs, n_seg);
+  }
+  if (lo >= hi) return;  // block-uniform: nothing left for this block
   const int n_blk = (ctx + 15) >> 4;
   for (int i = threadIdx.x; i <= n_blk; i += 256)  // entry n_blk duplicates the last page (odd page counts)
     pages[i] = block_table[(size_t)rm.seq * max_blocks + (i < n_blk ? i : n_blk - 1)];
 
-  // ---- q operand: column j < group holds head hk*group + j; hi/lo bf16 split ---------------------
+  // ---- q operand: hi/lo bf16 split; columns beyond the set are zero -------------------------------
   u32x4_t q_hi[4], q_lo[4];
   {
-    const float* qh = q + ((size_t)r * n_q + (size_t)hk * group + (j < group ? j : 0)) * kD;
+    const float* qh = q + ((size_t)col_row * n_q + col_head) * kD;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      uint32_t hi[4], lo[4];
+      uint32_t hi16[4], lo16[4];
 #pragma unroll
       for (int e = 0; e < 8; e += 2) {
         float x0 = 0.f, x1 = 0.f;
-        if (j < group) { x0 = qh[32 * s + 8 * g + e]; x1 = qh[32 * s + 8 * g + e + 1]; }
+        if (col_valid) { x0 = qh[32 * s + 8 * g + e]; x1 = qh[32 * s + 8 * g + e + 1]; }
         const uint32_t h0 = f2bf(x0), h1 = f2bf(x1);
-        hi[e >> 1] = h0 | (h1 << 16);
-        lo[e >> 1] = pack2bf(x0 - bf2f(h0), x1 - bf2f(h1));
+        hi16[e >> 1] = h0 | (h1 << 16);
+        lo16[e >> 1] = pack2bf(x0 - bf2f(h0), x1 - bf2f(h1));
       }
-      q_hi[s] = (u32x4_t){hi[0], hi[1], hi[2], hi[3]};
-      q_lo[s] = (u32x4_t){lo[0], lo[1], lo[2], lo[3]};
+      q_hi[s] = (u32x4_t){hi16[0], hi16[1], hi16[2], hi16[3]};
+      q_lo[s] = (u32x4_t){lo16[0], lo16[1], lo16[2], lo16[3]};
     }
   }
   __syncthreads();
@@ -107,15 +184,12 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
   const u32x4_t* kb = k_pool + (size_t)hk * (2 * kPageElems / 8);
   const u32x4_t* vb = v_pool + (size_t)hk * (2 * kPageElems / 8);
   const int n_it = (ctx + 31) >> 5;  // 32-key steps
-  // Segment partials of short contexts (<= kLdsSegs segments) stay in LDS; longer ones go through the workspace.
-  const bool in_lds = n_seg <= kLdsSegs;
-  const int seg0 = blockIdx.z * kLdsSegs;                       // this block's segments: [seg0, seg0 + segs_here)
-  const int segs_here = min(kLdsSegs, n_seg - seg0);            // a multiple of 4
-  float* pbase = in_lds ? (float*)(pages + lds_part_offset) : part + (size_t)r * n_q * max_segs * kPartStride;
-  const int seg_stride = in_lds ? n_seg : max_segs;          // segments per head in the chosen buffer
-  const int head0 = in_lds ? 0 : hk * group;                 // LDS holds this block's heads only
-  const int seg_per_wave = segs_here >> 2;
-  auto seg_begin = [&](int sgm) { return (int)(((unsigned)sgm * (unsigned)n_it) / (unsigned)n_seg); };  // < 2^31: n_it < 2^16, sgm <= 288
+  // Segment partials of short contexts (<= kLdsSegs segments) stay in LDS; longer ones and the shared ones go
+  // through the workspace.  pcol: this lane's column, indexed by the absolute segment number.
+  float* const gcol = part + ((size_t)col_row * n_q + col_head) * max_segs * kPartStride;
+  float* const lds_part = (float*)(pages + lds_part_offset);
+  float* const pcol = in_lds ? lds_part + (size_t)j * n_seg * kPartStride : gcol;
+  auto seg_begin = [&](int sgm) { return attn_seg_begin(sgm, n_it, n_seg); };
 
   f32x4_t o_acc[8];
   float m_run, l_run;
@@ -126,8 +200,8 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
     l_run = 0.f;
   };
   reset();
-  int seg = seg0 + wave * seg_per_wave;
-  const int seg_end = seg + seg_per_wave;
+  int seg = lo + (wave * (hi - lo)) / 4;  // contiguous, balanced share of the block's segments
+  const int seg_end = lo + ((wave + 1) * (hi - lo)) / 4;
   const int it_begin = seg_begin(seg), it_end = seg_begin(seg_end);
   while (seg < seg_end && seg_begin(seg + 1) == seg_begin(seg)) ++seg;  // skip leading empty segments
   int boundary = seg < seg_end ? seg_begin(seg + 1) : it_end;
@@ -181,8 +255,8 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
     if (it + 1 == boundary) {  // wave-uniform
       float l_tot = l_run + __shfl_xor(l_run, 16, kWave);
       l_tot += __shfl_xor(l_tot, 32, kWave);
-      if (j < group) {
-        float* p = pbase + ((size_t)(head0 + j) * seg_stride + seg) * kPartStride;
+      if (col_valid) {
+        float* p = pcol + (size_t)seg * kPartStride;
 #pragma unroll
         for (int b = 0; b < 8; ++b) {
           p[16 * b + 4 * g] = o_acc[b][0]; p[16 * b + 4 * g + 1] = o_acc[b][1];
@@ -226,41 +300,36 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
     }
   }
 
-  if (!in_lds) return;  // long context: attn_merge_bf16_kernel combines the partials of all blocks
-  // ---- merge: wave w takes heads w, w+4 of the group; lane owns dims 2*lane, 2*lane+1 ------------
+  if (!in_lds) return;  // the merge kernel combines the partials in the workspace
+  // ---- merge: wave w takes heads w, w+4 of the group -------------------------------------------------
   __threadfence_block();
   __syncthreads();
   for (int hh = wave; hh < group; hh += 4) {
     const int head = hk * group + hh;
-    const float* p = pbase + (size_t)(head0 + hh) * seg_stride * kPartStride;
-    float M = -INFINITY;
-    for (int c = 0; c < n_seg; ++c)
-      if (seg_begin(c + 1) != seg_begin(c)) M = fmaxf(M, p[(size_t)c * kPartStride + kD]);
-    float o0 = 0.f, o1 = 0.f, den = 0.f;
-    for (int c = 0; c < n_seg; ++c) {
-      if (seg_begin(c + 1) == seg_begin(c)) continue;  // empty segment: nothing was written
-      const float* pc = p + (size_t)c * kPartStride;
-      const float w = __expf(pc[kD] - M);
-      den += w * pc[kD + 1];
-      o0 += w * pc[2 * lane];
-      o1 += w * pc[2 * lane + 1];
-    }
-    const float inv = 1.0f / den;
-    *(uint32_t*)(o_out + frag_offset(r, head * kD + 2 * lane, (n_q * kD) >> 6)) = pack2bf(o0 * inv, o1 * inv);
+    const float* p = lds_part + (size_t)hh * n_seg * kPartStride;
+    const uint32_t o2 = merge_short([&](int c) { return p + (size_t)c * kPartStride; }, n_seg, n_it, lane);
+    *(uint32_t*)(o_out + frag_offset(r, head * kD + 2 * lane, (n_q * kD) >> 6)) = o2;
   }
 }
 
-// Merge of the long-context rows (more than kLdsSegs segments, none of them empty): one wave per (row, head).
-// The segment weights exp(m_c - M) are formed by the lanes in parallel (max and denominator by the wave's fixed
+// Merge of the rows whose partials are in the workspace, one wave per (row, head): rows of a set (short contexts:
+// the arithmetic of the in-block merge) and long-context rows (more than kLdsSegs segments, none of them empty).
+// For the latter the segment weights exp(m_c - M) are formed by the lanes in parallel (max and denominator by the wave's fixed
 // butterfly), then the O partials are accumulated in index order, eight loads in flight at a time.  Rows with
 // short contexts were finished by the first kernel.
 __global__ __launch_bounds__(64) void attn_merge_bf16_kernel(const float* __restrict__ part, const RowMeta* __restrict__ rows,
-                                                             int max_segs, uint16_t* __restrict__ o_out, int n_q) {
+                                                             int max_segs, uint16_t* __restrict__ o_out, int n_q,
+                                                             const int32_t* __restrict__ skip_segs) {
   const int head = blockIdx.x, r = blockIdx.y, lane = threadIdx.x;
   const int ctx = rows[r].pos + 1;
   const int n_seg = attn_num_segments(ctx);
-  if (n_seg <= kLdsSegs) return;
   const float* p = part + ((size_t)r * n_q + head) * max_segs * kPartStride;
+  if (n_seg <= kLdsSegs) {
+    if (!skip_segs || skip_segs[r] == 0) return;  // finished by its own block
+    const uint32_t o2 = merge_short([&](int c) { return p + (size_t)c * kPartStride; }, n_seg, (ctx + 31) >> 5, lane);
+    *(uint32_t*)(o_out + frag_offset(r, head * kD + 2 * lane, (n_q * kD) >> 6)) = o2;
+    return;
+  }
   constexpr int kMaxPerLane = 4;  // up to 256 segments = contexts up to 65536
   float mc[kMaxPerLane], lc[kMaxPerLane];
   float M = -INFINITY;
@@ -309,17 +378,21 @@ int attn_bf16_max_segments(int max_ctx) { return attn_num_segments(max_ctx); }
 
 void launch_attn_decode_bf16(hipStream_t s, const Geometry& g, const float* q, const RowMeta* rows,
                              const int32_t* block_table, const void* k_pool_layer, const void* v_pool_layer,
-                             float* part, int max_segs_alloc, int max_ctx_in_batch, void* o_out, int M) {
+                             float* part, int max_segs_alloc, int max_ctx_in_batch, void* o_out, int M,
+                             const int32_t* skip_segs, const AttnShared* shared, int n_shared, int max_shared_segs) {
   const int n_seg_max = attn_num_segments(max_ctx_in_batch);
-  dim3 grid(g.n_kv, M, attn_num_splits(n_seg_max));
   const int page_ints = ((max_ctx_in_batch + 15) / 16 + 1 + 3) & ~3;  // keeps the partials 16-byte aligned
+  if (n_shared <= 0) { skip_segs = nullptr; n_shared = 0; max_shared_segs = 0; }
+  const int z = std::max(attn_num_splits(n_seg_max), (max_shared_segs + 3) / 4);
+  dim3 grid(g.n_kv, M + n_shared, z);
   const int segs = n_seg_max > kLdsSegs ? kLdsSegs : n_seg_max;
   const size_t lds = (size_t)page_ints * 4 + (size_t)(g.n_q / g.n_kv) * segs * kPartStride * sizeof(float);
   attn_decode_bf16_kernel<<<grid, 256, lds, s>>>(q, rows, block_table, g.max_blocks, (const u32x4_t*)k_pool_layer,
                                                  (const u32x4_t*)v_pool_layer, part, max_segs_alloc, g.n_q, g.n_kv,
-                                                 1.0f / sqrtf((float)g.head_dim), (uint16_t*)o_out, page_ints);
-  if (n_seg_max > kLdsSegs)
-    attn_merge_bf16_kernel<<<dim3(g.n_q, M), 64, 0, s>>>(part, rows, max_segs_alloc, (uint16_t*)o_out, g.n_q);
+                                                 1.0f / sqrtf((float)g.head_dim), (uint16_t*)o_out, page_ints, M, skip_segs,
+                                                 shared);
+  if (n_seg_max > kLdsSegs || n_shared > 0)
+    attn_merge_bf16_kernel<<<dim3(g.n_q, M), 64, 0, s>>>(part, rows, max_segs_alloc, (uint16_t*)o_out, g.n_q, skip_segs);
 }
 
 }  // namespace rl

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "attn_plan.h"
+
 namespace rl {
 
 // One batch row = one (sequence, position) pair being pushed through the decoder.
@@ -61,9 +63,13 @@ void launch_page_copy(hipStream_t s, void* kv_pool, size_t layer_bytes, size_t p
 // segments that depend on the context length only and merged in index order; writes bf16 fragment-major
 // [M x n_q*d].  part: fp32 [M][n_q][max_segs][d+2] with max_segs = attn_bf16_max_segments(max_ctx).
 int attn_bf16_max_segments(int max_ctx);
+// skip_segs (per row, may be null): leading segments of the row that a set in `shared` covers; every row with a
+// non-zero entry must belong to exactly one set with that n_segs.  max_shared_segs = largest n_segs.
 void launch_attn_decode_bf16(hipStream_t s, const Geometry& g, const float* q, const RowMeta* rows,
                              const int32_t* block_table, const void* k_pool_layer, const void* v_pool_layer,
-                             float* part, int max_segs_alloc, int max_ctx_in_batch, void* o_out, int M);
+                             float* part, int max_segs_alloc, int max_ctx_in_batch, void* o_out, int M,
+                             const int32_t* skip_segs = nullptr, const AttnShared* shared = nullptr, int n_shared = 0,
+                             int max_shared_segs = 0);
 // fp32, any head_dim <= 256: one wave per (row, q head), whole context, output fp32 row-major [M][n_q*d].
 void launch_attn_f32(hipStream_t s, const Geometry& g, const float* q, const RowMeta* rows,
                      const int32_t* block_table, const void* k_pool_layer, const void* v_pool_layer,

@@ -46,7 +46,7 @@ size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 struct Layout {
   size_t block_table, rope, ring, x, x_last, h, part, q, attn_part, o, a, logits, samp_part, forced_z, tmp_tok, tmp_lp, total;
-  size_t slot_bytes, slot_upd, slot_tok;
+  size_t slot_bytes, slot_upd, slot_tok, slot_skip, slot_sets;
   int max_segs, n_tiles;
 };
 
@@ -85,7 +85,9 @@ void compute_layout(const rl_model_config& c, Layout* L) {
   L->n_tiles = (int)((V + kSampleTile - 1) / kSampleTile);
   L->slot_upd = align_up(R * sizeof(RowMeta));
   L->slot_tok = L->slot_upd + align_up(R * 3 * sizeof(int32_t));
-  L->slot_bytes = L->slot_tok + align_up(R * sizeof(int32_t));
+  L->slot_skip = L->slot_tok + align_up(R * sizeof(int32_t));
+  L->slot_sets = L->slot_skip + align_up(R * sizeof(int32_t));
+  L->slot_bytes = L->slot_sets + align_up(R / 2 * sizeof(AttnShared) + sizeof(AttnShared));
   L->block_table = take((size_t)c.max_seqs * (c.max_ctx / 16) * 4);
   L->rope = take((size_t)c.max_ctx * (d / 2) * sizeof(float2));
   L->ring = take(kRing * L->slot_bytes);
@@ -142,6 +144,7 @@ struct rl_model {
   bool ring_used[kRing];
   int ring_next = 0;
   float* capture = nullptr;
+  bool share_attention = true;  // compute segments inside shared prompt pages once per set of rows
   // profiling
   bool prof_on = false;
   std::vector<hipEvent_t> ev_pool;
@@ -195,7 +198,14 @@ rl_status ring_acquire(rl_model* m, int* slot_out) {
 
 // Run all decoder layers on the M rows whose residual stream sits in ws.x.  Leaves the last down-projection's
 // split partials pending; returns their count so that the caller's final residual_norm adds them.
-int run_layers(rl_model* m, hipStream_t st, int M, const RowMeta* rows, int max_ctx_in_batch) {
+struct SharedAttn {  // device pointers into the metadata slot of the call (empty: every row on its own)
+  const int32_t* skip = nullptr;
+  const AttnShared* sets = nullptr;
+  int n_sets = 0, max_segs = 0;
+};
+
+int run_layers(rl_model* m, hipStream_t st, int M, const RowMeta* rows, int max_ctx_in_batch,
+               const SharedAttn& sa = SharedAttn()) {
   const Geometry& g = m->geo;
   const bool bf = g.dtype == kBF16;
   const int H = g.hidden, nqd = g.n_q * g.head_dim, nqkv = (g.n_q + 2 * g.n_kv) * g.head_dim, F = g.ffn;
@@ -222,7 +232,8 @@ int run_layers(rl_model* m, hipStream_t st, int M, const RowMeta* rows, int max_
                             rows, bt, m->k_pool(l), m->v_pool(l), q, M); }
     if (bf) {
       Timer t(m, st, K_ATTN);
-      launch_attn_decode_bf16(st, g, q, rows, bt, m->k_pool(l), m->v_pool(l), apart, m->lay.max_segs, max_ctx_in_batch, o, M);
+      launch_attn_decode_bf16(st, g, q, rows, bt, m->k_pool(l), m->v_pool(l), apart, m->lay.max_segs, max_ctx_in_batch, o, M,
+                              sa.skip, sa.sets, sa.n_sets, sa.max_segs);
     } else {
       Timer t(m, st, K_ATTN);
       launch_attn_f32(st, g, q, rows, bt, m->k_pool(l), m->v_pool(l), (float*)o, M);
@@ -300,7 +311,8 @@ rl_status admit_decode(rl_model* m, int32_t n, const int32_t* seq_ids, std::vect
 
 // Build and upload the rows (and page grants) of one decode call; returns device pointers into the slot.
 rl_status upload_decode_meta(rl_model* m, hipStream_t st, int32_t n, const int32_t* seq_ids,
-                             const std::vector<PageGrant>& grants, const RowMeta** rows_dev, int* max_ctx_out) {
+                             const std::vector<PageGrant>& grants, const RowMeta** rows_dev, int* max_ctx_out,
+                             SharedAttn* sa) {
   int slot;
   rl_status rs = ring_acquire(m, &slot);
   if (rs != RL_OK) return rs;
@@ -315,8 +327,36 @@ rl_status upload_decode_meta(rl_model* m, hipStream_t st, int32_t n, const int32
   }
   int32_t* hu = (int32_t*)(hs + m->lay.slot_upd);
   for (size_t i = 0; i < grants.size(); ++i) { hu[3 * i] = grants[i].seq; hu[3 * i + 1] = grants[i].block; hu[3 * i + 2] = grants[i].page; }
+  // rows of sequences that hold prompt pages in common and stand at the same position share those segments
+  *sa = SharedAttn();
+  AttnPlan plan;
+  if (m->geo.dtype == kBF16 && m->share_attention) {
+    std::vector<int64_t> fam(n);
+    std::vector<int32_t> fam_blocks(n), pos(n);
+    bool any = false;
+    for (int i = 0; i < n; ++i) {
+      fam[i] = m->table->prefix_id(seq_ids[i]);
+      fam_blocks[i] = m->table->prefix_blocks(seq_ids[i]);
+      pos[i] = hr[i].pos;
+      any |= fam[i] != 0;
+    }
+    if (any) {
+      const int group = m->geo.n_q / m->geo.n_kv;
+      plan_shared_attention(n, fam.data(), fam_blocks.data(), pos.data(), std::min(4, 16 / group), &plan);
+    }
+  }
   Timer t(m, st, K_META);
   HIP_TRY(hipMemcpyAsync(ds, hs, (size_t)n * sizeof(RowMeta), hipMemcpyHostToDevice, st));
+  if (!plan.sets.empty()) {
+    memcpy(hs + m->lay.slot_skip, plan.skip.data(), (size_t)n * 4);
+    memcpy(hs + m->lay.slot_sets, plan.sets.data(), plan.sets.size() * sizeof(AttnShared));
+    HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_skip, hs + m->lay.slot_skip, (size_t)n * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_sets, hs + m->lay.slot_sets, plan.sets.size() * sizeof(AttnShared), hipMemcpyHostToDevice, st));
+    sa->skip = (const int32_t*)(ds + m->lay.slot_skip);
+    sa->sets = (const AttnShared*)(ds + m->lay.slot_sets);
+    sa->n_sets = (int)plan.sets.size();
+    sa->max_segs = plan.max_shared_segs;
+  }
   if (!grants.empty()) {
     HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_upd, hu, grants.size() * 12, hipMemcpyHostToDevice, st));
     launch_table_update(st, m->wsp<int32_t>(m->lay.block_table), m->geo.max_blocks, (const int32_t*)(ds + m->lay.slot_upd), (int)grants.size());
@@ -462,6 +502,12 @@ rl_status rl_debug_shuffle_free_pages(rl_model* m, uint64_t seed) {
   return RL_OK;
 }
 
+rl_status rl_debug_share_attention(rl_model* m, int32_t on) {
+  if (!m) return fail(RL_ERR_INVALID_ARG, "model is NULL");
+  m->share_attention = on != 0;
+  return RL_OK;
+}
+
 rl_status rl_set_capture(rl_model* m, float* buf) {
   if (!m) return fail(RL_ERR_INVALID_ARG, "model is NULL");
   m->capture = buf;
@@ -479,12 +525,13 @@ rl_status rl_decode_step(rl_model* m, void* stream, int32_t n, const int32_t* se
   if (rs != RL_OK) return rs;
   const RowMeta* rows;
   int max_ctx_in_batch;
-  rs = upload_decode_meta(m, st, n, seq_ids, grants, &rows, &max_ctx_in_batch);
+  SharedAttn sa;
+  rs = upload_decode_meta(m, st, n, seq_ids, grants, &rows, &max_ctx_in_batch, &sa);
   if (rs != RL_OK) return rs;
   float* x = m->wsp<float>(m->lay.x);
   { Timer t(m, st, K_EMBED);
     launch_embed(st, m->geo.dtype, m->embed, in_tokens, x, n, m->geo.hidden, m->geo.vocab); }
-  int pend = run_layers(m, st, n, rows, max_ctx_in_batch);
+  int pend = run_layers(m, st, n, rows, max_ctx_in_batch, sa);
   run_head(m, st, n, x, pend, rows, 1, forced_next, sp, out_tokens, out_logprobs, debug_logits);
   HIP_TRY(hipGetLastError());
   for (int i = 0; i < n; ++i) m->table->set_len(seq_ids[i], m->table->len(seq_ids[i]) + 1);
@@ -500,18 +547,56 @@ rl_status rl_decode_hidden(rl_model* m, void* stream, int32_t n, const int32_t* 
   if (rs != RL_OK) return rs;
   const RowMeta* rows;
   int max_ctx_in_batch;
-  rs = upload_decode_meta(m, st, n, seq_ids, grants, &rows, &max_ctx_in_batch);
+  SharedAttn sa;
+  rs = upload_decode_meta(m, st, n, seq_ids, grants, &rows, &max_ctx_in_batch, &sa);
   if (rs != RL_OK) return rs;
   float* x = m->wsp<float>(m->lay.x);
   const size_t bytes = (size_t)n * m->geo.hidden * 4;
   HIP_TRY(hipMemcpyAsync(x, hidden_in, bytes, hipMemcpyDeviceToDevice, st));
-  int pend = run_layers(m, st, n, rows, max_ctx_in_batch);
+  int pend = run_layers(m, st, n, rows, max_ctx_in_batch, sa);
   float* cap = m->capture ? m->capture + (size_t)m->geo.n_layers * m->cfg.max_rows * m->geo.hidden : nullptr;
   { Timer t(m, st, K_NORM);
     launch_residual_norm(st, m->geo.dtype, x, m->wsp<float>(m->lay.part), pend, nullptr, nullptr, cap, n, m->geo.hidden, m->geo.rms_eps); }
   HIP_TRY(hipMemcpyAsync(hidden_out, x, bytes, hipMemcpyDeviceToDevice, st));
   HIP_TRY(hipGetLastError());
   for (int i = 0; i < n; ++i) m->table->set_len(seq_ids[i], m->table->len(seq_ids[i]) + 1);
+  return RL_OK;
+}
+
+// Make each `dst` (valid id, inactive) a continuation of `src` (active) at `len` tokens: the pages that `len`
+// tokens fill completely are shared, a partial last page is copied into a page of dst's own.  The caller has
+// checked ids and free pages (one per dst when len % 16 != 0) and sets the lengths.  At most max_rows forks.
+struct Fork { int32_t src, dst, len; };
+static rl_status fork_seqs(rl_model* m, hipStream_t st, const std::vector<Fork>& forks) {
+  SeqTable& T = *m->table;
+  int32_t* bt = m->wsp<int32_t>(m->lay.block_table);
+  std::vector<int32_t> pairs;  // (src page, dst page)
+  for (const Fork& f : forks) {
+    const int full = f.len / SeqTable::kBlock;
+    T.activate(f.dst);
+    T.share_prefix(f.dst, f.src, full);
+    if (f.len % SeqTable::kBlock) {
+      T.reserve(f.dst, f.len, nullptr);
+      pairs.push_back(T.pages(f.src)[full]);
+      pairs.push_back(T.pages(f.dst)[full]);
+    }
+    // pageable source: the runtime stages it before returning, so the vector may change afterwards
+    if (!T.pages(f.dst).empty())
+      HIP_TRY(hipMemcpyAsync(bt + (size_t)f.dst * m->geo.max_blocks, T.pages(f.dst).data(), T.pages(f.dst).size() * 4, hipMemcpyHostToDevice, st));
+  }
+  if (!pairs.empty()) {
+    int slot;
+    rl_status rs = ring_acquire(m, &slot);
+    if (rs != RL_OK) return rs;
+    char* hs = m->host_ring + (size_t)slot * m->lay.slot_bytes;
+    char* ds = m->ws + m->lay.ring + (size_t)slot * m->lay.slot_bytes;
+    memcpy(hs + m->lay.slot_upd, pairs.data(), pairs.size() * 4);  // at most 2 * max_rows ints
+    HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_upd, hs + m->lay.slot_upd, pairs.size() * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipEventRecord(m->ring_ev[slot], st));
+    m->ring_used[slot] = true;
+    launch_page_copy(st, m->kv_pool, m->layer_kv_bytes, (size_t)m->geo.n_kv * 2 * m->kv_block_bytes, m->geo.n_layers,
+                     (const int32_t*)(ds + m->lay.slot_upd), (int)(pairs.size() / 2));
+  }
   return RL_OK;
 }
 
@@ -603,36 +688,11 @@ static rl_status prefill_impl(rl_model* m, hipStream_t st, int32_t n_prompts, in
 
   // ---- the other members of each group: shared full pages, private copy of the partial page ---------------
   if (group > 1) {
-    std::vector<int32_t> pairs;  // (src page, dst page)
-    for (int i = 0; i < n_prompts; ++i) {
-      const int32_t lead = seq_ids[i * group];
-      const int full = prompt_lens[i] / SeqTable::kBlock;
-      const bool partial = prompt_lens[i] % SeqTable::kBlock;
-      for (int j = 1; j < group; ++j) {
-        const int32_t s = seq_ids[i * group + j];
-        T.activate(s);
-        T.share_prefix(s, lead, full);
-        if (partial) {
-          T.reserve(s, prompt_lens[i], nullptr);
-          pairs.push_back(T.pages(lead)[full]);
-          pairs.push_back(T.pages(s)[full]);
-        }
-        HIP_TRY(hipMemcpyAsync(bt + (size_t)s * m->geo.max_blocks, T.pages(s).data(), T.pages(s).size() * 4, hipMemcpyHostToDevice, st));
-      }
-    }
-    if (!pairs.empty()) {
-      int slot;
-      rl_status rs = ring_acquire(m, &slot);
-      if (rs != RL_OK) return rs;
-      char* hs = m->host_ring + (size_t)slot * m->lay.slot_bytes;
-      char* ds = m->ws + m->lay.ring + (size_t)slot * m->lay.slot_bytes;
-      memcpy(hs + m->lay.slot_upd, pairs.data(), pairs.size() * 4);  // at most 2 * max_rows ints
-      HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_upd, hs + m->lay.slot_upd, pairs.size() * 4, hipMemcpyHostToDevice, st));
-      HIP_TRY(hipEventRecord(m->ring_ev[slot], st));
-      m->ring_used[slot] = true;
-      launch_page_copy(st, m->kv_pool, m->layer_kv_bytes, (size_t)m->geo.n_kv * 2 * m->kv_block_bytes, m->geo.n_layers,
-                       (const int32_t*)(ds + m->lay.slot_upd), (int)(pairs.size() / 2));
-    }
+    std::vector<Fork> forks;
+    for (int i = 0; i < n_prompts; ++i)
+      for (int j = 1; j < group; ++j) forks.push_back({seq_ids[i * group], seq_ids[i * group + j], prompt_lens[i]});
+    rl_status rs = fork_seqs(m, st, forks);
+    if (rs != RL_OK) return rs;
   }
 
   // logits at the last prompt position of every sequence; the sampled token sits at position prompt_len
@@ -671,6 +731,31 @@ rl_status rl_prefill_groups(rl_model* m, void* stream, int32_t n_prompts, int32_
     return fail(RL_ERR_INVALID_ARG, "NULL argument");
   return prefill_impl(m, (hipStream_t)stream, n_prompts, group_size, seq_ids, prompt_tokens, prompt_lens, sp, out_tokens,
                       out_logprobs);
+}
+
+rl_status rl_seq_fork(rl_model* m, void* stream, int32_t src_seq, int32_t n, const int32_t* new_seq_ids) {
+  if (!m || !new_seq_ids) return fail(RL_ERR_INVALID_ARG, "NULL argument");
+  if (n < 1 || n > (int32_t)m->cfg.max_rows) return fail(RL_ERR_INVALID_ARG, "n %d outside [1, max_rows=%u]", n, m->cfg.max_rows);
+  SeqTable& T = *m->table;
+  if (!T.active(src_seq)) return fail(RL_ERR_BAD_SEQ, "sequence %d is not active", src_seq);
+  std::vector<char> seen(T.max_seqs(), 0);
+  for (int i = 0; i < n; ++i) {
+    const int32_t s = new_seq_ids[i];
+    if (!T.valid_id(s)) return fail(RL_ERR_BAD_SEQ, "sequence id %d out of range", s);
+    if (T.active(s)) return fail(RL_ERR_BAD_SEQ, "sequence %d is already active", s);
+    if (seen[s]) return fail(RL_ERR_INVALID_ARG, "sequence %d appears twice", s);
+    seen[s] = 1;
+  }
+  const int32_t len = T.len(src_seq);
+  const int64_t need = (len % SeqTable::kBlock) ? n : 0;
+  if (need > T.free_pages()) return fail(RL_ERR_KV_FULL, "need %lld pages, %lld free", (long long)need, (long long)T.free_pages());
+  std::vector<Fork> forks;
+  for (int i = 0; i < n; ++i) forks.push_back({src_seq, new_seq_ids[i], len});
+  rl_status rs = fork_seqs(m, (hipStream_t)stream, forks);
+  if (rs != RL_OK) return rs;
+  HIP_TRY(hipGetLastError());
+  for (int i = 0; i < n; ++i) T.set_len(new_seq_ids[i], len);
+  return RL_OK;
 }
 
 rl_status rl_score(rl_model* m, void* stream, int32_t n, const int32_t* seq_ids, const int32_t* tokens,

@@ -26,7 +26,8 @@ class SeqTable {
 
   SeqTable(int max_seqs, int max_ctx, int64_t n_pages)
       : max_seqs_(max_seqs), max_ctx_(max_ctx), max_blocks_(max_ctx / kBlock), n_pages_(n_pages),
-        len_(max_seqs, -1), pages_(max_seqs), ref_(n_pages, 0), is_free_(n_pages, 1), free_count_(n_pages) {
+        len_(max_seqs, -1), pages_(max_seqs), prefix_id_(max_seqs, 0), prefix_blocks_(max_seqs, 0),
+        ref_(n_pages, 0), is_free_(n_pages, 1), free_count_(n_pages) {
     free_.reserve(2 * n_pages);
     // popped from the back: run starts first (0, kRun, 2 kRun, ...), then the remaining pages in ascending order
     for (int64_t p = n_pages - 1; p >= 0; --p)
@@ -57,6 +58,8 @@ class SeqTable {
   void activate(int32_t s) {
     len_[s] = 0;
     pages_[s].clear();
+    prefix_id_[s] = 0;
+    prefix_blocks_[s] = 0;
   }
 
   // Grow the page list of `s` to cover `tokens` tokens; the caller has checked free_pages().
@@ -80,13 +83,24 @@ class SeqTable {
   }
 
   // Make the (freshly activated, page-less) sequence `dst` share the first `n_blocks` pages of `src`.
+  // Both then carry the same family id: sequences with equal ids hold the same first prefix_blocks() pages.
   void share_prefix(int32_t dst, int32_t src, int n_blocks) {
     for (int b = 0; b < n_blocks; ++b) {
       const int32_t p = pages_[src][b];
       ++ref_[p];
       pages_[dst].push_back(p);
     }
+    if (n_blocks > 0) {
+      if (prefix_id_[src] == 0 || prefix_blocks_[src] != n_blocks) {
+        prefix_id_[src] = ++next_prefix_id_;
+        prefix_blocks_[src] = n_blocks;
+      }
+      prefix_id_[dst] = prefix_id_[src];
+      prefix_blocks_[dst] = n_blocks;
+    }
   }
+  int64_t prefix_id(int32_t s) const { return prefix_id_[s]; }
+  int32_t prefix_blocks(int32_t s) const { return prefix_blocks_[s]; }
   int32_t refcount(int32_t page) const { return ref_[page]; }
 
   // Deterministic shuffle of the free list (test aid: results must not depend on page placement).
@@ -138,6 +152,9 @@ class SeqTable {
   int64_t n_pages_;
   std::vector<int32_t> len_;  // -1 = inactive
   std::vector<std::vector<int32_t>> pages_;
+  std::vector<int64_t> prefix_id_;  // 0 = shares nothing
+  std::vector<int32_t> prefix_blocks_;
+  int64_t next_prefix_id_ = 0;
   std::vector<int32_t> free_;
   std::vector<int32_t> ref_;  // holders per page
   std::vector<char> is_free_;

@@ -1,5 +1,6 @@
 // C wrappers around the host sequence table so that its logic can be exercised without a GPU.
 // Built with g++ into its own small library by the CPU tests; not part of the product library.
+#include "attn_plan.h"
 #include "seq_table.h"
 
 extern "C" {
@@ -29,6 +30,28 @@ int st_reserve(void* t, int s, int tokens, int* grants_out, int max_grants) {
     ++n;
   }
   return (int)g.size();
+}
+
+long long st_prefix_id(void* t, int s) { return ((rl::SeqTable*)t)->prefix_id(s); }
+int st_prefix_blocks(void* t, int s) { return ((rl::SeqTable*)t)->prefix_blocks(s); }
+int st_attn_num_segments(int ctx) { return rl::attn_num_segments(ctx); }
+int st_attn_seg_begin(int sgm, int ctx) { return rl::attn_seg_begin(sgm, (ctx + 31) >> 5, rl::attn_num_segments(ctx)); }
+// plan of one decode batch: skip_out[n]; sets_out gets (rows[4], n_rows, n_segs) per set; returns the number of sets
+int st_plan_shared(void* t, int n, const int* seq_ids, const int* pos, int rows_per_set, int* skip_out, int* sets_out,
+                   int max_sets) {
+  auto* T = (rl::SeqTable*)t;
+  std::vector<int64_t> fam(n);
+  std::vector<int32_t> blocks(n);
+  for (int i = 0; i < n; ++i) { fam[i] = T->prefix_id(seq_ids[i]); blocks[i] = T->prefix_blocks(seq_ids[i]); }
+  rl::AttnPlan plan;
+  rl::plan_shared_attention(n, fam.data(), blocks.data(), pos, rows_per_set, &plan);
+  for (int i = 0; i < n; ++i) skip_out[i] = plan.skip[i];
+  for (size_t k = 0; k < plan.sets.size() && (int)k < max_sets; ++k) {
+    for (int e = 0; e < 4; ++e) sets_out[6 * k + e] = plan.sets[k].rows[e];
+    sets_out[6 * k + 4] = plan.sets[k].n_rows;
+    sets_out[6 * k + 5] = plan.sets[k].n_segs;
+  }
+  return (int)plan.sets.size();
 }
 
 }  // extern "C"

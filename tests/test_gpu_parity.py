@@ -184,6 +184,46 @@ def test_bf16_layer_decode_matches_oracle(amd, ctxs):
     ro.close()
 
 
+def test_bf16_layer_forked_rows_share_prompt_attention_and_match_oracle(amd):
+    """8B-dimension layer: three cached contexts are each continued as six sequences (shared full pages, copied
+    partial page).  The step computes the attention over the common pages once per set of rows; every row still
+    matches the oracle run on that row alone, and the bits equal those with the sharing switched off."""
+    ctxs, G = [2100, 5000, 700], 6
+    shape = ri.SHAPES["layer8b"]
+    w, wn = make_both(shape, 34)
+    wd = to_device(w)
+    B = len(ctxs) * G
+    pages = sum((c + 15) // 16 for c in ctxs) + 2 * B + 4
+    nkv, d, H = shape["n_kv"], shape["head_dim"], shape["hidden"]
+    ks = [ri.normal((c, nkv, d), 1.0, 34, 2000 + 2 * b, dtype=torch.bfloat16) for b, c in enumerate(ctxs)]
+    vs = [ri.normal((c, nkv, d), 1.0, 34, 2001 + 2 * b, dtype=torch.bfloat16) for b, c in enumerate(ctxs)]
+    x = ri.normal((B, H), 1.0, 34, 1999).to(torch.bfloat16).float()
+    outs = []
+    for share in (True, False):
+        ro = amd.Rollout(shape, wd, max_seqs=B, max_ctx=5040, max_rows=B, kv_pages=pages)
+        ro.rl_debug_shuffle_free_pages(5)
+        ro.rl_debug_share_attention(share)
+        for b in range(len(ctxs)):
+            ro.rl_seq_import_kv(b * G, [ks[b].to(DEV)], [vs[b].to(DEV)])
+            ro.rl_seq_fork(b * G, [b * G + j for j in range(1, G)])
+        assert ro.rl_kv_stats()[0] == pages - sum((c + 15) // 16 for c in ctxs) - (G - 1) * sum(1 for c in ctxs if c % 16)
+        order = ri.permutation(B, 34, 77).tolist()          # members of a prompt need not be adjacent rows
+        out = torch.empty(B, H)
+        out[order] = ro.rl_decode_hidden(order, x[order].to(DEV)).cpu()
+        nxt = ro.rl_decode_hidden(order, x[order].to(DEV)).cpu()     # a second step: own keys differ per member now
+        torch.cuda.synchronize()
+        outs.append((out, nxt))
+        assert all(ro.rl_seq_len(i) == ctxs[i // G] + 2 for i in range(B))
+        ro.close()
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    out = outs[0][0].numpy()
+    for i in range(B):
+        b = i // G
+        ref = _oracle_layer_row(shape, wn, ks[b], vs[b], x[i], ctxs[b])
+        err = rel_inf(out[i] - x[i].numpy(), ref - x[i].numpy())
+        assert err < 3e-2, (i, err)
+
+
 def test_bf16_layer_batch_and_page_placement_invariance(amd):
     ctxs = [40, 513, 100, 257, 31]
     shape, wn, ro, ks, vs, x = _layer_case(amd, ctxs, seed=32)
@@ -498,6 +538,61 @@ def test_prefill_groups_equals_independent_prefill(amd, kind):
     assert rb.rl_kv_stats() == (80, 80) and free_mid < 80
     ra.close()
     rb.close()
+
+
+def test_shared_prompt_attention_is_bit_identical_to_per_row(amd):
+    """Samples of one prompt at the same position have the attention over the common prompt pages computed once
+    per set of rows.  Logits, tokens and log-probs equal, bit for bit, those with the sharing switched off and
+    those of sequences prefilled one by one (which share nothing), for a prompt inside one block's segments, one
+    beyond 4096 keys (partials through the workspace) and a short one; with sets of four and of two, a left-over
+    row, members that retire, and members that fall out of step."""
+    shape = dict(ri.SHAPES["layer8b"], n_layers=2, hidden=512, n_q=8, n_kv=2, ffn=768, vocab=8192)
+    w, _ = make_both(shape, 63, std=0.05)
+    wd = to_device(w)
+    G, seed = 7, 5
+    lens = [1100, 4500, 300]
+    prompts = [ri.tokens((n,), shape["vocab"], 63, 940 + i).tolist() for i, n in enumerate(lens)]
+    ids = list(range(len(lens) * G))
+    kw = dict(max_seqs=24, max_ctx=4608, max_rows=64, kv_pages=2700)
+    ra = amd.Rollout(shape, wd, **kw)       # shared pages, shared attention
+    rb = amd.Rollout(shape, wd, **kw)       # shared pages, every row on its own
+    rc = amd.Rollout(shape, wd, **kw)       # nothing shared
+    rb.rl_debug_share_attention(False)
+    ta, la = ra.rl_prefill_groups(ids, G, prompts, 1.0, seed)
+    tb, lb = rb.rl_prefill_groups(ids, G, prompts, 1.0, seed)
+    tc, lc = rc.rl_prefill(ids, [prompts[i // G] for i in ids], 1.0, seed)
+    torch.cuda.synchronize()
+    assert torch.equal(ta, tb) and torch.equal(la, lb) and torch.equal(ta, tc) and torch.equal(la, lc)
+    V = shape["vocab"]
+
+    def step(active, tok):
+        zs = [torch.empty(len(active), V, device=DEV) for _ in range(3)]
+        outs = [r.rl_decode_step(active, tok, 1.0, seed, debug_logits=z) for r, z in zip((ra, rb, rc), zs)]
+        torch.cuda.synchronize()
+        for z, (t_, l_) in zip(zs[1:], outs[1:]):
+            assert torch.equal(zs[0], z) and torch.equal(outs[0][0], t_) and torch.equal(outs[0][1], l_)
+        return outs[0][0]
+
+    tok = {i: int(ta[k]) for k, i in enumerate(ids)}
+    active = list(ids)
+    for it in range(24):
+        if it == 6:                              # one member of each prompt retires: sets of four and two remain
+            gone = [0, G + 3, 2 * G + 6]
+            for r in (ra, rb, rc):
+                r.rl_free_seqs(gone)
+            active = [i for i in active if i not in gone]
+        if it == 12:                             # two members of the first prompt fall one step behind
+            behind = [1, 2]
+            sub = [i for i in active if i not in behind]
+            out = step(sub, torch.tensor([tok[i] for i in sub], dtype=torch.int32, device=DEV))
+            for k, i in enumerate(sub):
+                tok[i] = int(out[k])
+        order = active if it % 2 == 0 else active[::-1]          # row order inside the batch is free
+        out = step(order, torch.tensor([tok[i] for i in order], dtype=torch.int32, device=DEV))
+        for k, i in enumerate(order):
+            tok[i] = int(out[k])
+    for r in (ra, rb, rc):
+        r.close()
 
 
 # ------------------------------------------------------------------------------ teacher-forced scoring call

@@ -64,6 +64,11 @@ def st(tmp_path_factory):
     L.st_refcount.argtypes = [C.c_void_p, C.c_int]
     L.st_shuffle.argtypes = [C.c_void_p, C.c_ulonglong]
     L.st_reserve.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_int), C.c_int]
+    L.st_prefix_id.restype = C.c_longlong
+    L.st_prefix_id.argtypes = [C.c_void_p, C.c_int]
+    L.st_prefix_blocks.argtypes = [C.c_void_p, C.c_int]
+    L.st_plan_shared.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int), C.c_int,
+                                 C.POINTER(C.c_int), C.POINTER(C.c_int), C.c_int]
     return L
 
 
@@ -161,4 +166,66 @@ def test_lockstep_growth_keeps_sequences_physically_contiguous(st):
         st.st_activate(t, 3)
         g = _reserve(st, t, 3, 16 * 32)
         assert len({p for _, _, p in g}) == 32 and st.st_free_pages(t) == 0
+    st.st_destroy(t)
+
+
+def _plan(L, t, seqs, pos, rows_per_set):
+    n = len(seqs)
+    skip = (C.c_int * n)()
+    sets = (C.c_int * (6 * n))()
+    k = L.st_plan_shared(t, n, (C.c_int * n)(*seqs), (C.c_int * n)(*pos), rows_per_set, skip, sets, n)
+    return list(skip), [(list(sets[6 * i:6 * i + sets[6 * i + 4]]), sets[6 * i + 5]) for i in range(k)]
+
+
+def test_attention_segments_partition_every_context(st):
+    """The segment bounds are monotone, start at 0, end at the number of 32-key steps, and there are
+    4*ceil(ctx/1024) of them: every key of a context belongs to exactly one segment."""
+    for ctx in list(range(1, 200)) + [1023, 1024, 1025, 4095, 4096, 4097, 16383, 16384, 65536]:
+        n = st.st_attn_num_segments(ctx)
+        assert n == 4 * ((ctx + 1023) // 1024)
+        b = [st.st_attn_seg_begin(c, ctx) for c in range(n + 1)]
+        assert b[0] == 0 and b[-1] == (ctx + 31) // 32 and all(x <= y for x, y in zip(b, b[1:]))
+
+
+def test_shared_attention_plan(st):
+    """Sets hold rows of one sharing family at one position; the covered segments end inside the common pages;
+    a left-over single row, rows at other positions and sequences that share nothing stay on their own."""
+    t = st.st_create(16, 4096, 2000)
+    for s in range(12):
+        st.st_activate(t, s)
+    _reserve(st, t, 0, 1100)                       # leader of family A: 68 full pages
+    for s in range(1, 7):
+        st.st_share_prefix(t, s, 0, 68)
+    _reserve(st, t, 7, 300)                        # family B: 18 full pages
+    st.st_share_prefix(t, 8, 7, 18)
+    _reserve(st, t, 9, 1100)                       # shares nothing
+    assert st.st_prefix_id(t, 0) == st.st_prefix_id(t, 6) != 0 and st.st_prefix_blocks(t, 3) == 68
+    assert st.st_prefix_id(t, 7) == st.st_prefix_id(t, 8) not in (0, st.st_prefix_id(t, 0))
+    assert st.st_prefix_id(t, 9) == 0
+
+    def covered(ctx, shared_keys):                # brute force over the printed bounds
+        n = st.st_attn_num_segments(ctx)
+        k = 0
+        while k < n and st.st_attn_seg_begin(k + 1, ctx) * 32 <= shared_keys:
+            k += 1
+        return k
+
+    seqs = [0, 9, 1, 2, 7, 3, 8, 4, 5, 6]
+    pos = [1150, 1150, 1150, 1150, 320, 1150, 320, 1151, 1150, 1150]
+    skip, sets = _plan(st, t, seqs, pos, 4)
+    sA, sB = covered(1151, 68 * 16), covered(321, 18 * 16)
+    assert sA >= 6 and sB >= 2
+    # family A at position 1150: rows 0,2,3,5,8,9 -> a set of four and a set of two; row 7 stands elsewhere
+    assert sets == [([0, 2, 3, 5], sA), ([8, 9], sA), ([4, 6], sB)]
+    assert skip == [sA, 0, sA, sA, sB, sA, sB, 0, sA, sA]
+    # five rows with sets of four: the fifth computes everything itself
+    skip, sets = _plan(st, t, [0, 1, 2, 3, 4], [1150] * 5, 4)
+    assert sets == [([0, 1, 2, 3], sA)] and skip == [sA] * 4 + [0]
+    # right after the prompt the last shared page may hold the row's own position: never shared
+    skip, sets = _plan(st, t, [0, 1], [1088, 1088], 2)
+    assert sets and sets[0][1] == covered(1089, 1088) and st.st_attn_seg_begin(sets[0][1], 1089) * 32 <= 1088
+    # a sequence that is freed and reused forgets its family
+    st.st_release(t, 8)
+    st.st_activate(t, 8)
+    assert st.st_prefix_id(t, 8) == 0
     st.st_destroy(t)
