@@ -27,10 +27,10 @@ HBM_PEAK_GBS = 8000.0
 # 1 GiB device copy (FETCH_SIZE x 2.0000, WRITE_SIZE x 1.0000).  An entry is used only while the kernel's source
 # file still has the hash it had when the counters were taken; otherwise "traffic" is null.
 TRAFFIC_RATIO = {
-    ("layer", "attn_decode"): (1.053, "attn_bf16.hip", "4cb295c31eea2fa0"),
-    ("layer", "gemm_gate_up_swiglu"): (1.019, "gemm_bf16.hip", "27ea55bc8599fdc6"),
-    ("full", "attn_decode"): (1.077, "attn_bf16.hip", "4cb295c31eea2fa0"),
-    ("full", "gemm_gate_up_swiglu"): (1.010, "gemm_bf16.hip", "27ea55bc8599fdc6"),
+    ("layer", "attn_decode"): (1.005, "attn_bf16.hip", "ddedc73cd1fb2247"),
+    ("layer", "gemm_gate_up_swiglu"): (1.019, "gemm_bf16.hip", "02097299077dff05"),
+    ("full", "attn_decode"): (1.012, "attn_bf16.hip", "ddedc73cd1fb2247"),
+    ("full", "gemm_gate_up_swiglu"): (1.010, "gemm_bf16.hip", "02097299077dff05"),
 }
 
 
@@ -66,13 +66,17 @@ def parse():
                          "(for counter runs that should only see decode steps)")
     ap.add_argument("--group", type=int, default=1,
                     help="layer workload: every `group` consecutive sequences continue one cached context (shared pages)")
+    ap.add_argument("--grow", type=int, default=0,
+                    help="layer workload: untimed decode steps after the import (the members of a group get private "
+                         "tokens on top of the shared context)")
     ap.add_argument("--no-share-attention", action="store_true",
                     help="full workload: attention over the prompt pages once per row instead of once per set of samples")
     return ap.parse_args()
 
 
 def kernel_bytes(shape, M, ctx_sum, bf=2):
-    """Algorithmic HBM bytes of one launch of each kernel class at batch M (sum of contexts ctx_sum)."""
+    """Algorithmic HBM bytes of one launch of each kernel class at batch M.  ctx_sum: cached tokens the step must
+    read, summed over the batch, pages that several sequences hold in common counted once."""
     H, d, F, V = shape["hidden"], shape["head_dim"], shape["ffn"], shape["vocab"]
     nq, nkv = shape["n_q"], shape["n_kv"]
     nqkv, nqd = (nq + 2 * nkv) * d, nq * d
@@ -190,7 +194,7 @@ def main():
     else:
         shape = ri.SHAPES["layer8b"]
         B, ctx0 = args.batch, args.ctx
-        total_steps = args.warmup + args.steps + (0 if args.no_profile else args.profile_steps)
+        total_steps = args.grow + args.warmup + args.steps + (0 if args.no_profile else args.profile_steps)
         max_ctx = (ctx0 + total_steps + 1 + 15) // 16 * 16
         pages = B * (max_ctx // 16)
         w = ri.make_weights(shape, seed, device=dev, dtype=torch.bfloat16)
@@ -209,7 +213,11 @@ def main():
         x_in = ri.normal((B, shape["hidden"]), 1.0, seed, 1999, device=dev)
         x_out = torch.empty_like(x_in)
         prefill_s = None
-        workload = f"layer8b_1L_bf16_b{B}_ctx{ctx0}" + (f"_group{args.group}" if args.group > 1 else "")
+        workload = f"layer8b_1L_bf16_b{B}_ctx{ctx0}" + (f"_group{args.group}" if args.group > 1 else "") \
+            + (f"_plus{args.grow}" if args.grow else "")
+        G, P = args.group, ctx0
+        n_prompts = (B + G - 1) // G
+        ctx0 += args.grow
 
     from paper_2510_17891_amd.binding import _i32
     ids = _i32(seq_ids)
@@ -227,6 +235,9 @@ def main():
         def step():
             ro.rl_decode_hidden(ids, x_in, x_out)
 
+    if args.workload == "layer":
+        for _ in range(args.grow):
+            step()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -240,15 +251,20 @@ def main():
     ctx_end = ctx_begin + args.steps  # context of the last timed step is ctx_end - 1 (+1 for the fed token)
     ctx_avg = 0.5 * (ctx_begin + ctx_end - 1) + 1
     n_layers = shape["n_layers"]
-    kb_mid = kernel_bytes(shape, B, int(B * ctx_avg)) if shape["vocab"] else None
+    # tokens in pages that the G samples of a prompt hold in common are read once per prompt, not once per sample
+    shared_tok = (P // 16 * 16) if (G > 1 and args.prefill == "real") else 0
+
+    def ctx_sum(ctx):
+        return int(n_prompts * shared_tok + B * (ctx - shared_tok))
+
     step_bytes = None
     if args.workload == "full":
-        kbm = kernel_bytes(shape, B, int(B * ctx_avg))
+        kbm = kernel_bytes(shape, B, ctx_sum(ctx_avg))
         step_bytes = n_layers * (kbm["gemm_qkv"] + kbm["gemm_o"] + kbm["gemm_gate_up_swiglu"] + kbm["gemm_down"]
                                  + kbm["attn_decode"]) + kbm["gemm_lm_head"]
     else:
         shp = dict(shape, vocab=4)
-        kbm = kernel_bytes(shp, B, int(B * ctx_avg))
+        kbm = kernel_bytes(shp, B, ctx_sum(ctx_avg))
         step_bytes = kbm["gemm_qkv"] + kbm["gemm_o"] + kbm["gemm_gate_up_swiglu"] + kbm["gemm_down"] + kbm["attn_decode"]
 
     out = {
@@ -262,6 +278,10 @@ def main():
         "step_hbm_fraction": step_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9),
         "step_algorithmic_GB": step_bytes / 1e9,
     }
+    if shared_tok:
+        out["config"]["shared_prompt_tokens"] = shared_tok
+        out["step_algorithmic_GB_if_nothing_shared"] = (step_bytes + (n_layers if args.workload == "full" else 1)
+                                                        * (B - n_prompts) * shared_tok * shape["n_kv"] * 2 * shape["head_dim"] * 2) / 1e9
     if prefill_s is not None:
         out["prefill_s"] = prefill_s
         out["prefill_prompt_tokens_per_s"] = 4 * 1024 / prefill_s
@@ -279,7 +299,7 @@ def main():
         ro.rl_profile_enable(False)
         ctx_p = ctx_end + 0.5 * (args.profile_steps - 1) + 1
         shp = shape if shape["vocab"] else dict(shape, vocab=4)
-        kb = kernel_bytes(shp, B, int(B * ctx_p))
+        kb = kernel_bytes(shp, B, ctx_sum(ctx_p))
         kernels = {}
         for name, (cnt, ms) in prof.items():
             if cnt == 0:
