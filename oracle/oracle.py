@@ -61,6 +61,15 @@ def lib():
         L.orc_sample.argtypes = [_f32p, C.c_int32, C.c_float, C.c_uint64, C.c_uint32, C.c_uint32,
                                  C.c_int32, C.POINTER(C.c_int32), _f64p]
         L.orc_log_softmax.argtypes = [_f32p, C.c_int32, C.c_float, _f64p]
+        L.orc_order_key.restype = C.c_uint32
+        L.orc_order_key.argtypes = [C.c_float]
+        L.orc_fexp_weight.restype = C.c_uint64
+        L.orc_fexp_weight.argtypes = [C.c_float]
+        L.orc_truncation.restype = C.c_int32
+        L.orc_truncation.argtypes = [_f32p, C.c_int32, C.c_float, C.c_int32, C.c_float, C.POINTER(C.c_uint8)]
+        L.orc_sample_truncated.argtypes = [_f32p, C.c_int32, C.c_float, C.c_int32, C.c_float, C.c_uint64, C.c_uint32,
+                                           C.c_uint32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_double),
+                                           C.POINTER(C.c_int32)]
         L.orc_sample_histogram.argtypes = [_f32p, C.c_int32, C.c_float, C.c_uint64, C.c_uint32,
                                            C.c_uint32, C.c_int64, C.POINTER(C.c_int64)]
         _i32p = C.POINTER(C.c_int32)
@@ -159,6 +168,32 @@ def sample(z, temperature, seed, seq, pos, forced=-1):
     lp = C.c_double()
     lib().orc_sample(_p(z), z.size, temperature, seed, seq, pos, forced, C.byref(tok), C.byref(lp))
     return int(tok.value), float(lp.value)
+
+
+def order_key(z):
+    return int(lib().orc_order_key(float(z)))
+
+
+def fexp_weight(x):
+    return int(lib().orc_fexp_weight(float(x)))
+
+
+def truncation(z, invT, top_k, top_p):
+    """Mask (uint8 [V]) of the tokens that top-k / top-p keep."""
+    z = f32(z)
+    keep = np.zeros(z.size, dtype=np.uint8)
+    n = lib().orc_truncation(_p(z), z.size, invT, top_k, top_p, keep.ctypes.data_as(C.POINTER(C.c_uint8)))
+    assert int(keep.sum()) == n
+    return keep
+
+
+def sample_truncated(z, temperature, top_k, top_p, seed, seq, pos, forced=-1):
+    """(token, log-probability under the truncated distribution, number of kept tokens)."""
+    z = f32(z)
+    tok, lp, kept = C.c_int32(), C.c_double(), C.c_int32()
+    lib().orc_sample_truncated(_p(z), z.size, temperature, top_k, top_p, seed, seq, pos, forced, C.byref(tok),
+                               C.byref(lp), C.byref(kept))
+    return int(tok.value), float(lp.value), int(kept.value)
 
 
 def log_softmax(z, invT=1.0):

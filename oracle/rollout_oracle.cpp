@@ -27,6 +27,7 @@
 // cases worked by hand, class weights, both printed forms of the clipped term.  No function here is
 // "parity unpinned".
 
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
@@ -362,6 +363,104 @@ void orc_sample_histogram(const float* z, int32_t vocab, float temperature, uint
     orc_sample(z, vocab, temperature, seed, seq, pos0 + (uint32_t)t, -1, &tok, &lp);
     counts[tok] += 1;
   }
+}
+
+// ---------------------------------------------------------------------------
+// Truncated sampling (top-k, top-p): the sampling settings Appendix D states for the data-generating models
+// (temperature 0.6 / top-p 0.95, 0.7 / 0.8).  The paper gives no definition; this is the usual one, made exactly
+// reproducible by integer probability masses.
+//
+//   order     tokens by descending logit, equal logits by ascending index; "descending" is the total order of the
+//             bit patterns (orc_order_key), so -0 comes after +0.
+//   mass      W_i = orc_fexp_weight(fma(z_i, invT, -(z_max * invT))): a project-defined fp32 exp scaled to 2^32 and
+//             truncated to an integer, so that sums are exact and independent of their order.
+//   top-k     keep the first K = min(k, V) tokens of the order (k = 0: all).
+//   top-p     P = trunc(p * 2^32), S = mass of those K tokens, T = max(1, floor(P * S / 2^32)); keep the shortest
+//             prefix of the order whose mass reaches T (p <= 0 or p >= 1: no top-p cut).
+//   draw      Gumbel-max over the kept tokens with the same per-token noise as orc_sample; the log-probability is
+//             that of the renormalised distribution over the kept tokens (double here).
+//   T = 0     greedy: the cuts are ignored (the argmax is always kept), lp as in orc_sample.
+//   forced    lp of the forced token under the truncated distribution, -inf if it was cut.
+// ---------------------------------------------------------------------------
+uint32_t orc_order_key(float z) {  // ascending key = ascending value
+  uint32_t b;
+  std::memcpy(&b, &z, 4);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+uint64_t orc_fexp_weight(float x) {
+  if (!(x > -22.0f)) return 0;  // below 2^-31.7 (and -inf)
+  const float t = x * 0x1.715476p+0f;  // log2(e)
+  const float n = std::nearbyintf(t);  // ties to even
+  const float f = fmaf(x, 0x1.715476p+0f, -n);
+  float p = 0x1.430912p-13f;           // 2^f = sum (f ln2)^k / k!, k = 6 .. 0
+  p = fmaf(p, f, 0x1.5d87fep-10f);
+  p = fmaf(p, f, 0x1.3b2ab6p-7f);
+  p = fmaf(p, f, 0x1.c6b08ep-5f);
+  p = fmaf(p, f, 0x1.ebfbe0p-3f);
+  p = fmaf(p, f, 0x1.62e430p-1f);
+  p = fmaf(p, f, 1.0f);
+  return (uint64_t)std::ldexp(p, (int)n + 32);  // power-of-two scaling is exact; conversion truncates
+}
+
+// Number of tokens kept; keep[i] (optional) is set to 1 for kept tokens.
+int32_t orc_truncation(const float* z, int32_t vocab, float invT, int32_t top_k, float top_p, uint8_t* keep) {
+  std::vector<int32_t> order(vocab);
+  for (int32_t i = 0; i < vocab; ++i) order[i] = i;
+  std::stable_sort(order.begin(), order.end(),
+                   [&](int32_t a, int32_t b) { return orc_order_key(z[a]) > orc_order_key(z[b]); });
+  const float s_max = z[order[0]] * invT;
+  const int32_t K = (top_k > 0 && top_k < vocab) ? top_k : vocab;
+  int32_t n = K;
+  if (top_p > 0.0f && top_p < 1.0f) {
+    unsigned __int128 S = 0;
+    for (int32_t j = 0; j < K; ++j) S += orc_fexp_weight(fmaf(z[order[j]], invT, -s_max));
+    const uint64_t P = (uint64_t)(top_p * 4294967296.0f);
+    unsigned __int128 T = (S * P) >> 32;
+    if (T < 1) T = 1;
+    unsigned __int128 c = 0;
+    for (n = 0; n < K;) {
+      c += orc_fexp_weight(fmaf(z[order[n]], invT, -s_max));
+      ++n;
+      if (c >= T) break;
+    }
+  }
+  if (keep) {
+    std::memset(keep, 0, vocab);
+    for (int32_t j = 0; j < n; ++j) keep[order[j]] = 1;
+  }
+  return n;
+}
+
+void orc_sample_truncated(const float* z, int32_t vocab, float temperature, int32_t top_k, float top_p, uint64_t seed,
+                          uint32_t seq, uint32_t pos, int32_t forced, int32_t* tok_out, double* lp_out,
+                          int32_t* kept_out) {
+  if (!(temperature > 0.0f)) {
+    orc_sample(z, vocab, temperature, seed, seq, pos, forced, tok_out, lp_out);
+    if (kept_out) *kept_out = vocab;
+    return;
+  }
+  const float invT = 1.0f / temperature;
+  std::vector<uint8_t> keep(vocab);
+  const int32_t n = orc_truncation(z, vocab, invT, top_k, top_p, keep.data());
+  if (kept_out) *kept_out = n;
+  int32_t best = forced;
+  if (forced < 0) {
+    float best_y = -INFINITY;
+    for (int32_t i = 0; i < vocab; ++i) {
+      if (!keep[i]) continue;
+      const float y = fmaf(z[i], invT, orc_gumbel(orc_token_bits(seed, seq, pos, (uint32_t)i)));
+      if (best < 0 || y > best_y) { best_y = y; best = i; }
+    }
+  }
+  double M = -INFINITY;
+  for (int32_t i = 0; i < vocab; ++i)
+    if (keep[i]) M = std::fmax(M, (double)z[i] * (double)invT);
+  double sum = 0.0;
+  for (int32_t i = 0; i < vocab; ++i)
+    if (keep[i]) sum += std::exp((double)z[i] * (double)invT - M);
+  *tok_out = best;
+  *lp_out = keep[best] ? (double)z[best] * (double)invT - (M + std::log(sum)) : -INFINITY;
 }
 
 // ---------------------------------------------------------------------------
