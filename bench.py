@@ -69,6 +69,9 @@ def parse():
     ap.add_argument("--grow", type=int, default=0,
                     help="layer workload: untimed decode steps after the import (the members of a group get private "
                          "tokens on top of the shared context)")
+    ap.add_argument("--temperature", type=float, default=1.0, help="full workload: sampling temperature")
+    ap.add_argument("--top-k", type=int, default=0, help="full workload: top-k cut (0: none)")
+    ap.add_argument("--top-p", type=float, default=0.0, help="full workload: top-p cut (0: none)")
     ap.add_argument("--no-share-attention", action="store_true",
                     help="full workload: attention over the prompt pages once per row instead of once per set of samples")
     return ap.parse_args()
@@ -189,7 +192,8 @@ def main():
             tok = prompts[0, :B].to(dev).contiguous()
             torch.cuda.synchronize()
             prefill_s = None
-        workload = f"full8b_36L_bf16_{B}seq_prompt{P}_T1.0"
+        workload = f"full8b_36L_bf16_{B}seq_prompt{P}_T{args.temperature}" \
+            + (f"_topk{args.top_k}" if args.top_k else "") + (f"_topp{args.top_p}" if args.top_p else "")
         ctx0 = P
     else:
         shape = ri.SHAPES["layer8b"]
@@ -228,7 +232,8 @@ def main():
 
         def step():
             ot, ol = bufs[state["i"] & 1]
-            ro.rl_decode_step(ids, state["cur"], 1.0, seed, out_tokens=ot, out_logprobs=ol)
+            ro.rl_decode_step(ids, state["cur"], args.temperature, seed, out_tokens=ot, out_logprobs=ol,
+                              top_k=args.top_k, top_p=args.top_p)
             state["cur"] = ot
             state["i"] += 1
     else:
@@ -274,7 +279,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": workload, "batch": B, "context_first_timed_step": ctx_begin + 1,
-                   "context_last_timed_step": ctx_end, "kv_block": 16, "temperature": 1.0},
+                   "context_last_timed_step": ctx_end, "kv_block": 16, "temperature": args.temperature},
         "step_hbm_fraction": None, "step_algorithmic_GB": None,
     }
     # The per-sequence byte formula (weights once + 4096 B per cached token per layer per sequence) is the unit of

@@ -111,10 +111,22 @@ typedef struct {
   void* workspace;
 } rl_weights;
 
+/*
+ * Sampling settings.  The RL rollouts of the paper draw from the untruncated policy (the ratios of Section 2.3
+ * need pi_theta_old of the token that was drawn); top_k / top_p serve the truncated settings Appendix D lists
+ * for data generation (temperature 0.6 / top-p 0.95, 0.7 / 0.8).  With a cut the tokens are ordered by descending
+ * logit (ties: lower id first), top_k keeps the first top_k of them, top_p then the shortest prefix whose
+ * probability mass (under temperature, renormalised over the top_k set) reaches top_p; the draw and the returned
+ * log-probability refer to the renormalised distribution over the kept tokens (a forced token outside it has
+ * log-probability -inf).  Masses are exact integers, so the kept set is reproducible bit for bit.  Greedy
+ * (temperature 0) ignores both cuts.  rl_score never truncates.
+ */
 typedef struct {
   float temperature; /* 0 => greedy */
-  uint32_t reserved;
+  uint32_t top_k;    /* 0 (or > vocab) => no top-k cut */
   uint64_t seed;
+  float top_p;       /* outside (0, 1) => no top-p cut */
+  uint32_t reserved; /* 0 */
 } rl_sampling;
 
 /* Bytes of one KV page (kv_block tokens, all layers, K and V) for this configuration; 0 on bad config. */

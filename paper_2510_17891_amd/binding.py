@@ -45,7 +45,8 @@ class rl_weights(C.Structure):
 
 
 class rl_sampling(C.Structure):
-    _fields_ = [("temperature", C.c_float), ("reserved", C.c_uint32), ("seed", C.c_uint64)]
+    _fields_ = [("temperature", C.c_float), ("top_k", C.c_uint32), ("seed", C.c_uint64), ("top_p", C.c_float),
+                ("reserved", C.c_uint32)]
 
 
 class rl_objective_params(C.Structure):
@@ -231,25 +232,25 @@ class Rollout:
             pass
 
     # ---- the four calls of the boundary --------------------------------------------------------
-    def rl_prefill(self, seq_ids, prompts, temperature, seed):
+    def rl_prefill(self, seq_ids, prompts, temperature, seed, top_k=0, top_p=0.0):
         """prompts: list of int sequences.  Returns (tokens int32[n], logprobs fp32[n]) on the device."""
         n = len(seq_ids)
         flat = [int(t) for p in prompts for t in p]
         out_t = torch.empty(n, dtype=torch.int32, device=self.device)
         out_lp = torch.empty(n, dtype=torch.float32, device=self.device)
-        sp = rl_sampling(temperature, 0, seed)
+        sp = rl_sampling(temperature, top_k, seed, top_p, 0)
         check(lib().rl_prefill(self.h, _stream(), n, _i32(seq_ids), _i32(flat), _i32([len(p) for p in prompts]),
                                C.byref(sp), _ptr(out_t), _ptr(out_lp)))
         return out_t, out_lp
 
-    def rl_prefill_groups(self, seq_ids, group_size, prompts, temperature, seed):
+    def rl_prefill_groups(self, seq_ids, group_size, prompts, temperature, seed, top_k=0, top_p=0.0):
         """prompts: one int sequence per group; seq_ids: len(prompts) * group_size ids, group-major."""
         n = len(seq_ids)
         assert n == len(prompts) * group_size
         flat = [int(t) for p in prompts for t in p]
         out_t = torch.empty(n, dtype=torch.int32, device=self.device)
         out_lp = torch.empty(n, dtype=torch.float32, device=self.device)
-        sp = rl_sampling(temperature, 0, seed)
+        sp = rl_sampling(temperature, top_k, seed, top_p, 0)
         check(lib().rl_prefill_groups(self.h, _stream(), len(prompts), group_size, _i32(seq_ids), _i32(flat),
                                       _i32([len(p) for p in prompts]), C.byref(sp), _ptr(out_t), _ptr(out_lp)))
         return out_t, out_lp
@@ -263,11 +264,11 @@ class Rollout:
         return out
 
     def rl_decode_step(self, seq_ids, in_tokens, temperature, seed, forced_next=None, debug_logits=None,
-                       out_tokens=None, out_logprobs=None):
+                       out_tokens=None, out_logprobs=None, top_k=0, top_p=0.0):
         n = len(seq_ids)
         out_t = out_tokens if out_tokens is not None else torch.empty(n, dtype=torch.int32, device=self.device)
         out_lp = out_logprobs if out_logprobs is not None else torch.empty(n, dtype=torch.float32, device=self.device)
-        sp = rl_sampling(temperature, 0, seed)
+        sp = rl_sampling(temperature, top_k, seed, top_p, 0)
         ids = seq_ids if isinstance(seq_ids, C.Array) else _i32(seq_ids)
         check(lib().rl_decode_step(self.h, _stream(), n, ids, _ptr(in_tokens), _ptr(forced_next), C.byref(sp),
                                    _ptr(out_t), _ptr(out_lp), _ptr(debug_logits)))
@@ -287,11 +288,11 @@ class Rollout:
         check(lib().rl_seq_len(self.h, seq_id, C.byref(n)))
         return n.value
 
-    def rl_sample_logits(self, logits, seq_ids, positions, temperature, seed, forced=None):
+    def rl_sample_logits(self, logits, seq_ids, positions, temperature, seed, forced=None, top_k=0, top_p=0.0):
         n = logits.shape[0]
         out_t = torch.empty(n, dtype=torch.int32, device=self.device)
         out_lp = torch.empty(n, dtype=torch.float32, device=self.device)
-        sp = rl_sampling(temperature, 0, seed)
+        sp = rl_sampling(temperature, top_k, seed, top_p, 0)
         check(lib().rl_sample_logits(self.h, _stream(), n, _ptr(logits), _i32(seq_ids), _i32(positions),
                                      _ptr(forced), C.byref(sp), _ptr(out_t), _ptr(out_lp)))
         return out_t, out_lp

@@ -109,9 +109,15 @@ constexpr int kSampleTile = 2048;  // vocabulary entries per first-stage block o
 // Gumbel-max sampling with log-probabilities from fp32 logits [M][V] in memory (two stages).
 // part: [M][ceil(V/2048)][8] floats; forced may be null; forced_z: [M] floats.
 // The RNG position of row r is rows[r].pos + pos_offset.
+// top_k / top_p cut the distribution first (0 / outside (0,1): no cut; ignored when greedy); cut_buf: scratch of
+// M * sample_cut_bytes_per_row() bytes (256-byte aligned), needed when sample_is_truncated().  V % 4 == 0, V < 2^22.
+size_t sample_cut_bytes_per_row();
+inline bool sample_is_truncated(int V, int top_k, float top_p) {
+  return (top_k > 0 && top_k < V) || (top_p > 0.0f && top_p < 1.0f);
+}
 void launch_sample(hipStream_t s, const float* logits, int M, int V, const RowMeta* rows, int pos_offset,
                    const int32_t* forced, float temperature, uint64_t seed, float* part, float* forced_z,
-                   int32_t* out_tokens, float* out_logprobs);
+                   int32_t* out_tokens, float* out_logprobs, int top_k = 0, float top_p = 0.f, void* cut_buf = nullptr);
 // Second stage alone, over the [M][n_tiles][8] partials the sampling epilogue of the bf16 projection left.
 void launch_sample_merge(hipStream_t s, const float* part, int n_tiles, int M, int V, const int32_t* forced,
                          const float* forced_z, float temperature, int32_t* out_tokens, float* out_logprobs);

@@ -45,7 +45,7 @@ constexpr int T_MAX_SCORE = 4096;  // sequences per scoring call
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 struct Layout {
-  size_t block_table, rope, ring, x, x_last, h, part, q, attn_part, o, a, logits, samp_part, forced_z, tmp_tok, tmp_lp, total;
+  size_t block_table, rope, ring, x, x_last, h, part, q, attn_part, o, a, logits, samp_part, forced_z, tmp_tok, tmp_lp, cuts, total;
   size_t slot_bytes, slot_upd, slot_tok, slot_skip, slot_sets;
   int max_segs, n_tiles;
 };
@@ -64,6 +64,7 @@ rl_status check_config(const rl_model_config* c) {
   if (c->max_ctx == 0 || c->max_ctx % 16) return fail(RL_ERR_INVALID_ARG, "max_ctx must be a positive multiple of 16");
   if (c->hidden % 8 || c->hidden > 8192 || c->head_dim % 2 || c->head_dim > 128 || c->ffn % 8 || c->vocab % 4)
     return fail(RL_ERR_UNSUPPORTED, "need hidden %% 8 == 0, hidden <= 8192, even head_dim <= 128, ffn %% 8 == 0, vocab %% 4 == 0");
+  if (c->vocab >= (1u << 22)) return fail(RL_ERR_UNSUPPORTED, "vocab must be below 2^22");
   if (c->dtype == RL_BF16) {
     const uint32_t qd = c->n_q_heads * c->head_dim, nqkv = (c->n_q_heads + 2 * c->n_kv_heads) * c->head_dim;
     if (c->head_dim != 128 || c->n_q_heads / c->n_kv_heads > 8) return fail(RL_ERR_UNSUPPORTED, "bf16 needs head_dim 128 and group <= 8");
@@ -109,15 +110,17 @@ void compute_layout(const rl_model_config& c, Layout* L) {
   L->attn_part = take(c.dtype == RL_BF16 ? R * nq * (size_t)L->max_segs * (d + 2) * 4 : 256);
   L->o = take(Rp * nq * d * act);
   L->a = take(Rp * F * act);
-  // bf16: logits never reach memory (sampling happens in the projection's epilogue, 64 entries per partial);
+  // bf16: logits never reach memory (sampling happens in the projection's epilogue, 64 entries per partial) unless
+  // the distribution is truncated (top-k / top-p need the whole row before any token can be drawn);
   // fp32: logits are written and scanned by the stand-alone sampler (2048 entries per partial).  rl_sample_logits
   // uses the stand-alone sampler in both cases.
-  L->logits = take(V && c.dtype == RL_F32 ? R * V * 4 : 256);
+  L->logits = take(V ? R * V * 4 : 256);
   const size_t tiles_fused = V / 64 + 1;
   L->samp_part = take(V ? R * (tiles_fused > (size_t)L->n_tiles ? tiles_fused : (size_t)L->n_tiles) * 32 : 256);
   L->forced_z = take(R * 4);
   L->tmp_tok = take(R * 4);
   L->tmp_lp = take(R * 4);
+  L->cuts = take(V ? R * sample_cut_bytes_per_row() : 256);
   L->total = off;
 }
 
@@ -267,7 +270,9 @@ void run_head(rl_model* m, hipStream_t st, int M, float* xbuf, int pend, const R
     launch_residual_norm(st, g.dtype, xbuf, pend ? part : nullptr, pend, m->final_norm, h, cap, M, g.hidden, g.rms_eps); }
   float* spart = m->wsp<float>(m->lay.samp_part);
   float* fz = m->wsp<float>(m->lay.forced_z);
-  if (g.dtype == kBF16) {
+  const int top_k = sp->top_k > (uint32_t)g.vocab ? 0 : (int)sp->top_k;
+  const bool truncated = !score_only && sp->temperature > 0.f && sample_is_truncated(g.vocab, top_k, sp->top_p);
+  if (g.dtype == kBF16 && !truncated) {
     SampleEpilogue se;
     se.rows = rows; se.pos_offset = pos_offset;
     se.greedy = !(sp->temperature > 0.f);
@@ -280,10 +285,13 @@ void run_head(rl_model* m, hipStream_t st, int M, float* xbuf, int pend, const R
     { Timer t(m, st, K_SAMPLE);
       launch_sample_merge(st, spart, g.vocab >> 6, M, g.vocab, forced, fz, sp->temperature, out_tokens, out_lp); }
   } else {
+    // logits to memory (a truncated distribution needs the whole row first), then the stand-alone sampler
     { Timer t(m, st, K_LMHEAD);
-      launch_gemm_f32(st, (const float*)h, (const float*)m->lm_head, logits, M, g.vocab, g.hidden, kEpiPartial); }
+      if (g.dtype == kBF16) launch_gemm_bf16(st, h, m->lm_head, logits, M, g.vocab, g.hidden, kEpiPartial, false);
+      else launch_gemm_f32(st, (const float*)h, (const float*)m->lm_head, logits, M, g.vocab, g.hidden, kEpiPartial); }
     { Timer t(m, st, K_SAMPLE);
-      launch_sample(st, logits, M, g.vocab, rows, pos_offset, forced, sp->temperature, sp->seed, spart, fz, out_tokens, out_lp); }
+      launch_sample(st, logits, M, g.vocab, rows, pos_offset, forced, sp->temperature, sp->seed, spart, fz, out_tokens, out_lp,
+                    truncated ? top_k : 0, truncated ? sp->top_p : 0.f, m->wsp<void>(m->lay.cuts)); }
     if (debug_logits)
       (void)hipMemcpyAsync(debug_logits, logits, (size_t)M * g.vocab * 4, hipMemcpyDeviceToDevice, st);
   }
@@ -793,7 +801,7 @@ rl_status rl_score(rl_model* m, void* stream, int32_t n, const int32_t* seq_ids,
   float* x = m->wsp<float>(m->lay.x);
   int32_t* tmp_tok = m->wsp<int32_t>(m->lay.tmp_tok);
   float* tmp_lp = m->wsp<float>(m->lay.tmp_lp);
-  rl_sampling sp{temperature, 0u, 0ull};
+  rl_sampling sp{temperature, 0u, 0ull, 0.f, 0u};
   int si = 0, pos = 0;
   int64_t done = 0, tok_off = 0, out_off = 0;
   std::vector<int64_t> tok_base(n), out_base(n);
@@ -881,7 +889,8 @@ rl_status rl_sample_logits(rl_model* m, void* stream, int32_t n, const float* lo
   HIP_TRY(hipEventRecord(m->ring_ev[slot], st));
   m->ring_used[slot] = true;
   launch_sample(st, logits, n, m->geo.vocab, (const RowMeta*)ds, 0, forced, sp->temperature, sp->seed,
-                m->wsp<float>(m->lay.samp_part), m->wsp<float>(m->lay.forced_z), out_tokens, out_logprobs);
+                m->wsp<float>(m->lay.samp_part), m->wsp<float>(m->lay.forced_z), out_tokens, out_logprobs,
+                sp->top_k > (uint32_t)m->geo.vocab ? 0 : (int)sp->top_k, sp->top_p, m->wsp<void>(m->lay.cuts));
   HIP_TRY(hipGetLastError());
   return RL_OK;
 }

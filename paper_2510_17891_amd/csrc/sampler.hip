@@ -13,7 +13,8 @@ __global__ __launch_bounds__(256) void sample_stage1_kernel(const float* __restr
                                                             const RowMeta* __restrict__ rows, int pos_offset, float inv_t,
                                                             int greedy, uint32_t seed_lo, uint32_t seed_hi,
                                                             const int32_t* __restrict__ forced, float* __restrict__ forced_z,
-                                                            float* __restrict__ part, int n_tiles) {
+                                                            float* __restrict__ part, int n_tiles,
+                                                            const OrderCut* __restrict__ cuts) {
   __shared__ float sh_y[4], sh_z[4], sh_m[4], sh_s[4];
   __shared__ int sh_i[4];
   const int tile = blockIdx.x, r = blockIdx.y;
@@ -21,6 +22,8 @@ __global__ __launch_bounds__(256) void sample_stage1_kernel(const float* __restr
   const uint32_t pos = (uint32_t)(rm.pos + pos_offset), seq = (uint32_t)rm.seq;
   const float* z = logits + (size_t)r * V;
   const int f = forced ? forced[r] : -1;
+  OrderCut cut{0u, 0x7fffffff};  // keeps everything
+  if (cuts) cut = cuts[r];
   Best best{-INFINITY, -1, 0.f};
   float m = -INFINITY, s = 0.f;
   const int i_end = min(V, (tile + 1) * kSampleTile);
@@ -32,6 +35,10 @@ __global__ __launch_bounds__(256) void sample_stage1_kernel(const float* __restr
       const int i = i0 + e;
       if (i >= i_end) break;
       const float zi = z[i];
+      if (!kept_by(cut, order_key(zi), i)) {  // cut off by top-k / top-p: probability zero
+        if (i == f) forced_z[r] = -INFINITY;
+        continue;
+      }
       const float y = greedy ? zi : __fmaf_rn(zi, inv_t, gumbel(rnd[e]));
       best = better(best, Best{y, i, zi});
       lse_merge(m, s, zi * inv_t, 1.0f);
@@ -94,17 +101,299 @@ __global__ __launch_bounds__(1024) void sample_stage2_kernel(const float* __rest
   }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// Top-k / top-p cut of every row: the last kept token of the order, found by radix selection.  A selection runs in
+// five stages, three over the digits of the order key from the top (11, 11, 10 bits; count or integer mass per bin,
+// bins scanned from the largest down until the target is reached) and two over the digits of the index (11, 11 bits,
+// ascending) among the tokens that share the cut's key.  Each stage is one launch with several blocks per row: a
+// block first redoes the scan of the previous stage's histogram (every block gets the same answer), then adds its
+// slice of the row to this stage's histogram in LDS and from there to the row's histogram in memory.  Integer masses
+// make every sum exact, whatever its order, so the cut is reproducible bit for bit.
+// ------------------------------------------------------------------------------------------------
+constexpr int kCutBins = 2048;
+constexpr int kCutStages = 5;
+
+struct CutState {  // after the scan of a stage's histogram
+  uint32_t prefix;   // selected digits of the order key so far
+  uint32_t iprefix;  // selected digits of the index so far
+  unsigned long long rem;  // count or mass still to be covered inside the selection
+};
+struct CutRow {  // per row, zeroed before a selection starts
+  unsigned long long hist[2 * kCutStages][kCutBins];
+  CutState st[2 * kCutStages];
+  uint32_t kmax;
+  uint32_t pad;
+};
+
+__device__ __forceinline__ int cut_shift(int stage) { return stage == 0 ? 21 : stage == 1 ? 10 : stage == 2 ? 0 : stage == 3 ? 11 : 0; }
+__device__ __forceinline__ int cut_width(int stage) { return stage == 2 ? 10 : 11; }
+
+// Calls fn(i, z[i]) for the tokens of float4 groups [g_begin, g_end) of the row (V % 4 == 0, rows 16-byte aligned),
+// eight 16-byte loads in flight per thread.
+template <typename F>
+__device__ __forceinline__ void for_each_token(const float* __restrict__ z, int g_begin, int g_end, int tid, int nthr, F fn) {
+  for (int g0 = g_begin + tid; g0 < g_end; g0 += 8 * nthr) {
+    float4 v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int g = g0 + e * nthr;
+      v[e] = g < g_end ? ((const float4*)z)[g] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int g = g0 + e * nthr;
+      if (g < g_end) { fn(4 * g, v[e].x); fn(4 * g + 1, v[e].y); fn(4 * g + 2, v[e].z); fn(4 * g + 3, v[e].w); }
+    }
+  }
+}
+
+// One wave: the position (in scan order: descending or ascending bin) at which the running sum of `hist` first
+// reaches `rem`; the last position is taken when none does.  Returns the bin; *rem_out = what is still to be covered
+// inside it; *total_out = sum of all bins.  Every lane returns the same values.
+template <bool kDescending, int kPer>
+__device__ __forceinline__ int scan_select_n(const unsigned long long* __restrict__ hist, unsigned long long rem, int lane,
+                                             unsigned long long* rem_out) {
+  constexpr int n_bins = 64 * kPer;
+  // this lane's kPer positions (consecutive in scan order), loaded once as 16-byte pairs
+  unsigned long long c[kPer];
+  const int first = kDescending ? n_bins - (lane + 1) * kPer : lane * kPer;  // lowest bin of the lane's range
+#pragma unroll
+  for (int e = 0; e < kPer; e += 2) {
+    const ulonglong2 v = *(const ulonglong2*)(hist + first + e);
+    c[kDescending ? kPer - 1 - e : e] = v.x;
+    c[kDescending ? kPer - 2 - e : e + 1] = v.y;
+  }
+  unsigned long long local = 0;
+#pragma unroll
+  for (int e = 0; e < kPer; ++e) local += c[e];
+  unsigned long long incl = local;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const unsigned long long t = __shfl_up(incl, o, kWave);
+    if (lane >= o) incl += t;
+  }
+  unsigned long long cum = incl - local;  // sum of the positions before this lane's
+  int hit = -1;
+  unsigned long long before = 0;
+#pragma unroll
+  for (int e = 0; e < kPer; ++e) {
+    const int pos = lane * kPer + e;
+    if (hit < 0 && pos < n_bins - 1 && cum + c[e] >= rem) { hit = pos; before = cum; }
+    if (pos < n_bins - 1) cum += c[e];  // in the last lane: ends as the sum of all positions but the last
+  }
+  const unsigned long long any = __ballot(hit >= 0);
+  const int src = any ? (int)__builtin_ctzll(any) : 63;
+  if (!any) { hit = n_bins - 1; before = cum; }
+  hit = __shfl(hit, src, kWave);
+  before = __shfl(before, src, kWave);
+  *rem_out = rem - before;
+  return kDescending ? n_bins - 1 - hit : hit;
+}
+template <bool kDescending>
+__device__ __forceinline__ int scan_select(const unsigned long long* __restrict__ hist, int n_bins, unsigned long long rem,
+                                           int lane, unsigned long long* rem_out) {
+  return n_bins == 2048 ? scan_select_n<kDescending, 32>(hist, rem, lane, rem_out)
+                        : scan_select_n<kDescending, 16>(hist, rem, lane, rem_out);
+}
+
+__device__ __forceinline__ unsigned long long wave_total(const unsigned long long* __restrict__ hist, int n_bins, int lane) {
+  unsigned long long s = 0;
+  for (int b = lane; b < n_bins; b += 64) s += hist[b];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, kWave);
+  return s;
+}
+
+// Four (bin, count-or-mass) entries in registers.  The top digit of the order key takes only a handful of values over
+// a row of logits, so in the first stage nearly every token would hit the same few LDS words; a thread collects them
+// here and adds each entry to the histogram once.
+struct BinCache {
+  int bin[4];
+  unsigned long long val[4];
+  int next;
+  __device__ __forceinline__ void init() {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { bin[e] = -1; val[e] = 0; }
+    next = 0;
+  }
+  __device__ __forceinline__ void add(int b, unsigned long long w, unsigned long long* h) {
+    bool hit = false;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (bin[e] == b) { val[e] += w; hit = true; }
+    if (hit) return;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (next == e) {
+        if (bin[e] >= 0) atomicAdd(&h[bin[e]], val[e]);
+        bin[e] = b;
+        val[e] = w;
+      }
+    next = (next + 1) & 3;
+  }
+  __device__ __forceinline__ void flush(unsigned long long* h) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (bin[e] >= 0) atomicAdd(&h[bin[e]], val[e]);
+  }
+};
+
+__global__ __launch_bounds__(256) void cut_zero_kernel(CutRow* __restrict__ ws) {
+  uint4* p = (uint4*)(ws + blockIdx.y);
+  const int n = (int)(sizeof(CutRow) / 16);
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+// grid (slices, rows): largest order key of the row -> ws[row].kmax
+__global__ __launch_bounds__(256) void cut_kmax_kernel(const float* __restrict__ logits, int V, CutRow* __restrict__ ws) {
+  const int r = blockIdx.y, tid = threadIdx.x;
+  const float* z = logits + (size_t)r * V;
+  const int n4 = V >> 2, per = (n4 + gridDim.x - 1) / gridDim.x;
+  const int g_begin = blockIdx.x * per, g_end = min(n4, g_begin + per);
+  uint32_t kmax = 0;
+  for_each_token(z, g_begin, g_end, tid, 256, [&](int, float zi) { kmax = max(kmax, order_key(zi)); });
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, kWave));
+  if ((tid & 63) == 0 && kmax != 0) atomicMax(&ws[r].kmax, kmax);
+}
+
+// Stage `stage` (0..4) of selection `sel` (0: first, 1: second) of every row; stage == kCutStages only finishes the
+// selection and writes the cut.  kMass: bins hold integer masses and the first stage's target is
+// max(1, floor(p_fixed * S / 2^32)), S = mass of all allowed tokens (p_fixed == 0: the target is `target`);
+// otherwise bins hold counts and the target is `target`.  allowed_cuts (may be null): only tokens kept by that
+// earlier cut take part.
+template <bool kMass>
+__global__ __launch_bounds__(256) void cut_stage_kernel(const float* __restrict__ logits, int V, float inv_t, int stage, int sel,
+                                                        unsigned long long target, unsigned long long p_fixed,
+                                                        const OrderCut* __restrict__ allowed_cuts,
+                                                        CutRow* __restrict__ ws, OrderCut* __restrict__ cuts_out) {
+  __shared__ unsigned long long lh[kCutBins];
+  __shared__ CutState sh_st;
+  const int r = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
+  CutRow& row = ws[r];
+  const int slot = sel * kCutStages + stage;
+  const float* z = logits + (size_t)r * V;
+  const float s_max = __fmul_rn(order_value(row.kmax), inv_t);
+  OrderCut allowed{0u, 0x7fffffff};
+  if (allowed_cuts) allowed = allowed_cuts[r];
+
+  // ---- state after the previous stage (first wave; the answer is the same in every block of the row) ----------
+  if (tid < 64) {
+    CutState st{0u, 0u, target};
+    if (stage > 0) {
+      const unsigned long long* ph = row.hist[slot - 1];
+      const int pbins = 1 << cut_width(stage - 1);
+      if (stage == 1) {
+        if (kMass && p_fixed != 0) {
+          const unsigned long long S = wave_total(ph, pbins, lane);
+          st.rem = (__umul64hi(S, p_fixed) << 32) | ((S * p_fixed) >> 32);  // S < 2^50, p_fixed < 2^32
+          if (st.rem < 1) st.rem = 1;
+        }
+      } else {
+        st = row.st[slot - 2];
+      }
+      unsigned long long rem_out;
+      if (stage <= 3) {  // previous stage was a key digit: scan from the largest bin down
+        const int b = scan_select<true>(ph, pbins, st.rem, lane, &rem_out);
+        st.prefix |= (uint32_t)b << cut_shift(stage - 1);
+        if (stage == 3) {  // key complete: tokens with this key, in ascending index order -- how many are needed
+          if (kMass) {
+            const unsigned long long w = fexp_weight(__fmaf_rn(order_value(st.prefix), inv_t, -s_max));
+            rem_out = w > 0 ? (rem_out + w - 1) / w : 1ull;
+          }
+          if (rem_out < 1) rem_out = 1;
+        }
+      } else {           // previous stage was an index digit: scan upwards
+        const int b = scan_select<false>(ph, pbins, st.rem, lane, &rem_out);
+        st.iprefix |= (uint32_t)b << cut_shift(stage - 1);
+      }
+      st.rem = rem_out;
+      if (blockIdx.x == 0 && lane == 0) {
+        if (stage < kCutStages) row.st[slot - 1] = st;
+        else cuts_out[r] = OrderCut{st.prefix, (int32_t)st.iprefix};
+      }
+    }
+    if (lane == 0) sh_st = st;
+  }
+  if (stage == kCutStages) return;  // block-uniform
+  for (int b = tid; b < kCutBins; b += 256) lh[b] = 0ull;
+  __syncthreads();
+  const CutState st = sh_st;
+
+  // ---- this block's slice of the row into the stage's histogram ------------------------------------------
+  const int n4 = V >> 2, per = (n4 + gridDim.x - 1) / gridDim.x;
+  const int g_begin = blockIdx.x * per, g_end = min(n4, g_begin + per);
+  const int shift = cut_shift(stage), mask = (1 << cut_width(stage)) - 1;
+  if (stage == 0) {
+    BinCache bc;
+    bc.init();
+    for_each_token(z, g_begin, g_end, tid, 256, [&](int i, float zi) {
+      const uint32_t k = order_key(zi);
+      if (!kept_by(allowed, k, i)) return;
+      bc.add((int)(k >> shift), kMass ? fexp_weight(__fmaf_rn(zi, inv_t, -s_max)) : 1ull, lh);
+    });
+    bc.flush(lh);
+  } else if (stage < 3) {
+    const int above = shift + cut_width(stage);
+    for_each_token(z, g_begin, g_end, tid, 256, [&](int i, float zi) {
+      const uint32_t k = order_key(zi);
+      if ((k >> above) != (st.prefix >> above) || !kept_by(allowed, k, i)) return;
+      atomicAdd(&lh[(k >> shift) & mask], kMass ? fexp_weight(__fmaf_rn(zi, inv_t, -s_max)) : 1ull);
+    });
+  } else {
+    for_each_token(z, g_begin, g_end, tid, 256, [&](int i, float zi) {
+      const uint32_t k = order_key(zi);
+      if (k != st.prefix || !kept_by(allowed, k, i)) return;
+      if (stage == 4 && ((uint32_t)i >> 11) != (st.iprefix >> 11)) return;
+      atomicAdd(&lh[((uint32_t)i >> shift) & mask], 1ull);
+    });
+  }
+  __syncthreads();
+  for (int b = tid; b < kCutBins; b += 256)
+    if (lh[b] != 0ull) atomicAdd(&row.hist[slot][b], lh[b]);
+}
+
 }  // namespace
+
+size_t sample_cut_bytes_per_row() { return sizeof(CutRow) + 2 * sizeof(OrderCut); }
 
 void launch_sample(hipStream_t st, const float* logits, int M, int V, const RowMeta* rows, int pos_offset,
                    const int32_t* forced, float temperature, uint64_t seed, float* part, float* forced_z,
-                   int32_t* out_tokens, float* out_logprobs) {
+                   int32_t* out_tokens, float* out_logprobs, int top_k, float top_p, void* cut_buf) {
   const int n_tiles = (V + kSampleTile - 1) / kSampleTile;
   const int greedy = !(temperature > 0.f);
   const float inv_t = greedy ? 1.0f : 1.0f / temperature;
   dim3 grid(n_tiles, M);
+  const OrderCut* cuts = nullptr;
+  if (!greedy && sample_is_truncated(V, top_k, top_p)) {  // greedy ignores the cuts: the argmax is always kept
+    CutRow* ws = (CutRow*)cut_buf;
+    OrderCut* cut_k = (OrderCut*)((char*)cut_buf + (size_t)M * sizeof(CutRow));  // [M] after top-k, then [M] final
+    OrderCut* cut_p = cut_k + M;
+    int slices = 512 / M;
+    slices = slices < 1 ? 1 : (slices > 64 ? 64 : slices);
+    const dim3 sg(slices, M);
+    cut_zero_kernel<<<dim3(8, M), 256, 0, st>>>(ws);
+    cut_kmax_kernel<<<sg, 256, 0, st>>>(logits, V, ws);
+    const bool use_k = top_k > 0 && top_k < V, use_p = top_p > 0.0f && top_p < 1.0f;
+    const OrderCut* allowed = nullptr;
+    if (use_k) {
+      for (int stage = 0; stage <= kCutStages; ++stage)
+        cut_stage_kernel<false><<<stage < kCutStages ? sg : dim3(1, M), 256, 0, st>>>(logits, V, inv_t, stage, 0,
+                                                                                    (unsigned long long)top_k, 0ull, nullptr, ws, cut_k);
+      allowed = cut_k;
+      cuts = cut_k;
+    }
+    if (use_p) {
+      const unsigned long long P = (unsigned long long)(top_p * 4294967296.0f);  // exact scaling, truncated
+      for (int stage = 0; stage <= kCutStages; ++stage)
+        cut_stage_kernel<true><<<stage < kCutStages ? sg : dim3(1, M), 256, 0, st>>>(logits, V, inv_t, stage, 1, 1ull, P, allowed,
+                                                                                   ws, cut_p);
+      cuts = cut_p;
+    }
+  }
   sample_stage1_kernel<<<grid, 256, 0, st>>>(logits, V, rows, pos_offset, inv_t, greedy, (uint32_t)(seed & 0xffffffffu),
-                                             (uint32_t)(seed >> 32), forced, forced_z, part, n_tiles);
+                                             (uint32_t)(seed >> 32), forced, forced_z, part, n_tiles, cuts);
   sample_stage2_kernel<<<M, 1024, 0, st>>>(part, n_tiles, V, forced, forced_z, inv_t, out_tokens, out_logprobs);
 }
 

@@ -6,6 +6,13 @@
 //   g    = -flog(-flog(u)),  flog(x): x = m 2^e with m in [sqrt(1/2), sqrt(2)), f = m - 1,
 //          p = Horner(c8..c0; f) with one fma per step, flog = fma(e, ln2, p * f)
 //   y_i  = fma(z_i, 1/T, g)     token = argmax y_i, lowest index on ties
+// Truncated sampling (top-k / top-p; the sampling settings of Appendix D) adds, equally exact:
+//   order  tokens by descending order_key(z_i) (total order of the bit patterns), equal keys by ascending index
+//   W_i    = fexp_weight(fma(z_i, 1/T, -(z_max * 1/T))): exp scaled to 2^32 and truncated to an integer --
+//            t = x log2e, n = rint(t), f = fma(x, log2e, -n), 2^f by the degree-6 Taylor polynomial in f ln2
+//            (one fma per step), scaled by 2^(n+32); 0 for x <= -22
+//   top-k  the first min(k, V) tokens of the order;  top-p: with P = trunc(p 2^32), S = mass of those tokens,
+//          T = max(1, floor(P S / 2^32)), the shortest prefix of the order whose mass reaches T
 #pragma once
 #include "device_utils.h"
 
@@ -50,6 +57,34 @@ __device__ __forceinline__ float gumbel(uint32_t bits) {
   const float t = -flog(u);
   return -flog(t);
 }
+
+__device__ __forceinline__ uint32_t order_key(float z) {  // ascending key = ascending value
+  const uint32_t b = __float_as_uint(z);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float order_value(uint32_t key) {  // inverse of order_key
+  return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
+}
+__device__ __forceinline__ unsigned long long fexp_weight(float x) {
+  if (!(x > -22.0f)) return 0ull;
+  const float t = __fmul_rn(x, 0x1.715476p+0f);
+  const float n = rintf(t);
+  const float f = __fmaf_rn(x, 0x1.715476p+0f, -n);
+  float p = 0x1.430912p-13f;
+  p = __fmaf_rn(p, f, 0x1.5d87fep-10f);
+  p = __fmaf_rn(p, f, 0x1.3b2ab6p-7f);
+  p = __fmaf_rn(p, f, 0x1.c6b08ep-5f);
+  p = __fmaf_rn(p, f, 0x1.ebfbe0p-3f);
+  p = __fmaf_rn(p, f, 0x1.62e430p-1f);
+  p = __fmaf_rn(p, f, 1.0f);
+  return (unsigned long long)ldexpf(p, (int)n + 32);
+}
+// A cut of the order: token i with key k is kept iff it does not come after (key, idx).
+struct OrderCut {
+  uint32_t key;
+  int32_t idx;
+};
+__device__ __forceinline__ bool kept_by(OrderCut c, uint32_t k, int i) { return k > c.key || (k == c.key && i <= c.idx); }
 
 struct Best {
   float y;   // perturbed score

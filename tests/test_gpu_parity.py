@@ -131,6 +131,60 @@ def test_tiny_fp32_sampled_rollout_ids_bit_exact_given_logits(amd):
     ro.close()
 
 
+@pytest.mark.parametrize("vocab,bf16", [(4096, False), (151936, True), (1000, False)])
+def test_truncated_sampler_cut_and_draw_bit_exact(amd, vocab, bf16):
+    """Top-k / top-p (Appendix D's sampling settings): the kept set is probed through forced tokens on both sides of
+    the oracle's cut (finite log-probability inside, -inf outside), and the drawn ids equal the oracle's."""
+    ro = _sampler_model(amd, vocab, bf16)
+    n = 8
+    z = ri.normal((n, vocab), 2.0, 6, 71)
+    z[1, 17] = z[1, 900] = z[1, 333] = z[1, 4]          # equal logits that a cut can fall between
+    z[2, :] = 0.25                                        # all equal: the lowest ids are kept
+    z[3, 5] = float("-inf")
+    z[4] *= 4.0                                           # peaked: top-p keeps a handful
+    z[5] *= 0.05                                          # flat: top-p keeps almost everything
+    z[6, 100:140] = z[6, 99]                              # a long run of ties
+    z[7, 7] = -0.0
+    z[7, 8] = 0.0
+    zd = z.to(DEV)
+    seqs, poss = [3, 0, 7, 63, 1, 2, 9, 11], [0, 1, 65535, 77, 2048, 16383, 5, 6]
+    settings = [(0.6, 0, 0.95), (0.7, 0, 0.8), (1.0, 50, 0.0), (1.0, 1, 0.0), (1.3, 40, 0.9), (1.0, 0, 1e-6),
+                (0.5, vocab - 1, 0.999), (1.0, 3, 0.5)]
+    for T, k, p in settings:
+        seed = 1000 + k
+        tok, lp = ro.rl_sample_logits(zd, seqs, poss, T, seed, top_k=k, top_p=p)
+        torch.cuda.synchronize()
+        inside, outside = [], []
+        for r in range(n):
+            t_ref, lp_ref, kept = orc.sample_truncated(z[r].numpy(), T, k, p, seed, seqs[r], poss[r])
+            assert int(tok[r]) == t_ref, (T, k, p, r, kept)
+            assert abs(float(lp[r]) - lp_ref) < 1e-5 * max(1.0, abs(lp_ref)), (T, k, p, r, float(lp[r]), lp_ref)
+            keep = orc.truncation(z[r].numpy(), float(np.float32(1.0) / np.float32(T)), k, p).astype(bool)
+            keys = np.array([orc.order_key(v) for v in z[r].numpy()], np.int64)
+            order = np.lexsort((np.arange(vocab), -keys))
+            assert keep[order[:kept]].all() and kept == keep.sum()
+            inside.append(int(order[kept - 1]))                          # last kept token
+            outside.append(int(order[kept]) if kept < vocab else -1)     # first one cut
+        for forced in (inside, outside):
+            f = torch.tensor(forced, dtype=torch.int32, device=DEV)
+            tok, lp = ro.rl_sample_logits(zd, seqs, poss, T, seed, forced=f, top_k=k, top_p=p)
+            torch.cuda.synchronize()
+            for r in range(n):
+                t_ref, lp_ref, _ = orc.sample_truncated(z[r].numpy(), T, k, p, seed, seqs[r], poss[r], forced=forced[r])
+                assert int(tok[r]) == t_ref
+                if np.isfinite(lp_ref):
+                    assert abs(float(lp[r]) - lp_ref) < 1e-5 * max(1.0, abs(lp_ref)), (T, k, p, r)
+                else:
+                    assert float(lp[r]) == lp_ref, (T, k, p, r, forced[r], float(lp[r]))
+    # no cut requested, or greedy: exactly the plain sampler
+    for T, k, p in [(0.9, 0, 1.0), (0.9, vocab, 0.0), (0.0, 5, 0.5)]:
+        a = ro.rl_sample_logits(zd, seqs, poss, T, 77, top_k=k, top_p=p)
+        b = ro.rl_sample_logits(zd, seqs, poss, T, 77)
+        torch.cuda.synchronize()
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    ro.close()
+
+
 # ------------------------------------------------------------------------- bf16, one layer at 8B dimensions
 def _layer_case(amd, ctxs, seed, max_rows=None, shuffle=None):
     """Import random N(0,1) bf16 KV of the given lengths, run one decode step on N(0,1) hidden rows."""
@@ -486,6 +540,37 @@ def test_tiny_fp32_ragged_continuous_batch(amd):
             assert rel_inf(zg, z) < 1e-4, (idx, t)
             t_ref, lp_ref = orc.sample(zg, 1.0, seed, slot, pos)
             assert t_ref == a["toks"][t] and abs(lp_ref - a["lps"][t]) < 1e-5, (idx, t)
+    ro.close()
+
+
+@pytest.mark.parametrize("kind", ["tiny_f32", "small_bf16"])
+def test_rollout_with_truncated_sampling_reproduced_from_logits(amd, kind):
+    """Prefill + decode with temperature 0.6 / top-p 0.95 (and a top-k step): every drawn id and log-probability is
+    what the oracle's truncated sampler gives on the logits the step produced."""
+    if kind == "tiny_f32":
+        shape = ri.SHAPES["tiny"]
+        w, _ = make_both(shape, 81)
+    else:
+        shape = dict(ri.SHAPES["layer8b"], n_layers=2, hidden=512, n_q=4, n_kv=1, ffn=768, vocab=8192)
+        w, _ = make_both(shape, 81, std=0.05)
+    V = shape["vocab"]
+    ro = amd.Rollout(shape, to_device(w), max_seqs=8, max_ctx=96, max_rows=8, kv_pages=40)
+    lens = [20, 33, 7]
+    prompts = [ri.tokens((n,), V, 81, 970 + i).tolist() for i, n in enumerate(lens)]
+    ids, seed = [4, 0, 6], 4242
+    tok, lp = ro.rl_prefill(ids, prompts, 0.6, seed, top_p=0.95)
+    z = torch.empty(3, V, device=DEV)
+    pos = list(lens)
+    for step in range(12):
+        k, p = (0, 0.95) if step % 3 else (30, 0.8)
+        tok, lp = ro.rl_decode_step(ids, tok, 0.6, seed, debug_logits=z, top_k=k, top_p=p)
+        torch.cuda.synchronize()
+        pos = [q + 1 for q in pos]
+        zc = z.cpu().numpy()
+        for r in range(3):
+            t_ref, lp_ref, kept = orc.sample_truncated(zc[r], 0.6, k, p, seed, ids[r], pos[r])
+            assert int(tok[r]) == t_ref and 1 <= kept < V, (step, r)
+            assert abs(float(lp[r]) - lp_ref) < 1e-5 * max(1.0, abs(lp_ref))
     ro.close()
 
 
