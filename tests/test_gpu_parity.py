@@ -185,6 +185,59 @@ def test_truncated_sampler_cut_and_draw_bit_exact(amd, vocab, bf16):
     ro.close()
 
 
+def test_fork_errors_and_long_run_of_steps(amd):
+    """rl_seq_fork's error paths leave the pool untouched; a forked sequence continues exactly like its source
+    (fp32: same logits at the same position); 200 steps run through the 64-slot metadata ring several times."""
+    B = amd.binding
+    shape = ri.SHAPES["tiny"]
+    w, wn = make_both(shape, 52)
+    ro = amd.Rollout(shape, to_device(w), max_seqs=6, max_ctx=256, max_rows=6, kv_pages=48)
+    p = ri.tokens((21,), shape["vocab"], 52, 941).tolist()
+    tok, _ = ro.rl_prefill([0], [p], 0.0, 0)
+    free0 = ro.rl_kv_stats()[0]
+    for bad, status in [((1, [2]), B.RL_ERR_BAD_SEQ),        # source not active
+                        ((0, [0]), B.RL_ERR_BAD_SEQ),        # target already active
+                        ((0, [6]), B.RL_ERR_BAD_SEQ),        # id out of range
+                        ((0, [2, 2]), B.RL_ERR_INVALID_ARG)]:
+        with pytest.raises(B.RLError) as e:
+            ro.rl_seq_fork(*bad)
+        assert e.value.status == status and ro.rl_kv_stats()[0] == free0
+    small = amd.Rollout(shape, to_device(w), max_seqs=6, max_ctx=64, max_rows=6, kv_pages=3)
+    small.rl_prefill([0], [p], 0.0, 0)                        # 2 pages, 1 free; a fork needs one page per member
+    with pytest.raises(B.RLError) as e:
+        small.rl_seq_fork(0, [1, 2])
+    assert e.value.status == B.RL_ERR_KV_FULL and small.rl_kv_stats() == (1, 3)
+    small.rl_seq_fork(0, [1])
+    assert small.rl_kv_stats() == (0, 3) and small.rl_seq_len(1) == 21
+    small.close()
+    ro.rl_seq_fork(0, [3, 5])
+    assert ro.rl_kv_stats()[0] == free0 - 2 and ro.rl_seq_len(5) == 21
+    ids = [0, 3, 5]
+    cur = torch.cat([tok, tok, tok])
+    z = torch.empty(3, shape["vocab"], device=DEV)
+    om = orc.OracleModel(dims_of(shape), wn, max_ctx=256)
+    zo = om.prefill(0, p)
+    for step in range(200):
+        feed = cur
+        cur, lp = ro.rl_decode_step(ids, feed, 1.0, 7, debug_logits=z)
+        if step < 3 or step == 199:
+            torch.cuda.synchronize()
+            zc = z.cpu().numpy()
+            if step == 0:                                     # same history, same token: the three rows are equal
+                assert np.array_equal(zc[0], zc[1]) and np.array_equal(zc[0], zc[2])
+                zo = om.forward_token(0, int(feed[0]))
+                assert rel_inf(zc[0], zo) < 1e-4
+            for r in range(3):
+                t_ref, lp_ref = orc.sample(zc[r], 1.0, 7, ids[r], 22 + step)
+                assert int(cur[r]) == t_ref and abs(float(lp[r]) - lp_ref) < 1e-5 * max(1.0, abs(lp_ref))
+    torch.cuda.synchronize()
+    assert [ro.rl_seq_len(i) for i in ids] == [221, 221, 221]
+    assert len({int(t) for t in cur}) > 1                     # different random streams: the samples have diverged
+    ro.rl_free_seqs(ids)
+    assert ro.rl_kv_stats() == (48, 48)
+    ro.close()
+
+
 # ------------------------------------------------------------------------- bf16, one layer at 8B dimensions
 def _layer_case(amd, ctxs, seed, max_rows=None, shuffle=None):
     """Import random N(0,1) bf16 KV of the given lengths, run one decode step on N(0,1) hidden rows."""
