@@ -53,7 +53,10 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=512)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", choices=["full", "layer", "copy"], default="full")
+    ap.add_argument("--workload", choices=["full", "layer", "copy", "ragged"], default="full")
+    ap.add_argument("--length-scale", type=float, default=1.0,
+                    help="ragged workload: multiply the drawn prompt and final lengths (1.0: prompts U[256,1024], "
+                         "final lengths U[1024,8192])")
     ap.add_argument("--profile-steps", type=int, default=8, help="extra steps run with per-kernel events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
@@ -159,6 +162,51 @@ def main():
         dr = (time.perf_counter() - t0) / args.steps
         print(json.dumps({"workload": "copy_1GiB", "bytes_read": n, "bytes_written": n, "us_per_copy": dt * 1e6,
                           "copy_GBs_read_plus_write": 2 * n / dt / 1e9, "read_only_sum_GBs": n / dr / 1e9}))
+        return
+
+    if args.workload == "ragged":
+        # Whole rollout with ragged lengths and continuous batching: 16 prompts x 8 samples, prompt length per prompt
+        # U[256,1024], final length per sequence U[1024,8192] (pre-drawn), sequences retire one by one.
+        from paper_2510_17891_amd import generate_groups, group_page_need
+        shape = ri.SHAPES["full8b"]
+        n_prompts, G = 16, 8
+        sc = args.length_scale
+        p_len = [max(1, int(v * sc)) for v in ri.lengths(n_prompts, 256, 1024, seed, 910).tolist()]
+        f_len = [max(2, int(v * sc)) for v in ri.lengths(n_prompts * G, 1024, 8192, seed, 911).tolist()]
+        limits = [max(1, f_len[k] - p_len[k // G]) for k in range(n_prompts * G)]
+        prompts = [ri.tokens((n,), shape["vocab"], seed, 920 + i).tolist() for i, n in enumerate(p_len)]
+        pages = sum(group_page_need(p_len[i], limits[i * G:(i + 1) * G]) for i in range(n_prompts))
+        max_ctx = (max(p_len[k // G] + limits[k] for k in range(n_prompts * G)) + 15) // 16 * 16
+        w = ri.make_weights(shape, seed, device=dev, dtype=torch.bfloat16)
+        ro = Rollout(shape, w, max_seqs=n_prompts * G, max_ctx=max_ctx, max_rows=256, kv_pages=pages)
+        del w
+        torch.cuda.empty_cache()
+        torch.cuda.synchronize()
+        trace = []
+        t0 = time.perf_counter()
+        toks, lps = generate_groups(ro, prompts, G, limits, 1.0, seed, on_step=lambda s, n: trace.append(n))
+        elapsed = time.perf_counter() - t0
+        n_tok = sum(len(t) for t in toks)
+        assert [len(t) for t in toks] == limits
+        # algorithmic bytes: weights once per step + every cached token of every stepped sequence (shared prompt pages
+        # counted per sequence, as the per-sequence formula does)
+        steps = len(trace)
+        kv_tokens = sum(sum(range(p_len[k // G] + 1, p_len[k // G] + limits[k])) for k in range(n_prompts * G))
+        wbytes = 2 * (shape["n_layers"] * (shape["hidden"] * (shape["n_q"] + 2 * shape["n_kv"]) * shape["head_dim"]
+                                          + shape["n_q"] * shape["head_dim"] * shape["hidden"]
+                                          + 3 * shape["ffn"] * shape["hidden"]) + shape["vocab"] * shape["hidden"])
+        total_bytes = steps * wbytes + kv_tokens * shape["n_layers"] * shape["n_kv"] * 2 * shape["head_dim"] * 2
+        print(json.dumps({
+            "metric": "generated tokens/s (8B-shaped bf16 decode) + % peak HBM GB/s, 1 MI355X",
+            "value": n_tok / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": 0,
+            "ms_per_step": elapsed / max(1, steps) * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": f"full8b_ragged_{n_prompts}x{G}_scale{sc}", "prompts": "U[256,1024] per prompt",
+                       "final_lengths": "U[1024,8192] per sequence", "generated_tokens": n_tok, "kv_pages": pages,
+                       "prefill": "inside the timed region, prompts run once per group", "temperature": 1.0},
+            "whole_run_s": elapsed, "hbm_fraction_per_sequence_formula": total_bytes / elapsed / (HBM_PEAK_GBS * 1e9),
+            "active_sequences_first_mid_last": [trace[0], trace[len(trace) // 2], trace[-1]] if trace else None}))
+        ro.close()
         return
 
     if args.workload == "full":

@@ -1,0 +1,166 @@
+"""Group rollout loop on top of the C boundary: G sampled outputs per prompt (Section 2.3), generated with
+continuous batching inside a fixed KV pool.
+
+This is the host step scheduler: it decides which groups are resident, which sequences are stepped, and when pages
+go back to the pool.  Every arithmetic step (prefill, decode, sampling, log-probabilities) happens inside the
+library; the loop only marshals ids and keeps views of the per-step output rows.
+
+Scheduling never changes results: sequence (i, j) always has id i*G + j, its random stream is keyed by that id and
+the token position, and the kernels are batch-invariant, so the tokens and log-probabilities are the same whatever
+the pool size, admission order or batch composition.
+"""
+import torch
+
+from .binding import RLError, RL_ERR_KV_FULL
+
+KV_BLOCK = 16
+
+
+def _pages(tokens):
+    return (tokens + KV_BLOCK - 1) // KV_BLOCK
+
+
+def group_page_need(prompt_len, new_tokens):
+    """Pages a group holds at its largest: the prompt's full pages once, and per member the pages that its partial
+    prompt page and its own tokens add.  The last sampled token is never fed back, so a member caches
+    prompt_len + new - 1 tokens at most."""
+    shared = prompt_len // KV_BLOCK
+    return shared + sum(max(_pages(prompt_len + max(n, 1) - 1), _pages(prompt_len)) - shared for n in new_tokens)
+
+
+def generate_groups(ro, prompts, group_size, max_new_tokens, temperature=1.0, seed=0, top_k=0, top_p=0.0,
+                    eos_id=None, on_step=None):
+    """Sample `group_size` outputs for every prompt.
+
+    prompts         list of token-id lists
+    max_new_tokens  int, or one int per sequence (len(prompts) * group_size, group-major): the length limit of
+                    Appendix D, or pre-drawn lengths for synthetic workloads
+    eos_id          stop a sequence after it samples this id (costs one small device-to-host copy per step)
+    on_step         optional callback(step_index, n_active) for progress reporting
+
+    Returns (tokens, logprobs): per sequence a list of ids and a list of floats, group-major.
+    Needs max_seqs >= len(prompts) * group_size; groups are admitted in order whenever the pool can hold them up
+    to their length limit, so a decode step can never run out of pages; a group that cannot fit an empty pool
+    raises RLError(RL_ERR_KV_FULL).
+    """
+    G = group_size
+    n_seq = len(prompts) * G
+    limits = [int(max_new_tokens)] * n_seq if isinstance(max_new_tokens, int) else [int(v) for v in max_new_tokens]
+    assert len(limits) == n_seq and all(v >= 1 for v in limits)
+    assert ro.cfg.max_seqs >= n_seq, "one sequence id per output is needed"
+    max_rows = ro.cfg.max_rows
+    assert G <= max_rows, "a group is prefilled in one call"
+    dev = ro.device
+    total_pages = ro.rl_kv_stats()[1]
+    reserved = 0                       # pages promised to resident groups
+    need = [group_page_need(len(p), limits[i * G:(i + 1) * G]) for i, p in enumerate(prompts)]
+    next_group = 0
+    members_left = {}                  # group -> sequences still running
+    active = []                        # sequence ids in batch order
+    count = [0] * n_seq                # tokens generated so far
+    where = {}                         # sequence id -> (device row tensor, column) of its latest token
+    rows_t, rows_lp, rows_ids = [], [], []   # per call: device outputs and the ids they belong to
+    step = 0
+
+    def admit():
+        """Prefill waiting groups while the pool can hold them; members that are already done leave at once."""
+        nonlocal next_group, reserved
+        first = len(rows_ids)
+        admit_more()
+        done = []
+        for ids, tok in zip(rows_ids[first:], rows_t[first:]):
+            done += check_finished(ids, tok)
+        retire(done)
+
+    def admit_more():
+        nonlocal next_group, reserved
+        while next_group < len(prompts):
+            g = next_group
+            if need[g] > total_pages:
+                raise RLError(RL_ERR_KV_FULL, f"group {g} needs {need[g]} pages, the pool has {total_pages}")
+            if reserved + need[g] > total_pages:
+                return
+            ids = list(range(g * G, (g + 1) * G))
+            tok, lp = ro.rl_prefill_groups(ids, G, [prompts[g]], temperature, seed, top_k=top_k, top_p=top_p)
+            reserved += need[g]
+            next_group += 1
+            rows_t.append(tok)
+            rows_lp.append(lp)
+            rows_ids.append(ids)
+            members_left[g] = G
+            for c, s in enumerate(ids):
+                count[s] = 1
+                where[s] = (tok, c)
+                active.append(s)
+
+    def retire(finished):
+        nonlocal reserved
+        if not finished:
+            return
+        ro.rl_free_seqs(finished)
+        gone = set(finished)
+        active[:] = [s for s in active if s not in gone]
+        for s in finished:
+            where.pop(s)
+            g = s // G
+            members_left[g] -= 1
+            if members_left[g] == 0:   # the reservation covers the group's shared pages until its last member leaves
+                reserved -= need[g]
+                del members_left[g]
+
+    def check_finished(ids, tok_row):
+        host = tok_row.cpu().tolist() if eos_id is not None else None
+        done = []
+        for c, s in enumerate(ids):
+            if count[s] >= limits[s] or (host is not None and host[c] == eos_id):
+                done.append(s)
+        return done
+
+    while active or next_group < len(prompts):
+        admit()
+        if not active:
+            continue
+        for b0 in range(0, len(active), max_rows):
+            ids = active[b0:b0 + max_rows]
+            # the token each sequence sampled last is what it is fed now
+            src = [where[s] for s in ids]
+            if all(t is src[0][0] for t, _ in src) and [c for _, c in src] == list(range(len(ids))) \
+                    and src[0][0].numel() == len(ids):
+                feed = src[0][0]                          # same batch as the call that produced it
+            else:                                         # the batch changed: one gather over the rows involved
+                base, parts, index = {}, [], []
+                for t, c in src:
+                    if id(t) not in base:
+                        base[id(t)] = sum(p.numel() for p in parts)
+                        parts.append(t)
+                    index.append(base[id(t)] + c)
+                feed = torch.cat(parts)[torch.tensor(index, device=dev)]
+            tok, lp = ro.rl_decode_step(ids, feed, temperature, seed, top_k=top_k, top_p=top_p)
+            rows_t.append(tok)
+            rows_lp.append(lp)
+            rows_ids.append(list(ids))
+            for c, s in enumerate(ids):
+                count[s] += 1
+                where[s] = (tok, c)
+        n_calls = (len(active) + max_rows - 1) // max_rows
+        finished = []
+        for ids, tok in zip(rows_ids[-n_calls:], rows_t[-n_calls:]):
+            finished += check_finished(ids, tok)
+        retire(finished)
+        step += 1
+        if on_step is not None:
+            on_step(step, len(active))
+
+    torch.cuda.synchronize(dev)
+    tokens = [[] for _ in range(n_seq)]
+    logprobs = [[] for _ in range(n_seq)]
+    all_t = torch.cat(rows_t).cpu().tolist() if rows_t else []
+    all_lp = torch.cat(rows_lp).cpu().tolist() if rows_lp else []
+    k = 0
+    for ids in rows_ids:
+        for s in ids:
+            if len(tokens[s]) < limits[s] and not (eos_id is not None and tokens[s] and tokens[s][-1] == eos_id):
+                tokens[s].append(all_t[k])
+                logprobs[s].append(all_lp[k])
+            k += 1
+    return tokens, logprobs

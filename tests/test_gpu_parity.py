@@ -627,6 +627,54 @@ def test_rollout_with_truncated_sampling_reproduced_from_logits(amd, kind):
     ro.close()
 
 
+def test_group_rollout_loop_is_schedule_independent_and_matches_oracle(amd):
+    """generate_groups: 5 prompts x 3 samples with pre-drawn ragged lengths in a pool that holds two groups at a
+    time.  The tokens and log-probabilities equal those of a run with a pool for everything (the schedule does not
+    matter), sequence by sequence the oracle's teacher-forced logits reproduce every draw, and with an end token
+    the outputs stop right after it."""
+    shape = ri.SHAPES["tiny"]
+    w, wn = make_both(shape, ri.BASE_SEED + 4)
+    G, seed = 3, 777
+    p_len = ri.lengths(5, 5, 40, seed, 962).tolist()
+    prompts = [ri.tokens((n,), shape["vocab"], seed, 980 + i).tolist() for i, n in enumerate(p_len)]
+    limits = ri.lengths(5 * G, 1, 30, seed, 963).tolist()
+    limits[4] = 1                                                  # a sequence that ends with its first token
+    needs = [amd.group_page_need(len(p), limits[i * G:(i + 1) * G]) for i, p in enumerate(prompts)]
+    wd = to_device(w)
+    small = amd.Rollout(shape, wd, max_seqs=15, max_ctx=80, max_rows=4, kv_pages=max(needs) + sorted(needs)[1])
+    big = amd.Rollout(shape, wd, max_seqs=15, max_ctx=80, max_rows=15, kv_pages=sum(needs))
+    actives = []
+    ta, la = amd.generate_groups(small, prompts, G, limits, 1.0, seed, on_step=lambda s, n: actives.append(n))
+    tb, lb = amd.generate_groups(big, prompts, G, limits, 1.0, seed)
+    assert ta == tb and la == lb
+    assert [len(t) for t in ta] == limits
+    assert small.rl_kv_stats()[0] == small.rl_kv_stats()[1] and big.rl_kv_stats()[0] == big.rl_kv_stats()[1]
+    assert max(actives) <= 2 * G + G and min(actives) >= 0 and len(actives) > max(limits)   # several waves
+    for k in (0, 4, 7, 14):                                       # oracle on whole sequences
+        i = k // G
+        om = orc.OracleModel(dims_of(shape), wn, max_ctx=80)
+        z = om.prefill(0, prompts[i])
+        pos = p_len[i]
+        for t in range(limits[k]):
+            t_ref, lp_ref = orc.sample(z, 1.0, seed, k, pos)
+            assert t_ref == ta[k][t] and abs(lp_ref - la[k][t]) < 2e-5, (k, t)
+            if t + 1 < limits[k]:
+                z = om.forward_token(0, ta[k][t])
+                pos += 1
+    # an end token: every output is cut right after its first occurrence, and is otherwise unchanged
+    flat = [t for seq in ta for t in seq[:-1]]
+    eos = max(set(flat), key=flat.count)
+    tc, lc = amd.generate_groups(small, prompts, G, limits, 1.0, seed, eos_id=eos)
+    hit = 0
+    for k in range(5 * G):
+        cut = ta[k].index(eos) + 1 if eos in ta[k] else len(ta[k])
+        assert tc[k] == ta[k][:cut] and lc[k] == la[k][:cut]
+        hit += cut < len(ta[k])
+    assert hit >= 1
+    small.close()
+    big.close()
+
+
 # ------------------------------------------------------------------ grouped sampling with shared prompt pages
 @pytest.mark.parametrize("kind", ["tiny_f32", "small_bf16"])
 def test_prefill_groups_equals_independent_prefill(amd, kind):
