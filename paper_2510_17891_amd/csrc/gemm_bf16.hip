@@ -217,6 +217,136 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const u32x4_t* __restric
   }
 }
 
+// The K-split kernel with a 128-row weight tile (two 64-row pairs, four 32-row blocks per wave).  Every block reads
+// the whole activation panel once, so halving the number of blocks halves that traffic; from about 48 rows on the
+// panel reads of the 64-row tiling are as large as the weight stream itself and the launch is bound by what L2
+// delivers.  Used where the halved grid still fills the chip.  Same K ranges per wave, same order: same bits.
+template <int MB>
+struct FragsW {
+  u32x4_t a[4][4];
+  u32x4_t b[MB][4];
+};
+
+template <int MB, int EPI, int ST>
+__global__ __launch_bounds__(256, 1) void gemm_bf16_wide_kernel(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ W,
+                                                              void* __restrict__ out, int M, int N, int K, int kb_per_wave,
+                                                              SampleEpilogue se) {
+  __shared__ float red[4][16][64];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int KB = K >> 6;
+  const int m_blk0 = blockIdx.z * MB;
+  const int n_blocks_m = (M + 31) >> 5;
+  const int n_tiles = EPI == kEpiSwiGLU ? (N >> 5) : (N >> 6);
+  int tile[2], rb[4];
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    tile[p] = min((int)blockIdx.x * 2 + p, n_tiles - 1);  // an odd tile count: the last block's second pair shadows its first
+    if (EPI == kEpiSwiGLU) { rb[2 * p] = tile[p]; rb[2 * p + 1] = tile[p] + (N >> 5); }
+    else                   { rb[2 * p] = tile[p] * 2; rb[2 * p + 1] = tile[p] * 2 + 1; }
+  }
+  const bool second_valid = (int)blockIdx.x * 2 + 1 < n_tiles;
+  const u32x4_t* wp[4];
+#pragma unroll
+  for (int b = 0; b < 4; ++b) wp[b] = W + (size_t)rb[b] * KB * 256 + lane;
+  const u32x4_t* xb[MB];
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) {
+    int b = m_blk0 + mb;
+    if (b >= n_blocks_m) b = n_blocks_m - 1;  // clamp: surplus column blocks are computed but never stored
+    xb[mb] = X + (size_t)b * KB * 256 + lane;
+  }
+  f32x16_t acc[4][MB];
+#pragma unroll
+  for (int b = 0; b < 4; ++b)
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[b][mb][r] = 0.f;
+
+  auto load = [&](FragsW<MB>& f, int kb) __attribute__((always_inline)) {
+    const int o = kb * 256;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+#pragma unroll
+      for (int b = 0; b < 4; ++b) f.a[b][t] = __builtin_nontemporal_load(wp[b] + o + t * 64);
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) f.b[mb][t] = xb[mb][o + t * 64];
+    }
+  };
+  auto mma = [&](const FragsW<MB>& f) __attribute__((always_inline)) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+          acc[b][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, f.a[b][t]),
+                                                               __builtin_bit_cast(bf16x8_t, f.b[mb][t]), acc[b][mb], 0, 0, 0);
+  };
+
+  const int kb0 = (blockIdx.y * 4 + wave) * kb_per_wave;
+  const int n = kb_per_wave;
+  FragsW<MB> f[ST];
+#pragma unroll
+  for (int s = 0; s < ST; ++s) load(f[s], kb0 + s);  // the launcher guarantees ST <= n
+  const int full = n / ST, rem = n - full * ST;
+  int b = 0;
+  for (int r = 0; r + 1 < full; ++r) {  // steady state: every buffer is refilled
+#pragma unroll
+    for (int s = 0; s < ST; ++s) {
+      mma(f[s]);
+      __builtin_amdgcn_sched_barrier(0);
+      load(f[s], kb0 + b + s + ST);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    b += ST;
+  }
+  if (full > 0) {  // last full round: refill only what the remainder round will use
+#pragma unroll
+    for (int s = 0; s < ST; ++s) {
+      mma(f[s]);
+      __builtin_amdgcn_sched_barrier(0);
+      if (s < rem) load(f[s], kb0 + b + s + ST);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+#pragma unroll
+  for (int s = 0; s < ST; ++s)
+    if (s < rem) mma(f[s]);
+
+  // ---- add the four waves' accumulators (fixed order) and write: column block mb is finished by wave mb % 4 ----
+  const int col = lane & 31, hb = lane >> 5;
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) {
+    float sum[4][16];
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+      __syncthreads();
+#pragma unroll
+      for (int r = 0; r < 16; ++r) red[wave][r][lane] = acc[nb][mb][r];
+      __syncthreads();
+      if (wave == (mb & 3)) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          sum[nb][r] = (red[0][r][lane] + red[1][r][lane]) + (red[2][r][lane] + red[3][r][lane]);
+      }
+    }
+    if (wave != (mb & 3)) continue;
+    const int m = (m_blk0 + mb) * 32 + col;
+    if (m >= M) continue;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      if (p == 1 && !second_valid) break;
+      float pair[2][16];
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) pair[nb][r] = sum[2 * p + nb][r];
+      store_block<EPI>(pair, m, hb, rb[2 * p], rb[2 * p + 1], blockIdx.y, M, N, out, se, tile[p]);
+    }
+  }
+}
+
 // Variant for 64 < M <= 256: the four waves take different batch-column blocks (MBW blocks of 32 each) instead of
 // different K quarters, so a wave needs only 32*MBW accumulator columns and the block still streams W once (the
 // four waves read the same weight tile at about the same time; only the first read leaves L2).  To keep a row's
@@ -567,6 +697,28 @@ void launch_mb(hipStream_t s, const void* X, const void* W, void* out, int M, in
   }
 }
 
+template <int MB, int ST>
+void launch_wide(hipStream_t s, const void* X, const void* W, void* out, int M, int N, int K, int epi, bool allow_split,
+                 const SampleEpilogue& se) {
+  Plan p = make_plan(N, K, epi, allow_split);  // same K split as the narrow tiling: bit-identical results
+  const int m_tiles = (M + 32 * MB - 1) / (32 * MB);
+  const int tiles = epi == kEpiSwiGLU ? (N >> 5) : (N >> 6);
+  dim3 grid((tiles + 1) / 2, epi == kEpiPartial ? p.splits : 1, m_tiles);
+  if (epi == kEpiSwiGLU)
+    gemm_bf16_wide_kernel<MB, kEpiSwiGLU, ST><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
+  else if (epi == kEpiSample)
+    gemm_bf16_wide_kernel<MB, kEpiSample, ST><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
+  else
+    gemm_bf16_wide_kernel<MB, kEpiPartial, ST><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
+}
+
+// Blocks of the 128-row tiling for (N, K): it is used where they still fill the chip.
+int wide_blocks(int N, int K, int epi, bool allow_split) {
+  const Plan p = make_plan(N, K, epi, allow_split);
+  const int tiles = epi == kEpiSwiGLU ? (N >> 5) : (N >> 6);
+  return ((tiles + 1) / 2) * (epi == kEpiPartial ? p.splits : 1);
+}
+
 }  // namespace
 
 int gemm_bf16_splits(int N, int K, int epi) { return make_plan(N, K, epi, true).splits; }
@@ -657,7 +809,13 @@ void launch_gemm_bf16(hipStream_t s, const void* X, const void* W, void* out, in
   static const SampleEpilogue none{};
   const SampleEpilogue& e = se ? *se : none;
   if (epi == kEpiSample) allow_split = false;
-  if (M <= 32) launch_st<1>(s, X, W, out, M, N, K, epi, allow_split, 4, e);
+  // 128-row tiles for the K-split projections whose halved grid still fills the chip (QKV at the 8B shape: 16 -> 15 us
+  // at 32 rows, 20.5 -> 17.8 us at 64); measured a loss for gate/up and the output projection, which keep 64-row tiles.
+  const bool wide = epi == kEpiPartial && make_plan(N, K, epi, allow_split).splits > 1 &&
+                    wide_blocks(N, K, epi, allow_split) >= 192 && make_plan(N, K, epi, allow_split).kb_per_wave >= 2;
+  if (M <= 32 && wide) launch_wide<1, 2>(s, X, W, out, M, N, K, epi, allow_split, e);
+  else if (M <= 32) launch_st<1>(s, X, W, out, M, N, K, epi, allow_split, 4, e);
+  else if (M <= 64 && wide) launch_wide<2, 2>(s, X, W, out, M, N, K, epi, allow_split, e);
   else if (M <= 64) launch_st<2>(s, X, W, out, M, N, K, epi, allow_split, 2, e);
   else if (M <= 128) launch_cols<1>(s, X, W, out, M, N, K, epi, allow_split, e);
   else launch_cols<2>(s, X, W, out, M, N, K, epi, allow_split, e);
