@@ -10,8 +10,10 @@ namespace rl {
 
 // One batch row = one (sequence, position) pair being pushed through the decoder.
 struct RowMeta {
-  int32_t seq;  // sequence id (row of the block table, RNG stream)
-  int32_t pos;  // absolute position of the token fed in this row
+  int32_t seq;   // sequence id (row of the block table, RNG stream)
+  int32_t pos;   // absolute position of the token fed in this row
+  int32_t page;  // KV page that holds position pos (the host knows it; saves the append kernel a dependent load)
+  int32_t pad;
 };
 
 enum Dtype : int { kF32 = 0, kBF16 = 1 };

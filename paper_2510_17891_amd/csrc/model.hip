@@ -331,6 +331,8 @@ rl_status upload_decode_meta(rl_model* m, hipStream_t st, int32_t n, const int32
   for (int i = 0; i < n; ++i) {
     hr[i].seq = seq_ids[i];
     hr[i].pos = m->table->len(seq_ids[i]);
+    hr[i].page = m->table->pages(seq_ids[i])[hr[i].pos >> 4];  // reserved by admit_decode
+    hr[i].pad = 0;
     if (hr[i].pos + 1 > max_ctx) max_ctx = hr[i].pos + 1;
   }
   int32_t* hu = (int32_t*)(hs + m->lay.slot_upd);
@@ -670,6 +672,8 @@ static rl_status prefill_impl(rl_model* m, hipStream_t st, int32_t n_prompts, in
     for (int r = 0; r < M; ++r) {
       hr[r].seq = seq_ids[pi * group];
       hr[r].pos = pos;
+      hr[r].page = T.pages(hr[r].seq)[pos >> 4];
+      hr[r].pad = 0;
       ht[r] = prompt_tokens[tok_base[pi] + pos];
       if (pos + 1 > max_ctx) max_ctx = pos + 1;
       if (pos + 1 == prompt_lens[pi]) { lasts.push_back({r, pi}); ++pi; pos = 0; }
@@ -711,7 +715,7 @@ static rl_status prefill_impl(rl_model* m, hipStream_t st, int32_t n_prompts, in
     char* hs = m->host_ring + (size_t)slot * m->lay.slot_bytes;
     char* ds = m->ws + m->lay.ring + (size_t)slot * m->lay.slot_bytes;
     RowMeta* hr = (RowMeta*)hs;
-    for (int i = 0; i < n_all; ++i) { hr[i].seq = seq_ids[i]; hr[i].pos = prompt_lens[i / group]; }
+    for (int i = 0; i < n_all; ++i) { hr[i].seq = seq_ids[i]; hr[i].pos = prompt_lens[i / group]; hr[i].page = 0; hr[i].pad = 0; }
     HIP_TRY(hipMemcpyAsync(ds, hs, (size_t)n_all * sizeof(RowMeta), hipMemcpyHostToDevice, st));
     HIP_TRY(hipEventRecord(m->ring_ev[slot], st));
     m->ring_used[slot] = true;
@@ -821,6 +825,8 @@ rl_status rl_score(rl_model* m, void* stream, int32_t n, const int32_t* seq_ids,
     for (int r = 0; r < M; ++r) {
       hr[r].seq = seq_ids[si];
       hr[r].pos = pos;
+      hr[r].page = T.pages(hr[r].seq)[pos >> 4];
+      hr[r].pad = 0;
       ht[r] = tokens[tok_base[si] + pos];
       if (pos + 1 > max_ctx) max_ctx = pos + 1;
       if (pos + 1 == lens[si]) { hf[r] = 0; hf[R + r] = -1; ++si; pos = 0; }
@@ -884,7 +890,7 @@ rl_status rl_sample_logits(rl_model* m, void* stream, int32_t n, const float* lo
   char* hs = m->host_ring + (size_t)slot * m->lay.slot_bytes;
   char* ds = m->ws + m->lay.ring + (size_t)slot * m->lay.slot_bytes;
   RowMeta* hr = (RowMeta*)hs;
-  for (int i = 0; i < n; ++i) { hr[i].seq = seq_ids[i]; hr[i].pos = positions[i]; }
+  for (int i = 0; i < n; ++i) { hr[i].seq = seq_ids[i]; hr[i].pos = positions[i]; hr[i].page = 0; hr[i].pad = 0; }
   HIP_TRY(hipMemcpyAsync(ds, hs, (size_t)n * sizeof(RowMeta), hipMemcpyHostToDevice, st));
   HIP_TRY(hipEventRecord(m->ring_ev[slot], st));
   m->ring_used[slot] = true;

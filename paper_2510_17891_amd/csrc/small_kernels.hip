@@ -146,8 +146,7 @@ __global__ __launch_bounds__(64) void qk_rope_append_kernel(const float* __restr
   const bool is_q = hh < n_q, is_k = !is_q && hh < n_q + n_kv;
   // Everything that depends only on the row's (seq, pos) is requested first, so that it travels together with the
   // partial sums instead of after them.
-  int64_t page = 0;
-  if (!is_q) page = block_table[(size_t)rm.seq * max_blocks + (rm.pos >> 4)];
+  const int64_t page = rm.page;
   // lanes may own more than one pair when d/2 > 64
   for (int i = lane; i < ((half + 63) & ~63); i += 64) {
     const bool live = i < half;
