@@ -129,9 +129,9 @@ __device__ __forceinline__ void kv_store(void* pool_layer, int64_t page, int hk,
   }
 }
 
-// One wave per (row, head).  Lane i < d/2 owns the rotary pair (i, i + d/2).
+// One wave per (row, head), four heads per block.  Lane i < d/2 owns the rotary pair (i, i + d/2).
 template <bool BF16>
-__global__ __launch_bounds__(64) void qk_rope_append_kernel(const float* __restrict__ part, int S, size_t split_stride,
+__global__ __launch_bounds__(256) void qk_rope_append_kernel(const float* __restrict__ part, int S, size_t split_stride,
                                                             const void* __restrict__ q_gain,
                                                             const void* __restrict__ k_gain,
                                                             const float2* __restrict__ rope, const RowMeta* __restrict__ rows,
@@ -139,7 +139,8 @@ __global__ __launch_bounds__(64) void qk_rope_append_kernel(const float* __restr
                                                             void* __restrict__ k_pool, void* __restrict__ v_pool,
                                                             float* __restrict__ q_out, int n_q, int n_kv, int d,
                                                             int qk_norm, float eps) {
-  const int hh = blockIdx.x, r = blockIdx.y, lane = threadIdx.x;
+  const int hh = blockIdx.x * 4 + (threadIdx.x >> 6), r = blockIdx.y, lane = threadIdx.x & 63;
+  if (hh >= n_q + 2 * n_kv) return;  // wave-uniform; no barriers in this kernel
   const int half = d >> 1;
   const int n_tot = (n_q + 2 * n_kv) * d;
   const RowMeta rm = rows[r];
@@ -202,14 +203,14 @@ __global__ __launch_bounds__(64) void qk_rope_append_kernel(const float* __restr
 void launch_qk_rope_append(hipStream_t s, const Geometry& g, const float* qkv_part, int S, const void* q_gain,
                            const void* k_gain, const float2* rope_table, const RowMeta* rows,
                            const int32_t* block_table, void* k_pool_layer, void* v_pool_layer, float* q_out, int M) {
-  dim3 grid(g.n_q + 2 * g.n_kv, M);
+  dim3 grid((g.n_q + 2 * g.n_kv + 3) / 4, M);
   size_t stride = (size_t)M * (g.n_q + 2 * g.n_kv) * g.head_dim;
   if (g.dtype == kBF16)
-    qk_rope_append_kernel<true><<<grid, 64, 0, s>>>(qkv_part, S, stride, q_gain, k_gain, rope_table, rows, block_table,
+    qk_rope_append_kernel<true><<<grid, 256, 0, s>>>(qkv_part, S, stride, q_gain, k_gain, rope_table, rows, block_table,
                                                     g.max_blocks, k_pool_layer, v_pool_layer, q_out, g.n_q, g.n_kv,
                                                     g.head_dim, g.qk_norm, g.rms_eps);
   else
-    qk_rope_append_kernel<false><<<grid, 64, 0, s>>>(qkv_part, S, stride, q_gain, k_gain, rope_table, rows, block_table,
+    qk_rope_append_kernel<false><<<grid, 256, 0, s>>>(qkv_part, S, stride, q_gain, k_gain, rope_table, rows, block_table,
                                                      g.max_blocks, k_pool_layer, v_pool_layer, q_out, g.n_q, g.n_kv,
                                                      g.head_dim, g.qk_norm, g.rms_eps);
 }
