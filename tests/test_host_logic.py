@@ -229,3 +229,34 @@ def test_shared_attention_plan(st):
     st.st_activate(t, 8)
     assert st.st_prefix_id(t, 8) == 0
     st.st_destroy(t)
+
+
+def test_group_page_need_matches_the_allocator(st):
+    """The rollout loop admits a group when the pool can hold it up to its length limits; its estimate must equal what
+    the allocator really hands out when the group is prefilled (shared full pages, one partial-page copy per member)
+    and every member is decoded to its limit."""
+    from paper_2510_17891_amd.rollout_loop import group_page_need
+    for P, limits in [(37, [1, 5, 30]), (32, [1, 1, 1]), (5, [12, 11, 28, 1]), (48, [17, 16, 1, 33]), (1, [16, 17])]:
+        G = len(limits)
+        t = st.st_create(G, 4096, 1000)
+        st.st_activate(t, 0)
+        _reserve(st, t, 0, P)
+        st.st_set_len(t, 0, P)
+        for j in range(1, G):
+            st.st_activate(t, j)
+            st.st_share_prefix(t, j, 0, P // 16)
+            if P % 16:
+                _reserve(st, t, j, P)
+            st.st_set_len(t, j, P)
+        peak = 1000 - st.st_free_pages(t)
+        # a member that has sampled `new` tokens has been fed new - 1 of them
+        for j, new in enumerate(limits):
+            for k in range(new - 1):
+                _reserve(st, t, j, P + k + 1)
+                st.st_set_len(t, j, P + k + 1)
+        peak = max(peak, 1000 - st.st_free_pages(t))
+        assert peak == group_page_need(P, limits), (P, limits)
+        for j in range(G):
+            st.st_release(t, j)
+        assert st.st_free_pages(t) == 1000
+        st.st_destroy(t)
