@@ -72,6 +72,7 @@ def parse():
     ap.add_argument("--grow", type=int, default=0,
                     help="layer workload: untimed decode steps after the import (the members of a group get private "
                          "tokens on top of the shared context)")
+    ap.add_argument("--n-prompts", type=int, default=4, help="full workload: prompts (x 8 samples each); 4 is the headline")
     ap.add_argument("--temperature", type=float, default=1.0, help="full workload: sampling temperature")
     ap.add_argument("--top-k", type=int, default=0, help="full workload: top-k cut (0: none)")
     ap.add_argument("--top-p", type=float, default=0.0, help="full workload: top-p cut (0: none)")
@@ -211,7 +212,7 @@ def main():
 
     if args.workload == "full":
         shape = ri.SHAPES["full8b"]
-        n_prompts, G, P = 4, 8, 1024
+        n_prompts, G, P = args.n_prompts, 8, 1024
         B = n_prompts * G
         total_steps = args.warmup + args.steps + (0 if args.no_profile else args.profile_steps)
         max_ctx = (P + total_steps + 1 + 15) // 16 * 16
@@ -342,8 +343,8 @@ def main():
         out["step_hbm_fraction_shared_pages_once"] = step_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9)
     if prefill_s is not None:
         out["prefill_s"] = prefill_s
-        out["prefill_prompt_tokens_per_s"] = 4 * 1024 / prefill_s
-        out["config"]["prefill"] = "4 prompts x 1024 tokens run once each, pages shared by the 8 samples of a prompt"
+        out["prefill_prompt_tokens_per_s"] = n_prompts * 1024 / prefill_s
+        out["config"]["prefill"] = f"{n_prompts} prompts x 1024 tokens run once each, pages shared by the 8 samples of a prompt"
     elif args.workload == "full":
         out["config"]["prompt_kv"] = "imported N(0,1)"
 
