@@ -207,7 +207,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const u32x4_t* __restric
       if (wave == (mb & 3)) {
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-          sum[nb][r] = (red[0][r][lane] + red[1][r][lane]) + (red[2][r][lane] + red[3][r][lane]);
+          sum[nb][r] = ((red[0][r][lane] + red[1][r][lane]) + red[2][r][lane]) + red[3][r][lane];
       }
     }
     if (wave != (mb & 3)) continue;
@@ -328,7 +328,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_wide_kernel(const u32x4_t* _
       if (wave == (mb & 3)) {
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-          sum[nb][r] = (red[0][r][lane] + red[1][r][lane]) + (red[2][r][lane] + red[3][r][lane]);
+          sum[nb][r] = ((red[0][r][lane] + red[1][r][lane]) + red[2][r][lane]) + red[3][r][lane];
       }
     }
     if (wave != (mb & 3)) continue;
@@ -351,7 +351,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_wide_kernel(const u32x4_t* _
 // different K quarters, so a wave needs only 32*MBW accumulator columns and the block still streams W once (the
 // four waves read the same weight tile at about the same time; only the first read leaves L2).  To keep a row's
 // result bit-identical to the K-split variants, every wave still forms the four K-quarter sums separately and adds
-// them as (q0 + q1) + (q2 + q3).
+// them in that order, ((q0 + q1) + q2) + q3, which needs two accumulator sets.
 template <int MBW, int EPI, int ST>
 __global__ __launch_bounds__(256) void gemm_bf16_cols_kernel(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ W,
                                                              void* __restrict__ out, int M, int N, int K, int kb_per_quarter,
@@ -404,19 +404,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_cols_kernel(const u32x4_t* __re
       for (int s = 0; s < ST; ++s) mma_frags<MBW>(f[s], a);
     }
   };
-  f32x16_t acc[2][MBW], other[2][MBW], s01[2][MBW];
-  quarter(s01, 0, false);
-  quarter(other, 1, false);
+  f32x16_t acc[2][MBW], other[2][MBW];
+  quarter(acc, 0, false);
 #pragma unroll
-  for (int nb = 0; nb < 2; ++nb)
+  for (int q = 1; q < 4; ++q) {
+    quarter(other, q, q == 3);
 #pragma unroll
-    for (int mb = 0; mb < MBW; ++mb) s01[nb][mb] += other[nb][mb];
-  quarter(other, 2, false);
-  quarter(acc, 3, true);
+    for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-  for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-    for (int mb = 0; mb < MBW; ++mb) acc[nb][mb] = s01[nb][mb] + (other[nb][mb] + acc[nb][mb]);
+      for (int mb = 0; mb < MBW; ++mb) acc[nb][mb] += other[nb][mb];
+  }
 
   const int col = lane & 31, hb = lane >> 5;
 #pragma unroll
@@ -526,19 +523,15 @@ __global__ __launch_bounds__(256, MBW == 1 ? 2 : 1) void gemm_bf16_lds_kernel(co
       iter(a, i + 3, std::integral_constant<int, 3>{});
     }
   };
-  f32x16_t acc[2][MBW], other[2][MBW], s01[2][MBW];
-  quarter(s01, 0);
-  quarter(other, 1);
+  f32x16_t acc[2][MBW], other[2][MBW];
+  quarter(acc, 0);
+  for (int q = 1; q < 4; ++q) {
+    quarter(other, q);
 #pragma unroll
-  for (int nb = 0; nb < 2; ++nb)
+    for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-    for (int mb = 0; mb < MBW; ++mb) s01[nb][mb] += other[nb][mb];
-  quarter(other, 2);
-  quarter(acc, 3);
-#pragma unroll
-  for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-    for (int mb = 0; mb < MBW; ++mb) acc[nb][mb] = s01[nb][mb] + (other[nb][mb] + acc[nb][mb]);
+      for (int mb = 0; mb < MBW; ++mb) acc[nb][mb] += other[nb][mb];
+  }
 
   if (!has_rows) return;
   const int col = lane & 31, hb = lane >> 5;
@@ -555,12 +548,12 @@ __global__ __launch_bounds__(256, MBW == 1 ? 2 : 1) void gemm_bf16_lds_kernel(co
   }
 }
 
-// Wide tile for batches of 65..128 rows: the block owns two 64-row weight tiles (four 32-row blocks) and the four waves
-// split the batch columns, 32 each.  What every block must pull through L2 per k block is its weight tile plus the
-// whole activation panel, and with 64-row tiles the panel re-reads (one per block) are twice the weight stream: the
+// Wide tile for batches of 65..256 rows: the block owns two 64-row weight tiles (four 32-row blocks) and the four waves
+// split the batch columns, 32*MBW each.  What every block must pull through L2 per k block is its weight tile plus the
+// whole activation panel, and with 64-row tiles the panel re-reads (one per block) are 2-4x the weight stream: the
 // projection is then bound by what the L2 can deliver, not by HBM.  Doubling the tile halves the number of blocks and
-// with it the panel traffic.  Same K quarters, same order inside a quarter: same bits.
-template <int EPI, int XS>
+// with it the panel traffic.  Same K quarters, same order inside a quarter, quarters added in order: same bits.
+template <int MBW, int EPI, int XS>
 __global__ __launch_bounds__(256, 1) void gemm_bf16_lds4_kernel(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ W,
                                                               void* __restrict__ out, int M, int N, int K,
                                                               int kb_per_quarter, SampleEpilogue se) {
@@ -568,9 +561,8 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_lds4_kernel(const u32x4_t* _
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int KB = K >> 6;
   const int n_blocks_m = (M + 31) >> 5;
-  int m_blk = blockIdx.z * 4 + wave;
-  const bool has_rows = m_blk < n_blocks_m;
-  if (!has_rows) m_blk = n_blocks_m - 1;  // idle waves shadow a valid block (they still carry tiles and barriers)
+  const int m_blk0 = (blockIdx.z * 4 + wave) * MBW;
+  const bool has_rows = m_blk0 < n_blocks_m;
 
   // row blocks: pair p = 64-row tile 2x + p (the second pair shadows the first when the tile count is odd)
   const int n_tiles = EPI == kEpiSwiGLU ? (N >> 5) : (N >> 6);
@@ -585,13 +577,19 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_lds4_kernel(const u32x4_t* _
   const u32x4_t* wp[4];
 #pragma unroll
   for (int b = 0; b < 4; ++b) wp[b] = W + (size_t)rb[b] * KB * 256 + tid;
-  const u32x4_t* xb = X + (size_t)m_blk * KB * 256 + lane;
+  const u32x4_t* xb[MBW];
+#pragma unroll
+  for (int mb = 0; mb < MBW; ++mb) {
+    int blk = m_blk0 + mb;
+    if (blk >= n_blocks_m) blk = n_blocks_m - 1;  // idle waves and surplus blocks shadow a valid one (never stored)
+    xb[mb] = X + (size_t)blk * KB * 256 + lane;
+  }
   const int n = 4 * kb_per_quarter;
   const int kb0 = blockIdx.y * n;
   auto kb_of = [&](int i) { return kb0 + (i < n ? i : n - 1); };  // clamped: no conditional loads in the pipeline
 
-  u32x4_t wr[4][4];      // weight registers: slot s holds a k block with index = s (mod 4)
-  u32x4_t xr[XS][4];     // activation fragments: slot s holds a k block with index = s (mod XS)
+  u32x4_t wr[4][4];          // weight registers: slot s holds a k block with index = s (mod 4)
+  u32x4_t xr[XS][MBW][4];    // activation fragments: slot s holds a k block with index = s (mod XS)
 #pragma unroll
   for (int s = 0; s < 4; ++s)
 #pragma unroll
@@ -599,14 +597,16 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_lds4_kernel(const u32x4_t* _
 #pragma unroll
   for (int s = 0; s < XS; ++s)
 #pragma unroll
-    for (int t = 0; t < 4; ++t) xr[s][t] = xb[(size_t)kb_of(s) * 256 + t * 64];
+    for (int mb = 0; mb < MBW; ++mb)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) xr[s][mb][t] = xb[mb][(size_t)kb_of(s) * 256 + t * 64];
 #pragma unroll
   for (int b = 0; b < 4; ++b) {
     wlds[0][b][tid] = wr[0][b];
     wr[0][b] = __builtin_nontemporal_load(wp[b] + (size_t)kb_of(4) * 256);
   }
 
-  auto iter = [&](f32x16_t (&a)[4], int i, auto jc) __attribute__((always_inline)) {
+  auto iter = [&](f32x16_t (&a)[4][MBW], int i, auto jc) __attribute__((always_inline)) {
     constexpr int j = decltype(jc)::value, jn = (j + 1) & 3, jx = j % XS;
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
@@ -619,20 +619,27 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_lds4_kernel(const u32x4_t* _
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, xr[jx][t]);
 #pragma unroll
-      for (int b = 0; b < 4; ++b)
-        a[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wlds[j][b][t * 64 + lane]), bfrag, a[b],
-                                                       0, 0, 0);
+      for (int b = 0; b < 4; ++b) {
+        const bf16x8_t afrag = __builtin_bit_cast(bf16x8_t, wlds[j][b][t * 64 + lane]);
+#pragma unroll
+        for (int mb = 0; mb < MBW; ++mb)
+          a[b][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, __builtin_bit_cast(bf16x8_t, xr[jx][mb][t]), a[b][mb], 0,
+                                                             0, 0);
+      }
     }
 #pragma unroll
-    for (int t = 0; t < 4; ++t) xr[jx][t] = xb[(size_t)kb_of(i + XS) * 256 + t * 64];
+    for (int mb = 0; mb < MBW; ++mb)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) xr[jx][mb][t] = xb[mb][(size_t)kb_of(i + XS) * 256 + t * 64];
   };
-  auto quarter = [&](f32x16_t (&a)[4], int q) __attribute__((always_inline)) {
+  auto quarter = [&](f32x16_t (&a)[4][MBW], int q) __attribute__((always_inline)) {
 #pragma unroll
     for (int b = 0; b < 4; ++b)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) a[b][r] = 0.f;
+      for (int mb = 0; mb < MBW; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) a[b][mb][r] = 0.f;
     for (int i = q * kb_per_quarter; i < (q + 1) * kb_per_quarter; i += 4) {
       iter(a, i, std::integral_constant<int, 0>{});
       iter(a, i + 1, std::integral_constant<int, 1>{});
@@ -640,29 +647,32 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_lds4_kernel(const u32x4_t* _
       iter(a, i + 3, std::integral_constant<int, 3>{});
     }
   };
-  f32x16_t acc[4], other[4], s01[4];
-  quarter(s01, 0);
-  quarter(other, 1);
+  f32x16_t acc[4][MBW], other[4][MBW];
+  quarter(acc, 0);
+  for (int q = 1; q < 4; ++q) {
+    quarter(other, q);
 #pragma unroll
-  for (int b = 0; b < 4; ++b) s01[b] += other[b];
-  quarter(other, 2);
-  quarter(acc, 3);
+    for (int b = 0; b < 4; ++b)
 #pragma unroll
-  for (int b = 0; b < 4; ++b) acc[b] = s01[b] + (other[b] + acc[b]);
+      for (int mb = 0; mb < MBW; ++mb) acc[b][mb] += other[b][mb];
+  }
 
   if (!has_rows) return;
   const int col = lane & 31, hb = lane >> 5;
-  const int m = m_blk * 32 + col;
-  if (m >= M) return;
 #pragma unroll
-  for (int p = 0; p < 2; ++p) {
-    if (p == 1 && !second_valid) break;
-    float sum[2][16];
+  for (int mb = 0; mb < MBW; ++mb) {
+    const int m = (m_blk0 + mb) * 32 + col;
+    if (m >= M) continue;
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
+    for (int p = 0; p < 2; ++p) {
+      if (p == 1 && !second_valid) break;
+      float sum[2][16];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sum[nb][r] = acc[2 * p + nb][r];
-    store_block<EPI>(sum, m, hb, rb[2 * p], rb[2 * p + 1], blockIdx.y, M, N, out, se, tile[p]);
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum[nb][r] = acc[2 * p + nb][mb][r];
+      store_block<EPI>(sum, m, hb, rb[2 * p], rb[2 * p + 1], blockIdx.y, M, N, out, se, tile[p]);
+    }
   }
 }
 
@@ -770,19 +780,19 @@ void launch_lds(hipStream_t s, const void* X, const void* W, void* out, int M, i
   }
 }
 
-template <int XS>
+template <int MBW, int XS>
 void launch_lds4(hipStream_t s, const void* X, const void* W, void* out, int M, int N, int K, int epi, bool allow_split,
                  const SampleEpilogue& se) {
   Plan p = make_plan(N, K, epi, allow_split);  // same K split as the other variants: bit-identical results
-  const int m_tiles = (M + 127) / 128;
+  const int m_tiles = (M + 128 * MBW - 1) / (128 * MBW);
   const int tiles = epi == kEpiSwiGLU ? (N >> 5) : (N >> 6);
   dim3 grid((tiles + 1) / 2, epi == kEpiPartial ? p.splits : 1, m_tiles);
   if (epi == kEpiSwiGLU)
-    gemm_bf16_lds4_kernel<kEpiSwiGLU, XS><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
+    gemm_bf16_lds4_kernel<MBW, kEpiSwiGLU, XS><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
   else if (epi == kEpiSample)
-    gemm_bf16_lds4_kernel<kEpiSample, XS><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
+    gemm_bf16_lds4_kernel<MBW, kEpiSample, XS><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
   else
-    gemm_bf16_lds4_kernel<kEpiPartial, XS><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
+    gemm_bf16_lds4_kernel<MBW, kEpiPartial, XS><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
 }
 
 template <int MBW>
@@ -794,8 +804,11 @@ void launch_cols(hipStream_t s, const void* X, const void* W, void* out, int M, 
     const Plan p = make_plan(N, K, epi, allow_split);
     const int tiles = epi == kEpiSwiGLU ? (N >> 5) : (N >> 6);
     const int wide_blocks = ((tiles + 1) / 2) * (epi == kEpiPartial ? p.splits : 1);
-    if (MBW == 1 && wide_blocks >= 192) launch_lds4<4>(s, X, W, out, M, N, K, epi, allow_split, se);
-    else launch_lds<MBW, MBW == 1 ? 4 : 2>(s, X, W, out, M, N, K, epi, allow_split, se);
+    // (at 129..256 rows the wide tile needs 2 x 128 accumulator registers and measured slower: not instantiated)
+    if constexpr (MBW == 1) {
+      if (wide_blocks >= 192) { launch_lds4<1, 4>(s, X, W, out, M, N, K, epi, allow_split, se); return; }
+    }
+    launch_lds<MBW, MBW == 1 ? 4 : 2>(s, X, W, out, M, N, K, epi, allow_split, se);
     return;
   }
   // two buffers in flight per wave when the quarter length allows it (it does for every 8B-shaped matrix)
