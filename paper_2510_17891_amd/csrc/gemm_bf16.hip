@@ -806,7 +806,8 @@ void launch_cols(hipStream_t s, const void* X, const void* W, void* out, int M, 
     const int wide_blocks = ((tiles + 1) / 2) * (epi == kEpiPartial ? p.splits : 1);
     // (at 129..256 rows the wide tile needs 2 x 128 accumulator registers and measured slower: not instantiated)
     if constexpr (MBW == 1) {
-      if (wide_blocks >= 192) { launch_lds4<1, 4>(s, X, W, out, M, N, K, epi, allow_split, se); return; }
+      // (not for the sampling epilogue: its per-block arithmetic wants two blocks per CU to hide behind; measured)
+      if (wide_blocks >= 192 && epi != kEpiSample) { launch_lds4<1, 4>(s, X, W, out, M, N, K, epi, allow_split, se); return; }
     }
     launch_lds<MBW, MBW == 1 ? 4 : 2>(s, X, W, out, M, N, K, epi, allow_split, se);
     return;
