@@ -46,10 +46,10 @@ void launch_residual_norm(hipStream_t s, int dtype, float* x, const float* part,
                           void* h_out, float* capture, int M, int H, float eps);
 
 // Sum the split partials of the QKV projection, apply per-head RMSNorm (q,k) and the rotation (q,k) at
-// each row's position, write q as fp32 [M][n_q][d] and append k,v to the row's KV page.
+// each row's position, write q as fp32 [M][n_q][d] and append k,v to the row's KV page (rows[r].page).
 void launch_qk_rope_append(hipStream_t s, const Geometry& g, const float* qkv_part, int S, const void* q_gain,
-                           const void* k_gain, const float2* rope_table, const RowMeta* rows,
-                           const int32_t* block_table, void* k_pool_layer, void* v_pool_layer, float* q_out, int M);
+                           const void* k_gain, const float2* rope_table, const RowMeta* rows, void* k_pool_layer,
+                           void* v_pool_layer, float* q_out, int M);
 
 // Scatter contiguous [n_tokens][n_kv][d] K and V (model dtype) into the pages of one sequence.
 void launch_kv_import(hipStream_t s, const Geometry& g, const void* k_src, const void* v_src, int n_tokens,

@@ -232,7 +232,7 @@ int run_layers(rl_model* m, hipStream_t st, int M, const RowMeta* rows, int max_
       else launch_gemm_f32(st, (const float*)h, (const float*)m->wqkv[l], part, M, nqkv, H, kEpiPartial); }
     { Timer t(m, st, K_ROPE_APPEND);
       launch_qk_rope_append(st, g, part, s_qkv, g.qk_norm ? m->q_norm[l] : nullptr, g.qk_norm ? m->k_norm[l] : nullptr, rope,
-                            rows, bt, m->k_pool(l), m->v_pool(l), q, M); }
+                            rows, m->k_pool(l), m->v_pool(l), q, M); }
     if (bf) {
       Timer t(m, st, K_ATTN);
       launch_attn_decode_bf16(st, g, q, rows, bt, m->k_pool(l), m->v_pool(l), apart, m->lay.max_segs, max_ctx_in_batch, o, M,

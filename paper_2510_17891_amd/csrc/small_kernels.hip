@@ -135,7 +135,6 @@ __global__ __launch_bounds__(256) void qk_rope_append_kernel(const float* __rest
                                                             const void* __restrict__ q_gain,
                                                             const void* __restrict__ k_gain,
                                                             const float2* __restrict__ rope, const RowMeta* __restrict__ rows,
-                                                            const int32_t* __restrict__ block_table, int max_blocks,
                                                             void* __restrict__ k_pool, void* __restrict__ v_pool,
                                                             float* __restrict__ q_out, int n_q, int n_kv, int d,
                                                             int qk_norm, float eps) {
@@ -201,17 +200,17 @@ __global__ __launch_bounds__(256) void qk_rope_append_kernel(const float* __rest
 }
 
 void launch_qk_rope_append(hipStream_t s, const Geometry& g, const float* qkv_part, int S, const void* q_gain,
-                           const void* k_gain, const float2* rope_table, const RowMeta* rows,
-                           const int32_t* block_table, void* k_pool_layer, void* v_pool_layer, float* q_out, int M) {
+                           const void* k_gain, const float2* rope_table, const RowMeta* rows, void* k_pool_layer,
+                           void* v_pool_layer, float* q_out, int M) {
   dim3 grid((g.n_q + 2 * g.n_kv + 3) / 4, M);
   size_t stride = (size_t)M * (g.n_q + 2 * g.n_kv) * g.head_dim;
   if (g.dtype == kBF16)
-    qk_rope_append_kernel<true><<<grid, 256, 0, s>>>(qkv_part, S, stride, q_gain, k_gain, rope_table, rows, block_table,
-                                                    g.max_blocks, k_pool_layer, v_pool_layer, q_out, g.n_q, g.n_kv,
+    qk_rope_append_kernel<true><<<grid, 256, 0, s>>>(qkv_part, S, stride, q_gain, k_gain, rope_table, rows,
+                                                    k_pool_layer, v_pool_layer, q_out, g.n_q, g.n_kv,
                                                     g.head_dim, g.qk_norm, g.rms_eps);
   else
-    qk_rope_append_kernel<false><<<grid, 256, 0, s>>>(qkv_part, S, stride, q_gain, k_gain, rope_table, rows, block_table,
-                                                     g.max_blocks, k_pool_layer, v_pool_layer, q_out, g.n_q, g.n_kv,
+    qk_rope_append_kernel<false><<<grid, 256, 0, s>>>(qkv_part, S, stride, q_gain, k_gain, rope_table, rows,
+                                                     k_pool_layer, v_pool_layer, q_out, g.n_q, g.n_kv,
                                                      g.head_dim, g.qk_norm, g.rms_eps);
 }
 
