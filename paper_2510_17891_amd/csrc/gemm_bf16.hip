@@ -92,7 +92,12 @@ __device__ __forceinline__ void store_block(const float (&sum)[2][16], int m, in
     const uint32_t pos = (uint32_t)(rm.pos + se.pos_offset), seq = (uint32_t)rm.seq;
     const int f = se.forced ? se.forced[m] : -1;
     Best best{-INFINITY, -1, 0.f};
+    // log-sum-exp of the lane's 32 entries: their maximum first, then one exponential per entry
     float lm = -INFINITY, ls = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) lm = fmaxf(lm, sum[nb][r] * se.inv_t);
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
@@ -105,7 +110,7 @@ __device__ __forceinline__ void store_block(const float (&sum)[2][16], int m, in
           const float zi = sum[nb][4 * q + e];
           const float y = se.greedy ? zi : __fmaf_rn(zi, se.inv_t, gumbel(rnd[e]));
           best = better(best, Best{y, n0 + e, zi});
-          lse_merge(lm, ls, zi * se.inv_t, 1.0f);
+          if (lm != -INFINITY) ls += __expf(zi * se.inv_t - lm);
           if (n0 + e == f) se.forced_z[m] = zi;
         }
         if (se.logits_out)
