@@ -559,7 +559,7 @@ __global__ __launch_bounds__(256, MBW == 1 ? 2 : 1) void gemm_bf16_lds_kernel(co
 // projection is then bound by what the L2 can deliver, not by HBM.  Doubling the tile halves the number of blocks and
 // with it the panel traffic.  Same K quarters, same order inside a quarter, quarters added in order: same bits.
 template <int MBW, int EPI, int XS>
-__global__ __launch_bounds__(256, 1) void gemm_bf16_lds4_kernel(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ W,
+__global__ __launch_bounds__(256, 2) void gemm_bf16_lds4_kernel(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ W,
                                                               void* __restrict__ out, int M, int N, int K,
                                                               int kb_per_quarter, SampleEpilogue se) {
   __shared__ u32x4_t wlds[4][4][256];  // four stages x four row blocks x 4 KiB
@@ -811,8 +811,7 @@ void launch_cols(hipStream_t s, const void* X, const void* W, void* out, int M, 
     const int wide_blocks = ((tiles + 1) / 2) * (epi == kEpiPartial ? p.splits : 1);
     // (at 129..256 rows the wide tile needs 2 x 128 accumulator registers and measured slower: not instantiated)
     if constexpr (MBW == 1) {
-      // (not for the sampling epilogue: its per-block arithmetic wants two blocks per CU to hide behind; measured)
-      if (wide_blocks >= 192 && epi != kEpiSample) { launch_lds4<1, 4>(s, X, W, out, M, N, K, epi, allow_split, se); return; }
+      if (wide_blocks >= 192) { launch_lds4<1, 2>(s, X, W, out, M, N, K, epi, allow_split, se); return; }
     }
     launch_lds<MBW, MBW == 1 ? 4 : 2>(s, X, W, out, M, N, K, epi, allow_split, se);
     return;
