@@ -561,12 +561,20 @@ __global__ __launch_bounds__(256, MBW == 1 ? 2 : 1) void gemm_bf16_lds_kernel(co
 template <int MBW, int EPI, int XS>
 __global__ __launch_bounds__(256, 2) void gemm_bf16_lds4_kernel(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ W,
                                                               void* __restrict__ out, int M, int N, int K,
-                                                              int kb_per_quarter, SampleEpilogue se) {
+                                                              int kb_per_quarter, int tiles_x, SampleEpilogue se) {
   __shared__ u32x4_t wlds[4][4][256];  // four stages x four row blocks x 4 KiB
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int KB = K >> 6;
   const int n_blocks_m = (M + 31) >> 5;
-  const int m_blk0 = (blockIdx.z * 4 + wave) * MBW;
+  // Two batch tiles (gridDim.z == 2 is folded into x by the launcher: tiles_x > 0): the two blocks of a weight tile
+  // get x indices 8 apart, so they land on the same die at about the same time and share the weights in its L2.
+  int tile_x = blockIdx.x, m_tile = blockIdx.z;
+  if (tiles_x > 0) {
+    const int grp = blockIdx.x >> 4, r = blockIdx.x & 15;
+    m_tile = r >> 3;
+    tile_x = grp * 8 + (r & 7);
+  }
+  const int m_blk0 = (m_tile * 4 + wave) * MBW;
   const bool has_rows = m_blk0 < n_blocks_m;
 
   // row blocks: pair p = 64-row tile 2x + p (the second pair shadows the first when the tile count is odd)
@@ -574,11 +582,11 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_lds4_kernel(const u32x4_t* _
   int tile[2], rb[4];
 #pragma unroll
   for (int p = 0; p < 2; ++p) {
-    tile[p] = min((int)blockIdx.x * 2 + p, n_tiles - 1);
+    tile[p] = min(tile_x * 2 + p, n_tiles - 1);
     if (EPI == kEpiSwiGLU) { rb[2 * p] = tile[p]; rb[2 * p + 1] = tile[p] + (N >> 5); }
     else                   { rb[2 * p] = tile[p] * 2; rb[2 * p + 1] = tile[p] * 2 + 1; }
   }
-  const bool second_valid = (int)blockIdx.x * 2 + 1 < n_tiles;
+  const bool second_valid = tile_x * 2 + 1 < n_tiles;
   const u32x4_t* wp[4];
 #pragma unroll
   for (int b = 0; b < 4; ++b) wp[b] = W + (size_t)rb[b] * KB * 256 + tid;
@@ -791,28 +799,29 @@ void launch_lds4(hipStream_t s, const void* X, const void* W, void* out, int M, 
   Plan p = make_plan(N, K, epi, allow_split);  // same K split as the other variants: bit-identical results
   const int m_tiles = (M + 128 * MBW - 1) / (128 * MBW);
   const int tiles = epi == kEpiSwiGLU ? (N >> 5) : (N >> 6);
-  dim3 grid((tiles + 1) / 2, epi == kEpiPartial ? p.splits : 1, m_tiles);
+  const int tx = (tiles + 1) / 2;
+  const bool fold = m_tiles == 2 && (tx & 7) == 0;  // pair the two batch tiles of a weight tile on one die
+  dim3 grid(fold ? 2 * tx : tx, epi == kEpiPartial ? p.splits : 1, fold ? 1 : m_tiles);
+  const int tiles_x = fold ? tx : 0;
   if (epi == kEpiSwiGLU)
-    gemm_bf16_lds4_kernel<MBW, kEpiSwiGLU, XS><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
+    gemm_bf16_lds4_kernel<MBW, kEpiSwiGLU, XS><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, tiles_x, se);
   else if (epi == kEpiSample)
-    gemm_bf16_lds4_kernel<MBW, kEpiSample, XS><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
+    gemm_bf16_lds4_kernel<MBW, kEpiSample, XS><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, tiles_x, se);
   else
-    gemm_bf16_lds4_kernel<MBW, kEpiPartial, XS><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
+    gemm_bf16_lds4_kernel<MBW, kEpiPartial, XS><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, tiles_x, se);
 }
 
 template <int MBW>
 void launch_cols(hipStream_t s, const void* X, const void* W, void* out, int M, int N, int K, int epi, bool allow_split,
                  const SampleEpilogue& se) {
   if (make_plan(N, K, epi, allow_split).kb_per_wave % 4 == 0) {  // weight tiles shared through LDS
-    // The wide tile pays for at most 128 rows (beyond, the second batch tile re-reads the weights through L2 and
-    // the gain is gone: measured) and where it still leaves enough blocks to fill the chip.
+    // The wide tile pays where it still leaves enough blocks to fill the chip.
     const Plan p = make_plan(N, K, epi, allow_split);
     const int tiles = epi == kEpiSwiGLU ? (N >> 5) : (N >> 6);
     const int wide_blocks = ((tiles + 1) / 2) * (epi == kEpiPartial ? p.splits : 1);
-    // (at 129..256 rows the wide tile needs 2 x 128 accumulator registers and measured slower: not instantiated)
-    if constexpr (MBW == 1) {
-      if (wide_blocks >= 192) { launch_lds4<1, 2>(s, X, W, out, M, N, K, epi, allow_split, se); return; }
-    }
+    // 129..256 rows run as two batch tiles of 128 whose blocks are paired on one die (a 128 x 256 tile per block
+    // would need 2 x 128 accumulator registers and measured slower).
+    if (wide_blocks >= 192) { launch_lds4<1, 2>(s, X, W, out, M, N, K, epi, allow_split, se); return; }
     launch_lds<MBW, MBW == 1 ? 4 : 2>(s, X, W, out, M, N, K, epi, allow_split, se);
     return;
   }
