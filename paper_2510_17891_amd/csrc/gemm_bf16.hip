@@ -821,7 +821,7 @@ void launch_cols(hipStream_t s, const void* X, const void* W, void* out, int M, 
     const int wide_blocks = ((tiles + 1) / 2) * (epi == kEpiPartial ? p.splits : 1);
     // 129..256 rows run as two batch tiles of 128 whose blocks are paired on one die (a 128 x 256 tile per block
     // would need 2 x 128 accumulator registers and measured slower).
-    if (wide_blocks >= 192) { launch_lds4<1, 2>(s, X, W, out, M, N, K, epi, allow_split, se); return; }
+    if (wide_blocks * ((M + 127) / 128) >= 192) { launch_lds4<1, 2>(s, X, W, out, M, N, K, epi, allow_split, se); return; }
     launch_lds<MBW, MBW == 1 ? 4 : 2>(s, X, W, out, M, N, K, epi, allow_split, se);
     return;
   }
