@@ -276,6 +276,7 @@ def _oracle_layer_row(shape, wn, k, v, x_row, ctx):
     [300 + 7 * i for i in range(37)],                  # 37 rows: two column blocks with a ragged tail
     [33],                                              # a single row
     [16383, 8191, 4096, 4095, 1024, 1023],             # longest context; both sides of the LDS/workspace merge switch
+    [65519, 40000],                                    # the largest context the bf16 path accepts: 256 segments
 ])
 def test_bf16_layer_decode_matches_oracle(amd, ctxs):
     shape, wn, ro, ks, vs, x = _layer_case(amd, ctxs, seed=31, shuffle=9)
