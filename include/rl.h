@@ -80,7 +80,7 @@ typedef enum { RL_F32 = 0, RL_BF16 = 1 } rl_dtype;
 
 typedef struct {
   uint32_t struct_size; /* sizeof(rl_model_config), checked */
-  uint32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+  uint32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab; /* vocab % 4 == 0, < 2^22; 0: no head */
   float rms_eps, rope_base;
   uint32_t qk_norm;  /* 1: per-head RMSNorm of q and k before the rotation */
   uint32_t dtype;    /* rl_dtype of weights and KV; RL_BF16 needs head_dim 128 and 8B-like multiples */
