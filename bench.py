@@ -27,9 +27,9 @@ HBM_PEAK_GBS = 8000.0
 # 1 GiB device copy (FETCH_SIZE x 2.0000, WRITE_SIZE x 1.0000).  An entry is used only while the kernel's source
 # file still has the hash it had when the counters were taken; otherwise "traffic" is null.
 TRAFFIC_RATIO = {
-    ("layer", "attn_decode"): (1.005, "attn_bf16.hip", "ddedc73cd1fb2247"),
+    ("layer", "attn_decode"): (1.016, "attn_bf16.hip", "a7cbc1850a5104cd"),
     ("layer", "gemm_gate_up_swiglu"): (1.019, "gemm_bf16.hip", "75c34910d0294a8f"),
-    ("full", "attn_decode"): (1.012, "attn_bf16.hip", "ddedc73cd1fb2247"),
+    ("full", "attn_decode"): (1.035, "attn_bf16.hip", "a7cbc1850a5104cd"),
     ("full", "gemm_gate_up_swiglu"): (1.010, "gemm_bf16.hip", "75c34910d0294a8f"),
 }
 
@@ -78,6 +78,8 @@ def parse():
     ap.add_argument("--top-p", type=float, default=0.0, help="full workload: top-p cut (0: none)")
     ap.add_argument("--no-share-attention", action="store_true",
                     help="full workload: attention over the prompt pages once per row instead of once per set of samples")
+    ap.add_argument("--separate-append", action="store_true",
+                    help="rotation and KV append as a kernel of their own instead of inside the decode attention kernel")
     return ap.parse_args()
 
 
@@ -93,7 +95,8 @@ def kernel_bytes(shape, M, ctx_sum, bf=2):
         "gemm_gate_up_swiglu": 2 * F * H * bf + M * H * bf + M * F * bf,
         "gemm_down": H * F * bf + M * F * bf + M * H * 4,
         "gemm_lm_head": V * H * bf + M * H * bf + M * V * 4,
-        "attn_decode": ctx_sum * nkv * 2 * d * bf + M * nqd * 4 * 2,
+        # K/V pages, the QKV projection's output (summed, rotated and appended inside the kernel), the bf16 output
+        "attn_decode": ctx_sum * nkv * 2 * d * bf + M * nqkv * 4 + M * nqd * bf + M * 2 * nkv * d * bf,
     }
 
 
@@ -223,6 +226,8 @@ def main():
         torch.cuda.empty_cache()
         if args.no_share_attention:
             ro.rl_debug_share_attention(False)
+        if args.separate_append:
+            ro.rl_debug_attention_appends(False)
         prompts = ri.tokens((n_prompts, P), shape["vocab"], seed, 900)
         prompt_list = [prompts[i // G].tolist() for i in range(B)]
         seq_ids = list(range(B))
@@ -256,6 +261,8 @@ def main():
             ro.rl_debug_shuffle_free_pages(seed)  # block tables are a random permutation of the pool
         if args.no_share_attention:
             ro.rl_debug_share_attention(False)
+        if args.separate_append:
+            ro.rl_debug_attention_appends(False)
         for b in range(0, B, args.group):
             k = ri.normal((ctx0, shape["n_kv"], shape["head_dim"]), 1.0, seed, 2000 + 2 * b, device=dev, dtype=torch.bfloat16)
             v = ri.normal((ctx0, shape["n_kv"], shape["head_dim"]), 1.0, seed, 2001 + 2 * b, device=dev, dtype=torch.bfloat16)

@@ -318,6 +318,14 @@ rl_status rl_debug_shuffle_free_pages(rl_model* m, uint64_t seed);
 rl_status rl_debug_share_attention(rl_model* m, int32_t on);
 
 /*
+ * Test aid: switch off (on = 0) or on again (the default) the fused form of a bf16 decode step in which the
+ * attention kernel itself forms the rotated queries and writes the new keys and values into their pages, instead
+ * of a separate kernel before it.  Results of every other call must not change by a single bit.  No effect on
+ * fp32 models and on calls that feed several positions of one sequence (prefill, scoring).
+ */
+rl_status rl_debug_attention_appends(rl_model* m, int32_t on);
+
+/*
  * Per-kernel timing.  While enabled, every kernel launch of decode/prefill calls is bracketed by
  * HIP events on the caller's stream.  rl_profile_read synchronises those events, returns per kernel
  * class the number of launches and their total milliseconds since the last read, and clears them.

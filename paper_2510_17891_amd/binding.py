@@ -21,7 +21,7 @@ EXPORTS = [
     "rl_kv_page_bytes", "rl_query_workspace", "rl_init_model", "rl_destroy_model", "rl_prefill", "rl_prefill_groups", "rl_score", "rl_hrd_objective",
     "rl_decode_step", "rl_free_seqs", "rl_last_error", "rl_kv_stats", "rl_seq_len", "rl_sample_logits",
     "rl_seq_import_kv", "rl_decode_hidden", "rl_set_capture", "rl_pack_weight",
-    "rl_debug_shuffle_free_pages", "rl_debug_share_attention", "rl_seq_fork", "rl_profile_enable", "rl_profile_read",
+    "rl_debug_shuffle_free_pages", "rl_debug_share_attention", "rl_debug_attention_appends", "rl_seq_fork", "rl_profile_enable", "rl_profile_read",
 ]
 
 
@@ -97,6 +97,7 @@ def lib():
         L.rl_pack_weight.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64]
         L.rl_debug_shuffle_free_pages.argtypes = [C.c_void_p, C.c_uint64]
         L.rl_debug_share_attention.argtypes = [C.c_void_p, C.c_int32]
+        L.rl_debug_attention_appends.argtypes = [C.c_void_p, C.c_int32]
         L.rl_seq_fork.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, _i32p]
         L.rl_profile_enable.argtypes = [C.c_void_p, C.c_int32]
         L.rl_profile_read.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
@@ -330,6 +331,9 @@ class Rollout:
 
     def rl_debug_share_attention(self, on):
         check(lib().rl_debug_share_attention(self.h, int(on)))
+
+    def rl_debug_attention_appends(self, on):
+        check(lib().rl_debug_attention_appends(self.h, int(on)))
 
     def rl_profile_enable(self, on):
         check(lib().rl_profile_enable(self.h, 1 if on else 0))

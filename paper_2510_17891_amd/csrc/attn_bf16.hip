@@ -29,10 +29,17 @@
 // segments; both kinds leave their partials in the workspace and the merge kernel combines them with the
 // arithmetic of the in-block merge.  A column of the matrix product does not depend on its neighbours and the
 // segment bounds are the same, so a row's bits equal those of the row computed alone.
+//
+// Decode steps (one row per sequence) run the variant that also does what would otherwise be a kernel of its own
+// before this one: it sums the QKV projection's split partials, normalises and rotates the heads of its columns, and
+// appends the row's new key and value to the cache.  The only consumer of a row's new key and value inside the launch
+// is the wave that owns the row's last 32-key step; it gets them from LDS into its operand registers and stores
+// them to the page when its work is done, so no wave ever waits for those (small, scattered) stores.
 #include <algorithm>
 
 #include "device_utils.h"
 #include "kernels.h"
+#include "rope_device.h"
 
 namespace rl {
 
@@ -46,14 +53,16 @@ constexpr int kPageElems = kPageTokens * kD;  // 2048 bf16 = 4 KiB per (page, kv
 constexpr int kPartStride = kD + 2;           // floats per (row, head, segment): O[128], max, sum
 constexpr int kLdsSegs = 16;                  // contexts up to 4096 keep their segment partials in LDS
 
+template <bool WRITTEN> struct PoolPtr { typedef const u32x4_t* __restrict__ type; };
+template <> struct PoolPtr<true> { typedef const u32x4_t* type; };
+
 struct PagePair {
   u32x4_t k[2][4];  // [page a|b][mfma step s]: keys x dims 32s..32s+31
   u32x4_t v[2][4];  // [page a|b][jj]: dims 32jj..32jj+31 (two 16-dim blocks) x this lane's 4 keys
 };
 
-__device__ __forceinline__ void load_pair(PagePair& pp, const u32x4_t* __restrict__ kbase,
-                                          const u32x4_t* __restrict__ vbase, int64_t page_a, int64_t page_b, int n_kv,
-                                          int lane) {
+__device__ __forceinline__ void load_pair(PagePair& pp, const u32x4_t* kbase, const u32x4_t* vbase, int64_t page_a,
+                                          int64_t page_b, int n_kv, int lane) {
   // per layer the pool is [page][kv head][K | V]: the K and V blocks of a (page, head) are adjacent
   const size_t oa = (size_t)page_a * n_kv * (2 * kPageElems / 8) + lane;
   const size_t ob = (size_t)page_b * n_kv * (2 * kPageElems / 8) + lane;
@@ -107,17 +116,38 @@ __device__ __forceinline__ uint32_t merge_short(F seg_ptr, int n_seg, int n_it, 
   return pack2bf(o0 * inv, o1 * inv);
 }
 
+// The QKV projection's split sums and what turns them into queries, keys and values (kernel-side AttnAppend).
+__device__ __forceinline__ void hold(HeadPairLoads& ld) {
+#pragma unroll
+  for (int sp = 0; sp < kHeadPairMaxS; ++sp) asm volatile("" : "+v"(ld.a[sp][0]), "+v"(ld.a[sp][1]));
+}
+
+static_assert(kAttnAppendMaxSplits == kHeadPairMaxS, "the launcher's limit is the one of the loads");
+struct AppendArgs {
+  const float* qkv_part;
+  int S;  // <= kHeadPairMaxS
+  size_t split_stride;
+  const void* q_gain;
+  const void* k_gain;
+  const float2* rope;
+  float eps;
+};
+
 // grid: x = kv head, y = row, then set of rows (y >= n_rows), z = split.  block = four waves.
 // Row block: the row's segments from skip_segs[row] (or 0) on, up to kLdsSegs per block.  Set block: up to four of
 // the leading shared[y - n_rows].n_segs segments for all rows of the set.
+// APPEND: q is not read; every block forms the queries of its columns from the split sums, and the last wave of the
+// row block that holds a row's last segment forms the row's new key and value, uses them in its last step and then
+// writes them into their page.  The pools are therefore not declared read-only in that variant.
+template <bool APPEND>
 __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* __restrict__ q, const RowMeta* __restrict__ rows,
                                                                const int32_t* __restrict__ block_table, int max_blocks,
-                                                               const u32x4_t* __restrict__ k_pool,
-                                                               const u32x4_t* __restrict__ v_pool, float* __restrict__ part,
+                                                               typename PoolPtr<APPEND>::type k_pool,
+                                                               typename PoolPtr<APPEND>::type v_pool, float* __restrict__ part,
                                                                int max_segs, int n_q, int n_kv, float scale,
                                                                uint16_t* __restrict__ o_out, int lds_part_offset,
-                                                               int n_rows, const int32_t* __restrict__ skip_segs,
-                                                               const AttnShared* __restrict__ shared) {
+                                                               int lds_q_offset, int n_rows, const int32_t* __restrict__ skip_segs,
+                                                               const AttnShared* __restrict__ shared, AppendArgs ap) {
   extern __shared__ int32_t pages[];  // block-table slice of this row: ceil(ctx/16) entries (+1 pad), then partials
   const int hk = blockIdx.x;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -157,13 +187,113 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
   }
   if (lo >= hi) return;  // block-uniform: nothing left for this block
   const int n_blk = (ctx + 15) >> 4;
-  for (int i = threadIdx.x; i <= n_blk; i += 256)  // entry n_blk duplicates the last page (odd page counts)
-    pages[i] = block_table[(size_t)rm.seq * max_blocks + (i < n_blk ? i : n_blk - 1)];
+  const int n_it = (ctx + 31) >> 5;  // 32-key steps
+  auto seg_begin = [&](int sgm) { return attn_seg_begin(sgm, n_it, n_seg); };
+  int seg = lo + (wave * (hi - lo)) / 4;  // contiguous, balanced share of the block's segments
+  const int seg_end = lo + ((wave + 1) * (hi - lo)) / 4;
+  const int it_begin = seg_begin(seg), it_end = seg_begin(seg_end);
+  const u32x4_t* kb = k_pool + (size_t)hk * (2 * kPageElems / 8);
+  const u32x4_t* vb = v_pool + (size_t)hk * (2 * kPageElems / 8);
+  if (!APPEND) {
+    for (int i = threadIdx.x; i <= n_blk; i += 256)  // entry n_blk duplicates the last page (odd page counts)
+      pages[i] = block_table[(size_t)rm.seq * max_blocks + (i < n_blk ? i : n_blk - 1)];
+  }
+
+  // ---- APPEND: queries of this block's columns into LDS, the row's new key and value for the appending wave ----
+  bool appends = false;  // wave-uniform: this wave owns the row's last step and with it the new key and value
+  float* const lds_part = (float*)(pages + lds_part_offset);
+  float* const lds_q = (float*)(pages + lds_q_offset);  // [16 columns][128], APPEND only
+  uint16_t* const lds_new = (uint16_t*)(lds_q + 16 * kD);  // the row's new key [128] and value [128] as bf16, APPEND only
+  if (APPEND) {
+    // Tasks of a wave: the query heads of columns w, w+4, ...; the last wave of the row block that holds the
+    // row's last segment also takes the new key and value.  That wave is the only reader of the page entries they
+    // belong to (the block's last 32-key step): it puts them into the operands of that step from LDS, and writes
+    // them to the page after its last step, when nothing waits for the stores any more.
+    // All loads (split sums, rotation, gains, block table) are issued before anything is consumed.
+    const int n_cols = n_members * group;  // <= 16
+    int set_rows[4] = {0, 0, 0, 0};         // fetched together, ahead of the loads that need them
+    if (is_set) {
+      const AttnShared* sh = shared + (blockIdx.y - n_rows);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) set_rows[e] = sh->rows[e];
+    }
+    const int uw = __builtin_amdgcn_readfirstlane(wave);  // lets the compiler see that the task choice is per wave
+    appends = !is_set && hi == n_seg && uw == 3;
+    const int n_tot = (n_q + 2 * n_kv) * kD;
+    float2 cs = ap.rope[(size_t)rm.pos * (kD / 2) + lane];  // the rows of a set have one position
+    uint32_t gq0 = 0, gq1 = 0, gk0 = 0, gk1 = 0;            // gains as stored (bf16)
+    if (ap.q_gain) { gq0 = ((const uint16_t*)ap.q_gain)[lane]; gq1 = ((const uint16_t*)ap.q_gain)[lane + kD / 2]; }
+    HeadPairLoads lq[4], lk, lv;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int t = uw + 4 * u;
+      if (t < n_cols) {
+        const int m = t / group;  // member of the set
+        const int trow = is_set ? (m == 0 ? set_rows[0] : m == 1 ? set_rows[1] : m == 2 ? set_rows[2] : set_rows[3]) : r;
+        head_pair_issue(lq[u], ap.qkv_part + (size_t)trow * n_tot + (size_t)(hk * group + t % group) * kD, ap.S, ap.split_stride,
+                        kD, lane);
+      }
+    }
+    if (appends) {
+      const float* row_part = ap.qkv_part + (size_t)r * n_tot;
+      head_pair_issue(lk, row_part + (size_t)(n_q + hk) * kD, ap.S, ap.split_stride, kD, lane);
+      head_pair_issue(lv, row_part + (size_t)(n_q + n_kv + hk) * kD, ap.S, ap.split_stride, kD, lane);
+      if (ap.k_gain) { gk0 = ((const uint16_t*)ap.k_gain)[lane]; gk1 = ((const uint16_t*)ap.k_gain)[lane + kD / 2]; }
+    }
+    for (int i = threadIdx.x; i <= n_blk; i += 256)  // entry n_blk duplicates the last page (odd page counts)
+      pages[i] = block_table[(size_t)rm.seq * max_blocks + (i < n_blk ? i : n_blk - 1)];
+    // Everything loaded above is first touched below this line: the empty statements keep the compiler from moving
+    // the arithmetic (and with it the waits) up between the loads.
+    asm volatile("" : "+v"(cs.x), "+v"(cs.y), "+v"(gq0), "+v"(gq1), "+v"(gk0), "+v"(gk1));
+    // Five heads side by side: the (up to) four query columns of this wave and the new key.  Slots without a task
+    // hold whatever their registers held; their results are not stored.
+    HeadPair hp[5];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      hold(lq[u]);
+      hp[u].cs = cs; hp[u].g0 = bf2f(gq0); hp[u].g1 = bf2f(gq1);
+      head_pair_sum(hp[u], lq[u], ap.S);
+    }
+    hold(lk);
+    hold(lv);
+    hp[4].cs = cs; hp[4].g0 = bf2f(gk0); hp[4].g1 = bf2f(gk1);
+    head_pair_sum(hp[4], lk, ap.S);
+    const bool normalise = ap.q_gain != nullptr;
+    if (n_cols > 4) {  // block-uniform: several columns per wave
+      head_pairs_finish<5>(hp, kD, normalise, ap.eps);
+    } else if (appends) {  // wave-uniform: one column and the key
+      HeadPair two[2] = {hp[0], hp[4]};
+      head_pairs_finish<2>(two, kD, normalise, ap.eps);
+      hp[0] = two[0];
+      hp[4] = two[1];
+    } else {
+      HeadPair one[1] = {hp[0]};
+      head_pairs_finish<1>(one, kD, normalise, ap.eps);
+      hp[0] = one[0];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int t = uw + 4 * u;
+      if (t < n_cols) {
+        lds_q[t * kD + lane] = hp[u].v0;
+        lds_q[t * kD + kD / 2 + lane] = hp[u].v1;
+      }
+    }
+    if (appends) {  // the new key and value, rounded, wait in LDS for this wave's last step
+      HeadPair hv;
+      head_pair_sum(hv, lv, ap.S);
+      lds_new[lane] = (uint16_t)f2bf(hp[4].v0);
+      lds_new[lane + kD / 2] = (uint16_t)f2bf(hp[4].v1);
+      lds_new[kD + lane] = (uint16_t)f2bf(hv.v0);
+      lds_new[kD + lane + kD / 2] = (uint16_t)f2bf(hv.v1);
+    }
+    __syncthreads();  // pages[] and the queries are in LDS
+  }
 
   // ---- q operand: hi/lo bf16 split; columns beyond the set are zero -------------------------------
   u32x4_t q_hi[4], q_lo[4];
   {
-    const float* qh = q + ((size_t)col_row * n_q + col_head) * kD;
+    const float* qh = APPEND ? lds_q + j * kD : q + ((size_t)col_row * n_q + col_head) * kD;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       uint32_t hi16[4], lo16[4];
@@ -179,18 +309,12 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
       q_lo[s] = (u32x4_t){lo16[0], lo16[1], lo16[2], lo16[3]};
     }
   }
-  __syncthreads();
+  if (!APPEND) __syncthreads();  // pages[] is filled
 
-  const u32x4_t* kb = k_pool + (size_t)hk * (2 * kPageElems / 8);
-  const u32x4_t* vb = v_pool + (size_t)hk * (2 * kPageElems / 8);
-  const int n_it = (ctx + 31) >> 5;  // 32-key steps
   // Segment partials of short contexts (<= kLdsSegs segments) stay in LDS; longer ones and the shared ones go
   // through the workspace.  pcol: this lane's column, indexed by the absolute segment number.
   float* const gcol = part + ((size_t)col_row * n_q + col_head) * max_segs * kPartStride;
-  float* const lds_part = (float*)(pages + lds_part_offset);
   float* const pcol = in_lds ? lds_part + (size_t)j * n_seg * kPartStride : gcol;
-  auto seg_begin = [&](int sgm) { return attn_seg_begin(sgm, n_it, n_seg); };
-
   f32x4_t o_acc[8];
   float m_run, l_run;
   auto reset = [&]() {
@@ -200,9 +324,6 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
     l_run = 0.f;
   };
   reset();
-  int seg = lo + (wave * (hi - lo)) / 4;  // contiguous, balanced share of the block's segments
-  const int seg_end = lo + ((wave + 1) * (hi - lo)) / 4;
-  const int it_begin = seg_begin(seg), it_end = seg_begin(seg_end);
   while (seg < seg_end && seg_begin(seg + 1) == seg_begin(seg)) ++seg;  // skip leading empty segments
   int boundary = seg < seg_end ? seg_begin(seg + 1) : it_end;
 
@@ -274,6 +395,49 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
     load_pair(pp, kb, vb, pages[2 * it], pages[2 * it + 1], n_kv, lane);
   };
 
+  // The appending wave's last step: the entries of the new token (key pos & 15 of page (pos >> 4) & 1 of the pair)
+  // are replaced by the rounded new key and value; what memory holds there is stale.
+  auto patch_new = [&](PagePair& pp) __attribute__((always_inline)) {
+    const int t = rm.pos & 15, pg = (rm.pos >> 4) & 1;
+    // K operand: the lane whose row is key t holds 8 dims per step, one 16-byte piece of the new key
+    const bool k_lane = (lane & 15) == t;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const u32x4_t kn = *(const u32x4_t*)(lds_new + 32 * s + 8 * g);
+#pragma unroll
+      for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pp.k[p][s][e] = (k_lane && pg == p) ? kn[e] : pp.k[p][s][e];
+    }
+    // V operand: keys 4g..4g+3 of dims 32jj + dl (registers 0, 1) and 32jj + 16 + dl (registers 2, 3)
+    const bool v_lane = g == (t >> 2);
+    const int sh = (t & 1) * 16, hi_pair = (t >> 1) & 1;
+    const uint32_t keep = ~(0xffffu << sh);
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+#pragma unroll
+      for (int par = 0; par < 2; ++par) {
+        const uint32_t vn = (uint32_t)lds_new[kD + (2 * jj + par) * 16 + j] << sh;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+#pragma unroll
+          for (int p = 0; p < 2; ++p) {
+            const uint32_t old = pp.v[p][jj][2 * par + h];
+            pp.v[p][jj][2 * par + h] = (v_lane && h == hi_pair && pg == p) ? ((old & keep) | vn) : old;
+          }
+        }
+      }
+    }
+  };
+  // ... and its stores, once nothing of the wave's work is behind them
+  auto store_new = [&]() __attribute__((always_inline)) {
+    const int t = rm.pos & 15;
+    kv_store_bf16_bits((void*)k_pool, rm.page, hk, n_kv, t, lane, lds_new[lane], false);
+    kv_store_bf16_bits((void*)k_pool, rm.page, hk, n_kv, t, lane + kD / 2, lds_new[lane + kD / 2], false);
+    kv_store_bf16_bits((void*)v_pool, rm.page, hk, n_kv, t, lane, lds_new[kD + lane], true);
+    kv_store_bf16_bits((void*)v_pool, rm.page, hk, n_kv, t, lane + kD / 2, lds_new[kD + lane + kD / 2], true);
+  };
+
   // Two register buffers, refilled unconditionally inside the loop so that the compiler's wait counts let the
   // other buffer's 16 loads stay in flight while one is consumed; the ragged end is peeled off below.
   if (it_begin < it_end) {
@@ -294,13 +458,18 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
       fetch(pb, it + 1);
       __builtin_amdgcn_sched_barrier(0);
       step(pa, it);
+      if (APPEND && appends) patch_new(pb);
       step(pb, it + 1);
     } else {  // one step left
+      if (APPEND && appends) patch_new(pa);
       step(pa, it);
     }
   }
 
-  if (!in_lds) return;  // the merge kernel combines the partials in the workspace
+  if (!in_lds) {  // the merge kernel combines the partials in the workspace
+    if (APPEND && appends) store_new();
+    return;
+  }
   // ---- merge: wave w takes heads w, w+4 of the group -------------------------------------------------
   __threadfence_block();
   __syncthreads();
@@ -310,6 +479,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
     const uint32_t o2 = merge_short([&](int c) { return p + (size_t)c * kPartStride; }, n_seg, n_it, lane);
     *(uint32_t*)(o_out + frag_offset(r, head * kD + 2 * lane, (n_q * kD) >> 6)) = o2;
   }
+  if (APPEND && appends) store_new();
 }
 
 // Merge of the rows whose partials are in the workspace, one wave per (row, head): rows of a set (short contexts:
@@ -377,20 +547,32 @@ __global__ __launch_bounds__(64) void attn_merge_bf16_kernel(const float* __rest
 int attn_bf16_max_segments(int max_ctx) { return attn_num_segments(max_ctx); }
 
 void launch_attn_decode_bf16(hipStream_t s, const Geometry& g, const float* q, const RowMeta* rows,
-                             const int32_t* block_table, const void* k_pool_layer, const void* v_pool_layer,
-                             float* part, int max_segs_alloc, int max_ctx_in_batch, void* o_out, int M,
-                             const int32_t* skip_segs, const AttnShared* shared, int n_shared, int max_shared_segs) {
+                             const int32_t* block_table, void* k_pool_layer, void* v_pool_layer, float* part,
+                             int max_segs_alloc, int max_ctx_in_batch, void* o_out, int M, const int32_t* skip_segs,
+                             const AttnShared* shared, int n_shared, int max_shared_segs, const AttnAppend* append) {
   const int n_seg_max = attn_num_segments(max_ctx_in_batch);
   const int page_ints = ((max_ctx_in_batch + 15) / 16 + 1 + 3) & ~3;  // keeps the partials 16-byte aligned
   if (n_shared <= 0) { skip_segs = nullptr; n_shared = 0; max_shared_segs = 0; }
   const int z = std::max(attn_num_splits(n_seg_max), (max_shared_segs + 3) / 4);
   dim3 grid(g.n_kv, M + n_shared, z);
   const int segs = n_seg_max > kLdsSegs ? kLdsSegs : n_seg_max;
-  const size_t lds = (size_t)page_ints * 4 + (size_t)(g.n_q / g.n_kv) * segs * kPartStride * sizeof(float);
-  attn_decode_bf16_kernel<<<grid, 256, lds, s>>>(q, rows, block_table, g.max_blocks, (const u32x4_t*)k_pool_layer,
-                                                 (const u32x4_t*)v_pool_layer, part, max_segs_alloc, g.n_q, g.n_kv,
-                                                 1.0f / sqrtf((float)g.head_dim), (uint16_t*)o_out, page_ints, M, skip_segs,
-                                                 shared);
+  const int part_floats = (g.n_q / g.n_kv) * segs * kPartStride;  // even
+  const int q_ints = append ? 16 * kD + kD : 0;  // the queries of up to 16 columns, the new key and value (bf16)
+  const size_t lds = (size_t)(page_ints + part_floats + q_ints) * 4;
+  const float scale = 1.0f / sqrtf((float)g.head_dim);
+  AppendArgs ap = {};
+  if (append) {
+    ap.qkv_part = append->qkv_part; ap.S = append->S;
+    ap.split_stride = (size_t)M * (g.n_q + 2 * g.n_kv) * g.head_dim;
+    ap.q_gain = append->q_gain; ap.k_gain = append->k_gain; ap.rope = append->rope_table; ap.eps = g.rms_eps;
+    attn_decode_bf16_kernel<true><<<grid, 256, lds, s>>>(q, rows, block_table, g.max_blocks, (const u32x4_t*)k_pool_layer,
+                                                         (const u32x4_t*)v_pool_layer, part, max_segs_alloc, g.n_q, g.n_kv,
+                                                         scale, (uint16_t*)o_out, page_ints, page_ints + part_floats, M, skip_segs, shared, ap);
+  } else {
+    attn_decode_bf16_kernel<false><<<grid, 256, lds, s>>>(q, rows, block_table, g.max_blocks, (const u32x4_t*)k_pool_layer,
+                                                          (const u32x4_t*)v_pool_layer, part, max_segs_alloc, g.n_q, g.n_kv,
+                                                          scale, (uint16_t*)o_out, page_ints, page_ints + part_floats, M, skip_segs, shared, ap);
+  }
   if (n_seg_max > kLdsSegs || n_shared > 0)
     attn_merge_bf16_kernel<<<dim3(g.n_q, M), 64, 0, s>>>(part, rows, max_segs_alloc, (uint16_t*)o_out, g.n_q, skip_segs);
 }

@@ -67,11 +67,24 @@ void launch_page_copy(hipStream_t s, void* kv_pool, size_t layer_bytes, size_t p
 int attn_bf16_max_segments(int max_ctx);
 // skip_segs (per row, may be null): leading segments of the row that a set in `shared` covers; every row with a
 // non-zero entry must belong to exactly one set with that n_segs.  max_shared_segs = largest n_segs.
+// append (may be null): the kernel forms the rows' queries, new keys and new values from the QKV projection's split
+// sums itself and writes the keys and values into the pages (RowMeta::page); `q` is then unused and
+// launch_qk_rope_append is not called.  Only for batches with one row per sequence: the block of a row is then the
+// only one that needs the row's new key, and it takes it from registers, not from the page.  The arithmetic is the
+// one of launch_qk_rope_append, bit for bit.
+constexpr int kAttnAppendMaxSplits = 4;
+struct AttnAppend {
+  const float* qkv_part;  // [S][M][(n_q + 2 n_kv) * d]
+  int S;                  // <= kAttnAppendMaxSplits
+  const void* q_gain;     // per-head RMSNorm gains: both set, or both null
+  const void* k_gain;
+  const float2* rope_table;
+};
 void launch_attn_decode_bf16(hipStream_t s, const Geometry& g, const float* q, const RowMeta* rows,
-                             const int32_t* block_table, const void* k_pool_layer, const void* v_pool_layer,
+                             const int32_t* block_table, void* k_pool_layer, void* v_pool_layer,
                              float* part, int max_segs_alloc, int max_ctx_in_batch, void* o_out, int M,
                              const int32_t* skip_segs = nullptr, const AttnShared* shared = nullptr, int n_shared = 0,
-                             int max_shared_segs = 0);
+                             int max_shared_segs = 0, const AttnAppend* append = nullptr);
 // fp32, any head_dim <= 256: one wave per (row, q head), whole context, output fp32 row-major [M][n_q*d].
 void launch_attn_f32(hipStream_t s, const Geometry& g, const float* q, const RowMeta* rows,
                      const int32_t* block_table, const void* k_pool_layer, const void* v_pool_layer,

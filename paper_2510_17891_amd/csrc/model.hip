@@ -148,6 +148,7 @@ struct rl_model {
   int ring_next = 0;
   float* capture = nullptr;
   bool share_attention = true;  // compute segments inside shared prompt pages once per set of rows
+  bool attention_appends = true;  // decode steps: the attention kernel forms q and appends k, v itself
   // profiling
   bool prof_on = false;
   std::vector<hipEvent_t> ev_pool;
@@ -207,8 +208,10 @@ struct SharedAttn {  // device pointers into the metadata slot of the call (empt
   int n_sets = 0, max_segs = 0;
 };
 
+// one_row_per_seq: the batch is a decode step, which lets the bf16 attention kernel take over the rotation and the
+// KV append (a row's block is then the only reader of the key it writes).
 int run_layers(rl_model* m, hipStream_t st, int M, const RowMeta* rows, int max_ctx_in_batch,
-               const SharedAttn& sa = SharedAttn()) {
+               const SharedAttn& sa = SharedAttn(), bool one_row_per_seq = false) {
   const Geometry& g = m->geo;
   const bool bf = g.dtype == kBF16;
   const int H = g.hidden, nqd = g.n_q * g.head_dim, nqkv = (g.n_q + 2 * g.n_kv) * g.head_dim, F = g.ffn;
@@ -230,13 +233,18 @@ int run_layers(rl_model* m, hipStream_t st, int M, const RowMeta* rows, int max_
     { Timer t(m, st, K_QKV);
       if (bf) { launch_gemm_bf16(st, h, m->wqkv[l], part, M, nqkv, H, kEpiPartial); s_qkv = gemm_bf16_splits(nqkv, H, kEpiPartial); }
       else launch_gemm_f32(st, (const float*)h, (const float*)m->wqkv[l], part, M, nqkv, H, kEpiPartial); }
-    { Timer t(m, st, K_ROPE_APPEND);
-      launch_qk_rope_append(st, g, part, s_qkv, g.qk_norm ? m->q_norm[l] : nullptr, g.qk_norm ? m->k_norm[l] : nullptr, rope,
-                            rows, m->k_pool(l), m->v_pool(l), q, M); }
+    const void* q_gain = g.qk_norm ? m->q_norm[l] : nullptr;
+    const void* k_gain = g.qk_norm ? m->k_norm[l] : nullptr;
+    const bool fused = bf && one_row_per_seq && m->attention_appends && s_qkv <= kAttnAppendMaxSplits;
+    if (!fused) {
+      Timer t(m, st, K_ROPE_APPEND);
+      launch_qk_rope_append(st, g, part, s_qkv, q_gain, k_gain, rope, rows, m->k_pool(l), m->v_pool(l), q, M);
+    }
     if (bf) {
       Timer t(m, st, K_ATTN);
+      const AttnAppend ap = {part, s_qkv, q_gain, k_gain, rope};
       launch_attn_decode_bf16(st, g, q, rows, bt, m->k_pool(l), m->v_pool(l), apart, m->lay.max_segs, max_ctx_in_batch, o, M,
-                              sa.skip, sa.sets, sa.n_sets, sa.max_segs);
+                              sa.skip, sa.sets, sa.n_sets, sa.max_segs, fused ? &ap : nullptr);
     } else {
       Timer t(m, st, K_ATTN);
       launch_attn_f32(st, g, q, rows, bt, m->k_pool(l), m->v_pool(l), (float*)o, M);
@@ -518,6 +526,12 @@ rl_status rl_debug_share_attention(rl_model* m, int32_t on) {
   return RL_OK;
 }
 
+rl_status rl_debug_attention_appends(rl_model* m, int32_t on) {
+  if (!m) return fail(RL_ERR_INVALID_ARG, "model is NULL");
+  m->attention_appends = on != 0;
+  return RL_OK;
+}
+
 rl_status rl_set_capture(rl_model* m, float* buf) {
   if (!m) return fail(RL_ERR_INVALID_ARG, "model is NULL");
   m->capture = buf;
@@ -541,7 +555,7 @@ rl_status rl_decode_step(rl_model* m, void* stream, int32_t n, const int32_t* se
   float* x = m->wsp<float>(m->lay.x);
   { Timer t(m, st, K_EMBED);
     launch_embed(st, m->geo.dtype, m->embed, in_tokens, x, n, m->geo.hidden, m->geo.vocab); }
-  int pend = run_layers(m, st, n, rows, max_ctx_in_batch, sa);
+  int pend = run_layers(m, st, n, rows, max_ctx_in_batch, sa, true);
   run_head(m, st, n, x, pend, rows, 1, forced_next, sp, out_tokens, out_logprobs, debug_logits);
   HIP_TRY(hipGetLastError());
   for (int i = 0; i < n; ++i) m->table->set_len(seq_ids[i], m->table->len(seq_ids[i]) + 1);
@@ -563,7 +577,7 @@ rl_status rl_decode_hidden(rl_model* m, void* stream, int32_t n, const int32_t* 
   float* x = m->wsp<float>(m->lay.x);
   const size_t bytes = (size_t)n * m->geo.hidden * 4;
   HIP_TRY(hipMemcpyAsync(x, hidden_in, bytes, hipMemcpyDeviceToDevice, st));
-  int pend = run_layers(m, st, n, rows, max_ctx_in_batch, sa);
+  int pend = run_layers(m, st, n, rows, max_ctx_in_batch, sa, true);
   float* cap = m->capture ? m->capture + (size_t)m->geo.n_layers * m->cfg.max_rows * m->geo.hidden : nullptr;
   { Timer t(m, st, K_NORM);
     launch_residual_norm(st, m->geo.dtype, x, m->wsp<float>(m->lay.part), pend, nullptr, nullptr, cap, n, m->geo.hidden, m->geo.rms_eps); }

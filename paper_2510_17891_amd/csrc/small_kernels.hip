@@ -2,6 +2,7 @@
 // These move little data per step; they are written for few launches and simple indexing.
 #include "device_utils.h"
 #include "kernels.h"
+#include "rope_device.h"
 
 namespace rl {
 
@@ -103,32 +104,6 @@ void launch_residual_norm(hipStream_t s, int dtype, float* x, const float* part,
     residual_norm_kernel<false><<<M, threads, 0, s>>>(x, part, S, stride, gain, h_out, capture, H, eps);
 }
 
-// ------------------------------------------------------------------------------------------------
-// KV page element offsets.
-//   fp32 pages: plain [16 tokens][d].
-//   bf16 pages (d = 128): K as [d/8][16 tokens][8] so that the 16 keys x 32 dims an MFMA step needs are
-//   one coalesced 1 KiB read; V as [d/32][4 key groups][16 dims][2 x 4 keys] so that a lane's 16 bytes
-//   are four keys of two dims -- the transposed operand of the P*V product with no shuffle.
-// ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ int k_page_offset_bf16(int t, int dd) { return ((dd >> 3) * 16 + t) * 8 + (dd & 7); }
-__device__ __forceinline__ int v_page_offset_bf16(int t, int dd) {
-  int dblk = dd >> 4, dl = dd & 15, jj = dblk >> 1, par = dblk & 1, g = t >> 2;
-  return ((jj * 64 + g * 16 + dl) * 8) + par * 4 + (t & 3);
-}
-
-template <bool BF16>
-__device__ __forceinline__ void kv_store(void* pool_layer, int64_t page, int hk, int n_kv, int d, int t, int dd,
-                                         float val, bool is_v) {
-  const size_t page_elems = (size_t)kPageTokens * d;
-  const size_t base = ((size_t)page * n_kv + hk) * 2 * page_elems;  // [page][kv head][K | V]; V's base pointer is one block in
-  if (BF16) {
-    int off = is_v ? v_page_offset_bf16(t, dd) : k_page_offset_bf16(t, dd);
-    ((uint16_t*)pool_layer)[base + off] = (uint16_t)f2bf(val);
-  } else {
-    ((float*)pool_layer)[base + (size_t)t * d + dd] = val;
-  }
-}
-
 // One wave per (row, head), four heads per block.  Lane i < d/2 owns the rotary pair (i, i + d/2).
 template <bool BF16>
 __global__ __launch_bounds__(256) void qk_rope_append_kernel(const float* __restrict__ part, int S, size_t split_stride,
@@ -147,54 +122,24 @@ __global__ __launch_bounds__(256) void qk_rope_append_kernel(const float* __rest
   // Everything that depends only on the row's (seq, pos) is requested first, so that it travels together with the
   // partial sums instead of after them.
   const int64_t page = rm.page;
-  // lanes may own more than one pair when d/2 > 64
+  const bool rotate = is_q || is_k;
+  const float* head_part = part + (size_t)r * n_tot + (size_t)hh * d;
+  const void* gain = qk_norm ? (is_q ? q_gain : k_gain) : nullptr;
+  // lanes may own more than one pair when d/2 > 64 (without per-head normalisation only: the host rejects wider
+  // normalised heads for this kernel)
   for (int i = lane; i < ((half + 63) & ~63); i += 64) {
-    const bool live = i < half;
-    float2 cs = make_float2(1.f, 0.f);
-    float g0 = 1.f, g1 = 1.f;
-    if (live && (is_q || is_k)) {
-      cs = rope[(size_t)rm.pos * half + i];
-      if (qk_norm) {
-        if (BF16) {
-          const uint16_t* g = (const uint16_t*)(is_q ? q_gain : k_gain);
-          g0 = bf2f(g[i]); g1 = bf2f(g[i + half]);
-        } else {
-          const float* g = (const float*)(is_q ? q_gain : k_gain);
-          g0 = g[i]; g1 = g[i + half];
-        }
-      }
-    }
-    float v0 = 0.f, v1 = 0.f;
-    if (live) {
-#pragma unroll 4
-      for (int sp = 0; sp < S; ++sp) {
-        const float* p = part + sp * split_stride + (size_t)r * n_tot + (size_t)hh * d;
-        v0 += p[i];
-        v1 += p[i + half];
-      }
-    }
-    if (is_q || is_k) {
-      if (qk_norm) {
-        // d <= 128 here (one pass); wider heads are rejected by the host for this kernel
-        const float ss = wave_sum(v0 * v0 + v1 * v1);
-        const float inv = 1.0f / sqrtf(ss / (float)d + eps);
-        v0 = v0 * inv * g0;
-        v1 = v1 * inv * g1;
-      }
-      const float r0 = v0 * cs.x - v1 * cs.y;
-      const float r1 = v1 * cs.x + v0 * cs.y;
-      v0 = r0; v1 = r1;
-    }
-    if (!live) continue;
+    HeadPair hp = head_pair_load<BF16>(head_part, S, split_stride, d, i, rotate, rope + (size_t)rm.pos * half, gain);
+    head_pair_finish(hp, d, rotate, qk_norm != 0, eps);
+    if (i >= half) continue;
     if (is_q) {
       float* q = q_out + ((size_t)r * n_q + hh) * d;
-      q[i] = v0;
-      q[i + half] = v1;
+      q[i] = hp.v0;
+      q[i + half] = hp.v1;
     } else {
       const int hk = is_k ? hh - n_q : hh - n_q - n_kv;
       const int t = rm.pos & 15;
-      kv_store<BF16>(is_k ? k_pool : v_pool, page, hk, n_kv, d, t, i, v0, !is_k);
-      kv_store<BF16>(is_k ? k_pool : v_pool, page, hk, n_kv, d, t, i + half, v1, !is_k);
+      kv_store<BF16>(is_k ? k_pool : v_pool, page, hk, n_kv, d, t, i, hp.v0, !is_k);
+      kv_store<BF16>(is_k ? k_pool : v_pool, page, hk, n_kv, d, t, i + half, hp.v1, !is_k);
     }
   }
 }

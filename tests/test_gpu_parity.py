@@ -732,29 +732,36 @@ def test_shared_prompt_attention_is_bit_identical_to_per_row(amd):
     per set of rows.  Logits, tokens and log-probs equal, bit for bit, those with the sharing switched off and
     those of sequences prefilled one by one (which share nothing), for a prompt inside one block's segments, one
     beyond 4096 keys (partials through the workspace) and a short one; with sets of four and of two, a left-over
-    row, members that retire, and members that fall out of step."""
+    row, members that retire, and members that fall out of step.  A fourth instance runs the rotation and the KV
+    append as a kernel of their own instead of inside the attention kernel: same bits again, step after step (so
+    the keys and values it leaves in the pages are the same too)."""
     shape = dict(ri.SHAPES["layer8b"], n_layers=2, hidden=512, n_q=8, n_kv=2, ffn=768, vocab=8192)
     w, _ = make_both(shape, 63, std=0.05)
     wd = to_device(w)
     G, seed = 7, 5
-    lens = [1100, 4500, 300]
+    lens = [1100, 4500, 300, 5]                  # the last one: a single 32-key step at first, no full prompt page
     prompts = [ri.tokens((n,), shape["vocab"], 63, 940 + i).tolist() for i, n in enumerate(lens)]
     ids = list(range(len(lens) * G))
-    kw = dict(max_seqs=24, max_ctx=4608, max_rows=64, kv_pages=2700)
+    kw = dict(max_seqs=32, max_ctx=4608, max_rows=64, kv_pages=2750)
     ra = amd.Rollout(shape, wd, **kw)       # shared pages, shared attention
     rb = amd.Rollout(shape, wd, **kw)       # shared pages, every row on its own
     rc = amd.Rollout(shape, wd, **kw)       # nothing shared
+    rd = amd.Rollout(shape, wd, **kw)       # shared pages and attention, separate rotation + append kernel
     rb.rl_debug_share_attention(False)
+    rd.rl_debug_attention_appends(False)
     ta, la = ra.rl_prefill_groups(ids, G, prompts, 1.0, seed)
     tb, lb = rb.rl_prefill_groups(ids, G, prompts, 1.0, seed)
     tc, lc = rc.rl_prefill(ids, [prompts[i // G] for i in ids], 1.0, seed)
+    td, ld = rd.rl_prefill_groups(ids, G, prompts, 1.0, seed)
     torch.cuda.synchronize()
     assert torch.equal(ta, tb) and torch.equal(la, lb) and torch.equal(ta, tc) and torch.equal(la, lc)
+    assert torch.equal(ta, td) and torch.equal(la, ld)
     V = shape["vocab"]
+    every = (ra, rb, rc, rd)
 
     def step(active, tok):
-        zs = [torch.empty(len(active), V, device=DEV) for _ in range(3)]
-        outs = [r.rl_decode_step(active, tok, 1.0, seed, debug_logits=z) for r, z in zip((ra, rb, rc), zs)]
+        zs = [torch.empty(len(active), V, device=DEV) for _ in every]
+        outs = [r.rl_decode_step(active, tok, 1.0, seed, debug_logits=z) for r, z in zip(every, zs)]
         torch.cuda.synchronize()
         for z, (t_, l_) in zip(zs[1:], outs[1:]):
             assert torch.equal(zs[0], z) and torch.equal(outs[0][0], t_) and torch.equal(outs[0][1], l_)
@@ -762,10 +769,10 @@ def test_shared_prompt_attention_is_bit_identical_to_per_row(amd):
 
     tok = {i: int(ta[k]) for k, i in enumerate(ids)}
     active = list(ids)
-    for it in range(24):
+    for it in range(36):                         # every slot of a page, both pages of a 32-key step
         if it == 6:                              # one member of each prompt retires: sets of four and two remain
             gone = [0, G + 3, 2 * G + 6]
-            for r in (ra, rb, rc):
+            for r in every:
                 r.rl_free_seqs(gone)
             active = [i for i in active if i not in gone]
         if it == 12:                             # two members of the first prompt fall one step behind
@@ -778,7 +785,7 @@ def test_shared_prompt_attention_is_bit_identical_to_per_row(amd):
         out = step(order, torch.tensor([tok[i] for i in order], dtype=torch.int32, device=DEV))
         for k, i in enumerate(order):
             tok[i] = int(out[k])
-    for r in (ra, rb, rc):
+    for r in every:
         r.close()
 
 
