@@ -51,7 +51,9 @@ def measured_traffic(workload, kernel, algorithmic_bytes):
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=512)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed decode steps; default: full workload 1015 (with the prefill token and 8 warm-up steps "
+                         "that is the 1024 generated tokens per sequence of the workload), others 512")
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", choices=["full", "layer", "copy", "ragged"], default="full")
     ap.add_argument("--length-scale", type=float, default=1.0,
@@ -80,7 +82,10 @@ def parse():
                     help="full workload: attention over the prompt pages once per row instead of once per set of samples")
     ap.add_argument("--separate-append", action="store_true",
                     help="rotation and KV append as a kernel of their own instead of inside the decode attention kernel")
-    return ap.parse_args()
+    args = ap.parse_args()
+    if args.steps is None:
+        args.steps = 1015 if args.workload == "full" else 512
+    return args
 
 
 def kernel_bytes(shape, M, ctx_sum, bf=2):

@@ -30,29 +30,30 @@ void launch_embed(hipStream_t s, int dtype, const void* embed, const int32_t* to
 // that the few dependent memory round trips of this latency-bound step are as short as possible.  The split
 // partials of the preceding projection are summed in a fixed order, so results do not depend on the batch.
 // ------------------------------------------------------------------------------------------------
+// gain: H gains; without a norm (has_gain = 0) any readable H-element array of the model's dtype.
 template <bool BF16>
 __global__ __launch_bounds__(1024) void residual_norm_kernel(float* __restrict__ x, const float* __restrict__ part,
                                                              int S, size_t split_stride, const void* __restrict__ gain,
-                                                             void* __restrict__ h_out, float* __restrict__ capture,
-                                                             int H, float eps) {
+                                                             int has_gain, void* __restrict__ h_out,
+                                                             float* __restrict__ capture, int H, float eps) {
   __shared__ float red[16];
   const int r = blockIdx.x, nthr = blockDim.x;
   float* xr = x + (size_t)r * H;
   float ss = 0.f;
   constexpr int kMaxPass = 2;  // H <= 1024 threads * 4 * kMaxPass, checked by the host
   float4 keep[kMaxPass];
-  float4 gv[kMaxPass];  // gains, fetched together with the data so that only one memory round trip precedes the sum
+  // Gains are requested together with the data, as stored (bf16: two words per thread), and first touched after the
+  // sums: converting them here would make the compiler wait for them before it even asks for the data.
+  uint4 graw[kMaxPass];
 #pragma unroll
   for (int pass = 0; pass < kMaxPass; ++pass) {
     const int i0 = (pass * nthr + threadIdx.x) * 4;
-    gv[pass] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (gain != nullptr && i0 < H) {
-      if (BF16) {
-        const uint2 gb = *(const uint2*)((const uint16_t*)gain + i0);
-        gv[pass] = make_float4(bf2f(gb.x & 0xffffu), bf2f(gb.x >> 16), bf2f(gb.y & 0xffffu), bf2f(gb.y >> 16));
-      } else {
-        gv[pass] = *(const float4*)((const float*)gain + i0);
-      }
+    const int ig = i0 < H ? i0 : 0;  // unconditional loads (a branch here costs a wait); `gain` is always readable
+    if (BF16) {
+      const uint2 gb = *(const uint2*)((const uint16_t*)gain + ig);
+      graw[pass] = make_uint4(gb.x, gb.y, 0u, 0u);
+    } else {
+      graw[pass] = *(const uint4*)((const float*)gain + ig);
     }
   }
 #pragma unroll
@@ -72,7 +73,10 @@ __global__ __launch_bounds__(1024) void residual_norm_kernel(float* __restrict__
     keep[pass] = v;
     ss += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
   }
-  if (gain == nullptr) return;
+  if (!has_gain) return;
+#pragma unroll
+  for (int pass = 0; pass < kMaxPass; ++pass)
+    asm volatile("" : "+v"(graw[pass].x), "+v"(graw[pass].y), "+v"(graw[pass].z), "+v"(graw[pass].w));
   ss = wave_sum(ss);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
   __syncthreads();
@@ -83,7 +87,14 @@ __global__ __launch_bounds__(1024) void residual_norm_kernel(float* __restrict__
   for (int pass = 0; pass < kMaxPass; ++pass) {
     const int i0 = (pass * nthr + threadIdx.x) * 4;
     if (i0 >= H) continue;
-    const float4 v = keep[pass], g = gv[pass];
+    const float4 v = keep[pass];
+    float4 g;
+    if (BF16) {
+      g = make_float4(bf2f(graw[pass].x & 0xffffu), bf2f(graw[pass].x >> 16), bf2f(graw[pass].y & 0xffffu), bf2f(graw[pass].y >> 16));
+    } else {
+      g = make_float4(__uint_as_float(graw[pass].x), __uint_as_float(graw[pass].y), __uint_as_float(graw[pass].z),
+                      __uint_as_float(graw[pass].w));
+    }
     if (BF16) {
       *(uint2*)((uint16_t*)h_out + frag_offset(r, i0, H >> 6)) =
           make_uint2(pack2bf(v.x * inv * g.x, v.y * inv * g.y), pack2bf(v.z * inv * g.z, v.w * inv * g.w));
@@ -98,10 +109,12 @@ void launch_residual_norm(hipStream_t s, int dtype, float* x, const float* part,
   size_t stride = (size_t)M * H;
   int threads = ((H / 4 + 63) / 64) * 64;
   if (threads > 1024) threads = 1024;
+  const int has_gain = gain != nullptr;
+  const void* g = has_gain ? gain : x;  // read and ignored without a norm
   if (dtype == kBF16)
-    residual_norm_kernel<true><<<M, threads, 0, s>>>(x, part, S, stride, gain, h_out, capture, H, eps);
+    residual_norm_kernel<true><<<M, threads, 0, s>>>(x, part, S, stride, g, has_gain, h_out, capture, H, eps);
   else
-    residual_norm_kernel<false><<<M, threads, 0, s>>>(x, part, S, stride, gain, h_out, capture, H, eps);
+    residual_norm_kernel<false><<<M, threads, 0, s>>>(x, part, S, stride, g, has_gain, h_out, capture, H, eps);
 }
 
 // One wave per (row, head), four heads per block.  Lane i < d/2 owns the rotary pair (i, i + d/2).
