@@ -362,13 +362,37 @@ def main():
 
     # ---- per-kernel durations from HIP events on the launch stream, same steps, same state --------------
     if not args.no_profile:
-        ro.rl_profile_enable(True)
-        for _ in range(args.profile_steps):
-            step()
-        torch.cuda.synchronize()
-        prof = ro.rl_profile_read()
-        ro.rl_profile_enable(False)
-        ctx_p = ctx_end + 0.5 * (args.profile_steps - 1) + 1
+        if args.workload == "full" and args.prefill == "real":
+            # The timed region once more, from the same prompts and seed (the same tokens), with the events switched
+            # on for every stride-th step: launch durations over the contexts of the timed region, not after it.
+            ro.rl_free_seqs(seq_ids)
+            tok, _ = ro.rl_prefill_groups(seq_ids, G, [prompts[i].tolist() for i in range(n_prompts)], 1.0, seed)
+            state["cur"], state["i"] = tok, 0
+            for _ in range(args.warmup):
+                step()
+            stride = max(1, args.steps // 128)
+            ctx_seen = []
+            for k in range(args.steps):
+                on = k % stride == 0
+                if on:
+                    ro.rl_profile_enable(True)
+                    ctx_seen.append(ctx_begin + k + 1)
+                step()
+                if on:
+                    ro.rl_profile_enable(False)
+            torch.cuda.synchronize()
+            prof = ro.rl_profile_read()
+            ctx_p = sum(ctx_seen) / len(ctx_seen)
+            out["config"]["kernel_timing"] = f"HIP events on every {stride}th step of a second pass over the timed region"
+        else:
+            ro.rl_profile_enable(True)
+            for _ in range(args.profile_steps):
+                step()
+            torch.cuda.synchronize()
+            prof = ro.rl_profile_read()
+            ro.rl_profile_enable(False)
+            ctx_p = ctx_end + 0.5 * (args.profile_steps - 1) + 1
+            out["config"]["kernel_timing"] = f"HIP events on {args.profile_steps} steps after the timed region"
         shp = shape if shape["vocab"] else dict(shape, vocab=4)
         kb = kernel_bytes(shp, B, ctx_sum(ctx_p))
         kernels = {}
