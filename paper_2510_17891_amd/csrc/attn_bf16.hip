@@ -172,7 +172,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
   const bool col_valid = j < n_members * group;
   const int col_head = hk * group + j % group;
   const RowMeta rm = rows[r];
-  const int ctx = rm.pos + 1;  // keys 0..pos (the row's own key was appended before this kernel)
+  const int ctx = rm.pos + 1;  // keys 0..pos; the row's own key is in its page already, or (APPEND) formed here
   const int n_seg = attn_num_segments(ctx);
   const bool in_lds = !is_set && skip == 0 && n_seg <= kLdsSegs;  // merged by this block
   // this block's segments [lo, hi)
