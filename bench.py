@@ -55,10 +55,10 @@ def parse():
                     help="timed decode steps; default: full workload 1015 (with the prefill token and 8 warm-up steps "
                          "that is the 1024 generated tokens per sequence of the workload), others 512")
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", choices=["full", "layer", "copy", "ragged"], default="full")
+    ap.add_argument("--workload", choices=["full", "layer", "copy", "ragged", "max"], default="full")
     ap.add_argument("--length-scale", type=float, default=1.0,
                     help="ragged workload: multiply the drawn prompt and final lengths (1.0: prompts U[256,1024], "
-                         "final lengths U[1024,8192])")
+                         "final lengths U[1024,8192]); max workload: multiply prompt 2048 and total context 16384")
     ap.add_argument("--profile-steps", type=int, default=8, help="extra steps run with per-kernel events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
@@ -213,6 +213,59 @@ def main():
             "config": {"workload": f"full8b_ragged_{n_prompts}x{G}_scale{sc}", "prompts": "U[256,1024] per prompt",
                        "final_lengths": "U[1024,8192] per sequence", "generated_tokens": n_tok, "kv_pages": pages,
                        "prefill": "inside the timed region, prompts run once per group", "temperature": 1.0},
+            "whole_run_s": elapsed, "hbm_fraction_per_sequence_formula": total_bytes / elapsed / (HBM_PEAK_GBS * 1e9),
+            "active_sequences_first_mid_last": [trace[0], trace[len(trace) // 2], trace[-1]] if trace else None}))
+        ro.close()
+        return
+
+    if args.workload == "max":
+        # The largest rollout batch (Appendix D limits): 32 prompts x 8 samples, prompt 2048, generated up to 16384 tokens
+        # of context, KV pool = what the card holds beside the weights.  The 256 sequences need 618 GB of KV, so groups
+        # are admitted as pages allow (generate_groups reserves a group's pages up to its limit) and the rest waits.
+        from paper_2510_17891_amd import generate_groups, group_page_need
+        shape = ri.SHAPES["full8b"]
+        n_prompts, G = 32, 8
+        sc = args.length_scale
+        P, total = max(16, int(2048 * sc)), max(32, int(16384 * sc))
+        limits = [total - P] * (n_prompts * G)
+        prompts = [ri.tokens((P,), shape["vocab"], seed, 960 + i).tolist() for i in range(n_prompts)]
+        need_group = group_page_need(P, limits[:G])
+        w = ri.make_weights(shape, seed, device=dev, dtype=torch.bfloat16)
+        page_bytes = 16 * shape["n_layers"] * shape["n_kv"] * shape["head_dim"] * 2 * 2
+        # kv_pages=None: the pool takes what the card holds once the packed weights and the workspace are placed
+        ro = Rollout(shape, w, max_seqs=n_prompts * G, max_ctx=(total + 15) // 16 * 16, max_rows=256, kv_pages=None,
+                     consume_weights=True, kv_slack_bytes=4 << 30)
+        del w
+        pages = ro.rl_kv_stats()[1]
+        torch.cuda.synchronize()
+        trace = []
+        t0 = time.perf_counter()
+
+        def progress(s_, n_):
+            trace.append(n_)
+            if s_ % 1000 == 0:
+                print(f"step {s_}: {n_} sequences active, {time.perf_counter() - t0:.0f} s", file=sys.stderr, flush=True)
+
+        toks, lps = generate_groups(ro, prompts, G, limits, 1.0, seed, on_step=progress)
+        elapsed = time.perf_counter() - t0
+        n_tok = sum(len(t) for t in toks)
+        assert [len(t) for t in toks] == limits and all(len(l) == len(t) for l, t in zip(lps, toks))
+        steps = len(trace)
+        kv_tokens = n_prompts * G * sum(range(P + 1, total))
+        wbytes = 2 * (shape["n_layers"] * (shape["hidden"] * (shape["n_q"] + 2 * shape["n_kv"]) * shape["head_dim"]
+                                          + shape["n_q"] * shape["head_dim"] * shape["hidden"]
+                                          + 3 * shape["ffn"] * shape["hidden"]) + shape["vocab"] * shape["hidden"])
+        total_bytes = steps * wbytes + kv_tokens * shape["n_layers"] * shape["n_kv"] * 2 * shape["head_dim"] * 2
+        print(json.dumps({
+            "metric": "generated tokens/s (8B-shaped bf16 decode) + % peak HBM GB/s, 1 MI355X",
+            "value": n_tok / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": 0,
+            "ms_per_step": elapsed / max(1, steps) * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": f"full8b_max_{n_prompts}x{G}_prompt{P}_to{total}", "generated_tokens": n_tok,
+                       "kv_pages": pages, "kv_pool_GB": pages * page_bytes / 1e9, "pages_per_group": need_group,
+                       "groups_resident_at_once": pages // need_group,
+                       "prefill": "inside the timed region, prompts run once per group", "temperature": 1.0,
+                       "logprob_per_token": True},
             "whole_run_s": elapsed, "hbm_fraction_per_sequence_formula": total_bytes / elapsed / (HBM_PEAK_GBS * 1e9),
             "active_sequences_first_mid_last": [trace[0], trace[len(trace) // 2], trace[-1]] if trace else None}))
         ro.close()

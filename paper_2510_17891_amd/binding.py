@@ -172,7 +172,11 @@ class Rollout:
     the layouts rl.h prescribes; the logical tensors are not kept.
     """
 
-    def __init__(self, shape, weights, max_seqs, max_ctx, max_rows, kv_pages, device="cuda:0"):
+    def __init__(self, shape, weights, max_seqs, max_ctx, max_rows, kv_pages, device="cuda:0", consume_weights=False,
+                 kv_slack_bytes=2 << 30):
+        """kv_pages: pages in the KV pool, or None for as many as the card holds once the packed weights and the
+        workspace are placed (less kv_slack_bytes).  consume_weights: the entries of `weights` are removed as they are
+        packed, so that a model of 16 GB does not exist twice on the card at any time."""
         L = lib()
         self.shape = dict(shape)
         self.device = torch.device(device)
@@ -184,11 +188,6 @@ class Rollout:
             raise RLError(RL_ERR_UNSUPPORTED, L.rl_last_error().decode())
         need = C.c_uint64()
         check(L.rl_query_workspace(C.byref(cfg), C.byref(need)))
-        cfg.kv_pool_bytes = page * kv_pages
-        cfg.workspace_bytes = need.value
-        self.cfg = cfg
-        self.kv_pool = torch.empty(cfg.kv_pool_bytes, dtype=torch.uint8, device=self.device)
-        self.workspace = torch.empty(cfg.workspace_bytes, dtype=torch.uint8, device=self.device)
         self._keep = []
         n_layers = shape["n_layers"]
 
@@ -197,22 +196,45 @@ class Rollout:
             self._keep.append((a, tensors))
             return C.cast(a, _pp)
 
+        def take(d, k):
+            return d.pop(k) if consume_weights else d[k]
+
+        def packed(d, keys):
+            parts = [take(d, k) for k in keys]
+            src = parts[0].contiguous() if len(parts) == 1 else torch.cat(parts, 0)
+            del parts
+            out = rl_pack_weight(src)
+            del src
+            return out
+
         lay = weights["layers"]
         w = rl_weights()
         if shape["vocab"] > 0:
-            self.embed = weights["embed"].contiguous()
-            self.lm_head = rl_pack_weight(weights["lm_head"].contiguous())
+            self.embed = take(weights, "embed").contiguous()
+            self.lm_head = packed(weights, ["lm_head"])
             w.embed, w.lm_head = self.embed.data_ptr(), self.lm_head.data_ptr()
-        self.final_norm = weights["final_norm"].contiguous()
+        self.final_norm = take(weights, "final_norm").contiguous()
         w.final_norm = self.final_norm.data_ptr()
-        w.attn_norm = arr([l["attn_norm"].contiguous() for l in lay])
-        w.mlp_norm = arr([l["mlp_norm"].contiguous() for l in lay])
-        w.q_norm = arr([l["q_norm"].contiguous() for l in lay])
-        w.k_norm = arr([l["k_norm"].contiguous() for l in lay])
-        w.wqkv = arr([rl_pack_weight(torch.cat([l["wq"], l["wk"], l["wv"]], 0).contiguous()) for l in lay])
-        w.wo = arr([rl_pack_weight(l["wo"].contiguous()) for l in lay])
-        w.w_gate_up = arr([rl_pack_weight(torch.cat([l["w_gate"], l["w_up"]], 0).contiguous()) for l in lay])
-        w.w_down = arr([rl_pack_weight(l["w_down"].contiguous()) for l in lay])
+        w.attn_norm = arr([take(l, "attn_norm").contiguous() for l in lay])
+        w.mlp_norm = arr([take(l, "mlp_norm").contiguous() for l in lay])
+        w.q_norm = arr([take(l, "q_norm").contiguous() for l in lay])
+        w.k_norm = arr([take(l, "k_norm").contiguous() for l in lay])
+        w.wqkv = arr([packed(l, ["wq", "wk", "wv"]) for l in lay])
+        w.wo = arr([packed(l, ["wo"]) for l in lay])
+        w.w_gate_up = arr([packed(l, ["w_gate", "w_up"]) for l in lay])
+        w.w_down = arr([packed(l, ["w_down"]) for l in lay])
+        if kv_pages is None:
+            torch.cuda.synchronize(self.device)
+            torch.cuda.empty_cache()
+            free_b, _ = torch.cuda.mem_get_info(self.device)
+            kv_pages = int((free_b - need.value - kv_slack_bytes) // page)
+            if kv_pages < 1:
+                raise RLError(RL_ERR_KV_FULL, "no room for a KV pool beside the weights")
+        cfg.kv_pool_bytes = page * kv_pages
+        cfg.workspace_bytes = need.value
+        self.cfg = cfg
+        self.kv_pool = torch.empty(cfg.kv_pool_bytes, dtype=torch.uint8, device=self.device)
+        self.workspace = torch.empty(cfg.workspace_bytes, dtype=torch.uint8, device=self.device)
         w.kv_pool, w.workspace = self.kv_pool.data_ptr(), self.workspace.data_ptr()
         torch.cuda.synchronize(self.device)
         h = C.c_void_p()

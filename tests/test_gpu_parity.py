@@ -391,6 +391,31 @@ def test_bf16_small_model_teacher_forced_logits(amd):
 
 
 # ------------------------------------------------------------------------------------------- error handling
+def test_rollout_consumes_weights_and_sizes_pool_itself(amd):
+    """consume_weights empties the caller's dict while packing (one copy of the model on the card); with
+    kv_pages=None the pool takes what is left beside weights and workspace.  Same outputs as a plain instance."""
+    shape = ri.SHAPES["tiny"]
+    w, _ = make_both(shape, 41)
+    prompts = ri.tokens((3, 20), shape["vocab"], 41, 930).tolist()
+    ra = amd.Rollout(shape, to_device(w), max_seqs=4, max_ctx=64, max_rows=64, kv_pages=16)
+    wd = to_device(w)
+    free_before, total = torch.cuda.mem_get_info()
+    rb = amd.Rollout(shape, wd, max_seqs=4, max_ctx=64, max_rows=64, kv_pages=None, consume_weights=True,
+                     kv_slack_bytes=free_before - (256 << 20))      # leaves about 256 MiB for workspace and pool
+    assert set(wd.keys()) == {"layers"} and all(len(l) == 0 for l in wd["layers"])
+    n_pages = rb.rl_kv_stats()[1]
+    assert n_pages >= 16 and rb.cfg.kv_pool_bytes < (2 << 30)
+    ta, la = ra.rl_prefill([0, 1, 2], prompts, 1.0, 3)
+    tb, lb = rb.rl_prefill([0, 1, 2], prompts, 1.0, 3)
+    for _ in range(3):
+        ta, la = ra.rl_decode_step([0, 1, 2], ta, 1.0, 3)
+        tb, lb = rb.rl_decode_step([0, 1, 2], tb, 1.0, 3)
+    torch.cuda.synchronize()
+    assert torch.equal(ta, tb) and torch.equal(la, lb)
+    ra.close()
+    rb.close()
+
+
 def test_error_paths_leave_state_untouched(amd):
     B = amd.binding
     shape = ri.SHAPES["tiny"]
