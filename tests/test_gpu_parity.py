@@ -348,37 +348,46 @@ def test_bf16_layer_batch_and_page_placement_invariance(amd):
 
 
 # --------------------------------------------------------------------------- bf16 small full model, logits
-def test_bf16_small_model_teacher_forced_logits(amd):
-    """2-layer bf16 decoder (8B head geometry, narrow): prefill + teacher-forced decode; logits within 3e-2,
-    argmax agreement >= 99 %, sampled ids reproduced by the oracle sampler from the GPU's logits."""
-    shape = dict(ri.SHAPES["layer8b"], n_layers=2, hidden=512, n_q=4, n_kv=1, ffn=768, vocab=8192)
+@pytest.mark.parametrize("n_q,n_kv,qk_norm", [(4, 1, 1), (8, 1, 1), (2, 2, 1), (4, 2, 0)])
+def test_bf16_small_model_teacher_forced_logits(amd, n_q, n_kv, qk_norm):
+    """2-layer bf16 decoder (8B head size, narrow), query groups of 4, 8, 1 and 2 heads per kv head, with and without
+    the per-head norm: prefill (three separate prompts and one prompt sampled three times, whose samples share
+    pages) + teacher-forced decode; logits within 3e-2, argmax agreement >= 99 %, sampled ids reproduced by the
+    oracle sampler from the GPU's logits."""
+    shape = dict(ri.SHAPES["layer8b"], n_layers=2, hidden=512, n_q=n_q, n_kv=n_kv, ffn=768, vocab=8192, qk_norm=qk_norm)
     w, wn = make_both(shape, 41, std=0.05)
-    ro = amd.Rollout(shape, to_device(w), max_seqs=4, max_ctx=320, max_rows=40, kv_pages=64)
+    ro = amd.Rollout(shape, to_device(w), max_seqs=6, max_ctx=320, max_rows=40, kv_pages=80)
     om = orc.OracleModel(dims_of(shape), wn, max_ctx=320)
-    lens = [270, 3, 33]
-    prompts = [ri.tokens((n,), shape["vocab"], 41, 920 + i).tolist() for i, n in enumerate(lens)]
-    seqs = [2, 0, 1]
+    lens = [270, 3, 33, 70, 70, 70]
+    prompts = [ri.tokens((n,), shape["vocab"], 41, 920 + i).tolist() for i, n in enumerate(lens[:4])]
+    prompts += [prompts[3], prompts[3]]
+    seqs = [2, 0, 1, 3, 4, 5]
     seed = 77
-    tok, lp = ro.rl_prefill(seqs, prompts, 1.0, seed)
+    ro.rl_prefill(seqs[:3], prompts[:3], 1.0, seed)
+    ro.rl_prefill_groups(seqs[3:], 3, [prompts[3]], 1.0, seed)
     torch.cuda.synchronize()
     for i, s in enumerate(seqs):
         om.prefill(s, prompts[i])
-    steps = 24
-    forced_all = ri.tokens((steps, 3), shape["vocab"], 41, 930)
-    logits = torch.empty(3, shape["vocab"], device=DEV)
-    cur = ri.tokens((3,), shape["vocab"], 41, 929).to(DEV)
+    n = len(seqs)
+    steps = 20
+    forced_all = ri.tokens((steps, n), shape["vocab"], 41, 930)
+    logits = torch.empty(n, shape["vocab"], device=DEV)
+    cur = ri.tokens((n,), shape["vocab"], 41, 929).to(DEV)
     agree, total, worst = 0, 0, 0.0
     for step in range(steps):
         forced = forced_all[step].clone()
-        forced[step % 3] = -1                         # leave one row sampled each step
+        forced[step % n] = -1                         # leave one row sampled each step
         tok, lp = ro.rl_decode_step(seqs, cur, 1.0, seed, forced_next=forced.to(DEV), debug_logits=logits)
         torch.cuda.synchronize()
         zg = logits.cpu().numpy()
         for i, s in enumerate(seqs):
             z = om.forward_token(s, int(cur[i]))
             worst = max(worst, float(rel_inf(zg[i], z)))
-            agree += int(np.argmax(zg[i]) == np.argmax(z))
+            a_gpu, a_orc = int(np.argmax(zg[i])), int(np.argmax(z))
+            agree += int(a_gpu == a_orc)
             total += 1
+            # where the two disagree the oracle's own margin between the two candidates is inside the logit tolerance
+            assert z[a_orc] - z[a_gpu] <= 2 * 3e-2 * np.abs(z).max()
             t_ref, lp_ref = orc.sample(zg[i], 1.0, seed, s, lens[i] + step + 1, forced=int(forced[i]))
             assert int(tok[i]) == t_ref
             assert abs(float(lp[i]) - lp_ref) < 1e-4
@@ -386,7 +395,8 @@ def test_bf16_small_model_teacher_forced_logits(amd):
             assert abs(float(lp[i]) - lp_orc) < 5e-2
         cur = tok
     assert worst < 3e-2, worst
-    assert agree >= 0.99 * total, (agree, total)
+    # the narrowest variants have nearly flat logits (near-ties flip inside the tolerance)
+    assert agree >= (0.99 if n_q * 128 >= 512 else 0.9) * total, (agree, total)
     ro.close()
 
 
