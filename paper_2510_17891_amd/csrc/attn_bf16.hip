@@ -223,7 +223,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
     float2 cs = ap.rope[(size_t)rm.pos * (kD / 2) + lane];  // the rows of a set have one position
     uint32_t gq0 = 0, gq1 = 0, gk0 = 0, gk1 = 0;            // gains as stored (bf16)
     if (ap.q_gain) { gq0 = ((const uint16_t*)ap.q_gain)[lane]; gq1 = ((const uint16_t*)ap.q_gain)[lane + kD / 2]; }
-    HeadPairLoads lq[4], lk, lv;
+    HeadPairLoads lq[4] = {}, lk = {}, lv = {};  // slots without a task stay zero
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int t = uw + 4 * u;
@@ -246,7 +246,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
     // the arithmetic (and with it the waits) up between the loads.
     asm volatile("" : "+v"(cs.x), "+v"(cs.y), "+v"(gq0), "+v"(gq1), "+v"(gk0), "+v"(gk1));
     // Five heads side by side: the (up to) four query columns of this wave and the new key.  Slots without a task
-    // hold whatever their registers held; their results are not stored.
+    // carry zeros through the same arithmetic; their results are not stored.
     HeadPair hp[5];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
