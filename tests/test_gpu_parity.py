@@ -292,11 +292,12 @@ def test_bf16_layer_decode_matches_oracle(amd, ctxs):
     ro.close()
 
 
-def test_bf16_layer_forked_rows_share_prompt_attention_and_match_oracle(amd):
-    """8B-dimension layer: three cached contexts are each continued as six sequences (shared full pages, copied
-    partial page).  The step computes the attention over the common pages once per set of rows; every row still
-    matches the oracle run on that row alone, and the bits equal those with the sharing switched off."""
-    ctxs, G = [2100, 5000, 700], 6
+@pytest.mark.parametrize("ctxs,G", [([2100, 5000, 700], 6), ([1024] * 4, 8)])
+def test_bf16_layer_forked_rows_share_prompt_attention_and_match_oracle(amd, ctxs, G):
+    """8B-dimension layer: cached contexts are each continued as G sequences (shared full pages, copied partial
+    page).  The step computes the attention over the common pages once per set of rows; every row still matches
+    the oracle run on that row alone, and the bits equal those with the sharing switched off.  The second case is
+    the launch shape of the 32-sequence rollout workload: 4 prompts of 1024 tokens x 8 samples, 32 rows."""
     shape = ri.SHAPES["layer8b"]
     w, wn = make_both(shape, 34)
     wd = to_device(w)
