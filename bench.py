@@ -139,8 +139,8 @@ def cpu_baseline_full(shape, ctx, n_seq=2):
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (rollouts shard by whole sequences with no per-step "
-              "communication; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py runs on one GPU only (a rollout shards by whole sequences, with no communication per step, so "
+              "N GPUs are N independent copies of this run); use --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch
     import rollout_inputs as ri
