@@ -239,9 +239,9 @@ def test_fork_errors_and_long_run_of_steps(amd):
 
 
 # ------------------------------------------------------------------------- bf16, one layer at 8B dimensions
-def _layer_case(amd, ctxs, seed, max_rows=None, shuffle=None):
+def _layer_case(amd, ctxs, seed, max_rows=None, shuffle=None, **shape_over):
     """Import random N(0,1) bf16 KV of the given lengths, run one decode step on N(0,1) hidden rows."""
-    shape = ri.SHAPES["layer8b"]
+    shape = dict(ri.SHAPES["layer8b"], **shape_over)
     w, wn = make_both(shape, seed)
     B = len(ctxs)
     max_ctx = (max(ctxs) + 1 + 15) // 16 * 16 + 16
@@ -289,6 +289,20 @@ def test_bf16_layer_decode_matches_oracle(amd, ctxs):
         err = rel_inf(out[b] - x[b].numpy(), ref - x[b].numpy())
         assert err < 3e-2, (b, c, err)
         assert ro.rl_seq_len(b) == c + 1
+    ro.close()
+
+
+def test_bf16_layer_eight_query_heads_per_kv_head_long_contexts(amd):
+    """The widest query group the bf16 path accepts (8 heads per kv head: the largest per-block merge area), at
+    contexts on both sides of the switch between the merge inside the block and the one through the workspace."""
+    ctxs = [4000, 3000, 100, 5000, 4096]
+    shape, wn, ro, ks, vs, x = _layer_case(amd, ctxs, seed=37, shuffle=3, hidden=1024, n_q=16, n_kv=2, ffn=1536)
+    B = len(ctxs)
+    out = ro.rl_decode_hidden(list(range(B)), x.to(DEV)).cpu().numpy()
+    for b, c in enumerate(ctxs):
+        ref = _oracle_layer_row(shape, wn, ks[b], vs[b], x[b], c)
+        err = rel_inf(out[b] - x[b].numpy(), ref - x[b].numpy())
+        assert err < 3e-2, (b, c, err)
     ro.close()
 
 
