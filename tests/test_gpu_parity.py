@@ -239,13 +239,13 @@ def test_fork_errors_and_long_run_of_steps(amd):
 
 
 # ------------------------------------------------------------------------- bf16, one layer at 8B dimensions
-def _layer_case(amd, ctxs, seed, max_rows=None, shuffle=None, **shape_over):
+def _layer_case(amd, ctxs, seed, max_rows=None, shuffle=None, extra_pages=0, **shape_over):
     """Import random N(0,1) bf16 KV of the given lengths, run one decode step on N(0,1) hidden rows."""
     shape = dict(ri.SHAPES["layer8b"], **shape_over)
     w, wn = make_both(shape, seed)
     B = len(ctxs)
     max_ctx = (max(ctxs) + 1 + 15) // 16 * 16 + 16
-    pages = sum((c + 1 + 15) // 16 for c in ctxs) + 4
+    pages = sum((c + 1 + 15) // 16 for c in ctxs) + 4 + extra_pages
     ro = amd.Rollout(shape, to_device(w), max_seqs=B, max_ctx=max_ctx, max_rows=max_rows or B, kv_pages=pages)
     if shuffle is not None:
         ro.rl_debug_shuffle_free_pages(shuffle)
@@ -289,6 +289,19 @@ def test_bf16_layer_decode_matches_oracle(amd, ctxs):
         err = rel_inf(out[b] - x[b].numpy(), ref - x[b].numpy())
         assert err < 3e-2, (b, c, err)
         assert ro.rl_seq_len(b) == c + 1
+    ro.close()
+
+
+def test_bf16_layer_pages_far_into_a_large_pool(amd):
+    """A 5.2 GB pool (80 000 pages of 64 KiB per layer) with the free list shuffled: the sequences' pages lie all
+    over it, most of them beyond 4 GiB from its start, which 32-bit offset arithmetic anywhere would not survive."""
+    ctxs = [700, 33, 1500, 260]
+    shape, wn, ro, ks, vs, x = _layer_case(amd, ctxs, seed=39, shuffle=11, extra_pages=80000)
+    out = ro.rl_decode_hidden(list(range(len(ctxs))), x.to(DEV)).cpu().numpy()
+    for b, c in enumerate(ctxs):
+        ref = _oracle_layer_row(shape, wn, ks[b], vs[b], x[b], c)
+        err = rel_inf(out[b] - x[b].numpy(), ref - x[b].numpy())
+        assert err < 3e-2, (b, c, err)
     ro.close()
 
 
