@@ -437,6 +437,8 @@ def test_rollout_consumes_weights_and_sizes_pool_itself(amd):
     prompts = ri.tokens((3, 20), shape["vocab"], 41, 930).tolist()
     ra = amd.Rollout(shape, to_device(w), max_seqs=4, max_ctx=64, max_rows=64, kv_pages=16)
     wd = to_device(w)
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()                    # what earlier tests left in the allocator's cache goes back first
     free_before, total = torch.cuda.mem_get_info()
     rb = amd.Rollout(shape, wd, max_seqs=4, max_ctx=64, max_rows=64, kv_pages=None, consume_weights=True,
                      kv_slack_bytes=free_before - (256 << 20))      # leaves about 256 MiB for workspace and pool
