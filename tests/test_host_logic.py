@@ -260,3 +260,15 @@ def test_group_page_need_matches_the_allocator(st):
             st.st_release(t, j)
         assert st.st_free_pages(t) == 1000
         st.st_destroy(t)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The measurement script covers one GPU; any other count ends with a message and a non-zero status before
+    anything touches a device."""
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    for extra_env, argv in (({}, ["--gpus", "2"]), ({"WORLD_SIZE": "2"}, [])):
+        env = dict(os.environ, **extra_env)
+        r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), *argv], capture_output=True, text=True,
+                           env=env, timeout=120)
+        assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
