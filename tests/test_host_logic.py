@@ -272,3 +272,19 @@ def test_bench_refuses_more_than_one_gpu():
         r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), *argv], capture_output=True, text=True,
                            env=env, timeout=120)
         assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_binding_fails_loudly_without_the_library():
+    """No fallback: when the shared library is not there, the first call through the binding raises and names the
+    build command."""
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = ("import paper_2510_17891_amd.binding as b\n"
+            "b.LIB_PATH = '/nonexistent/librl_rollout.so'\n"
+            "b._lib = None\n"
+            "try:\n"
+            "    b.lib()\n"
+            "except RuntimeError as e:\n"
+            "    print('raised:', e)\n")
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, cwd=root, timeout=120)
+    assert r.returncode == 0 and "raised:" in r.stdout and "paper_2510_17891_amd.build" in r.stdout
