@@ -29,6 +29,10 @@
 // segments; both kinds leave their partials in the workspace and the merge kernel combines them with the
 // arithmetic of the in-block merge.  A column of the matrix product does not depend on its neighbours and the
 // segment bounds are the same, so a row's bits equal those of the row computed alone.
+// Rows that feed neighbouring positions of one sequence (prefill, scoring) form sets in the same way when they lie
+// in one aligned window of 32 positions: equal step counts and segments, each row's keys a prefix of the next row's.
+// Such a set computes all segments of its rows, every column masked at its own context length, and the window's
+// keys are read once per set instead of once per row.
 //
 // Decode steps (one row per sequence) run the variant that also does what would otherwise be a kernel of its own
 // before this one: it sums the QKV projection's split partials, normalises and rotates the heads of its columns, and
@@ -173,6 +177,9 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
   const int col_head = hk * group + j % group;
   const RowMeta rm = rows[r];
   const int ctx = rm.pos + 1;  // keys 0..pos; the row's own key is in its page already, or (APPEND) formed here
+  // A set's members may stand at different positions of one 32-key window (rows of one sequence): same steps and
+  // segments, and each column is masked at its own length.  r is the member with the longest context.
+  const int ctx_col = is_set ? rows[col_row].pos + 1 : ctx;
   const int n_seg = attn_num_segments(ctx);
   const bool in_lds = !is_set && skip == 0 && n_seg <= kLdsSegs;  // merged by this block
   // this block's segments [lo, hi)
@@ -343,13 +350,13 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
     float mx = -INFINITY;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      sc[e] = (kbase + e < ctx) ? sa[e] * scale : -INFINITY;
-      sc[4 + e] = (kbase + 16 + e < ctx) ? sb[e] * scale : -INFINITY;
+      sc[e] = (kbase + e < ctx_col) ? sa[e] * scale : -INFINITY;
+      sc[4 + e] = (kbase + 16 + e < ctx_col) ? sb[e] * scale : -INFINITY;
       mx = fmaxf(mx, fmaxf(sc[e], sc[4 + e]));
     }
     mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
     mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-    const float m_new = fmaxf(m_run, mx);  // finite: key it*32 < ctx always holds for lane group 0
+    const float m_new = fmaxf(m_run, mx);  // finite: key it*32 is inside every column's context
     const float alpha = __expf(m_run - m_new);
     m_run = m_new;
     uint32_t pw[4];

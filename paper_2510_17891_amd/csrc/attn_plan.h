@@ -84,4 +84,32 @@ inline void plan_shared_attention(int n, const int64_t* prefix_id, const int32_t
   }
 }
 
+// Rows that feed consecutive positions of one sequence (prefill, scoring).  Positions inside one aligned window of
+// 32 have the same number of 32-key steps and hence the same segments, and every row's keys are a prefix of the
+// keys of the row after it: up to rows_per_set (<= 4) neighbouring rows of a window form a set that computes ALL their
+// segments side by side (n_segs = every segment, each column masked at its own context length), so the window's
+// keys are read once per set instead of once per row.  rows[0] of a set is its highest position (the block takes
+// its page list and step count from it).  seq[i], pos[i]: sequence and position of row i; rows of a sequence must
+// be adjacent and ascending, as the chunks of a prefill are.
+inline void plan_window_sets(int n, const int32_t* seq, const int32_t* pos, int rows_per_set, AttnPlan* plan) {
+  plan->skip.assign(n, 0);
+  plan->sets.clear();
+  plan->max_shared_segs = 0;
+  int i = 0;
+  while (i < n) {
+    int e = i + 1;
+    while (e < n && e - i < rows_per_set && seq[e] == seq[i] && pos[e] == pos[e - 1] + 1 && (pos[e] >> 5) == (pos[i] >> 5)) ++e;
+    if (e - i >= 2) {
+      AttnShared s;
+      s.n_rows = e - i;
+      s.n_segs = attn_num_segments(pos[e - 1] + 1);  // the same for every member
+      for (int k = 0; k < 4; ++k) s.rows[k] = e - 1 - (k < s.n_rows ? k : 0);
+      for (int k = i; k < e; ++k) plan->skip[k] = s.n_segs;
+      plan->sets.push_back(s);
+      plan->max_shared_segs = std::max(plan->max_shared_segs, s.n_segs);
+    }
+    i = e;
+  }
+}
+
 }  // namespace rl

@@ -325,6 +325,33 @@ rl_status admit_decode(rl_model* m, int32_t n, const int32_t* seq_ids, std::vect
   return RL_OK;
 }
 
+// Copy a plan of shared attention into the metadata slot (host side hs, device side ds) and describe it in *sa.
+rl_status upload_attn_plan(rl_model* m, hipStream_t st, char* hs, char* ds, int n, const AttnPlan& plan, SharedAttn* sa) {
+  *sa = SharedAttn();
+  if (plan.sets.empty()) return RL_OK;
+  memcpy(hs + m->lay.slot_skip, plan.skip.data(), (size_t)n * 4);
+  memcpy(hs + m->lay.slot_sets, plan.sets.data(), plan.sets.size() * sizeof(AttnShared));
+  HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_skip, hs + m->lay.slot_skip, (size_t)n * 4, hipMemcpyHostToDevice, st));
+  HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_sets, hs + m->lay.slot_sets, plan.sets.size() * sizeof(AttnShared), hipMemcpyHostToDevice, st));
+  sa->skip = (const int32_t*)(ds + m->lay.slot_skip);
+  sa->sets = (const AttnShared*)(ds + m->lay.slot_sets);
+  sa->n_sets = (int)plan.sets.size();
+  sa->max_segs = plan.max_shared_segs;
+  return RL_OK;
+}
+
+// Sets of neighbouring rows of one sequence for a chunk of prefill or scoring rows (bf16 only).
+rl_status upload_window_plan(rl_model* m, hipStream_t st, char* hs, char* ds, int n, const RowMeta* hr, SharedAttn* sa) {
+  *sa = SharedAttn();
+  if (m->geo.dtype != kBF16 || !m->share_attention) return RL_OK;
+  std::vector<int32_t> seq(n), pos(n);
+  for (int i = 0; i < n; ++i) { seq[i] = hr[i].seq; pos[i] = hr[i].pos; }
+  AttnPlan plan;
+  const int group = m->geo.n_q / m->geo.n_kv;
+  plan_window_sets(n, seq.data(), pos.data(), std::min(4, 16 / group), &plan);
+  return upload_attn_plan(m, st, hs, ds, n, plan, sa);
+}
+
 // Build and upload the rows (and page grants) of one decode call; returns device pointers into the slot.
 rl_status upload_decode_meta(rl_model* m, hipStream_t st, int32_t n, const int32_t* seq_ids,
                              const std::vector<PageGrant>& grants, const RowMeta** rows_dev, int* max_ctx_out,
@@ -365,16 +392,8 @@ rl_status upload_decode_meta(rl_model* m, hipStream_t st, int32_t n, const int32
   }
   Timer t(m, st, K_META);
   HIP_TRY(hipMemcpyAsync(ds, hs, (size_t)n * sizeof(RowMeta), hipMemcpyHostToDevice, st));
-  if (!plan.sets.empty()) {
-    memcpy(hs + m->lay.slot_skip, plan.skip.data(), (size_t)n * 4);
-    memcpy(hs + m->lay.slot_sets, plan.sets.data(), plan.sets.size() * sizeof(AttnShared));
-    HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_skip, hs + m->lay.slot_skip, (size_t)n * 4, hipMemcpyHostToDevice, st));
-    HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_sets, hs + m->lay.slot_sets, plan.sets.size() * sizeof(AttnShared), hipMemcpyHostToDevice, st));
-    sa->skip = (const int32_t*)(ds + m->lay.slot_skip);
-    sa->sets = (const AttnShared*)(ds + m->lay.slot_sets);
-    sa->n_sets = (int)plan.sets.size();
-    sa->max_segs = plan.max_shared_segs;
-  }
+  { rl_status rs = upload_attn_plan(m, st, hs, ds, n, plan, sa);
+    if (rs != RL_OK) return rs; }
   if (!grants.empty()) {
     HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_upd, hu, grants.size() * 12, hipMemcpyHostToDevice, st));
     launch_table_update(st, m->wsp<int32_t>(m->lay.block_table), m->geo.max_blocks, (const int32_t*)(ds + m->lay.slot_upd), (int)grants.size());
@@ -693,15 +712,18 @@ static rl_status prefill_impl(rl_model* m, hipStream_t st, int32_t n_prompts, in
       if (pos + 1 == prompt_lens[pi]) { lasts.push_back({r, pi}); ++pi; pos = 0; }
       else ++pos;
     }
+    SharedAttn sa;
     { Timer t(m, st, K_META);
       HIP_TRY(hipMemcpyAsync(ds, hs, (size_t)M * sizeof(RowMeta), hipMemcpyHostToDevice, st));
       HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_tok, ht, (size_t)M * 4, hipMemcpyHostToDevice, st));
+      rs = upload_window_plan(m, st, hs, ds, M, hr, &sa);
+      if (rs != RL_OK) return rs;
       HIP_TRY(hipEventRecord(m->ring_ev[slot], st));
       m->ring_used[slot] = true; }
     const RowMeta* rows = (const RowMeta*)ds;
     { Timer t(m, st, K_EMBED);
       launch_embed(st, m->geo.dtype, m->embed, (const int32_t*)(ds + m->lay.slot_tok), x, M, H, m->geo.vocab); }
-    int pend = run_layers(m, st, M, rows, max_ctx);
+    int pend = run_layers(m, st, M, rows, max_ctx, sa);
     // fold the pending partials into x, then keep the rows that end a prompt (one copy per group member)
     float* cap = m->capture ? m->capture + (size_t)m->geo.n_layers * m->cfg.max_rows * H : nullptr;
     { Timer t(m, st, K_NORM);
@@ -846,17 +868,19 @@ rl_status rl_score(rl_model* m, void* stream, int32_t n, const int32_t* seq_ids,
       if (pos + 1 == lens[si]) { hf[r] = 0; hf[R + r] = -1; ++si; pos = 0; }
       else { hf[r] = tokens[tok_base[si] + pos + 1]; hf[R + r] = (int32_t)(out_base[si] + pos); ++pos; }
     }
+    SharedAttn sa;
     { Timer t(m, st, K_META);
       HIP_TRY(hipMemcpyAsync(ds, hs, (size_t)M * sizeof(RowMeta), hipMemcpyHostToDevice, st));
       HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_tok, ht, (size_t)M * 4, hipMemcpyHostToDevice, st));
       HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_upd, hf, (size_t)2 * R * 4, hipMemcpyHostToDevice, st));
+      if (upload_window_plan(m, st, hs, ds, M, hr, &sa) != RL_OK) { result = RL_ERR_DEVICE; break; }
       HIP_TRY(hipEventRecord(m->ring_ev[slot], st));
       m->ring_used[slot] = true; }
     const RowMeta* rows = (const RowMeta*)ds;
     const int32_t* forced = (const int32_t*)(ds + m->lay.slot_upd);
     { Timer t(m, st, K_EMBED);
       launch_embed(st, m->geo.dtype, m->embed, (const int32_t*)(ds + m->lay.slot_tok), x, M, H, m->geo.vocab); }
-    int pend = run_layers(m, st, M, rows, max_ctx);
+    int pend = run_layers(m, st, M, rows, max_ctx, sa);
     run_head(m, st, M, x, pend, rows, 1, forced, &sp, tmp_tok, tmp_lp, nullptr, true);
     launch_scatter_f32(st, tmp_lp, forced + R, out_logprobs, M);
     done += M;

@@ -54,4 +54,16 @@ int st_plan_shared(void* t, int n, const int* seq_ids, const int* pos, int rows_
   return (int)plan.sets.size();
 }
 
+int st_plan_windows(int n, const int* seq, const int* pos, int rows_per_set, int* skip_out, int* sets_out, int max_sets) {
+  rl::AttnPlan plan;
+  rl::plan_window_sets(n, seq, pos, rows_per_set, &plan);
+  for (int i = 0; i < n; ++i) skip_out[i] = plan.skip[i];
+  for (size_t k = 0; k < plan.sets.size() && (int)k < max_sets; ++k) {
+    for (int e = 0; e < 4; ++e) sets_out[6 * k + e] = plan.sets[k].rows[e];
+    sets_out[6 * k + 4] = plan.sets[k].n_rows;
+    sets_out[6 * k + 5] = plan.sets[k].n_segs;
+  }
+  return (int)plan.sets.size();
+}
+
 }  // extern "C"

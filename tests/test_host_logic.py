@@ -231,6 +231,43 @@ def test_shared_attention_plan(st):
     st.st_destroy(t)
 
 
+def test_window_sets_of_prefill_rows(st):
+    """Rows of one sequence at neighbouring positions form sets only inside one aligned window of 32 positions (same
+    step count and segments), up to the given size, never across sequences or gaps; a set lists its highest position
+    first and covers every segment of its rows; single rows stay on their own."""
+    st.st_plan_windows.argtypes = [C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int), C.c_int, C.POINTER(C.c_int),
+                                   C.POINTER(C.c_int), C.c_int]
+
+    def plan(seq, pos, per_set):
+        n = len(seq)
+        skip = (C.c_int * n)()
+        sets = (C.c_int * (6 * n))()
+        k = st.st_plan_windows(n, (C.c_int * n)(*seq), (C.c_int * n)(*pos), per_set, skip, sets, n)
+        return list(skip), [tuple(sets[6 * i:6 * i + 6]) for i in range(k)]
+
+    # one sequence, positions 28..37: the window boundary at 32 cuts the sets; sets of four
+    seq, pos = [5] * 10, list(range(28, 38))
+    skip, sets = plan(seq, pos, 4)
+    members = [sorted(set(s[:4])) for s in sets]
+    assert members == [[0, 1, 2, 3], [4, 5, 6, 7], [8, 9]]
+    assert all(s[0] == max(s[:4]) for s in sets)                       # the longest context leads
+    assert [s[4] for s in sets] == [4, 4, 2]
+    for s in sets:
+        ctx = pos[s[0]] + 1
+        assert s[5] == st.st_attn_num_segments(ctx) and all(skip[r] == s[5] for r in set(s[:4]))
+        assert len({(pos[r] >> 5) for r in set(s[:4])}) == 1
+    # two sequences back to back, a position gap, a single left-over row, sets of two
+    seq = [1, 1, 1, 2, 2, 2, 2, 2]
+    pos = [0, 1, 2, 40, 41, 50, 51, 52]
+    skip, sets = plan(seq, pos, 2)
+    assert [sorted(set(s[:4])) for s in sets] == [[0, 1], [3, 4], [5, 6]]
+    assert skip[2] == 0 and skip[7] == 0
+    # a context just past 1024 keys has more segments than the one before it, but they are in different windows
+    seq, pos = [0] * 4, [1022, 1023, 1024, 1025]
+    skip, sets = plan(seq, pos, 4)
+    assert [sorted(set(s[:4])) for s in sets] == [[0, 1], [2, 3]] and [s[5] for s in sets] == [4, 8]
+
+
 def test_group_page_need_matches_the_allocator(st):
     """The rollout loop admits a group when the pool can hold it up to its length limits; its estimate must equal what
     the allocator really hands out when the group is prefilled (shared full pages, one partial-page copy per member)
