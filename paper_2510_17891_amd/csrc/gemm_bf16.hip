@@ -689,6 +689,136 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_lds4_kernel(const u32x4_t* _
   }
 }
 
+// The same tile with eight waves for 129..256 rows: one block holds a 128-row weight tile and all (up to) 256 batch
+// rows, 32 per wave, so the weight tile is staged once for both halves of the batch and a compute unit never holds
+// two blocks' worth of panel traffic while its neighbour holds one.  Each half of the block stages two of the four
+// row blocks.  Same K quarters, same order: same bits.
+template <int EPI, int XS>
+__global__ __launch_bounds__(512, 1) void gemm_bf16_lds8_kernel(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ W,
+                                                              void* __restrict__ out, int M, int N, int K,
+                                                              int kb_per_quarter, SampleEpilogue se) {
+  constexpr int MBW = 1;
+  __shared__ u32x4_t wlds[4][4][256];  // four stages x four row blocks x 4 KiB
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int KB = K >> 6;
+  const int n_blocks_m = (M + 31) >> 5;
+  const int half = tid >> 8, t256 = tid & 255;  // which pair of row blocks this thread stages, and where in them
+  const int tile_x = blockIdx.x;
+  const int m_blk0 = blockIdx.z * 8 + wave;
+  const bool has_rows = m_blk0 < n_blocks_m;
+
+  // row blocks: pair p = 64-row tile 2x + p (the second pair shadows the first when the tile count is odd)
+  const int n_tiles = EPI == kEpiSwiGLU ? (N >> 5) : (N >> 6);
+  int tile[2], rb[4];
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    tile[p] = min(tile_x * 2 + p, n_tiles - 1);
+    if (EPI == kEpiSwiGLU) { rb[2 * p] = tile[p]; rb[2 * p + 1] = tile[p] + (N >> 5); }
+    else                   { rb[2 * p] = tile[p] * 2; rb[2 * p + 1] = tile[p] * 2 + 1; }
+  }
+  const bool second_valid = tile_x * 2 + 1 < n_tiles;
+  const u32x4_t* wp[2];
+#pragma unroll
+  for (int b = 0; b < 2; ++b) wp[b] = W + (size_t)rb[2 * half + b] * KB * 256 + t256;
+  const u32x4_t* xb[MBW];
+#pragma unroll
+  for (int mb = 0; mb < MBW; ++mb) {
+    int blk = m_blk0 + mb;
+    if (blk >= n_blocks_m) blk = n_blocks_m - 1;  // idle waves and surplus blocks shadow a valid one (never stored)
+    xb[mb] = X + (size_t)blk * KB * 256 + lane;
+  }
+  const int n = 4 * kb_per_quarter;
+  const int kb0 = blockIdx.y * n;
+  auto kb_of = [&](int i) { return kb0 + (i < n ? i : n - 1); };  // clamped: no conditional loads in the pipeline
+
+  u32x4_t wr[4][2];          // weight registers: slot s holds a k block with index = s (mod 4)
+  u32x4_t xr[XS][MBW][4];    // activation fragments: slot s holds a k block with index = s (mod XS)
+#pragma unroll
+  for (int s = 0; s < 4; ++s)
+#pragma unroll
+    for (int b = 0; b < 2; ++b) wr[s][b] = __builtin_nontemporal_load(wp[b] + (size_t)kb_of(s) * 256);
+#pragma unroll
+  for (int s = 0; s < XS; ++s)
+#pragma unroll
+    for (int mb = 0; mb < MBW; ++mb)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) xr[s][mb][t] = xb[mb][(size_t)kb_of(s) * 256 + t * 64];
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    wlds[0][2 * half + b][t256] = wr[0][b];
+    wr[0][b] = __builtin_nontemporal_load(wp[b] + (size_t)kb_of(4) * 256);
+  }
+
+  auto iter = [&](f32x16_t (&a)[4][MBW], int i, auto jc) __attribute__((always_inline)) {
+    constexpr int j = decltype(jc)::value, jn = (j + 1) & 3, jx = j % XS;
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      wlds[jn][2 * half + b][t256] = wr[jn][b];
+      wr[jn][b] = __builtin_nontemporal_load(wp[b] + (size_t)kb_of(i + 5) * 256);
+    }
+    // barrier that orders LDS traffic only (a full one would drain the global loads in flight)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const bf16x8_t afrag = __builtin_bit_cast(bf16x8_t, wlds[j][b][t * 64 + lane]);
+#pragma unroll
+        for (int mb = 0; mb < MBW; ++mb)
+          a[b][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, __builtin_bit_cast(bf16x8_t, xr[jx][mb][t]), a[b][mb], 0,
+                                                             0, 0);
+      }
+    }
+#pragma unroll
+    for (int mb = 0; mb < MBW; ++mb)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) xr[jx][mb][t] = xb[mb][(size_t)kb_of(i + XS) * 256 + t * 64];
+  };
+  auto quarter = [&](f32x16_t (&a)[4][MBW], int q) __attribute__((always_inline)) {
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int mb = 0; mb < MBW; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) a[b][mb][r] = 0.f;
+    for (int i = q * kb_per_quarter; i < (q + 1) * kb_per_quarter; i += 4) {
+      iter(a, i, std::integral_constant<int, 0>{});
+      iter(a, i + 1, std::integral_constant<int, 1>{});
+      iter(a, i + 2, std::integral_constant<int, 2>{});
+      iter(a, i + 3, std::integral_constant<int, 3>{});
+    }
+  };
+  f32x16_t acc[4][MBW], other[4][MBW];
+  quarter(acc, 0);
+  for (int q = 1; q < 4; ++q) {
+    quarter(other, q);
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int mb = 0; mb < MBW; ++mb) acc[b][mb] += other[b][mb];
+  }
+
+  if (!has_rows) return;
+  const int col = lane & 31, hb = lane >> 5;
+#pragma unroll
+  for (int mb = 0; mb < MBW; ++mb) {
+    const int m = (m_blk0 + mb) * 32 + col;
+    if (m >= M) continue;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      if (p == 1 && !second_valid) break;
+      float sum[2][16];
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum[nb][r] = acc[2 * p + nb][mb][r];
+      store_block<EPI>(sum, m, hb, rb[2 * p], rb[2 * p + 1], blockIdx.y, M, N, out, se, tile[p]);
+    }
+  }
+}
+
 struct Plan {
   int splits;       // K splits across blocks
   int kb_per_wave;  // 64-wide k blocks per wave
@@ -811,6 +941,19 @@ void launch_lds4(hipStream_t s, const void* X, const void* W, void* out, int M, 
     gemm_bf16_lds4_kernel<MBW, kEpiPartial, XS><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, tiles_x, se);
 }
 
+void launch_lds8(hipStream_t s, const void* X, const void* W, void* out, int M, int N, int K, int epi, bool allow_split,
+                 const SampleEpilogue& se) {
+  Plan p = make_plan(N, K, epi, allow_split);  // same K split as the other variants: bit-identical results
+  const int tiles = epi == kEpiSwiGLU ? (N >> 5) : (N >> 6);
+  dim3 grid((tiles + 1) / 2, epi == kEpiPartial ? p.splits : 1, (M + 255) / 256);
+  if (epi == kEpiSwiGLU)
+    gemm_bf16_lds8_kernel<kEpiSwiGLU, 2><<<grid, 512, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
+  else if (epi == kEpiSample)
+    gemm_bf16_lds8_kernel<kEpiSample, 2><<<grid, 512, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
+  else
+    gemm_bf16_lds8_kernel<kEpiPartial, 2><<<grid, 512, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
+}
+
 template <int MBW>
 void launch_cols(hipStream_t s, const void* X, const void* W, void* out, int M, int N, int K, int epi, bool allow_split,
                  const SampleEpilogue& se) {
@@ -819,8 +962,10 @@ void launch_cols(hipStream_t s, const void* X, const void* W, void* out, int M, 
     const Plan p = make_plan(N, K, epi, allow_split);
     const int tiles = epi == kEpiSwiGLU ? (N >> 5) : (N >> 6);
     const int wide_blocks = ((tiles + 1) / 2) * (epi == kEpiPartial ? p.splits : 1);
-    // 129..256 rows run as two batch tiles of 128 whose blocks are paired on one die (a 128 x 256 tile per block
-    // would need 2 x 128 accumulator registers and measured slower).
+    // 129..256 rows: one block of eight waves per weight tile where that still gives >= 192 blocks (gate/up 82 -> 65 us,
+    // QKV 33 -> 29, output projection 538 -> 420 at 256 rows); the O and down projections would be left with 128 blocks
+    // (measured 21 -> 26 and 42 -> 50 us) and run as two batch tiles of 128 whose blocks are paired on one die.
+    if (M > 128 && wide_blocks >= 192) { launch_lds8(s, X, W, out, M, N, K, epi, allow_split, se); return; }
     if (wide_blocks * ((M + 127) / 128) >= 192) { launch_lds4<1, 2>(s, X, W, out, M, N, K, epi, allow_split, se); return; }
     launch_lds<MBW, MBW == 1 ? 4 : 2>(s, X, W, out, M, N, K, epi, allow_split, se);
     return;
