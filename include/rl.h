@@ -238,6 +238,17 @@ rl_status rl_seq_import_kv(rl_model* m, void* stream, int32_t seq_id, int32_t n_
                            const void* const* k_layers, const void* const* v_layers);
 
 /*
+ * Append n_tokens (>= 1) positions of given KV to an active sequence, behind the tokens it already caches (its own
+ * tokens, a prompt it shares with the other samples of its group, or imported ones); arrays as for
+ * rl_seq_import_kv.  Measurement and test aid: it places sequences at a stated context length (e.g. the shared
+ * 2048-token prompt of Appendix D plus several thousand private response tokens) without running that many decode
+ * steps.  The sequence may hold at most max_ctx - 1 tokens afterwards.
+ * Errors: INVALID_ARG, BAD_SEQ, KV_FULL, CTX_OVERFLOW (state untouched), DEVICE.
+ */
+rl_status rl_seq_append_kv(rl_model* m, void* stream, int32_t seq_id, int32_t n_tokens,
+                           const void* const* k_layers, const void* const* v_layers);
+
+/*
  * Decoder layers alone: like rl_decode_step but the residual stream entering layer 0 is given
  * (hidden_in, device [n_seqs x hidden] fp32) instead of looked up from a token, and the residual
  * stream leaving the last layer is returned (hidden_out, same shape) instead of being normalised,
@@ -264,8 +275,9 @@ rl_status rl_set_capture(rl_model* m, float* buf);
  *   mode 1  uniform-reward GRPO (Appendix C): r = beta r_correct + (1-beta) r_speedup, A = r - mean_j r,
  *           L_i = 1/G sum_j 1/|o_ij| sum_t A min(s_t, clip(s_t, 1-eps, 1+eps)).
  *   offsets    [n_prompts*G + 1] int32: output k (= i*G + j) owns tokens offsets[k] .. offsets[k+1]-1 of lp_new/lp_old
- *   n_plan     [n_prompts*G] int32 plan-token counts, or NULL: then tokens (response token ids, same indexing as
- *              lp_*) are scanned for delimiter_token (an output without it is all plan)
+ *   n_plan     [n_prompts*G] int32 plan-token counts (a count below 0 or above the output's length is clamped to that
+ *              range), or NULL: then tokens (response token ids, same indexing as lp_*) are scanned for
+ *              delimiter_token (an output without it is all plan)
  *   r_speedup, r_correct  [n_prompts*G] fp32 rewards
  *   seq_terms  [n_prompts*G] fp32 out: the 1/|o| sum of each output (before the 1/G and 1/n_prompts factors)
  *   n_plan_out [n_prompts*G] int32 out or NULL: the plan lengths used

@@ -20,7 +20,7 @@ RL_F32, RL_BF16 = 0, 1
 EXPORTS = [
     "rl_kv_page_bytes", "rl_query_workspace", "rl_init_model", "rl_destroy_model", "rl_prefill", "rl_prefill_groups", "rl_score", "rl_hrd_objective",
     "rl_decode_step", "rl_free_seqs", "rl_last_error", "rl_kv_stats", "rl_seq_len", "rl_sample_logits",
-    "rl_seq_import_kv", "rl_decode_hidden", "rl_set_capture", "rl_pack_weight",
+    "rl_seq_import_kv", "rl_seq_append_kv", "rl_decode_hidden", "rl_set_capture", "rl_pack_weight",
     "rl_debug_shuffle_free_pages", "rl_debug_share_attention", "rl_debug_attention_appends", "rl_seq_fork", "rl_profile_enable", "rl_profile_read",
 ]
 
@@ -92,6 +92,7 @@ def lib():
         L.rl_sample_logits.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, _i32p, _i32p,
                                        C.c_void_p, C.POINTER(rl_sampling), C.c_void_p, C.c_void_p]
         L.rl_seq_import_kv.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, _pp, _pp]
+        L.rl_seq_append_kv.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, _pp, _pp]
         L.rl_decode_hidden.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, _i32p, C.c_void_p, C.c_void_p]
         L.rl_set_capture.argtypes = [C.c_void_p, C.c_void_p]
         L.rl_pack_weight.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64]
@@ -159,8 +160,7 @@ def rl_hrd_objective(n_prompts, group_size, offsets, lp_new, lp_old, r_speedup, 
     st = lib().rl_hrd_objective(_stream(), n_prompts, group_size, _ptr(offsets), _ptr(n_plan), _ptr(tokens),
                                 delimiter_token, _ptr(lp_new), _ptr(lp_old), _ptr(r_speedup), _ptr(r_correct),
                                 C.byref(p), _ptr(seq), _ptr(npl), _ptr(out))
-    if st != RL_OK:
-        raise RLError(st, "rl_hrd_objective: bad arguments or launch failure")
+    check(st)
     return out, seq, npl
 
 
@@ -327,6 +327,14 @@ class Rollout:
         ka = (C.c_void_p * n_layers)(*[t.data_ptr() for t in k_layers])
         va = (C.c_void_p * n_layers)(*[t.data_ptr() for t in v_layers])
         check(lib().rl_seq_import_kv(self.h, _stream(), seq_id, n_tokens, C.cast(ka, _pp), C.cast(va, _pp)))
+
+    def rl_seq_append_kv(self, seq_id, k_layers, v_layers):
+        """Append [n_tokens, n_kv, head_dim] K/V per layer behind what the active sequence already caches."""
+        n_tokens = k_layers[0].shape[0]
+        n_layers = self.shape["n_layers"]
+        ka = (C.c_void_p * n_layers)(*[t.data_ptr() for t in k_layers])
+        va = (C.c_void_p * n_layers)(*[t.data_ptr() for t in v_layers])
+        check(lib().rl_seq_append_kv(self.h, _stream(), seq_id, n_tokens, C.cast(ka, _pp), C.cast(va, _pp)))
 
     def rl_decode_hidden(self, seq_ids, hidden_in, hidden_out=None):
         out = hidden_out if hidden_out is not None else torch.empty_like(hidden_in)

@@ -86,7 +86,8 @@ __host__ __device__ inline int attn_num_splits(int n_seg) { return n_seg <= kLds
 
 // Flat merge of the (at most kLdsSegs) segments of one head: running maximum, weights exp(m_c - M), sums in index
 // order; the lane owns dims 2*lane, 2*lane+1.  seg_ptr(c) -> [O(128), max, sum] of segment c (LDS or workspace);
-// all loads are issued before the arithmetic.  Returns the two normalised outputs packed as bf16.
+// all loads are issued before the arithmetic.  Returns the two normalised outputs packed as f16 (the operand type
+// of the output projection).
 template <typename F>
 __device__ __forceinline__ uint32_t merge_short(F seg_ptr, int n_seg, int n_it, int lane) {
   float mx[kLdsSegs], lx[kLdsSegs];
@@ -117,7 +118,7 @@ __device__ __forceinline__ uint32_t merge_short(F seg_ptr, int n_seg, int n_it, 
     }
   }
   const float inv = 1.0f / den;
-  return pack2bf(o0 * inv, o1 * inv);
+  return pack2h(o0 * inv, o1 * inv);
 }
 
 // The QKV projection's split sums and what turns them into queries, keys and values (kernel-side AttnAppend).
@@ -546,7 +547,7 @@ __global__ __launch_bounds__(64) void attn_merge_bf16_kernel(const float* __rest
     }
   }
   const float inv = 1.0f / den;
-  *(uint32_t*)(o_out + frag_offset(r, head * kD + 2 * lane, (n_q * kD) >> 6)) = pack2bf(o0 * inv, o1 * inv);
+  *(uint32_t*)(o_out + frag_offset(r, head * kD + 2 * lane, (n_q * kD) >> 6)) = pack2h(o0 * inv, o1 * inv);
 }
 
 }  // namespace

@@ -18,6 +18,14 @@ namespace {
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
+// A weight fragment as loaded (eight bf16) -> the f16 operand of the matrix core (exact, see bf2_to_h2).
+__device__ __forceinline__ u32x4_t w_to_f16(u32x4_t w) {
+  return (u32x4_t){bf2_to_h2(w[0]), bf2_to_h2(w[1]), bf2_to_h2(w[2]), bf2_to_h2(w[3])};
+}
+__device__ __forceinline__ f32x16_t mfma_f16(u32x4_t a, u32x4_t b, f32x16_t c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+}
+
 template <int MB>
 struct Frags {
   u32x4_t a[2][4];
@@ -50,12 +58,11 @@ __device__ __forceinline__ void mma_frags(const Frags<MB>& f, f32x16_t (&acc)[2]
 #pragma unroll
   for (int t = 0; t < 4; ++t)
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
+    for (int nb = 0; nb < 2; ++nb) {
+      const u32x4_t a = w_to_f16(f.a[nb][t]);
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
-        acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, f.a[nb][t]),
-                                                              __builtin_bit_cast(bf16x8_t, f.b[mb][t]), acc[nb][mb], 0,
-                                                              0, 0);
+      for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = mfma_f16(a, f.b[mb][t], acc[nb][mb]);
+    }
 }
 
 // Write one finished 64 x 32 output block held in MFMA accumulator order: lane (col, hb) has, for both row blocks,
@@ -83,7 +90,7 @@ __device__ __forceinline__ void store_block(const float (&sum)[2][16], int m, in
         a[e] = gte / (1.0f + __expf(-gte)) * up;
       }
       const int n = rb0 * 32 + 8 * q + 4 * hb;
-      *(uint2*)(o + frag_offset(m, n, N >> 6)) = make_uint2(pack2bf(a[0], a[1]), pack2bf(a[2], a[3]));
+      *(uint2*)(o + frag_offset(m, n, N >> 6)) = make_uint2(pack2h(a[0], a[1]), pack2h(a[2], a[3]));
     }
   } else {
     // lane (col, hb) holds 32 logits of row m: vocabulary ids (rb*32 + 8q + 4hb + e), in aligned groups of four,
@@ -282,11 +289,11 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_wide_kernel(const u32x4_t* _
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
-      for (int b = 0; b < 4; ++b)
+      for (int b = 0; b < 4; ++b) {
+        const u32x4_t a = w_to_f16(f.a[b][t]);
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-          acc[b][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, f.a[b][t]),
-                                                               __builtin_bit_cast(bf16x8_t, f.b[mb][t]), acc[b][mb], 0, 0, 0);
+        for (int mb = 0; mb < MB; ++mb) acc[b][mb] = mfma_f16(a, f.b[mb][t], acc[b][mb]);
+      }
   };
 
   const int kb0 = (blockIdx.y * 4 + wave) * kb_per_wave;
@@ -481,16 +488,16 @@ __global__ __launch_bounds__(256, MBW == 1 ? 2 : 1) void gemm_bf16_lds_kernel(co
     for (int mb = 0; mb < MBW; ++mb)
 #pragma unroll
       for (int t = 0; t < 4; ++t) xr[s][mb][t] = xb[mb][(size_t)kb_of(s) * 256 + t * 64];
-  wlds[0][0][tid] = wr[0][0];
-  wlds[0][1][tid] = wr[0][1];
+  wlds[0][0][tid] = w_to_f16(wr[0][0]);
+  wlds[0][1][tid] = w_to_f16(wr[0][1]);
   wr[0][0] = __builtin_nontemporal_load(w0 + (size_t)kb_of(4) * 256);
   wr[0][1] = __builtin_nontemporal_load(w1 + (size_t)kb_of(4) * 256);
 
   // One k block: publish the next tile, barrier, multiply this one.  j = i mod 4 at compile time.
   auto iter = [&](f32x16_t (&a)[2][MBW], int i, auto jc) __attribute__((always_inline)) {
     constexpr int j = decltype(jc)::value, jn = (j + 1) & 3, jx = j % XS;
-    wlds[jn][0][tid] = wr[jn][0];
-    wlds[jn][1][tid] = wr[jn][1];
+    wlds[jn][0][tid] = w_to_f16(wr[jn][0]);
+    wlds[jn][1][tid] = w_to_f16(wr[jn][1]);
     wr[jn][0] = __builtin_nontemporal_load(w0 + (size_t)kb_of(i + 5) * 256);
     wr[jn][1] = __builtin_nontemporal_load(w1 + (size_t)kb_of(i + 5) * 256);
     // Barrier that orders LDS traffic only: __syncthreads() would also drain every global load in flight
@@ -500,13 +507,12 @@ __global__ __launch_bounds__(256, MBW == 1 ? 2 : 1) void gemm_bf16_lds_kernel(co
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      const bf16x8_t a0 = __builtin_bit_cast(bf16x8_t, wlds[j][0][t * 64 + lane]);
-      const bf16x8_t a1 = __builtin_bit_cast(bf16x8_t, wlds[j][1][t * 64 + lane]);
+      const u32x4_t a0 = wlds[j][0][t * 64 + lane];
+      const u32x4_t a1 = wlds[j][1][t * 64 + lane];
 #pragma unroll
       for (int mb = 0; mb < MBW; ++mb) {
-        const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, xr[jx][mb][t]);
-        a[0][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bfrag, a[0][mb], 0, 0, 0);
-        a[1][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bfrag, a[1][mb], 0, 0, 0);
+        a[0][mb] = mfma_f16(a0, xr[jx][mb][t], a[0][mb]);
+        a[1][mb] = mfma_f16(a1, xr[jx][mb][t], a[1][mb]);
       }
     }
 #pragma unroll
@@ -615,7 +621,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_lds4_kernel(const u32x4_t* _
       for (int t = 0; t < 4; ++t) xr[s][mb][t] = xb[mb][(size_t)kb_of(s) * 256 + t * 64];
 #pragma unroll
   for (int b = 0; b < 4; ++b) {
-    wlds[0][b][tid] = wr[0][b];
+    wlds[0][b][tid] = w_to_f16(wr[0][b]);
     wr[0][b] = __builtin_nontemporal_load(wp[b] + (size_t)kb_of(4) * 256);
   }
 
@@ -623,7 +629,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_lds4_kernel(const u32x4_t* _
     constexpr int j = decltype(jc)::value, jn = (j + 1) & 3, jx = j % XS;
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
-      wlds[jn][b][tid] = wr[jn][b];
+      wlds[jn][b][tid] = w_to_f16(wr[jn][b]);
       wr[jn][b] = __builtin_nontemporal_load(wp[b] + (size_t)kb_of(i + 5) * 256);
     }
     // barrier that orders LDS traffic only (a full one would drain the global loads in flight)
@@ -634,11 +640,9 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_lds4_kernel(const u32x4_t* _
     for (int t = 0; t < 4; ++t) {
 #pragma unroll
       for (int b = 0; b < 4; ++b) {
-        const bf16x8_t afrag = __builtin_bit_cast(bf16x8_t, wlds[j][b][t * 64 + lane]);
+        const u32x4_t afrag = wlds[j][b][t * 64 + lane];
 #pragma unroll
-        for (int mb = 0; mb < MBW; ++mb)
-          a[b][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, __builtin_bit_cast(bf16x8_t, xr[jx][mb][t]), a[b][mb], 0,
-                                                             0, 0);
+        for (int mb = 0; mb < MBW; ++mb) a[b][mb] = mfma_f16(afrag, xr[jx][mb][t], a[b][mb]);
       }
     }
 #pragma unroll
@@ -745,7 +749,7 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_lds8_kernel(const u32x4_t* _
       for (int t = 0; t < 4; ++t) xr[s][mb][t] = xb[mb][(size_t)kb_of(s) * 256 + t * 64];
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
-    wlds[0][2 * half + b][t256] = wr[0][b];
+    wlds[0][2 * half + b][t256] = w_to_f16(wr[0][b]);
     wr[0][b] = __builtin_nontemporal_load(wp[b] + (size_t)kb_of(4) * 256);
   }
 
@@ -753,7 +757,7 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_lds8_kernel(const u32x4_t* _
     constexpr int j = decltype(jc)::value, jn = (j + 1) & 3, jx = j % XS;
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
-      wlds[jn][2 * half + b][t256] = wr[jn][b];
+      wlds[jn][2 * half + b][t256] = w_to_f16(wr[jn][b]);
       wr[jn][b] = __builtin_nontemporal_load(wp[b] + (size_t)kb_of(i + 5) * 256);
     }
     // barrier that orders LDS traffic only (a full one would drain the global loads in flight)
@@ -764,11 +768,9 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_lds8_kernel(const u32x4_t* _
     for (int t = 0; t < 4; ++t) {
 #pragma unroll
       for (int b = 0; b < 4; ++b) {
-        const bf16x8_t afrag = __builtin_bit_cast(bf16x8_t, wlds[j][b][t * 64 + lane]);
+        const u32x4_t afrag = wlds[j][b][t * 64 + lane];
 #pragma unroll
-        for (int mb = 0; mb < MBW; ++mb)
-          a[b][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, __builtin_bit_cast(bf16x8_t, xr[jx][mb][t]), a[b][mb], 0,
-                                                             0, 0);
+        for (int mb = 0; mb < MBW; ++mb) a[b][mb] = mfma_f16(afrag, xr[jx][mb][t], a[b][mb]);
       }
     }
 #pragma unroll

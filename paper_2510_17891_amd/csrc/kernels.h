@@ -8,6 +8,10 @@
 
 namespace rl {
 
+// Records the message that rl_last_error() returns on this thread and hands back `status` (an rl_status value), so
+// that every entry point, whichever source file it lives in, reports failures the same way.
+int set_error(int status, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
 // One batch row = one (sequence, position) pair being pushed through the decoder.
 struct RowMeta {
   int32_t seq;   // sequence id (row of the block table, RNG stream)
@@ -51,8 +55,9 @@ void launch_qk_rope_append(hipStream_t s, const Geometry& g, const float* qkv_pa
                            const void* k_gain, const float2* rope_table, const RowMeta* rows, void* k_pool_layer,
                            void* v_pool_layer, float* q_out, int M);
 
-// Scatter contiguous [n_tokens][n_kv][d] K and V (model dtype) into the pages of one sequence.
-void launch_kv_import(hipStream_t s, const Geometry& g, const void* k_src, const void* v_src, int n_tokens,
+// Scatter contiguous [n_tokens][n_kv][d] K and V (model dtype) into the pages of one sequence, as its positions
+// first_pos .. first_pos + n_tokens - 1 (the block-table row must already name their pages).
+void launch_kv_import(hipStream_t s, const Geometry& g, const void* k_src, const void* v_src, int first_pos, int n_tokens,
                       const int32_t* block_table_row, void* k_pool_layer, void* v_pool_layer);
 
 // Copy whole KV pages (all layers): pool byte layout [layer][page][page_bytes]; pairs = n x (src page, dst page)

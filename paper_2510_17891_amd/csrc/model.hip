@@ -19,11 +19,11 @@
 
 using namespace rl;
 
-namespace {
+namespace rl {
 
 thread_local std::string g_err = "";
 
-rl_status fail(rl_status st, const char* fmt, ...) {
+int set_error(int st, const char* fmt, ...) {
   char buf[512];
   va_list ap;
   va_start(ap, fmt);
@@ -32,6 +32,12 @@ rl_status fail(rl_status st, const char* fmt, ...) {
   g_err = buf;
   return st;
 }
+
+}  // namespace rl
+
+#define fail(st, ...) ((rl_status)rl::set_error((int)(st), __VA_ARGS__))
+
+namespace {
 
 #define HIP_TRY(expr)                                                                   \
   do {                                                                                  \
@@ -674,6 +680,9 @@ static rl_status prefill_impl(rl_model* m, hipStream_t st, int32_t n_prompts, in
     if (prompt_tokens[i] < 0 || prompt_tokens[i] >= m->geo.vocab) return fail(RL_ERR_INVALID_ARG, "token %d at %lld outside the vocabulary", prompt_tokens[i], (long long)i);
   if (need > T.free_pages()) return fail(RL_ERR_KV_FULL, "need %lld pages, %lld free", (long long)need, (long long)T.free_pages());
 
+  // Everything below changes sequence state; if a HIP call fails half way, the ids this call activated are released
+  // again (their pages return to the pool) before the error is reported.
+  auto run = [&]() -> rl_status {
   int32_t* bt = m->wsp<int32_t>(m->lay.block_table);
   for (int i = 0; i < n_prompts; ++i) {
     const int32_t s = seq_ids[i * group];
@@ -763,6 +772,12 @@ static rl_status prefill_impl(rl_model* m, hipStream_t st, int32_t n_prompts, in
   HIP_TRY(hipGetLastError());
   for (int i = 0; i < n_all; ++i) T.set_len(seq_ids[i], prompt_lens[i / group]);
   return RL_OK;
+  };
+  const rl_status rs = run();
+  if (rs != RL_OK)
+    for (int i = 0; i < n_all; ++i)
+      if (T.active(seq_ids[i])) T.release(seq_ids[i]);  // all were inactive on entry
+  return rs;
 }
 
 rl_status rl_prefill(rl_model* m, void* stream, int32_t n, const int32_t* seq_ids, const int32_t* prompt_tokens,
@@ -800,8 +815,12 @@ rl_status rl_seq_fork(rl_model* m, void* stream, int32_t src_seq, int32_t n, con
   std::vector<Fork> forks;
   for (int i = 0; i < n; ++i) forks.push_back({src_seq, new_seq_ids[i], len});
   rl_status rs = fork_seqs(m, (hipStream_t)stream, forks);
-  if (rs != RL_OK) return rs;
-  HIP_TRY(hipGetLastError());
+  if (rs == RL_OK && hipGetLastError() != hipSuccess) rs = fail(RL_ERR_DEVICE, "rl_seq_fork: kernel launch failed");
+  if (rs != RL_OK) {  // release what was activated (all new ids were inactive on entry)
+    for (int i = 0; i < n; ++i)
+      if (T.active(new_seq_ids[i])) T.release(new_seq_ids[i]);
+    return rs;
+  }
   for (int i = 0; i < n; ++i) T.set_len(new_seq_ids[i], len);
   return RL_OK;
 }
@@ -832,11 +851,16 @@ rl_status rl_score(rl_model* m, void* stream, int32_t n, const int32_t* seq_ids,
   if (need > T.free_pages()) return fail(RL_ERR_KV_FULL, "need %lld pages, %lld free", (long long)need, (long long)T.free_pages());
 
   int32_t* bt = m->wsp<int32_t>(m->lay.block_table);
+  rl_status result = RL_OK;
   for (int i = 0; i < n; ++i) {
     const int32_t s = seq_ids[i];
     T.activate(s);
     T.reserve(s, lens[i], nullptr);
-    HIP_TRY(hipMemcpyAsync(bt + (size_t)s * m->geo.max_blocks, T.pages(s).data(), T.pages(s).size() * 4, hipMemcpyHostToDevice, st));
+    const hipError_t e = hipMemcpyAsync(bt + (size_t)s * m->geo.max_blocks, T.pages(s).data(), T.pages(s).size() * 4, hipMemcpyHostToDevice, st);
+    if (e != hipSuccess) {  // give back what was taken so far: the ids were only scratch
+      for (int k = 0; k <= i; ++k) T.release(seq_ids[k]);
+      return fail(RL_ERR_DEVICE, "rl_score: block table upload: %s", hipGetErrorString(e));
+    }
   }
   float* x = m->wsp<float>(m->lay.x);
   int32_t* tmp_tok = m->wsp<int32_t>(m->lay.tmp_tok);
@@ -846,7 +870,6 @@ rl_status rl_score(rl_model* m, void* stream, int32_t n, const int32_t* seq_ids,
   int64_t done = 0, tok_off = 0, out_off = 0;
   std::vector<int64_t> tok_base(n), out_base(n);
   for (int i = 0; i < n; ++i) { tok_base[i] = tok_off; tok_off += lens[i]; out_base[i] = out_off; out_off += lens[i] - 1; }
-  rl_status result = RL_OK;
   while (done < total && result == RL_OK) {
     const int M = (int)std::min<int64_t>(R, total - done);
     int slot;
@@ -870,11 +893,13 @@ rl_status rl_score(rl_model* m, void* stream, int32_t n, const int32_t* seq_ids,
     }
     SharedAttn sa;
     { Timer t(m, st, K_META);
-      HIP_TRY(hipMemcpyAsync(ds, hs, (size_t)M * sizeof(RowMeta), hipMemcpyHostToDevice, st));
-      HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_tok, ht, (size_t)M * 4, hipMemcpyHostToDevice, st));
-      HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_upd, hf, (size_t)2 * R * 4, hipMemcpyHostToDevice, st));
+      hipError_t e = hipMemcpyAsync(ds, hs, (size_t)M * sizeof(RowMeta), hipMemcpyHostToDevice, st);
+      if (e == hipSuccess) e = hipMemcpyAsync(ds + m->lay.slot_tok, ht, (size_t)M * 4, hipMemcpyHostToDevice, st);
+      if (e == hipSuccess) e = hipMemcpyAsync(ds + m->lay.slot_upd, hf, (size_t)2 * R * 4, hipMemcpyHostToDevice, st);
+      if (e != hipSuccess) { result = fail(RL_ERR_DEVICE, "rl_score: metadata upload: %s", hipGetErrorString(e)); break; }
       if (upload_window_plan(m, st, hs, ds, M, hr, &sa) != RL_OK) { result = RL_ERR_DEVICE; break; }
-      HIP_TRY(hipEventRecord(m->ring_ev[slot], st));
+      e = hipEventRecord(m->ring_ev[slot], st);
+      if (e != hipSuccess) { result = fail(RL_ERR_DEVICE, "rl_score: hipEventRecord: %s", hipGetErrorString(e)); break; }
       m->ring_used[slot] = true; }
     const RowMeta* rows = (const RowMeta*)ds;
     const int32_t* forced = (const int32_t*)(ds + m->lay.slot_upd);
@@ -891,6 +916,28 @@ rl_status rl_score(rl_model* m, void* stream, int32_t n, const int32_t* seq_ids,
   return result;
 }
 
+// Append n_tokens positions of given K/V to the active sequence seq_id (length `len` >= 0): pages, block table,
+// scatter kernels.  The caller has validated ids, sizes and free pages.
+static rl_status append_kv(rl_model* m, hipStream_t st, int32_t seq_id, int32_t n_tokens, const void* const* k_layers,
+                           const void* const* v_layers) {
+  SeqTable& T = *m->table;
+  const int32_t len = T.len(seq_id);
+  const size_t have = T.pages(seq_id).size();
+  T.reserve(seq_id, len + n_tokens, nullptr);
+  int32_t* bt_row = m->wsp<int32_t>(m->lay.block_table) + (size_t)seq_id * m->geo.max_blocks;
+  if (n_tokens > 0) {
+    const size_t now = T.pages(seq_id).size();
+    // pageable source: the runtime stages it before returning, so the vector may change afterwards
+    if (now > have)
+      HIP_TRY(hipMemcpyAsync(bt_row + have, T.pages(seq_id).data() + have, (now - have) * 4, hipMemcpyHostToDevice, st));
+    for (int l = 0; l < m->geo.n_layers; ++l)
+      launch_kv_import(st, m->geo, k_layers[l], v_layers[l], len, n_tokens, bt_row, m->k_pool(l), m->v_pool(l));
+  }
+  HIP_TRY(hipGetLastError());
+  T.set_len(seq_id, len + n_tokens);
+  return RL_OK;
+}
+
 rl_status rl_seq_import_kv(rl_model* m, void* stream, int32_t seq_id, int32_t n_tokens, const void* const* k_layers,
                            const void* const* v_layers) {
   if (!m || !k_layers || !v_layers) return fail(RL_ERR_INVALID_ARG, "NULL argument");
@@ -901,18 +948,25 @@ rl_status rl_seq_import_kv(rl_model* m, void* stream, int32_t seq_id, int32_t n_
   for (int l = 0; l < m->geo.n_layers; ++l)
     if (n_tokens > 0 && (!k_layers[l] || !v_layers[l])) return fail(RL_ERR_INVALID_ARG, "layer %d KV pointer is NULL", l);
   if (SeqTable::blocks_for(n_tokens) > T.free_pages()) return fail(RL_ERR_KV_FULL, "need %d pages, %lld free", SeqTable::blocks_for(n_tokens), (long long)T.free_pages());
-  hipStream_t st = (hipStream_t)stream;
   T.activate(seq_id);
-  T.reserve(seq_id, n_tokens, nullptr);
-  int32_t* bt_row = m->wsp<int32_t>(m->lay.block_table) + (size_t)seq_id * m->geo.max_blocks;
-  if (n_tokens > 0) {
-    HIP_TRY(hipMemcpyAsync(bt_row, T.pages(seq_id).data(), T.pages(seq_id).size() * 4, hipMemcpyHostToDevice, st));
-    for (int l = 0; l < m->geo.n_layers; ++l)
-      launch_kv_import(st, m->geo, k_layers[l], v_layers[l], n_tokens, bt_row, m->k_pool(l), m->v_pool(l));
-  }
-  HIP_TRY(hipGetLastError());
-  T.set_len(seq_id, n_tokens);
-  return RL_OK;
+  const rl_status rs = append_kv(m, (hipStream_t)stream, seq_id, n_tokens, k_layers, v_layers);
+  if (rs != RL_OK) T.release(seq_id);
+  return rs;
+}
+
+rl_status rl_seq_append_kv(rl_model* m, void* stream, int32_t seq_id, int32_t n_tokens, const void* const* k_layers,
+                           const void* const* v_layers) {
+  if (!m || !k_layers || !v_layers) return fail(RL_ERR_INVALID_ARG, "NULL argument");
+  SeqTable& T = *m->table;
+  if (!T.active(seq_id)) return fail(RL_ERR_BAD_SEQ, "sequence %d is not active", seq_id);
+  if (n_tokens < 1) return fail(RL_ERR_INVALID_ARG, "n_tokens %d < 1", n_tokens);
+  if ((int64_t)T.len(seq_id) + n_tokens > T.max_ctx() - 1)
+    return fail(RL_ERR_CTX_OVERFLOW, "sequence %d would hold %lld tokens, max_ctx is %d", seq_id, (long long)T.len(seq_id) + n_tokens, T.max_ctx());
+  for (int l = 0; l < m->geo.n_layers; ++l)
+    if (!k_layers[l] || !v_layers[l]) return fail(RL_ERR_INVALID_ARG, "layer %d KV pointer is NULL", l);
+  const int missing = T.pages_missing(seq_id, T.len(seq_id) + n_tokens);
+  if (missing > T.free_pages()) return fail(RL_ERR_KV_FULL, "need %d pages, %lld free", missing, (long long)T.free_pages());
+  return append_kv(m, (hipStream_t)stream, seq_id, n_tokens, k_layers, v_layers);
 }
 
 rl_status rl_sample_logits(rl_model* m, void* stream, int32_t n, const float* logits, const int32_t* seq_ids,

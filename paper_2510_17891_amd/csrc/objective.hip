@@ -8,6 +8,7 @@
 
 #include "../../include/rl.h"
 #include "device_utils.h"
+#include "kernels.h"
 
 namespace rl {
 
@@ -49,7 +50,7 @@ __global__ __launch_bounds__(256) void objective_seq_kernel(int G, const int32_t
   // plan length: given, or up to and including the first delimiter (whole output if there is none)
   int n_plan;
   if (n_plan_in != nullptr) {
-    n_plan = n_plan_in[k];
+    n_plan = min(max(n_plan_in[k], 0), len);  // a count outside the output is read as "none" / "all of it"
   } else {
     if (threadIdx.x == 0) sh_first = len;
     __syncthreads();
@@ -94,15 +95,22 @@ extern "C" rl_status rl_hrd_objective(void* stream, int32_t n_prompts, int32_t g
                                       const float* lp_new, const float* lp_old, const float* r_speedup,
                                       const float* r_correct, const rl_objective_params* p, float* seq_terms,
                                       int32_t* n_plan_out, float* out_value) {
-  if (n_prompts < 1 || group_size < 1 || (int64_t)n_prompts * group_size > (1 << 24) || !offsets || !lp_new || !lp_old ||
-      !r_speedup || !r_correct || !p || !seq_terms || !out_value || (!n_plan && !tokens))
-    return RL_ERR_INVALID_ARG;
-  if (p->mode != 0 && p->mode != 1) return RL_ERR_INVALID_ARG;
+  if (n_prompts < 1 || group_size < 1 || (int64_t)n_prompts * group_size > (1 << 24))
+    return (rl_status)rl::set_error(RL_ERR_INVALID_ARG, "rl_hrd_objective: n_prompts %d x group_size %d outside [1, 2^24]",
+                                    n_prompts, group_size);
+  if (!offsets || !lp_new || !lp_old || !r_speedup || !r_correct || !p || !seq_terms || !out_value)
+    return (rl_status)rl::set_error(RL_ERR_INVALID_ARG, "rl_hrd_objective: NULL argument");
+  if (!n_plan && !tokens)
+    return (rl_status)rl::set_error(RL_ERR_INVALID_ARG, "rl_hrd_objective: neither n_plan nor tokens given");
+  if (p->mode != 0 && p->mode != 1)
+    return (rl_status)rl::set_error(RL_ERR_INVALID_ARG, "rl_hrd_objective: mode %d is neither 0 (HRD) nor 1 (uniform)", p->mode);
   hipStream_t st = (hipStream_t)stream;
   const int n = n_prompts * group_size;
   rl::objective_seq_kernel<<<n, 256, 0, st>>>(group_size, offsets, n_plan, tokens, delimiter_token, lp_new, lp_old,
                                               r_speedup, r_correct, p->alpha, p->eps_clip, p->beta, p->mode, seq_terms,
                                               n_plan_out);
   rl::objective_reduce_kernel<<<1, 256, 0, st>>>(seq_terms, n, out_value);
-  return hipGetLastError() == hipSuccess ? RL_OK : RL_ERR_DEVICE;
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return (rl_status)rl::set_error(RL_ERR_DEVICE, "rl_hrd_objective: %s", hipGetErrorString(e));
+  return RL_OK;
 }

@@ -97,7 +97,7 @@ __global__ __launch_bounds__(1024) void residual_norm_kernel(float* __restrict__
     }
     if (BF16) {
       *(uint2*)((uint16_t*)h_out + frag_offset(r, i0, H >> 6)) =
-          make_uint2(pack2bf(v.x * inv * g.x, v.y * inv * g.y), pack2bf(v.z * inv * g.z, v.w * inv * g.w));
+          make_uint2(pack2h(v.x * inv * g.x, v.y * inv * g.y), pack2h(v.z * inv * g.z, v.w * inv * g.w));
     } else {
       *(float4*)((float*)h_out + (size_t)r * H + i0) = make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w);
     }
@@ -173,33 +173,33 @@ void launch_qk_rope_append(hipStream_t s, const Geometry& g, const float* qkv_pa
 }
 
 // ------------------------------------------------------------------------------------------------
-// KV import: contiguous [n_tokens][n_kv][d] -> pages of one sequence.
+// KV import: contiguous [n_tokens][n_kv][d] -> positions first_pos .. first_pos + n_tokens - 1 of one sequence.
 // ------------------------------------------------------------------------------------------------
 template <typename T, bool BF16>
 __global__ __launch_bounds__(256) void kv_import_kernel(const T* __restrict__ k_src, const T* __restrict__ v_src,
-                                                        int n_tokens, const int32_t* __restrict__ bt_row,
+                                                        int first_pos, const int32_t* __restrict__ bt_row,
                                                         void* __restrict__ k_pool, void* __restrict__ v_pool, int n_kv,
                                                         int d) {
-  const int tok = blockIdx.x;
+  const int tok = first_pos + blockIdx.x;  // position in the sequence; source token blockIdx.x
   const int64_t page = bt_row[tok >> 4];
   const int t = tok & 15;
   for (int i = threadIdx.x; i < n_kv * d; i += 256) {
     int hk = i / d, dd = i - hk * d;
-    size_t src = (size_t)tok * n_kv * d + i;
+    size_t src = (size_t)blockIdx.x * n_kv * d + i;
     kv_store<BF16>(k_pool, page, hk, n_kv, d, t, dd, load_as_float(k_src, src), false);
     kv_store<BF16>(v_pool, page, hk, n_kv, d, t, dd, load_as_float(v_src, src), true);
   }
 }
 
-void launch_kv_import(hipStream_t s, const Geometry& g, const void* k_src, const void* v_src, int n_tokens,
+void launch_kv_import(hipStream_t s, const Geometry& g, const void* k_src, const void* v_src, int first_pos, int n_tokens,
                       const int32_t* block_table_row, void* k_pool_layer, void* v_pool_layer) {
   if (n_tokens <= 0) return;
   if (g.dtype == kBF16)
-    kv_import_kernel<uint16_t, true><<<n_tokens, 256, 0, s>>>((const uint16_t*)k_src, (const uint16_t*)v_src, n_tokens,
+    kv_import_kernel<uint16_t, true><<<n_tokens, 256, 0, s>>>((const uint16_t*)k_src, (const uint16_t*)v_src, first_pos,
                                                               block_table_row, k_pool_layer, v_pool_layer, g.n_kv,
                                                               g.head_dim);
   else
-    kv_import_kernel<float, false><<<n_tokens, 256, 0, s>>>((const float*)k_src, (const float*)v_src, n_tokens,
+    kv_import_kernel<float, false><<<n_tokens, 256, 0, s>>>((const float*)k_src, (const float*)v_src, first_pos,
                                                             block_table_row, k_pool_layer, v_pool_layer, g.n_kv,
                                                             g.head_dim);
 }
