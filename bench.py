@@ -1,11 +1,17 @@
 """Benchmark of the rollout hot path on one MI355X.
 
-Workload "full8b_32x1024+N" (default): the 36-layer 8B-shaped bf16 policy, 4 prompts x group 8 = 32 sequences
-with 1024-token prompts (uniform-random ids stand in for the paper's prompts, N(0,0.02) weights for the
-checkpoint).  The prompts are prefilled (timed separately), then EXACTLY --steps decode steps are timed; one
-step = embed, 36 layers (norm, QKV, rotary+append, paged attention, O, norm, gate/up+SwiGLU, down), final
-norm, lm_head, Gumbel-max sampling with log-probs, for all 32 sequences.  Everything is resident in HBM when the
-timed region starts.  Prints one JSON line.
+Workload "wave" (default): the largest batch one GPU holds at the paper's limits (Appendix D: 32 prompts per batch,
+prompts up to 2048 tokens, responses up to 16384, G samples per prompt).  The 36-layer 8B-shaped bf16 policy, 16
+prompts x group 8 = 128 resident sequences (what fits beside the weights when every sequence may grow to 16384
+tokens: one of the two waves of the 32-prompt batch), prompts of 2048 tokens prefilled once per group (pages shared
+by the 8 samples), every sample then placed at --ctx-mid tokens of context (default 9216, the mean of a run from
+2048 to 16384) by appending private N(0,1) keys and values, then EXACTLY --steps decode steps are timed; one step =
+embed, 36 layers (norm, QKV, rotary+append, paged attention, O, norm, gate/up+SwiGLU, down), final norm, lm_head,
+Gumbel-max sampling with log-probs, for all 128 sequences.  Everything is resident in HBM when the timed region
+starts.  The same model then runs the 32-sequence workload (4 prompts x 8, prompts 1024) for comparison; its
+figures are extra keys of the one JSON line that is printed.
+
+Workload "full": the 32-sequence workload alone (4 prompts x group 8, 1024-token prompts, 1024 generated tokens).
 
 Workload "layer8b_b64_ctx2048" (--workload layer): one decoder layer at the same dimensions, batch 64 over
 2048 cached tokens per sequence, one decode step per "step".
@@ -55,7 +61,12 @@ def parse():
                     help="timed decode steps; default: full workload 1015 (with the prefill token and 8 warm-up steps "
                          "that is the 1024 generated tokens per sequence of the workload), others 512")
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", choices=["full", "layer", "copy", "ragged", "max"], default="full")
+    ap.add_argument("--workload", choices=["wave", "full", "layer", "copy", "ragged", "max"], default="wave")
+    ap.add_argument("--ctx-mid", type=int, default=9216,
+                    help="wave workload: tokens of context per sequence when the timed region starts")
+    ap.add_argument("--wave-prompts", type=int, default=16, help="wave workload: resident prompts (x 8 samples each)")
+    ap.add_argument("--no-small-batch", action="store_true",
+                    help="wave workload: skip the 32-sequence comparison run")
     ap.add_argument("--length-scale", type=float, default=1.0,
                     help="ragged workload: multiply the drawn prompt and final lengths (1.0: prompts U[256,1024], "
                          "final lengths U[1024,8192]); max workload: multiply prompt 2048 and total context 16384")
@@ -84,7 +95,7 @@ def parse():
                     help="rotation and KV append as a kernel of their own instead of inside the decode attention kernel")
     args = ap.parse_args()
     if args.steps is None:
-        args.steps = 1015 if args.workload == "full" else 512
+        args.steps = {"full": 1015, "wave": 20}.get(args.workload, 512)
     return args
 
 
@@ -140,6 +151,185 @@ def cpu_baseline_full(shape, ctx, n_seq=16, head_fraction=8):
                       f"{n_seq * t_layers + t_head_measured:.1f} s of CPU work timed, sampler excluded"}
 
 
+def kernel_table(prof, kb):
+    """{kernel class: launches, mean microseconds, share of the summed durations, achieved GB/s} from the library's
+    event timings `prof` and the algorithmic bytes per launch `kb`."""
+    kernels = {}
+    for name, (cnt, ms) in prof.items():
+        if cnt == 0:
+            continue
+        avg_us = ms / cnt * 1e3
+        entry = {"launches": cnt, "avg_us": avg_us, "share": None}
+        if name in kb:
+            entry["achieved_GBs"] = kb[name] / (avg_us * 1e-6) / 1e9
+            entry["bytes"] = kb[name]
+        kernels[name] = entry
+    tot = sum(e["avg_us"] * e["launches"] for e in kernels.values())
+    for e in kernels.values():
+        e["share"] = e["avg_us"] * e["launches"] / tot
+    return kernels
+
+
+def step_bytes_of(shape, kbm):
+    return shape["n_layers"] * (kbm["gemm_qkv"] + kbm["gemm_o"] + kbm["gemm_gate_up_swiglu"] + kbm["gemm_down"]
+                                + kbm["attn_decode"]) + kbm["gemm_lm_head"]
+
+
+def run_wave(args):
+    """The default workload: one resident wave of the largest batch at mid-run context, then the 32-sequence batch."""
+    import torch
+    import rollout_inputs as ri
+    from paper_2510_17891_amd import Rollout
+    from paper_2510_17891_amd.binding import _i32
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    seed = ri.BASE_SEED + 2
+    shape = ri.SHAPES["full8b"]
+    L, nkv, d = shape["n_layers"], shape["n_kv"], shape["head_dim"]
+    n_prompts, G, P = args.wave_prompts, 8, 2048
+    B = n_prompts * G
+    ctx_mid = max(P, args.ctx_mid)
+    private = ctx_mid - P
+    n_steps = args.warmup + args.steps
+    max_ctx = (max(ctx_mid + n_steps, 1024 + 64 + n_steps) + 1 + 15) // 16 * 16
+    pages = n_prompts * (P // 16 + G * ((ctx_mid + n_steps + 15) // 16 - P // 16)) + 64
+    t_setup = time.perf_counter()
+    w = ri.make_weights(shape, seed, device=dev, dtype=torch.bfloat16)
+    ro = Rollout(shape, w, max_seqs=B, max_ctx=max_ctx, max_rows=256, kv_pages=pages, consume_weights=True)
+    del w
+    torch.cuda.empty_cache()
+    prompts = ri.tokens((n_prompts, P), shape["vocab"], seed, 960)
+    seq_ids = list(range(B))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    tok, lp = ro.rl_prefill_groups(seq_ids, G, [prompts[i].tolist() for i in range(n_prompts)], 1.0, seed)
+    torch.cuda.synchronize()
+    prefill_s = time.perf_counter() - t0
+    if private > 0:
+        # every sample gets its own response tokens' keys and values: N(0,1) on the bf16 grid, drawn per (sequence, layer)
+        for b in seq_ids:
+            kv = [ri.normal((private, nkv, d), 1.0, seed, 7000 + b * L + l, device=dev, dtype=torch.bfloat16)
+                  for l in range(L)]
+            ro.rl_seq_append_kv(b, kv, kv[::-1])
+            del kv
+        torch.cuda.synchronize()
+    setup_s = time.perf_counter() - t_setup
+    ids = _i32(seq_ids)
+    bufs = [(torch.empty(B, dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.float32, device=dev))
+            for _ in range(2)]
+    state = {"cur": tok, "i": 0}
+
+    def step(id_arr=ids, n=B):
+        ot, ol = bufs[state["i"] & 1]
+        ro.rl_decode_step(id_arr, state["cur"], 1.0, seed, out_tokens=ot[:n], out_logprobs=ol[:n])
+        state["cur"] = ot[:n]
+        state["i"] += 1
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # HIP events bracket every launch of every stride-th timed step (about 2 us per launch on those steps, inside `value`)
+    stride = 0 if args.no_profile else max(1, args.steps // 5)
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        on = stride and k % stride == 0
+        if on:
+            ro.rl_profile_enable(True)
+        step()
+        if on:
+            ro.rl_profile_enable(False)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    ctx_first = ctx_mid + args.warmup + 1            # keys the first timed step attends to (its own token included)
+    ctx_last = ctx_first + args.steps - 1
+    ctx_avg = 0.5 * (ctx_first + ctx_last)
+    shared_tok = P // 16 * 16
+
+    def ctx_sum(ctx, once):
+        return int((n_prompts if once else B) * shared_tok + B * (ctx - shared_tok))
+
+    kb_once = kernel_bytes(shape, B, ctx_sum(ctx_avg, True))
+    kb_each = kernel_bytes(shape, B, ctx_sum(ctx_avg, False))
+    out = {
+        "metric": "generated tokens/s (8B-shaped bf16 decode) + % peak HBM GB/s, 1 MI355X",
+        "value": B * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"full8b_36L_bf16_wave_{B}seq_prompt{P}_ctx{ctx_mid}_T1.0", "batch": B, "groups": n_prompts,
+                   "group_size": G, "context_first_timed_step": ctx_first, "context_last_timed_step": ctx_last,
+                   "kv_block": 16, "temperature": 1.0, "logprob_per_token": True, "shared_prompt_tokens": shared_tok,
+                   "prefill": f"{n_prompts} prompts x {P} tokens run once each, pages shared by the {G} samples of a prompt",
+                   "private_context": f"{private} tokens per sequence of appended N(0,1) keys and values",
+                   "kv_pool_GB": pages * rl_page_bytes(shape) / 1e9},
+        # step-level fractions: per-sequence byte formula (weights once + 4096 B per cached token, layer and sequence),
+        # and the smaller figure with the prompt pages that 8 samples hold in common counted once
+        "step_algorithmic_GB": step_bytes_of(shape, kb_each) / 1e9,
+        "step_hbm_fraction": step_bytes_of(shape, kb_each) / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9),
+        "step_GB_shared_pages_once": step_bytes_of(shape, kb_once) / 1e9,
+        "step_hbm_fraction_shared_pages_once": step_bytes_of(shape, kb_once) / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9),
+        "prefill_s": prefill_s, "prefill_prompt_tokens_per_s": n_prompts * P / prefill_s, "setup_s": setup_s,
+    }
+    if stride:
+        prof = ro.rl_profile_read()
+        out["config"]["kernel_timing"] = f"HIP events on every {stride}th step of the timed region"
+        kernels = kernel_table(prof, kb_once)
+        out["kernels"] = kernels
+        dom = max((n for n in kernels if n in kb_once), key=lambda n: kernels[n]["avg_us"] * kernels[n]["launches"])
+        out["roofline"] = {"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["achieved_GBs"], "peak": HBM_PEAK_GBS,
+                           "unit": "GB/s", "frac": kernels[dom]["achieved_GBs"] / HBM_PEAK_GBS,
+                           "traffic": measured_traffic("wave", dom, kb_once[dom]),
+                           "bytes_per_launch": kb_once[dom],
+                           "achieved_per_sequence_formula": kb_each[dom] / (kernels[dom]["avg_us"] * 1e-6) / 1e9}
+
+    # ---- the 32-sequence workload on the same model: 4 prompts x 8 samples, prompts of 1024 tokens ---------------
+    if not args.no_small_batch:
+        ro.rl_free_seqs(seq_ids)
+        n2, P2 = 4, 1024
+        B2 = n2 * G
+        ids2_list = list(range(B2))
+        ids2 = _i32(ids2_list)
+        prompts2 = ri.tokens((n2, P2), shape["vocab"], seed, 900)
+        t0 = time.perf_counter()
+        tok2, _ = ro.rl_prefill_groups(ids2_list, G, [prompts2[i].tolist() for i in range(n2)], 1.0, seed)
+        torch.cuda.synchronize()
+        prefill2_s = time.perf_counter() - t0
+        state["cur"], state["i"] = tok2, 0
+        for _ in range(args.warmup):
+            step(ids2, B2)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step(ids2, B2)
+        torch.cuda.synchronize()
+        el2 = time.perf_counter() - t0
+        small = {"workload": f"full8b_36L_bf16_{B2}seq_prompt{P2}_T1.0", "tokens_per_s": B2 * args.steps / el2,
+                 "ms_per_step": el2 / args.steps * 1e3, "context_first_timed_step": P2 + args.warmup + 1,
+                 "context_last_timed_step": P2 + args.warmup + args.steps, "prefill_s": prefill2_s}
+        c2 = P2 + args.warmup + 0.5 * (args.steps + 1)
+        sh2 = P2 // 16 * 16
+        kb2 = kernel_bytes(shape, B2, int(n2 * sh2 + B2 * (c2 - sh2)))
+        kb2_each = kernel_bytes(shape, B2, int(B2 * c2))
+        small["step_hbm_fraction"] = step_bytes_of(shape, kb2_each) / (el2 / args.steps) / (HBM_PEAK_GBS * 1e9)
+        small["step_hbm_fraction_shared_pages_once"] = step_bytes_of(shape, kb2) / (el2 / args.steps) / (HBM_PEAK_GBS * 1e9)
+        if not args.no_profile:
+            ro.rl_profile_enable(True)
+            for _ in range(args.profile_steps):
+                step(ids2, B2)
+            torch.cuda.synchronize()
+            ro.rl_profile_enable(False)
+            small["kernels"] = kernel_table(ro.rl_profile_read(), kb2)
+        out["batch32"] = small
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_full(shape, int(ctx_avg))
+    ro.close()
+    print(json.dumps(out))
+
+
+def rl_page_bytes(shape):
+    return 16 * shape["n_layers"] * shape["n_kv"] * shape["head_dim"] * 2 * 2
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -152,6 +342,10 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     seed = ri.BASE_SEED + 2
+
+    if args.workload == "wave":
+        run_wave(args)
+        return
 
     if args.workload == "copy":
         # Plain device copy of known size: the reference against which HBM byte counters are scaled, and the

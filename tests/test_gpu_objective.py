@@ -91,3 +91,26 @@ def test_objective_on_a_real_rollout_is_the_ratio_one_closed_form():
     assert torch.allclose(seq, want, atol=1e-5)
     assert abs(float(out) - float(want.mean())) < 1e-5
     ro.close()
+
+
+def test_objective_plan_counts_outside_the_output_are_clamped_and_errors_carry_text():
+    """A plan count below zero or above the output's length reads as "no plan token" / "all plan": the same value the
+    oracle gives (its test `t < n_plan` treats them so).  Failing calls leave a message for rl_last_error."""
+    from paper_2510_17891_amd import binding as B
+    off, toks, n_plan, lp_new, lp_old, rs, rc = _case(3, 4, 1, 40, seed=7)
+    lens = np.diff(off)
+    wild = n_plan.copy()
+    wild[0], wild[1], wild[2] = -5, lens[1] + 1000, 2 ** 31 - 1
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    J_ref, seq_ref = orc.hrd_objective(3, 4, off, wild, lp_new, lp_old, rs, rc, 0.1, 0.2, 0.0, 0)
+    out, seq, npl = B.rl_hrd_objective(3, 4, d(off), d(lp_new), d(lp_old), d(rs), d(rc), n_plan=d(wild))
+    torch.cuda.synchronize()
+    assert np.array_equal(npl.cpu().numpy(), np.clip(wild, 0, lens))
+    scale = max(1e-6, np.abs(seq_ref).max())
+    assert np.abs(seq.cpu().numpy() - seq_ref).max() < 2e-5 * scale and abs(float(out) - J_ref) < 2e-5 * scale
+    with pytest.raises(B.RLError) as e:
+        B.rl_hrd_objective(3, 4, d(off), d(lp_new), d(lp_old), d(rs), d(rc), mode=2, n_plan=d(n_plan))
+    assert e.value.status == B.RL_ERR_INVALID_ARG and "mode 2" in str(e.value)
+    with pytest.raises(B.RLError) as e:
+        B.rl_hrd_objective(3, 4, d(off), d(lp_new), d(lp_old), d(rs), d(rc))
+    assert e.value.status == B.RL_ERR_INVALID_ARG and "neither n_plan nor tokens" in str(e.value)

@@ -9,7 +9,7 @@ import pytest
 import torch
 
 import rollout_inputs as ri
-from helpers import dims_of, make_both, rel_inf, to_device
+from helpers import ArgmaxCount, dims_of, make_both, rel_inf, to_device
 from oracle import oracle as orc
 
 pytestmark = pytest.mark.gpu
@@ -360,6 +360,61 @@ def test_bf16_layer_forked_rows_share_prompt_attention_and_match_oracle(amd, ctx
         assert err < 3e-2, (i, err)
 
 
+def test_append_kv_equals_import_and_extends_forked_sequences(amd):
+    """rl_seq_append_kv: a context imported in two pieces (the cut inside a page) gives the bits of the same context
+    imported at once; samples forked from one cached prompt and then given private tokens of different lengths match
+    the oracle row by row (shared prompt pages + private tails); error paths leave the state untouched."""
+    B = amd.binding
+    shape = ri.SHAPES["layer8b"]
+    w, wn = make_both(shape, 36)
+    nkv, d, H = shape["n_kv"], shape["head_dim"], shape["hidden"]
+    ro = amd.Rollout(shape, to_device(w), max_seqs=8, max_ctx=1024, max_rows=8, kv_pages=160)
+    ro.rl_debug_shuffle_free_pages(21)
+    k = ri.normal((700, nkv, d), 1.0, 36, 2000, dtype=torch.bfloat16)
+    v = ri.normal((700, nkv, d), 1.0, 36, 2001, dtype=torch.bfloat16)
+    ro.rl_seq_import_kv(0, [k.to(DEV)], [v.to(DEV)])
+    ro.rl_seq_import_kv(1, [k[:299].to(DEV)], [v[:299].to(DEV)])
+    ro.rl_seq_append_kv(1, [k[299:].to(DEV).contiguous()], [v[299:].to(DEV).contiguous()])
+    assert ro.rl_seq_len(1) == 700
+    # a cached prompt of 100 tokens continued as three samples with 0, 37 and 50 private tokens
+    kp = ri.normal((100, nkv, d), 1.0, 36, 2002, dtype=torch.bfloat16)
+    vp = ri.normal((100, nkv, d), 1.0, 36, 2003, dtype=torch.bfloat16)
+    ro.rl_seq_import_kv(2, [kp.to(DEV)], [vp.to(DEV)])
+    ro.rl_seq_fork(2, [3, 4])
+    priv = {2: 0, 3: 37, 4: 50}
+    tails = {}
+    for s_id, n in priv.items():
+        if n:
+            tk = ri.normal((n, nkv, d), 1.0, 36, 2010 + 2 * s_id, dtype=torch.bfloat16)
+            tv = ri.normal((n, nkv, d), 1.0, 36, 2011 + 2 * s_id, dtype=torch.bfloat16)
+            ro.rl_seq_append_kv(s_id, [tk.to(DEV)], [tv.to(DEV)])
+            tails[s_id] = (tk, tv)
+    free_before = ro.rl_kv_stats()[0]
+    for args, status in [((5, [k[:4].to(DEV)], [v[:4].to(DEV)]), B.RL_ERR_BAD_SEQ),             # not active
+                         ((0, [k[:400].to(DEV)], [v[:400].to(DEV)]), B.RL_ERR_CTX_OVERFLOW)]:   # 700 + 400 > max_ctx - 1
+        with pytest.raises(B.RLError) as e:
+            ro.rl_seq_append_kv(*args)
+        assert e.value.status == status and ro.rl_kv_stats()[0] == free_before and ro.rl_seq_len(0) == 700
+    ids = [0, 1, 2, 3, 4]
+    x = ri.normal((5, H), 1.0, 36, 1999).to(torch.bfloat16).float()
+    x[1] = x[0]
+    out = ro.rl_decode_hidden(ids, x.to(DEV)).cpu()
+    torch.cuda.synchronize()
+    assert torch.equal(out[0], out[1])
+    out = out.numpy()
+    for r, s_id in enumerate(ids):
+        if s_id < 2:
+            kk, vv = k, v
+        elif priv[s_id]:
+            kk, vv = torch.cat([kp, tails[s_id][0]]), torch.cat([vp, tails[s_id][1]])
+        else:
+            kk, vv = kp, vp
+        ref = _oracle_layer_row(shape, wn, kk, vv, x[r], kk.shape[0])
+        err = rel_inf(out[r] - x[r].numpy(), ref - x[r].numpy())
+        assert err < 3e-2, (s_id, err)
+    ro.close()
+
+
 def test_bf16_layer_batch_and_page_placement_invariance(amd):
     ctxs = [40, 513, 100, 257, 31]
     shape, wn, ro, ks, vs, x = _layer_case(amd, ctxs, seed=32)
@@ -384,7 +439,7 @@ def test_bf16_small_model_teacher_forced_logits(amd, n_q, n_kv, qk_norm):
     oracle sampler from the GPU's logits."""
     shape = dict(ri.SHAPES["layer8b"], n_layers=2, hidden=512, n_q=n_q, n_kv=n_kv, ffn=768, vocab=8192, qk_norm=qk_norm)
     w, wn = make_both(shape, 41, std=0.05)
-    ro = amd.Rollout(shape, to_device(w), max_seqs=6, max_ctx=320, max_rows=40, kv_pages=80)
+    ro = amd.Rollout(shape, to_device(w), max_seqs=6, max_ctx=320, max_rows=40, kv_pages=90)
     om = orc.OracleModel(dims_of(shape), wn, max_ctx=320)
     lens = [270, 3, 33, 70, 70, 70]
     prompts = [ri.tokens((n,), shape["vocab"], 41, 920 + i).tolist() for i, n in enumerate(lens[:4])]
@@ -397,11 +452,11 @@ def test_bf16_small_model_teacher_forced_logits(amd, n_q, n_kv, qk_norm):
     for i, s in enumerate(seqs):
         om.prefill(s, prompts[i])
     n = len(seqs)
-    steps = 20
+    steps = 40
     forced_all = ri.tokens((steps, n), shape["vocab"], 41, 930)
     logits = torch.empty(n, shape["vocab"], device=DEV)
     cur = ri.tokens((n,), shape["vocab"], 41, 929).to(DEV)
-    agree, total, worst = 0, 0, 0.0
+    count, worst = ArgmaxCount(3e-2), 0.0
     for step in range(steps):
         forced = forced_all[step].clone()
         forced[step % n] = -1                         # leave one row sampled each step
@@ -411,11 +466,7 @@ def test_bf16_small_model_teacher_forced_logits(amd, n_q, n_kv, qk_norm):
         for i, s in enumerate(seqs):
             z = om.forward_token(s, int(cur[i]))
             worst = max(worst, float(rel_inf(zg[i], z)))
-            a_gpu, a_orc = int(np.argmax(zg[i])), int(np.argmax(z))
-            agree += int(a_gpu == a_orc)
-            total += 1
-            # where the two disagree the oracle's own margin between the two candidates is inside the logit tolerance
-            assert z[a_orc] - z[a_gpu] <= 2 * 3e-2 * np.abs(z).max()
+            count.add(zg[i], z)
             t_ref, lp_ref = orc.sample(zg[i], 1.0, seed, s, lens[i] + step + 1, forced=int(forced[i]))
             assert int(tok[i]) == t_ref
             assert abs(float(lp[i]) - lp_ref) < 1e-4
@@ -423,8 +474,8 @@ def test_bf16_small_model_teacher_forced_logits(amd, n_q, n_kv, qk_norm):
             assert abs(float(lp[i]) - lp_orc) < 5e-2
         cur = tok
     assert worst < 3e-2, worst
-    # the narrowest variants have nearly flat logits (near-ties flip inside the tolerance)
-    assert agree >= (0.99 if n_q * 128 >= 512 else 0.9) * total, (agree, total)
+    count.check(min_rows=100)          # the same rule for every variant
+    print(f"[n_q={n_q} n_kv={n_kv} qk_norm={qk_norm}] worst logit error {worst:.2e}; {count.summary()}")
     ro.close()
 
 
@@ -502,15 +553,15 @@ def test_error_paths_leave_state_untouched(amd):
 
 # ------------------------------------------------------------- full-size workloads, sampled against the oracle
 def test_layer8b_full_size_batch64_ctx2048_sampled_rows(amd):
-    """The benchmarked one-layer configuration (batch 64, 2048 cached tokens each, shuffled pages): rows
-    0, 21, 42, 63 against the oracle, every row finite, and the step repeated gives identical bits."""
+    """The one-layer workload at full size (batch 64, 2048 cached tokens each, shuffled pages): every row against
+    the oracle."""
     ctxs = [2048] * 64
     shape, wn, ro, ks, vs, x = _layer_case(amd, ctxs, seed=33, shuffle=77)
     out = ro.rl_decode_hidden(list(range(64)), x.to(DEV))
     torch.cuda.synchronize()
     out = out.cpu().numpy()
     assert np.isfinite(out).all()
-    for b in (0, 21, 42, 63):
+    for b in range(64):
         ref = _oracle_layer_row(shape, wn, ks[b], vs[b], x[b], 2048)
         err = rel_inf(out[b] - x[b].numpy(), ref - x[b].numpy())
         assert err < 3e-2, (b, err)
@@ -523,65 +574,179 @@ def test_bf16_layer_many_rows_uses_wide_tiles(amd):
         ctxs = [(7 * i) % 50 for i in range(n)]
         shape, wn, ro, ks, vs, x = _layer_case(amd, ctxs, seed=34)
         out = ro.rl_decode_hidden(list(range(n)), x.to(DEV)).cpu().numpy()
-        for b in (0, 31, 32, 63, 64, 65, n - 1):
+        for b in range(n):
             ref = _oracle_layer_row(shape, wn, ks[b], vs[b], x[b], ctxs[b])
             err = rel_inf(out[b] - x[b].numpy(), ref - x[b].numpy())
             assert err < 3e-2, (n, b, err)
         ro.close()
 
 
-def test_full8b_layer_sliced_parity_and_logits(amd):
-    """The 36-layer 8B-shaped model: prefill two prompts with capture of every layer boundary, then check layers
-    0, 17 and 35 slice by slice (the oracle layer is fed the GPU's layer input at every position, and must
-    reproduce the GPU's layer output), the final logits of one row, and the sampled first tokens."""
+@pytest.fixture(scope="module")
+def full8b(amd):
+    """The 36-layer 8B-shaped model on the card, shared by the tests below (drawing and packing it takes a while).
+    Layer weights for the oracle are redrawn from the same seeded streams, one layer at a time."""
     shape = ri.SHAPES["full8b"]
     seed = ri.BASE_SEED + 2
     w = ri.make_weights(shape, seed, device=DEV, dtype=torch.bfloat16)
-    keep = {l: {k: v.float().cpu().numpy() for k, v in w["layers"][l].items()} for l in (0, 17, 35)}
-    final_norm = w["final_norm"].float().cpu().numpy()
-    lm_head = w["lm_head"].float().cpu().numpy()
-    ro = amd.Rollout(shape, w, max_seqs=4, max_ctx=64, max_rows=64, kv_pages=16)
+    m = dict(shape=shape, seed=seed, dims=dims_of(shape),
+             final_norm=w["final_norm"].float().cpu().numpy(), lm_head=w["lm_head"].float().cpu().numpy(),
+             embed=w["embed"])
+    m["ro"] = amd.Rollout(shape, w, max_seqs=16, max_ctx=2064, max_rows=64, kv_pages=8 * 130 + 16, consume_weights=True)
     del w
     torch.cuda.empty_cache()
+    yield m
+    m["ro"].close()
+
+
+def _layer_weights_for_oracle(m, l):
+    return {k: np.ascontiguousarray(v.float().cpu().numpy())
+            for k, v in ri.make_layer(m["shape"], m["seed"], l, device=DEV, dtype=torch.bfloat16).items()}
+
+
+def test_full8b_prefill_every_layer_and_first_token(full8b):
+    """The 36-layer 8B-shaped model, prefill path: two prompts with capture of every layer boundary; each of the 36
+    oracle layers is fed the GPU's layer input at every position and must reproduce the GPU's layer output.  The
+    first sampled token is pinned through a second route: the same prompt minus its last token is prefilled and that
+    token fed as a decode step, which must give the same token and log-probability bit for bit and exposes the logits,
+    from which the oracle sampler must draw that very token; the log-probability is compared with the oracle head's."""
+    m = full8b
+    ro, shape, seed, dims = m["ro"], m["shape"], m["seed"], m["dims"]
+    L, V, nkv, d = shape["n_layers"], shape["vocab"], shape["n_kv"], shape["head_dim"]
     cap = ro.rl_set_capture(True)
-    lens = [37, 20]
-    prompts = [ri.tokens((n,), shape["vocab"], seed, 950 + i).tolist() for i, n in enumerate(lens)]
+    lens = [17, 6]
+    prompts = [ri.tokens((n,), V, seed, 950 + i).tolist() for i, n in enumerate(lens)]
     tok, lp = ro.rl_prefill([1, 3], prompts, 1.0, seed)
     torch.cuda.synchronize()
-    capn = cap.cpu().numpy()                           # [(L+1), max_rows, H]; rows = seq 1 positions, then seq 3
+    cap_pre = cap[:, :sum(lens)].cpu().numpy()          # [(L+1), rows, H]; rows = seq 1 positions, then seq 3
     row0 = [0, lens[0]]
-    dims = dims_of(shape)
-    for l in (0, 17, 35):
-        for si, n in enumerate(lens):
-            kc = np.zeros((n, shape["n_kv"], shape["head_dim"]), np.float32)
-            vc = np.zeros_like(kc)
-            worst = 0.0
-            for p in range(n):
-                x_in = np.ascontiguousarray(capn[l, row0[si] + p].copy())
-                xo = x_in.copy()
-                orc.layer_forward(dims, keep[l], xo, p, kc, vc)
-                got = capn[l + 1, row0[si] + p]
-                worst = max(worst, float(rel_inf(got - x_in, xo - x_in)))
-            assert worst < 3e-2, (l, si, worst)
-    for si, (s, n) in enumerate(zip([1, 3], lens)):
-        x_last = capn[36, row0[si] + n - 1]
-        z = orc.matvec(lm_head, orc.rmsnorm(x_last, final_norm, shape["rms_eps"]))
-        t_ref, lp_ref = orc.sample(z, 1.0, seed, s, n)
-        # the GPU's logits differ by bf16 rounding of the normalised activations; the id is compared only
-        # when the oracle's decision margin is not razor thin
-        assert abs(float(lp[si]) - lp_ref) < 5e-2 or int(tok[si]) != t_ref
-    # one decode step with logits: compare against the oracle head applied to the GPU's last residual
-    logits = torch.empty(2, shape["vocab"], device=DEV)
-    tok2, lp2 = ro.rl_decode_step([1, 3], tok, 1.0, seed, debug_logits=logits)
+    logits2 = torch.empty(2, V, device=DEV)
+    tok2, lp2 = ro.rl_decode_step([1, 3], tok, 1.0, seed, debug_logits=logits2)
     torch.cuda.synchronize()
-    capn = cap.cpu().numpy()
-    zg = logits.cpu().numpy()
-    for si, s in enumerate([1, 3]):
-        z = orc.matvec(lm_head, orc.rmsnorm(capn[36, si], final_norm, shape["rms_eps"]))
-        assert rel_inf(zg[si], z) < 3e-2
-        t_ref, lp_ref = orc.sample(zg[si], 1.0, seed, s, lens[si] + 1)
+    cap_step = cap[L, :2].cpu().numpy()
+    zg2 = logits2.cpu().numpy()
+    # the first sampled token again, as a decode step at the last prompt position (same ids: same random streams)
+    ro.rl_free_seqs([1, 3])
+    ro.rl_prefill([1, 3], [p[:-1] for p in prompts], 1.0, seed)
+    last = torch.tensor([p[-1] for p in prompts], dtype=torch.int32, device=DEV)
+    logits1 = torch.empty(2, V, device=DEV)
+    tok_b, lp_b = ro.rl_decode_step([1, 3], last, 1.0, seed, debug_logits=logits1)
+    torch.cuda.synchronize()
+    ro.rl_free_seqs([1, 3])
+    ro.rl_set_capture(False)
+    assert torch.equal(tok, tok_b) and torch.equal(lp, lp_b)     # prefill and decode give the same bits
+    zg1 = logits1.cpu().numpy()
+    for si, s_id in enumerate([1, 3]):
+        t_ref, lp_ref = orc.sample(zg1[si], 1.0, seed, s_id, lens[si])
+        assert int(tok[si]) == t_ref and abs(float(lp[si]) - lp_ref) < 1e-4
+        z = orc.matvec(m["lm_head"], orc.rmsnorm(cap_pre[L, row0[si] + lens[si] - 1], m["final_norm"], shape["rms_eps"]))
+        assert rel_inf(zg1[si], z) < 3e-2
+        _, lp_orc = orc.sample(z, 1.0, seed, s_id, lens[si], forced=t_ref)
+        assert abs(float(lp[si]) - lp_orc) < 5e-2, (si, float(lp[si]), lp_orc)
+        z = orc.matvec(m["lm_head"], orc.rmsnorm(cap_step[si], m["final_norm"], shape["rms_eps"]))
+        assert rel_inf(zg2[si], z) < 3e-2
+        t_ref, lp_ref = orc.sample(zg2[si], 1.0, seed, s_id, lens[si] + 1)
         assert int(tok2[si]) == t_ref and abs(float(lp2[si]) - lp_ref) < 1e-4
-    ro.close()
+    worst = 0.0
+    for l in range(L):
+        lw = _layer_weights_for_oracle(m, l)
+        for si, n in enumerate(lens):
+            kc = np.zeros((n, nkv, d), np.float32)
+            vc = np.zeros_like(kc)
+            for p in range(n):
+                x_in = np.ascontiguousarray(cap_pre[l, row0[si] + p].copy())
+                xo = x_in.copy()
+                orc.layer_forward(dims, lw, xo, p, kc, vc)
+                err = float(rel_inf(cap_pre[l + 1, row0[si] + p] - x_in, xo - x_in))
+                worst = max(worst, err)
+                assert err < 3e-2, (l, si, p, err)
+    print(f"[full8b prefill] worst layer error over 36 layers x {sum(lens)} rows: {worst:.2e}")
+
+
+def test_full8b_decode_at_rollout_contexts_end_to_end(full8b):
+    """The 36-layer 8B-shaped model, decode path at the contexts of the 32-sequence rollout workload: eight sequences
+    whose KV is imported (N(0,1) on the bf16 grid, identical on both sides) at 1024 and 2034 tokens run 13
+    teacher-forced steps (up to context 2047) = 104 rows.  The oracle runs the same rows end to end (its own
+    residual stream, its own appended keys and values, all 36 layers and the output projection): logits within 3e-2,
+    argmax agreement >= 99 %, log-probabilities within twice the logit bound, ids reproduced from the GPU's logits.  Two sequences
+    (one per context) are also checked layer by layer, first and last step, with the oracle layer fed the GPU's
+    layer input, and the output projection alone on the GPU's last residual."""
+    m = full8b
+    ro, shape, seed, dims = m["ro"], m["shape"], m["seed"], m["dims"]
+    L, H, V, nkv, d = shape["n_layers"], shape["hidden"], shape["vocab"], shape["n_kv"], shape["head_dim"]
+    n_dec, steps = 8, 13
+    ctx0 = [1024] * 4 + [2034] * 4
+    dec_ids = list(range(4, 4 + n_dec))
+    cap = ro.rl_set_capture(True)
+
+    def kv_of(b, l, which):
+        return ri.normal((ctx0[b], nkv, d), 1.0, seed, 5000 + (b * L + l) * 2 + which, device=DEV, dtype=torch.bfloat16)
+
+    for b in range(n_dec):
+        ro.rl_seq_import_kv(dec_ids[b], [kv_of(b, l, 0) for l in range(L)], [kv_of(b, l, 1) for l in range(L)])
+    fed = ri.tokens((steps + 1, n_dec), V, seed, 960)          # row t is fed at step t, row t+1 is forced
+    zg = np.empty((steps, n_dec, V), np.float32)
+    lp_g = np.empty((steps, n_dec), np.float32)
+    tok_g = np.empty((steps, n_dec), np.int64)
+    cap_dec = np.empty((steps, L + 1, n_dec, H), np.float32)
+    forced_all = fed[1:].clone()
+    logits = torch.empty(n_dec, V, device=DEV)
+    for t in range(steps):
+        forced_all[t, t % n_dec] = -1                          # one row per step is sampled
+        tk, lq = ro.rl_decode_step(dec_ids, fed[t].to(DEV), 1.0, seed, forced_next=forced_all[t].to(DEV),
+                                   debug_logits=logits)
+        torch.cuda.synchronize()
+        zg[t], lp_g[t], tok_g[t] = logits.cpu().numpy(), lq.cpu().numpy(), tk.cpu().numpy()
+        cap_dec[t] = cap[:, :n_dec].cpu().numpy()
+    assert all(ro.rl_seq_len(dec_ids[b]) == ctx0[b] + steps for b in range(n_dec))
+    ro.rl_free_seqs(dec_ids)
+    ro.rl_set_capture(False)
+    x_chain = m["embed"][fed[:steps].to(DEV).long()].float().cpu().numpy()    # [steps, n_dec, H]: the oracle's own stream
+    assert np.array_equal(x_chain, cap_dec[:, 0])                             # the gather is exact
+    sliced, sliced_steps = (0, 4), (0, steps - 1)                             # one sequence per context class
+    worst_layer = 0.0
+    for l in range(L):
+        lw = _layer_weights_for_oracle(m, l)
+        for b in range(n_dec):
+            kc = np.zeros((ctx0[b] + steps, nkv, d), np.float32)
+            vc = np.zeros_like(kc)
+            kc[:ctx0[b]] = kv_of(b, l, 0).float().cpu().numpy()
+            vc[:ctx0[b]] = kv_of(b, l, 1).float().cpu().numpy()
+            for t in range(steps):
+                pos = ctx0[b] + t
+                if b in sliced and t in sliced_steps:
+                    # The layer alone, fed the GPU's input; the earlier keys and values are the end-to-end oracle's.
+                    # It writes slot `pos`, which the end-to-end pass below overwrites with its own.
+                    x_in = np.ascontiguousarray(cap_dec[t, l, b].copy())
+                    xo = x_in.copy()
+                    orc.layer_forward(dims, lw, xo, pos, kc, vc)
+                    err = float(rel_inf(cap_dec[t, l + 1, b] - x_in, xo - x_in))
+                    worst_layer = max(worst_layer, err)
+                    assert err < 3e-2, (l, b, t, err)
+                x = np.ascontiguousarray(x_chain[t, b])
+                orc.layer_forward(dims, lw, x, pos, kc, vc)
+                x_chain[t, b] = x
+    count, worst, worst_lp = ArgmaxCount(3e-2), 0.0, 0.0
+    for t in range(steps):
+        for b in range(n_dec):
+            z = orc.matvec(m["lm_head"], orc.rmsnorm(x_chain[t, b], m["final_norm"], shape["rms_eps"]))
+            err = float(rel_inf(zg[t, b], z))
+            worst = max(worst, err)
+            assert err < 3e-2, (t, b, err)
+            count.add(zg[t, b], z)
+            pos = ctx0[b] + t + 1
+            t_ref, lp_ref = orc.sample(zg[t, b], 1.0, seed, dec_ids[b], pos, forced=int(forced_all[t, b]))
+            assert int(tok_g[t, b]) == t_ref and abs(float(lp_g[t, b]) - lp_ref) < 1e-4, (t, b)
+            # log-probability = z_tok - logsumexp(z): two terms, each within the logit bound 3e-2 max|z|
+            _, lp_orc = orc.sample(z, 1.0, seed, dec_ids[b], pos, forced=t_ref)
+            worst_lp = max(worst_lp, abs(float(lp_g[t, b]) - lp_orc))
+            assert abs(float(lp_g[t, b]) - lp_orc) < 2 * 3e-2 * np.abs(z).max(), (t, b, float(lp_g[t, b]), lp_orc)
+            if b in sliced and t in sliced_steps:             # the output projection alone, on the GPU's last residual
+                zs = orc.matvec(m["lm_head"], orc.rmsnorm(cap_dec[t, L, b], m["final_norm"], shape["rms_eps"]))
+                assert rel_inf(zg[t, b], zs) < 3e-2
+    assert count.rows >= 100
+    count.check(min_rows=50)
+    print(f"[full8b decode] worst layer error {worst_layer:.2e}, worst end-to-end logit error {worst:.2e}, worst "
+          f"log-probability error {worst_lp:.2e}; {count.summary()}")
 
 
 # ------------------------------------------------------ ragged rollout: sequences retire and new ones join
@@ -877,6 +1042,31 @@ def test_score_matches_oracle_log_softmax(amd):
     with pytest.raises(B.RLError) as e:
         ro.rl_score([0], [list(range(70))], 1.0)
     assert e.value.status == B.RL_ERR_CTX_OVERFLOW and ro.rl_kv_stats() == (12, 12)
+    ro.close()
+
+
+def test_score_bf16_matches_oracle_log_softmax(amd):
+    """The scoring call on the bf16 path (MFMA projections, windowed attention sets, output projection fused with the
+    log-sum-exp) against the oracle's log-softmax of its own teacher-forced logits, at two temperatures; sequences
+    longer than a chunk of rows, a two-token one, and one that ends exactly on a page."""
+    shape = dict(ri.SHAPES["layer8b"], n_layers=2, hidden=512, n_q=4, n_kv=1, ffn=768, vocab=8192)
+    w, wn = make_both(shape, 73, std=0.05)
+    ro = amd.Rollout(shape, to_device(w), max_seqs=8, max_ctx=128, max_rows=24, kv_pages=24)
+    lens = [70, 2, 32, 45]
+    seqs = [ri.tokens((n,), shape["vocab"], 73, 990 + i).tolist() for i, n in enumerate(lens)]
+    for T in (1.0, 0.7):
+        out = ro.rl_score([4, 0, 7, 2], seqs, T).cpu().numpy()
+        assert ro.rl_kv_stats() == (24, 24)
+        invT = float(np.float32(1.0) / np.float32(T))
+        k, worst = 0, 0.0
+        for i, q in enumerate(seqs):
+            om = orc.OracleModel(dims_of(shape), wn, max_ctx=128)
+            for t in range(len(q) - 1):
+                ls = orc.log_softmax(om.forward_token(0, q[t]), invT)
+                worst = max(worst, abs(float(out[k]) - float(ls[q[t + 1]])))
+                k += 1
+        assert k == out.size
+        assert worst < 5e-2, (T, worst)
     ro.close()
 
 
