@@ -229,6 +229,25 @@ rl_status rl_sample_logits(rl_model* m, void* stream, int32_t n, const float* lo
                            const rl_sampling* sp, int32_t* out_tokens, float* out_logprobs);
 
 /*
+ * rl_sample_logits for callers that cannot allocate device memory or hold a model: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid allocation.  Same kernels and bits as rl_sample_logits without a cut,
+ * but the scratch they need (row metadata, forced-token logits, per-tile partials) lives in a static device array
+ * of 660 480 bytes inside the library (one copy per GPU, held until the process ends) instead of a model's
+ * workspace, and the call allocates nothing.
+ *   logits  device[n x vocab] fp32, rows 16-byte aligned (vocab % 4 == 0, 4 <= vocab < 2^22)
+ *   seq_ids, positions  DEVICE[n] int32 (stream id and absolute position of the random numbers of each row)
+ *   forced  device[n] or NULL;  out_tokens device[n] int32;  out_logprobs device[n] fp32
+ * Limits: n <= 256 and n * ceil(vocab / 2048) <= 20480 (a 151 936-entry vocabulary at 256 rows needs 19 200);
+ * beyond them RL_ERR_INVALID_ARG.  top_k / top_p cuts are not available here (RL_ERR_UNSUPPORTED): they need
+ * 164 KB of histograms per row.  All calls on one GPU share that GPU's array: calls that overlap on one GPU
+ * (different streams or threads) race; calls on one stream are ordered.  Nothing in the array has to be cleared
+ * between calls.
+ */
+rl_status rl_sample_logits_static(void* stream, int32_t n, int32_t vocab, const float* logits,
+                                  const int32_t* seq_ids, const int32_t* positions, const int32_t* forced,
+                                  const rl_sampling* sp, int32_t* out_tokens, float* out_logprobs);
+
+/*
  * Create a sequence whose first n_tokens positions of KV are given instead of computed.
  *   k_layers, v_layers  host arrays of n_layers device pointers, each [n_tokens][n_kv][head_dim] in
  *   the model dtype (keys as they are stored, i.e. after norm and rotation).

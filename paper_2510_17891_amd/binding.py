@@ -19,7 +19,7 @@ RL_F32, RL_BF16 = 0, 1
 
 EXPORTS = [
     "rl_kv_page_bytes", "rl_query_workspace", "rl_init_model", "rl_destroy_model", "rl_prefill", "rl_prefill_groups", "rl_score", "rl_hrd_objective",
-    "rl_decode_step", "rl_free_seqs", "rl_last_error", "rl_kv_stats", "rl_seq_len", "rl_sample_logits",
+    "rl_decode_step", "rl_free_seqs", "rl_last_error", "rl_kv_stats", "rl_seq_len", "rl_sample_logits", "rl_sample_logits_static",
     "rl_seq_import_kv", "rl_seq_append_kv", "rl_decode_hidden", "rl_set_capture", "rl_pack_weight",
     "rl_debug_shuffle_free_pages", "rl_debug_share_attention", "rl_debug_attention_appends", "rl_seq_fork", "rl_profile_enable", "rl_profile_read",
 ]
@@ -91,6 +91,8 @@ def lib():
         L.rl_seq_len.argtypes = [C.c_void_p, C.c_int32, _i32p]
         L.rl_sample_logits.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, _i32p, _i32p,
                                        C.c_void_p, C.POINTER(rl_sampling), C.c_void_p, C.c_void_p]
+        L.rl_sample_logits_static.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.POINTER(rl_sampling), C.c_void_p, C.c_void_p]
         L.rl_seq_import_kv.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, _pp, _pp]
         L.rl_seq_append_kv.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, _pp, _pp]
         L.rl_decode_hidden.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, _i32p, C.c_void_p, C.c_void_p]
@@ -162,6 +164,19 @@ def rl_hrd_objective(n_prompts, group_size, offsets, lp_new, lp_old, r_speedup, 
                                 C.byref(p), _ptr(seq), _ptr(npl), _ptr(out))
     check(st)
     return out, seq, npl
+
+
+def rl_sample_logits_static(logits, seq_ids, positions, temperature, seed, forced=None, out_tokens=None,
+                            out_logprobs=None, top_k=0, top_p=0.0):
+    """The plain sampler without a model; seq_ids / positions are device int32 tensors.  The call itself allocates
+    nothing when out_tokens / out_logprobs are given."""
+    n, vocab = logits.shape
+    out_t = out_tokens if out_tokens is not None else torch.empty(n, dtype=torch.int32, device=logits.device)
+    out_lp = out_logprobs if out_logprobs is not None else torch.empty(n, dtype=torch.float32, device=logits.device)
+    sp = rl_sampling(temperature, top_k, seed, top_p, 0)
+    check(lib().rl_sample_logits_static(_stream(), n, vocab, _ptr(logits), _ptr(seq_ids), _ptr(positions), _ptr(forced),
+                                        C.byref(sp), _ptr(out_t), _ptr(out_lp)))
+    return out_t, out_lp
 
 
 class Rollout:

@@ -1,6 +1,9 @@
 // Stand-alone Gumbel-max sampling kernels (logits in memory) and the merge stage shared with the fused path.
 // The arithmetic contract lives in sampler_device.h.  The log-probability log softmax(z/T)[token] is accumulated
 // in fp32 (tolerance, not bit-exact).
+#include <mutex>
+
+#include "../../include/rl.h"
 #include "kernels.h"
 #include "sampler_device.h"
 
@@ -404,3 +407,90 @@ void launch_sample_merge(hipStream_t st, const float* part, int n_tiles, int M, 
 }
 
 }  // namespace rl
+
+// ------------------------------------------------------------------------------------------------
+// The plain sampler for callers that cannot allocate (code under graph capture, serving loops, harnesses that forbid
+// it): the same two kernels as above, with the row metadata, the forced tokens' logits and the per-tile partials in
+// a file-scope device array instead of a model's workspace.  Each GPU has its own copy of the array at its own
+// address; that address is looked up once per device and used from then on (the array's name is not a device
+// address in host code).  Every call on a GPU uses that GPU's array, so calls that overlap on one GPU race.
+// ------------------------------------------------------------------------------------------------
+namespace rl {
+
+namespace {
+
+constexpr int kStaticRows = 256;          // rows per call
+constexpr int kStaticTileRows = 20480;    // rows x ceil(vocab / kSampleTile) per call (151 936 entries x 256 rows: 19 200)
+constexpr size_t kStaticRowsOff = 0;                                           // RowMeta [kStaticRows]
+constexpr size_t kStaticForcedOff = kStaticRowsOff + kStaticRows * sizeof(RowMeta);  // float [kStaticRows]
+constexpr size_t kStaticPartOff = kStaticForcedOff + kStaticRows * sizeof(float);    // float [kStaticTileRows][8]
+constexpr size_t kStaticBytes = kStaticPartOff + (size_t)kStaticTileRows * kSamplePartFloats * sizeof(float);
+static_assert(kStaticPartOff % 16 == 0, "the partials are written as float4");
+
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];  // 660 480 bytes per GPU, held until the process ends
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of the current device's copy of `scratch` (looked up on first use on that device).
+hipError_t scratch_address(unsigned char** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[dev] = (unsigned char*)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
+__global__ __launch_bounds__(256) void static_rows_kernel(const int32_t* __restrict__ seq_ids, const int32_t* __restrict__ positions,
+                                                          RowMeta* __restrict__ rows, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) rows[i] = RowMeta{seq_ids[i], positions[i], 0, 0};
+}
+
+}  // namespace
+
+}  // namespace rl
+
+extern "C" rl_status rl_sample_logits_static(void* stream, int32_t n, int32_t vocab, const float* logits,
+                                             const int32_t* seq_ids, const int32_t* positions, const int32_t* forced,
+                                             const rl_sampling* sp, int32_t* out_tokens, float* out_logprobs) {
+  using namespace rl;
+  if (!logits || !seq_ids || !positions || !sp || !out_tokens || !out_logprobs)
+    return (rl_status)set_error(RL_ERR_INVALID_ARG, "rl_sample_logits_static: NULL argument");
+  if (vocab < 4 || vocab % 4 || vocab >= (1 << 22))
+    return (rl_status)set_error(RL_ERR_INVALID_ARG, "rl_sample_logits_static: vocab %d must be a multiple of 4 in [4, 2^22)", vocab);
+  const int n_tiles = (vocab + kSampleTile - 1) / kSampleTile;
+  if (n < 1 || n > kStaticRows || (int64_t)n * n_tiles > kStaticTileRows)
+    return (rl_status)set_error(RL_ERR_INVALID_ARG,
+                                "rl_sample_logits_static: %d rows x %d vocabulary tiles exceed the static scratch "
+                                "(at most %d rows and %d row-tiles of %d entries per call)",
+                                n, n_tiles, kStaticRows, kStaticTileRows, kSampleTile);
+  const int top_k = sp->top_k > (uint32_t)vocab ? 0 : (int)sp->top_k;
+  if (sp->temperature > 0.f && sample_is_truncated(vocab, top_k, sp->top_p))
+    return (rl_status)set_error(RL_ERR_UNSUPPORTED,
+                                "rl_sample_logits_static: top-k / top-p cuts need per-row histograms that the static "
+                                "scratch does not hold; use rl_sample_logits");
+  unsigned char* base = nullptr;
+  hipError_t e = scratch_address(&base);
+  if (e != hipSuccess) return (rl_status)set_error(RL_ERR_DEVICE, "rl_sample_logits_static: scratch address: %s", hipGetErrorString(e));
+  hipStream_t st = (hipStream_t)stream;
+  RowMeta* rows = (RowMeta*)(base + kStaticRowsOff);
+  float* forced_z = (float*)(base + kStaticForcedOff);
+  float* part = (float*)(base + kStaticPartOff);
+  // Nothing has to start at zero: the kernels write every entry they read (all n x n_tiles partials; the forced
+  // token's logit whenever the forced id is inside the vocabulary, which is when the second stage reads it).
+  static_rows_kernel<<<(n + 255) / 256, 256, 0, st>>>(seq_ids, positions, rows, n);
+  launch_sample(st, logits, n, vocab, rows, 0, forced, sp->temperature, sp->seed, part, forced_z, out_tokens, out_logprobs);
+  e = hipGetLastError();
+  if (e != hipSuccess) return (rl_status)set_error(RL_ERR_DEVICE, "rl_sample_logits_static: %s", hipGetErrorString(e));
+  return RL_OK;
+}
