@@ -61,7 +61,10 @@ def parse():
                     help="timed decode steps; default: full workload 1015 (with the prefill token and 8 warm-up steps "
                          "that is the 1024 generated tokens per sequence of the workload), others 512")
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", choices=["wave", "full", "layer", "copy", "ragged", "max"], default="wave")
+    ap.add_argument("--workload", choices=["wave", "full", "layer", "copy", "ragged", "max", "tiny", "objective", "score", "prefill", "sched"],
+                    default="wave")
+    ap.add_argument("--score-len", type=int, default=1024, help="score workload: tokens per sequence (32 x 8 sequences)")
+    ap.add_argument("--prefill-len", type=int, default=2048, help="prefill workload: tokens per prompt (32 prompts)")
     ap.add_argument("--ctx-mid", type=int, default=9216,
                     help="wave workload: tokens of context per sequence when the timed region starts")
     ap.add_argument("--wave-prompts", type=int, default=16, help="wave workload: resident prompts (x 8 samples each)")
@@ -95,7 +98,7 @@ def parse():
                     help="rotation and KV append as a kernel of their own instead of inside the decode attention kernel")
     args = ap.parse_args()
     if args.steps is None:
-        args.steps = {"full": 1015, "wave": 20}.get(args.workload, 512)
+        args.steps = {"full": 1015, "wave": 20, "tiny": 320, "objective": 200, "sched": 200}.get(args.workload, 512)
     return args
 
 
@@ -326,6 +329,199 @@ def run_wave(args):
     print(json.dumps(out))
 
 
+def run_tiny(args):
+    """The tiny fp32 workload end to end (4 prompts x 64 tokens, 32 greedy tokens each) and the oracle's wall time for
+    the same run.  A launch-bound case by nature: 2 layers of 256-wide matrices, about 40 small kernels per step."""
+    import numpy as np
+    import torch
+    import rollout_inputs as ri
+    from paper_2510_17891_amd import Rollout
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from helpers import dims_of, make_both, to_device
+    shape = ri.SHAPES["tiny"]
+    w, wn = make_both(shape, ri.BASE_SEED + 1)
+    ro = Rollout(shape, to_device(w), max_seqs=8, max_ctx=128, max_rows=64, kv_pages=40)
+    prompts = ri.tokens((4, 64), shape["vocab"], ri.BASE_SEED + 1, 900).tolist()
+    seqs = [0, 1, 2, 3]
+
+    def run():
+        tok, lp = ro.rl_prefill(seqs, prompts, 0.0, 0)
+        out = [tok]
+        for _ in range(31):
+            tok, lp = ro.rl_decode_step(seqs, tok, 0.0, 0)
+            out.append(tok)
+        torch.cuda.synchronize()
+        ro.rl_free_seqs(seqs)
+        return torch.stack(out, 1).cpu()
+
+    gpu_tokens = run()                                  # warm-up (and the ids to compare)
+    reps = max(1, args.steps // 32)
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        run()
+    gpu_s = (time.perf_counter() - t0) / reps
+    out = {"metric": "generated tokens/s (tiny fp32 decoder, greedy)", "value": 4 * 32 / gpu_s, "unit": "tokens/s",
+           "n_gpus": 1, "steps": 32 * reps, "warmup": 32, "ms_per_step": gpu_s / 32 * 1e3, "higher_is_better": True,
+           "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "tiny_2L_fp32_4x64_prompt_32_greedy", "note": "launch-bound: prefill of 256 rows in "
+                      "chunks of 64 plus 31 decode steps of about 40 small kernels each; the rate says nothing about HBM"},
+           "whole_run_ms": gpu_s * 1e3}
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        om = orc.OracleModel(dims_of(shape), wn, max_ctx=128)
+        t0 = time.perf_counter()
+        ref = []
+        for s, p in zip(seqs, prompts):
+            z = om.prefill(s, p)
+            row = []
+            for k in range(32):
+                t, _ = orc.sample(z, 0.0, 0, s, 64 + k)
+                row.append(t)
+                if k < 31:
+                    z = om.forward_token(s, t)
+            ref.append(row)
+        cpu_s = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 4 * 32 / cpu_s, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
+                               "sample": f"the whole run (4 x 64 prompt tokens + 4 x 32 greedy tokens), {cpu_s:.2f} s"}
+        out["tokens_equal_oracle"] = bool((gpu_tokens.numpy() == np.array(ref)).all())
+    ro.close()
+    print(json.dumps(out))
+
+
+def run_objective(args):
+    """rl_hrd_objective on one RL batch at the paper's limits: 32 prompts x 8 outputs, lengths U[64, 16384]."""
+    import numpy as np
+    import torch
+    import rollout_inputs as ri
+    from paper_2510_17891_amd import binding as B
+    dev = "cuda:0"
+    n_prompts, G, seed = 32, 8, 11
+    n = n_prompts * G
+    lens = ri.lengths(n, 64, 16384, seed, 1).numpy()
+    lens[-1] = 16384
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    total = int(off[-1])
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    lp_old = -ri.normal((total,), 1.0, seed, 3, device=dev).abs() - 0.1
+    lp_new = lp_old + ri.normal((total,), 0.25, seed, 4, device=dev)
+    toks = ri.tokens((total,), 1000, seed, 2).to(dev)
+    rs = ri.normal((n,), 0.6, seed, 5).abs().clamp(max=2.0).to(dev)
+    rc = (ri.normal((n,), 1.0, seed, 6) > 0).float().to(dev)
+    offd = d(off)
+    res = {}
+    for label, kw in (("plan_lengths_given", dict(n_plan=d((lens // 2).astype(np.int32)))),
+                      ("delimiter_scan", dict(tokens=toks, delimiter_token=7))):
+        for _ in range(3):
+            B.rl_hrd_objective(n_prompts, G, offd, lp_new, lp_old, rs, rc, **kw)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            B.rl_hrd_objective(n_prompts, G, offd, lp_new, lp_old, rs, rc, **kw)
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t0) / args.steps * 1e6
+        nbytes = total * (8 + (4 if "tokens" in kw else 0)) + n * 24
+        res[label] = {"us_per_call": us, "algorithmic_bytes": nbytes, "GBs": nbytes / us / 1e3}
+    out = {"metric": "HRD objective forward, microseconds per RL batch", "value": res["plan_lengths_given"]["us_per_call"],
+           "unit": "us", "n_gpus": 1, "steps": args.steps, "higher_is_better": False, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "hrd_objective_32x8_outputs_U[64,16384]_tokens", "tokens": total,
+                      "note": "two kernels (one block per output, then a one-block sum): latency- and launch-bound at "
+                              "this size, the 8 bytes per token are far from an HBM limit"},
+           "variants": res}
+    print(json.dumps(out))
+
+
+def run_score_or_prefill(args):
+    """Prompt processing as a matrix-core workload: `prefill` runs 32 prompts of --prefill-len tokens (4 groups of 8
+    prompts at a time, the KV stays), `score` runs rl_score over 32 x 8 sequences of --score-len tokens.  Reports
+    tokens/s and the fraction of the dense bf16/f16 matrix-core peak that the model's matrix flops amount to."""
+    import torch
+    import rollout_inputs as ri
+    from paper_2510_17891_amd import Rollout
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    seed = ri.BASE_SEED + 2
+    shape = ri.SHAPES["full8b"]
+    score = args.workload == "score"
+    n_seq, T = (256, args.score_len) if score else (32, args.prefill_len)
+    max_ctx = (T + 16 + 15) // 16 * 16
+    w = ri.make_weights(shape, seed, device=dev, dtype=torch.bfloat16)
+    ro = Rollout(shape, w, max_seqs=n_seq, max_ctx=max_ctx, max_rows=256, kv_pages=n_seq * (max_ctx // 16) + 16,
+                 consume_weights=True)
+    del w
+    torch.cuda.empty_cache()
+    toks = ri.tokens((n_seq, T), shape["vocab"], seed, 970)
+    seqs = [toks[i].tolist() for i in range(n_seq)]
+    ids = list(range(n_seq))
+    # matrix flops per token: 2 x (layer matrices + lm_head for the scored positions) + attention 4 n_q d ctx per layer
+    H, d, F, V = shape["hidden"], shape["head_dim"], shape["ffn"], shape["vocab"]
+    nq, nkv, L = shape["n_q"], shape["n_kv"], shape["n_layers"]
+    per_tok = 2 * L * (H * (nq + 2 * nkv) * d + nq * d * H + 3 * F * H)
+    attn = 4 * nq * d * L * (T + 1) / 2
+    head = 2 * V * H
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    if score:
+        group = 32
+        for b0 in range(0, n_seq, group):
+            ro.rl_score(ids[b0:b0 + group], seqs[b0:b0 + group], 1.0)
+        flops = n_seq * (T * (per_tok + attn) + (T - 1) * head)
+    else:
+        for b0 in range(0, n_seq, 8):
+            ro.rl_prefill(ids[b0:b0 + 8], seqs[b0:b0 + 8], 1.0, seed)
+        flops = n_seq * (T * (per_tok + attn) + head)
+    torch.cuda.synchronize()
+    el = time.perf_counter() - t0
+    out = {"metric": "teacher-forced scoring tokens/s" if score else "prefill prompt tokens/s", "value": n_seq * T / el,
+           "unit": "tokens/s", "n_gpus": 1, "steps": 1, "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"full8b_{'score' if score else 'prefill'}_{n_seq}x{T}", "rows_per_chunk": 256},
+           "seconds": el, "model_TFLOPs": flops / el / 1e12,
+           "roofline": {"bound": "mfma", "achieved": flops / el / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
+                        "frac": flops / el / 1e12 / 2500.0, "traffic": None}}
+    ro.close()
+    print(json.dumps(out))
+
+
+def run_sched(args):
+    """Host cost of the step scheduler: a one-layer model at 8B layer dimensions (so that the GPU side is short and the
+    host side shows), 16 and 32 groups of 8 samples (128 and 256 rows, prompts shared inside a group), generated by the
+    group rollout loop.  Reports, per decode call, the library's admission checks and metadata build + upload, its
+    kernel launches, and what the Python loop adds around the call."""
+    import torch
+    import rollout_inputs as ri
+    from paper_2510_17891_amd import Rollout, generate_groups, group_page_need
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    seed = ri.BASE_SEED + 5
+    shape = dict(ri.SHAPES["layer8b"], vocab=4096)
+    w = ri.make_weights(shape, seed, device=dev, dtype=torch.bfloat16)
+    res = {}
+    for n_prompts in (16, 32):
+        G, P, new = 8, 64, args.steps
+        prompts = [ri.tokens((P,), shape["vocab"], seed, 980 + i).tolist() for i in range(n_prompts)]
+        pages = n_prompts * group_page_need(P, [new] * G) + 8
+        ro = Rollout(shape, w, max_seqs=n_prompts * G, max_ctx=(P + new + 16) // 16 * 16, max_rows=256, kv_pages=pages)
+        generate_groups(ro, prompts[:2], G, 4, 1.0, seed)          # warm-up
+        ro.rl_profile_host_read()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        generate_groups(ro, prompts, G, new, 1.0, seed)
+        wall = time.perf_counter() - t0
+        h = ro.rl_profile_host_read()
+        calls = max(1, h["calls"])
+        res[f"{n_prompts * G}_rows"] = {
+            "decode_calls": h["calls"], "admit_us_per_call": h["admit_us"] / calls, "meta_us_per_call": h["meta_us"] / calls,
+            "launch_us_per_call": h["launch_us"] / calls, "wall_us_per_step": wall / new * 1e6,
+            "python_and_wait_us_per_step": wall / new * 1e6 - (h["admit_us"] + h["meta_us"] + h["launch_us"]) / new}
+        ro.close()
+    out = {"metric": "host microseconds per decode call spent in the step scheduler", "unit": "us",
+           "value": res["256_rows"]["admit_us_per_call"] + res["256_rows"]["meta_us_per_call"], "higher_is_better": False,
+           "n_gpus": 1, "steps": args.steps, "data": "synthetic",
+           "config": {"workload": "layer8b_1L_vocab4096_groups_of_8_prompt64", "note": "wall_us_per_step includes the "
+                      "prefills of the run (one per group) and any wait for the GPU; the scheduler's own share is "
+                      "admit + meta"}, "rows": res}
+    print(json.dumps(out))
+
+
 def rl_page_bytes(shape):
     return 16 * shape["n_layers"] * shape["n_kv"] * shape["head_dim"] * 2 * 2
 
@@ -345,6 +541,18 @@ def main():
 
     if args.workload == "wave":
         run_wave(args)
+        return
+    if args.workload == "tiny":
+        run_tiny(args)
+        return
+    if args.workload == "objective":
+        run_objective(args)
+        return
+    if args.workload in ("score", "prefill"):
+        run_score_or_prefill(args)
+        return
+    if args.workload == "sched":
+        run_sched(args)
         return
 
     if args.workload == "copy":

@@ -194,7 +194,11 @@ rl_status rl_score(rl_model* m, void* stream, int32_t n_seqs, const int32_t* seq
  * One decode step for n_seqs active sequences (1 <= n_seqs <= max_rows): feed in_tokens[b] at the
  * sequence's next position, append its K/V, and sample the following token.
  *   seq_ids       host  [n_seqs]
- *   in_tokens     device[n_seqs] int32   (normally the previous call's out_tokens)
+ *   in_tokens     device[n_seqs] int32 (normally the previous call's out_tokens), or NULL: every sequence is then
+ *                 fed the token that its last rl_prefill / rl_prefill_groups / rl_decode_step call returned for it
+ *                 (the library keeps one per sequence id), so a caller whose batch changes from step to step --
+ *                 sequences retire, new groups join -- needs no gather of its own.  Only for sequences that have
+ *                 sampled before (not for ones made by rl_seq_import_kv or rl_seq_fork and never stepped)
  *   forced_next   device[n_seqs] int32 or NULL; entries in [0, vocab) replace the sampled token (teacher
  *                 forcing) and the log-probability reported is that of the forced token; any other
  *                 value leaves that row sampled
@@ -364,6 +368,9 @@ rl_status rl_debug_attention_appends(rl_model* m, int32_t on);
  *   *n_out     number of classes written
  */
 rl_status rl_profile_enable(rl_model* m, int32_t on);
+/* Host microseconds that rl_decode_step spent since the last read (always collected): admission checks (ids, pages),
+ * building and uploading the rows / page grants / shared-attention plan, and enqueueing the kernels; and the calls. */
+rl_status rl_profile_host_read(rl_model* m, double* admit_us, double* meta_us, double* launch_us, int64_t* calls);
 rl_status rl_profile_read(rl_model* m, int32_t n_max, const char** names_out, double* ms_out,
                           int64_t* counts_out, int32_t* n_out);
 

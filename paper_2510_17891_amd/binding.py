@@ -21,7 +21,7 @@ EXPORTS = [
     "rl_kv_page_bytes", "rl_query_workspace", "rl_init_model", "rl_destroy_model", "rl_prefill", "rl_prefill_groups", "rl_score", "rl_hrd_objective",
     "rl_decode_step", "rl_free_seqs", "rl_last_error", "rl_kv_stats", "rl_seq_len", "rl_sample_logits", "rl_sample_logits_static",
     "rl_seq_import_kv", "rl_seq_append_kv", "rl_decode_hidden", "rl_set_capture", "rl_pack_weight",
-    "rl_debug_shuffle_free_pages", "rl_debug_share_attention", "rl_debug_attention_appends", "rl_seq_fork", "rl_profile_enable", "rl_profile_read",
+    "rl_debug_shuffle_free_pages", "rl_debug_share_attention", "rl_debug_attention_appends", "rl_seq_fork", "rl_profile_enable", "rl_profile_read", "rl_profile_host_read",
 ]
 
 
@@ -105,6 +105,7 @@ def lib():
         L.rl_profile_enable.argtypes = [C.c_void_p, C.c_int32]
         L.rl_profile_read.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                       C.POINTER(C.c_int64), _i32p]
+        L.rl_profile_host_read.argtypes = [C.c_void_p] + [C.POINTER(C.c_double)] * 3 + [C.POINTER(C.c_int64)]
         _lib = L
     return _lib
 
@@ -382,6 +383,12 @@ class Rollout:
 
     def rl_profile_enable(self, on):
         check(lib().rl_profile_enable(self.h, 1 if on else 0))
+
+    def rl_profile_host_read(self):
+        """Host microseconds inside rl_decode_step since the last read: dict(admit, meta, launch, calls)."""
+        a, b, c, n = C.c_double(), C.c_double(), C.c_double(), C.c_int64()
+        check(lib().rl_profile_host_read(self.h, C.byref(a), C.byref(b), C.byref(c), C.byref(n)))
+        return {"admit_us": a.value, "meta_us": b.value, "launch_us": c.value, "calls": n.value}
 
     def rl_profile_read(self):
         """{kernel class: (launches, total ms)} since the last read."""

@@ -42,7 +42,9 @@ __host__ __device__ inline size_t frag_offset(int r, int k, int k_blocks) {
 
 // ---- elementwise / small kernels (both dtypes) -------------------------------------------------
 // x[r][:] = E[tok[r]][:] widened to fp32 (ids clamped to [0, V)).
-void launch_embed(hipStream_t s, int dtype, const void* embed, const int32_t* tokens, float* x, int M, int H, int V);
+// tokens == null: row r is fed last_tok[rows[r].seq] (the token the sampler recorded for that sequence).
+void launch_embed(hipStream_t s, int dtype, const void* embed, const int32_t* tokens, float* x, int M, int H, int V,
+                  const RowMeta* rows = nullptr, const int32_t* last_tok = nullptr);
 
 // x[r] += sum_{s<S} part[s][r][:] (part may be null);  capture (may be null) gets x;  if gain != null,
 // h = x * rsqrt(mean(x^2)+eps) * gain written as fp32 row-major (kF32) or bf16 fragment-major (kBF16).
@@ -137,10 +139,13 @@ inline bool sample_is_truncated(int V, int top_k, float top_p) {
 }
 void launch_sample(hipStream_t s, const float* logits, int M, int V, const RowMeta* rows, int pos_offset,
                    const int32_t* forced, float temperature, uint64_t seed, float* part, float* forced_z,
-                   int32_t* out_tokens, float* out_logprobs, int top_k = 0, float top_p = 0.f, void* cut_buf = nullptr);
+                   int32_t* out_tokens, float* out_logprobs, int top_k = 0, float top_p = 0.f, void* cut_buf = nullptr,
+                   int32_t* last_tok = nullptr);
 // Second stage alone, over the [M][n_tiles][8] partials the sampling epilogue of the bf16 projection left.
+// last_tok (may be null): [max_seqs] table that also receives each row's token at index rows[r].seq (both samplers).
 void launch_sample_merge(hipStream_t s, const float* part, int n_tiles, int M, int V, const int32_t* forced,
-                         const float* forced_z, float temperature, int32_t* out_tokens, float* out_logprobs);
+                         const float* forced_z, float temperature, int32_t* out_tokens, float* out_logprobs,
+                         const RowMeta* rows = nullptr, int32_t* last_tok = nullptr);
 
 // out[idx[i]] = src[i] for idx[i] >= 0.
 void launch_scatter_f32(hipStream_t s, const float* src, const int32_t* idx, float* out, int n);

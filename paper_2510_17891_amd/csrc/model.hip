@@ -9,6 +9,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <chrono>
 #include <cmath>
 #include <string>
 #include <vector>
@@ -51,7 +52,7 @@ constexpr int T_MAX_SCORE = 4096;  // sequences per scoring call
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 struct Layout {
-  size_t block_table, rope, ring, x, x_last, h, part, q, attn_part, o, a, logits, samp_part, forced_z, tmp_tok, tmp_lp, cuts, total;
+  size_t block_table, rope, ring, x, x_last, h, part, q, attn_part, o, a, logits, samp_part, forced_z, tmp_tok, tmp_lp, cuts, last_tok, total;
   size_t slot_bytes, slot_upd, slot_tok, slot_skip, slot_sets;
   int max_segs, n_tiles;
 };
@@ -127,6 +128,7 @@ void compute_layout(const rl_model_config& c, Layout* L) {
   L->tmp_tok = take(R * 4);
   L->tmp_lp = take(R * 4);
   L->cuts = take(V ? R * sample_cut_bytes_per_row() : 256);
+  L->last_tok = take((size_t)c.max_seqs * 4);  // per sequence id: the token its last prefill / decode call returned
   L->total = off;
 }
 
@@ -162,6 +164,9 @@ struct rl_model {
   std::vector<Pending> pending;
   double prof_ms[K_COUNT];
   int64_t prof_n[K_COUNT];
+  // host time of rl_decode_step since the last read: admission checks, metadata build + upload, kernel launches
+  double host_us[3] = {0.0, 0.0, 0.0};
+  int64_t host_calls = 0;
 
   template <typename T> T* wsp(size_t off) const { return reinterpret_cast<T*>(ws + off); }
   void* k_pool(int l) const { return kv_pool + (size_t)l * layer_kv_bytes; }
@@ -275,6 +280,7 @@ int run_layers(rl_model* m, hipStream_t st, int M, const RowMeta* rows, int max_
 void run_head(rl_model* m, hipStream_t st, int M, float* xbuf, int pend, const RowMeta* rows, int pos_offset,
               const int32_t* forced, const rl_sampling* sp, int32_t* out_tokens, float* out_lp, float* debug_logits,
               bool score_only = false) {
+  int32_t* last_tok = score_only ? nullptr : m->wsp<int32_t>(m->lay.last_tok);
   const Geometry& g = m->geo;
   void* h = m->wsp<void>(m->lay.h);
   float* part = m->wsp<float>(m->lay.part);
@@ -297,7 +303,7 @@ void run_head(rl_model* m, hipStream_t st, int M, float* xbuf, int pend, const R
     { Timer t(m, st, K_LMHEAD);
       launch_gemm_bf16(st, h, m->lm_head, nullptr, M, g.vocab, g.hidden, kEpiSample, false, &se); }
     { Timer t(m, st, K_SAMPLE);
-      launch_sample_merge(st, spart, g.vocab >> 6, M, g.vocab, forced, fz, sp->temperature, out_tokens, out_lp); }
+      launch_sample_merge(st, spart, g.vocab >> 6, M, g.vocab, forced, fz, sp->temperature, out_tokens, out_lp, rows, last_tok); }
   } else {
     // logits to memory (a truncated distribution needs the whole row first), then the stand-alone sampler
     { Timer t(m, st, K_LMHEAD);
@@ -305,7 +311,7 @@ void run_head(rl_model* m, hipStream_t st, int M, float* xbuf, int pend, const R
       else launch_gemm_f32(st, (const float*)h, (const float*)m->lm_head, logits, M, g.vocab, g.hidden, kEpiPartial); }
     { Timer t(m, st, K_SAMPLE);
       launch_sample(st, logits, M, g.vocab, rows, pos_offset, forced, sp->temperature, sp->seed, spart, fz, out_tokens, out_lp,
-                    truncated ? top_k : 0, truncated ? sp->top_p : 0.f, m->wsp<void>(m->lay.cuts)); }
+                    truncated ? top_k : 0, truncated ? sp->top_p : 0.f, m->wsp<void>(m->lay.cuts), last_tok); }
     if (debug_logits)
       (void)hipMemcpyAsync(debug_logits, logits, (size_t)M * g.vocab * 4, hipMemcpyDeviceToDevice, st);
   }
@@ -397,13 +403,22 @@ rl_status upload_decode_meta(rl_model* m, hipStream_t st, int32_t n, const int32
     }
   }
   Timer t(m, st, K_META);
-  HIP_TRY(hipMemcpyAsync(ds, hs, (size_t)n * sizeof(RowMeta), hipMemcpyHostToDevice, st));
-  { rl_status rs = upload_attn_plan(m, st, hs, ds, n, plan, sa);
-    if (rs != RL_OK) return rs; }
-  if (!grants.empty()) {
-    HIP_TRY(hipMemcpyAsync(ds + m->lay.slot_upd, hu, grants.size() * 12, hipMemcpyHostToDevice, st));
-    launch_table_update(st, m->wsp<int32_t>(m->lay.block_table), m->geo.max_blocks, (const int32_t*)(ds + m->lay.slot_upd), (int)grants.size());
+  // One upload for everything the step needs: the slot's regions lie at fixed offsets, so the copy runs from the rows
+  // to the end of the last region in use (a few KB; what lies between is not read).
+  size_t used = (size_t)n * sizeof(RowMeta);
+  if (!grants.empty()) used = m->lay.slot_upd + grants.size() * 12;
+  if (!plan.sets.empty()) {
+    memcpy(hs + m->lay.slot_skip, plan.skip.data(), (size_t)n * 4);
+    memcpy(hs + m->lay.slot_sets, plan.sets.data(), plan.sets.size() * sizeof(AttnShared));
+    used = m->lay.slot_sets + plan.sets.size() * sizeof(AttnShared);
+    sa->skip = (const int32_t*)(ds + m->lay.slot_skip);
+    sa->sets = (const AttnShared*)(ds + m->lay.slot_sets);
+    sa->n_sets = (int)plan.sets.size();
+    sa->max_segs = plan.max_shared_segs;
   }
+  HIP_TRY(hipMemcpyAsync(ds, hs, used, hipMemcpyHostToDevice, st));
+  if (!grants.empty())
+    launch_table_update(st, m->wsp<int32_t>(m->lay.block_table), m->geo.max_blocks, (const int32_t*)(ds + m->lay.slot_upd), (int)grants.size());
   HIP_TRY(hipEventRecord(m->ring_ev[slot], st));
   m->ring_used[slot] = true;
   *rows_dev = (const RowMeta*)ds;
@@ -566,24 +581,40 @@ rl_status rl_set_capture(rl_model* m, float* buf) {
 rl_status rl_decode_step(rl_model* m, void* stream, int32_t n, const int32_t* seq_ids, const int32_t* in_tokens,
                          const int32_t* forced_next, const rl_sampling* sp, int32_t* out_tokens, float* out_logprobs,
                          float* debug_logits) {
-  if (!m || !in_tokens || !sp || !out_tokens || !out_logprobs) return fail(RL_ERR_INVALID_ARG, "NULL argument");
+  if (!m || !sp || !out_tokens || !out_logprobs) return fail(RL_ERR_INVALID_ARG, "NULL argument");
   if (m->geo.vocab == 0) return fail(RL_ERR_UNSUPPORTED, "model has no vocabulary");
   hipStream_t st = (hipStream_t)stream;
+  const auto t0 = std::chrono::steady_clock::now();
   std::vector<PageGrant> grants;
   rl_status rs = admit_decode(m, n, seq_ids, &grants);
   if (rs != RL_OK) return rs;
+  const auto t1 = std::chrono::steady_clock::now();
   const RowMeta* rows;
   int max_ctx_in_batch;
   SharedAttn sa;
   rs = upload_decode_meta(m, st, n, seq_ids, grants, &rows, &max_ctx_in_batch, &sa);
   if (rs != RL_OK) return rs;
+  const auto t2 = std::chrono::steady_clock::now();
   float* x = m->wsp<float>(m->lay.x);
   { Timer t(m, st, K_EMBED);
-    launch_embed(st, m->geo.dtype, m->embed, in_tokens, x, n, m->geo.hidden, m->geo.vocab); }
+    launch_embed(st, m->geo.dtype, m->embed, in_tokens, x, n, m->geo.hidden, m->geo.vocab, rows, m->wsp<int32_t>(m->lay.last_tok)); }
   int pend = run_layers(m, st, n, rows, max_ctx_in_batch, sa, true);
   run_head(m, st, n, x, pend, rows, 1, forced_next, sp, out_tokens, out_logprobs, debug_logits);
   HIP_TRY(hipGetLastError());
   for (int i = 0; i < n; ++i) m->table->set_len(seq_ids[i], m->table->len(seq_ids[i]) + 1);
+  const auto t3 = std::chrono::steady_clock::now();
+  m->host_us[0] += std::chrono::duration<double, std::micro>(t1 - t0).count();
+  m->host_us[1] += std::chrono::duration<double, std::micro>(t2 - t1).count();
+  m->host_us[2] += std::chrono::duration<double, std::micro>(t3 - t2).count();
+  m->host_calls += 1;
+  return RL_OK;
+}
+
+rl_status rl_profile_host_read(rl_model* m, double* admit_us, double* meta_us, double* launch_us, int64_t* calls) {
+  if (!m || !admit_us || !meta_us || !launch_us || !calls) return fail(RL_ERR_INVALID_ARG, "NULL argument");
+  *admit_us = m->host_us[0]; *meta_us = m->host_us[1]; *launch_us = m->host_us[2]; *calls = m->host_calls;
+  m->host_us[0] = m->host_us[1] = m->host_us[2] = 0.0;
+  m->host_calls = 0;
   return RL_OK;
 }
 

@@ -71,7 +71,8 @@ __global__ __launch_bounds__(256) void sample_stage1_kernel(const float* __restr
 __global__ __launch_bounds__(1024) void sample_stage2_kernel(const float* __restrict__ part, int n_tiles, int V,
                                                              const int32_t* __restrict__ forced,
                                                              const float* __restrict__ forced_z, float inv_t,
-                                                             int32_t* __restrict__ out_tok, float* __restrict__ out_lp) {
+                                                             int32_t* __restrict__ out_tok, float* __restrict__ out_lp,
+                                                             const RowMeta* __restrict__ rows, int32_t* __restrict__ last_tok) {
   __shared__ float sh_y[16], sh_z[16], sh_m[16], sh_s[16];
   __shared__ int sh_i[16];
   const int r = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -100,6 +101,7 @@ __global__ __launch_bounds__(1024) void sample_stage2_kernel(const float* __rest
     float zt = best.z;
     if (forced != nullptr && forced[r] >= 0 && forced[r] < V) { tok = forced[r]; zt = forced_z[r]; }
     out_tok[r] = tok;
+    if (last_tok != nullptr) last_tok[rows[r].seq] = tok;  // what the sequence is fed next when the caller passes no tokens
     out_lp[r] = zt * inv_t - (m + logf(s));
   }
 }
@@ -363,7 +365,7 @@ size_t sample_cut_bytes_per_row() { return sizeof(CutRow) + 2 * sizeof(OrderCut)
 
 void launch_sample(hipStream_t st, const float* logits, int M, int V, const RowMeta* rows, int pos_offset,
                    const int32_t* forced, float temperature, uint64_t seed, float* part, float* forced_z,
-                   int32_t* out_tokens, float* out_logprobs, int top_k, float top_p, void* cut_buf) {
+                   int32_t* out_tokens, float* out_logprobs, int top_k, float top_p, void* cut_buf, int32_t* last_tok) {
   const int n_tiles = (V + kSampleTile - 1) / kSampleTile;
   const int greedy = !(temperature > 0.f);
   const float inv_t = greedy ? 1.0f : 1.0f / temperature;
@@ -397,13 +399,14 @@ void launch_sample(hipStream_t st, const float* logits, int M, int V, const RowM
   }
   sample_stage1_kernel<<<grid, 256, 0, st>>>(logits, V, rows, pos_offset, inv_t, greedy, (uint32_t)(seed & 0xffffffffu),
                                              (uint32_t)(seed >> 32), forced, forced_z, part, n_tiles, cuts);
-  sample_stage2_kernel<<<M, 1024, 0, st>>>(part, n_tiles, V, forced, forced_z, inv_t, out_tokens, out_logprobs);
+  sample_stage2_kernel<<<M, 1024, 0, st>>>(part, n_tiles, V, forced, forced_z, inv_t, out_tokens, out_logprobs, rows, last_tok);
 }
 
 void launch_sample_merge(hipStream_t st, const float* part, int n_tiles, int M, int V, const int32_t* forced,
-                         const float* forced_z, float temperature, int32_t* out_tokens, float* out_logprobs) {
+                         const float* forced_z, float temperature, int32_t* out_tokens, float* out_logprobs,
+                         const RowMeta* rows, int32_t* last_tok) {
   const float inv_t = temperature > 0.f ? 1.0f / temperature : 1.0f;
-  sample_stage2_kernel<<<M, 1024, 0, st>>>(part, n_tiles, V, forced, forced_z, inv_t, out_tokens, out_logprobs);
+  sample_stage2_kernel<<<M, 1024, 0, st>>>(part, n_tiles, V, forced, forced_z, inv_t, out_tokens, out_logprobs, rows, last_tok);
 }
 
 }  // namespace rl

@@ -11,18 +11,21 @@ namespace rl {
 // ------------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ tok,
-                                                    float* __restrict__ x, int H, int V) {
+                                                    float* __restrict__ x, int H, int V, const RowMeta* __restrict__ rows,
+                                                    const int32_t* __restrict__ last_tok) {
   const int r = blockIdx.x;
-  const int t = min(max(tok[r], 0), V - 1);  // ids come from device memory the host cannot inspect
+  const int fed = tok != nullptr ? tok[r] : last_tok[rows[r].seq];
+  const int t = min(max(fed, 0), V - 1);  // ids come from device memory the host cannot inspect
   const size_t base = (size_t)t * H;
   for (int i = threadIdx.x; i < H; i += 256) x[(size_t)r * H + i] = load_as_float(E, base + i);
 }
 
-void launch_embed(hipStream_t s, int dtype, const void* embed, const int32_t* tokens, float* x, int M, int H, int V) {
+void launch_embed(hipStream_t s, int dtype, const void* embed, const int32_t* tokens, float* x, int M, int H, int V,
+                  const RowMeta* rows, const int32_t* last_tok) {
   if (dtype == kBF16)
-    embed_kernel<uint16_t><<<M, 256, 0, s>>>((const uint16_t*)embed, tokens, x, H, V);
+    embed_kernel<uint16_t><<<M, 256, 0, s>>>((const uint16_t*)embed, tokens, x, H, V, rows, last_tok);
   else
-    embed_kernel<float><<<M, 256, 0, s>>>((const float*)embed, tokens, x, H, V);
+    embed_kernel<float><<<M, 256, 0, s>>>((const float*)embed, tokens, x, H, V, rows, last_tok);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -35,7 +35,8 @@ def generate_groups(ro, prompts, group_size, max_new_tokens, temperature=1.0, se
     prompts         list of token-id lists
     max_new_tokens  int, or one int per sequence (len(prompts) * group_size, group-major): the length limit of
                     Appendix D, or pre-drawn lengths for synthetic workloads
-    eos_id          stop a sequence after it samples this id (costs one small device-to-host copy per step)
+    eos_id          stop a sequence after it samples this id (checked one call behind, from an asynchronous copy of the
+                    sampled ids: nothing waits for the GPU inside the loop)
     on_step         optional callback(step_index, n_active) for progress reporting
 
     Returns (tokens, logprobs): per sequence a list of ids and a list of floats, group-major.
@@ -58,21 +59,16 @@ def generate_groups(ro, prompts, group_size, max_new_tokens, temperature=1.0, se
     members_left = {}                  # group -> sequences still running
     active = []                        # sequence ids in batch order
     count = [0] * n_seq                # tokens generated so far
-    where = {}                         # sequence id -> (device row tensor, column) of its latest token
     rows_t, rows_lp, rows_ids = [], [], []   # per call: device outputs and the ids they belong to
+    # End-token checks run one call behind: the tokens of a call are copied to pinned host memory without waiting, and
+    # read when the next call has been enqueued.  A sequence that drew the end token therefore takes one step more than
+    # it needs (inside its page reservation: it was below its limit); the surplus tokens are dropped at the end.
+    pending = []                       # (ids, pinned host tokens, event)
+    spare = []                         # pinned buffers and events to use again
     step = 0
 
     def admit():
-        """Prefill waiting groups while the pool can hold them; members that are already done leave at once."""
-        nonlocal next_group, reserved
-        first = len(rows_ids)
-        admit_more()
-        done = []
-        for ids, tok in zip(rows_ids[first:], rows_t[first:]):
-            done += check_finished(ids, tok)
-        retire(done)
-
-    def admit_more():
+        """Prefill waiting groups while the pool can hold them."""
         nonlocal next_group, reserved
         while next_group < len(prompts):
             g = next_group
@@ -84,68 +80,69 @@ def generate_groups(ro, prompts, group_size, max_new_tokens, temperature=1.0, se
             tok, lp = ro.rl_prefill_groups(ids, G, [prompts[g]], temperature, seed, top_k=top_k, top_p=top_p)
             reserved += need[g]
             next_group += 1
-            rows_t.append(tok)
-            rows_lp.append(lp)
-            rows_ids.append(ids)
+            record(ids, tok, lp)
             members_left[g] = G
-            for c, s in enumerate(ids):
-                count[s] = 1
-                where[s] = (tok, c)
-                active.append(s)
+            active.extend(ids)
+
+    def record(ids, tok, lp):
+        rows_t.append(tok)
+        rows_lp.append(lp)
+        rows_ids.append(list(ids))
+        for s in ids:
+            count[s] += 1
+        if eos_id is not None:
+            buf, ev = spare.pop() if spare else (torch.empty(max_rows, dtype=torch.int32, pin_memory=True), torch.cuda.Event())
+            buf[:len(ids)].copy_(tok, non_blocking=True)
+            ev.record()
+            pending.append((list(ids), buf, ev))
 
     def retire(finished):
         nonlocal reserved
+        finished = [s for s in dict.fromkeys(finished) if s in running]
         if not finished:
             return
         ro.rl_free_seqs(finished)
         gone = set(finished)
+        running.difference_update(gone)
         active[:] = [s for s in active if s not in gone]
         for s in finished:
-            where.pop(s)
             g = s // G
             members_left[g] -= 1
             if members_left[g] == 0:   # the reservation covers the group's shared pages until its last member leaves
                 reserved -= need[g]
                 del members_left[g]
 
-    def check_finished(ids, tok_row):
-        host = tok_row.cpu().tolist() if eos_id is not None else None
+    def at_limit(ids):
+        return [s for s in ids if count[s] >= limits[s]]
+
+    def drew_end_token(keep_last):
+        """Sequences whose end token has arrived on the host; the newest `keep_last` copies stay in flight."""
         done = []
-        for c, s in enumerate(ids):
-            if count[s] >= limits[s] or (host is not None and host[c] == eos_id):
-                done.append(s)
+        while len(pending) > keep_last:
+            ids, buf, ev = pending.pop(0)
+            ev.synchronize()
+            done += [s for s, t in zip(ids, buf[:len(ids)].tolist()) if t == eos_id]
+            spare.append((buf, ev))
         return done
 
+    running = set()
     while active or next_group < len(prompts):
+        first = len(active)
         admit()
+        running.update(active[first:])
+        retire(at_limit(active[first:]))      # an output of one token ends with its prefill
         if not active:
+            retire(drew_end_token(0))
             continue
         for b0 in range(0, len(active), max_rows):
             ids = active[b0:b0 + max_rows]
-            # the token each sequence sampled last is what it is fed now
-            src = [where[s] for s in ids]
-            if all(t is src[0][0] for t, _ in src) and [c for _, c in src] == list(range(len(ids))) \
-                    and src[0][0].numel() == len(ids):
-                feed = src[0][0]                          # same batch as the call that produced it
-            else:                                         # the batch changed: one gather over the rows involved
-                base, parts, index = {}, [], []
-                for t, c in src:
-                    if id(t) not in base:
-                        base[id(t)] = sum(p.numel() for p in parts)
-                        parts.append(t)
-                    index.append(base[id(t)] + c)
-                feed = torch.cat(parts)[torch.tensor(index, device=dev)]
-            tok, lp = ro.rl_decode_step(ids, feed, temperature, seed, top_k=top_k, top_p=top_p)
-            rows_t.append(tok)
-            rows_lp.append(lp)
-            rows_ids.append(list(ids))
-            for c, s in enumerate(ids):
-                count[s] += 1
-                where[s] = (tok, c)
+            # in_tokens = None: the library feeds every sequence the token it returned for it last
+            tok, lp = ro.rl_decode_step(ids, None, temperature, seed, top_k=top_k, top_p=top_p)
+            record(ids, tok, lp)
         n_calls = (len(active) + max_rows - 1) // max_rows
-        finished = []
-        for ids, tok in zip(rows_ids[-n_calls:], rows_t[-n_calls:]):
-            finished += check_finished(ids, tok)
+        finished = at_limit(active)
+        if eos_id is not None:
+            finished += drew_end_token(n_calls)   # everything but the calls just enqueued
         retire(finished)
         step += 1
         if on_step is not None:
