@@ -68,6 +68,8 @@ def parse():
     ap.add_argument("--ctx-mid", type=int, default=9216,
                     help="wave workload: tokens of context per sequence when the timed region starts")
     ap.add_argument("--wave-prompts", type=int, default=16, help="wave workload: resident prompts (x 8 samples each)")
+    ap.add_argument("--kv-fp8", action="store_true",
+                    help="wave / full workloads: cache keys and values as fp8 (opt-in performance variant, not the headline)")
     ap.add_argument("--no-small-batch", action="store_true",
                     help="wave workload: skip the 32-sequence comparison run")
     ap.add_argument("--length-scale", type=float, default=1.0,
@@ -102,7 +104,7 @@ def parse():
     return args
 
 
-def kernel_bytes(shape, M, ctx_sum, bf=2):
+def kernel_bytes(shape, M, ctx_sum, bf=2, kv_bytes=2):
     """Algorithmic HBM bytes of one launch of each kernel class at batch M.  ctx_sum: cached tokens the step must
     read, summed over the batch, pages that several sequences hold in common counted once."""
     H, d, F, V = shape["hidden"], shape["head_dim"], shape["ffn"], shape["vocab"]
@@ -115,7 +117,7 @@ def kernel_bytes(shape, M, ctx_sum, bf=2):
         "gemm_down": H * F * bf + M * F * bf + M * H * 4,
         "gemm_lm_head": V * H * bf + M * H * bf + M * V * 4,
         # K/V pages, the QKV projection's output (summed, rotated and appended inside the kernel), the bf16 output
-        "attn_decode": ctx_sum * nkv * 2 * d * bf + M * nqkv * 4 + M * nqd * bf + M * 2 * nkv * d * bf,
+        "attn_decode": ctx_sum * nkv * 2 * d * kv_bytes + M * nqkv * 4 + M * nqd * bf + M * 2 * nkv * d * kv_bytes,
     }
 
 
@@ -198,7 +200,8 @@ def run_wave(args):
     pages = n_prompts * (P // 16 + G * ((ctx_mid + n_steps + 15) // 16 - P // 16)) + 64
     t_setup = time.perf_counter()
     w = ri.make_weights(shape, seed, device=dev, dtype=torch.bfloat16)
-    ro = Rollout(shape, w, max_seqs=B, max_ctx=max_ctx, max_rows=256, kv_pages=pages, consume_weights=True)
+    ro = Rollout(shape, w, max_seqs=B, max_ctx=max_ctx, max_rows=256, kv_pages=pages, consume_weights=True,
+                 kv_fp8=args.kv_fp8)
     del w
     torch.cuda.empty_cache()
     prompts = ri.tokens((n_prompts, P), shape["vocab"], seed, 960)
@@ -252,19 +255,21 @@ def run_wave(args):
     def ctx_sum(ctx, once):
         return int((n_prompts if once else B) * shared_tok + B * (ctx - shared_tok))
 
-    kb_once = kernel_bytes(shape, B, ctx_sum(ctx_avg, True))
-    kb_each = kernel_bytes(shape, B, ctx_sum(ctx_avg, False))
+    kvb = 1 if args.kv_fp8 else 2
+    kb_once = kernel_bytes(shape, B, ctx_sum(ctx_avg, True), kv_bytes=kvb)
+    kb_each = kernel_bytes(shape, B, ctx_sum(ctx_avg, False), kv_bytes=kvb)
     out = {
         "metric": "generated tokens/s (8B-shaped bf16 decode) + % peak HBM GB/s, 1 MI355X",
         "value": B * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"full8b_36L_bf16_wave_{B}seq_prompt{P}_ctx{ctx_mid}_T1.0", "batch": B, "groups": n_prompts,
+        "config": {"workload": f"full8b_36L_bf16_wave_{B}seq_prompt{P}_ctx{ctx_mid}_T1.0" + ("_kvfp8" if args.kv_fp8 else ""),
+                   "batch": B, "groups": n_prompts,
                    "group_size": G, "context_first_timed_step": ctx_first, "context_last_timed_step": ctx_last,
                    "kv_block": 16, "temperature": 1.0, "logprob_per_token": True, "shared_prompt_tokens": shared_tok,
                    "prefill": f"{n_prompts} prompts x {P} tokens run once each, pages shared by the {G} samples of a prompt",
                    "private_context": f"{private} tokens per sequence of appended N(0,1) keys and values",
-                   "kv_pool_GB": pages * rl_page_bytes(shape) / 1e9},
+                   "kv_pool_GB": pages * rl_page_bytes(shape) * kvb / 2 / 1e9},
         # step-level fractions: per-sequence byte formula (weights once + 4096 B per cached token, layer and sequence),
         # and the smaller figure with the prompt pages that 8 samples hold in common counted once
         "step_algorithmic_GB": step_bytes_of(shape, kb_each) / 1e9,
@@ -311,8 +316,8 @@ def run_wave(args):
                  "context_last_timed_step": P2 + args.warmup + args.steps, "prefill_s": prefill2_s}
         c2 = P2 + args.warmup + 0.5 * (args.steps + 1)
         sh2 = P2 // 16 * 16
-        kb2 = kernel_bytes(shape, B2, int(n2 * sh2 + B2 * (c2 - sh2)))
-        kb2_each = kernel_bytes(shape, B2, int(B2 * c2))
+        kb2 = kernel_bytes(shape, B2, int(n2 * sh2 + B2 * (c2 - sh2)), kv_bytes=kvb)
+        kb2_each = kernel_bytes(shape, B2, int(B2 * c2), kv_bytes=kvb)
         small["step_hbm_fraction"] = step_bytes_of(shape, kb2_each) / (el2 / args.steps) / (HBM_PEAK_GBS * 1e9)
         small["step_hbm_fraction_shared_pages_once"] = step_bytes_of(shape, kb2) / (el2 / args.steps) / (HBM_PEAK_GBS * 1e9)
         if not args.no_profile:

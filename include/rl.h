@@ -78,6 +78,16 @@ typedef enum {
 
 typedef enum { RL_F32 = 0, RL_BF16 = 1 } rl_dtype;
 
+/*
+ * How keys and values are cached.  RL_KV_SAME: in the model's dtype.  RL_KV_FP8 (bf16 models only): one byte per
+ * element, e4m3 as the matrix cores of the device encode it (nearest even, no scales, magnitudes above 448 end at
+ * 448): half the bytes per cached token, which is what a decode step at long contexts mostly reads.  A performance
+ * option outside the default path: the cached values then carry 4 significant bits, and results agree with the
+ * unrounded definition only to about that (see the design notes for the tolerance).  rl_seq_import_kv still takes
+ * bf16 arrays and rounds them.
+ */
+typedef enum { RL_KV_SAME = 0, RL_KV_FP8 = 2 } rl_kv_dtype;
+
 typedef struct {
   uint32_t struct_size; /* sizeof(rl_model_config), checked */
   uint32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab; /* vocab % 4 == 0, < 2^22; 0: no head */
@@ -88,6 +98,8 @@ typedef struct {
   uint32_t max_seqs; /* ids are in [0, max_seqs) */
   uint32_t max_ctx;  /* longest prompt + response, multiple of kv_block; bf16: at most 65536 */
   uint32_t max_rows; /* most sequences per decode call (<= 256); prefill is chunked to this internally */
+  uint32_t kv_dtype; /* rl_kv_dtype */
+  uint32_t reserved; /* 0 */
   uint64_t kv_pool_bytes;   /* size of rl_weights.kv_pool */
   uint64_t workspace_bytes; /* size of rl_weights.workspace, >= rl_query_workspace() */
 } rl_model_config;

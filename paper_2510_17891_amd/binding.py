@@ -16,6 +16,7 @@ RL_OK = 0
 RL_ERR_INVALID_ARG, RL_ERR_KV_FULL, RL_ERR_BAD_SEQ = -1, -2, -3
 RL_ERR_CTX_OVERFLOW, RL_ERR_DEVICE, RL_ERR_UNSUPPORTED = -4, -5, -6
 RL_F32, RL_BF16 = 0, 1
+RL_KV_SAME, RL_KV_FP8 = 0, 2
 
 EXPORTS = [
     "rl_kv_page_bytes", "rl_query_workspace", "rl_init_model", "rl_destroy_model", "rl_prefill", "rl_prefill_groups", "rl_score", "rl_hrd_objective",
@@ -31,7 +32,8 @@ class rl_model_config(C.Structure):
                 ("ffn", C.c_uint32), ("vocab", C.c_uint32), ("rms_eps", C.c_float),
                 ("rope_base", C.c_float), ("qk_norm", C.c_uint32), ("dtype", C.c_uint32),
                 ("kv_block", C.c_uint32), ("max_seqs", C.c_uint32), ("max_ctx", C.c_uint32),
-                ("max_rows", C.c_uint32), ("kv_pool_bytes", C.c_uint64), ("workspace_bytes", C.c_uint64)]
+                ("max_rows", C.c_uint32), ("kv_dtype", C.c_uint32), ("reserved", C.c_uint32),
+                ("kv_pool_bytes", C.c_uint64), ("workspace_bytes", C.c_uint64)]
 
 
 _pp = C.POINTER(C.c_void_p)
@@ -127,7 +129,7 @@ def _ptr(t):
     return C.c_void_p(t.data_ptr()) if t is not None else None
 
 
-def make_config(shape, dtype, max_seqs, max_ctx, max_rows, kv_pool_bytes=0, workspace_bytes=0):
+def make_config(shape, dtype, max_seqs, max_ctx, max_rows, kv_pool_bytes=0, workspace_bytes=0, kv_dtype=RL_KV_SAME):
     """rl_model_config from a shape dict (keys as in rollout_inputs.SHAPES)."""
     c = rl_model_config()
     c.struct_size = C.sizeof(rl_model_config)
@@ -138,6 +140,7 @@ def make_config(shape, dtype, max_seqs, max_ctx, max_rows, kv_pool_bytes=0, work
     c.dtype = dtype
     c.kv_block = 16
     c.max_seqs, c.max_ctx, c.max_rows = max_seqs, max_ctx, max_rows
+    c.kv_dtype, c.reserved = kv_dtype, 0
     c.kv_pool_bytes, c.workspace_bytes = kv_pool_bytes, workspace_bytes
     return c
 
@@ -189,16 +192,17 @@ class Rollout:
     """
 
     def __init__(self, shape, weights, max_seqs, max_ctx, max_rows, kv_pages, device="cuda:0", consume_weights=False,
-                 kv_slack_bytes=2 << 30):
+                 kv_slack_bytes=2 << 30, kv_fp8=False):
         """kv_pages: pages in the KV pool, or None for as many as the card holds once the packed weights and the
         workspace are placed (less kv_slack_bytes).  consume_weights: the entries of `weights` are removed as they are
-        packed, so that a model of 16 GB does not exist twice on the card at any time."""
+        packed, so that a model of 16 GB does not exist twice on the card at any time.  kv_fp8: cache keys and values as
+        fp8 (bf16 models only; a performance option, see rl.h)."""
         L = lib()
         self.shape = dict(shape)
         self.device = torch.device(device)
         self.tdtype = weights["final_norm"].dtype
         self.dtype = RL_BF16 if self.tdtype == torch.bfloat16 else RL_F32
-        cfg = make_config(shape, self.dtype, max_seqs, max_ctx, max_rows)
+        cfg = make_config(shape, self.dtype, max_seqs, max_ctx, max_rows, kv_dtype=RL_KV_FP8 if kv_fp8 else RL_KV_SAME)
         page = L.rl_kv_page_bytes(C.byref(cfg))
         if page == 0:
             raise RLError(RL_ERR_UNSUPPORTED, L.rl_last_error().decode())

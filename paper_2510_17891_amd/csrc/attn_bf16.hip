@@ -40,6 +40,7 @@
 // is the wave that owns the row's last 32-key step; it gets them from LDS into its operand registers and stores
 // them to the page when its work is done, so no wave ever waits for those (small, scattered) stores.
 #include <algorithm>
+#include <type_traits>
 
 #include "device_utils.h"
 #include "kernels.h"
@@ -56,6 +57,8 @@ constexpr int kD = 128;
 constexpr int kPageElems = kPageTokens * kD;  // 2048 bf16 = 4 KiB per (page, kv head), K or V
 constexpr int kPartStride = kD + 2;           // floats per (row, head, segment): O[128], max, sum
 constexpr int kLdsSegs = 16;                  // contexts up to 4096 keep their segment partials in LDS
+
+constexpr int kPairU4(bool kv8) { return kv8 ? 2 * kPageElems / 16 : 2 * kPageElems / 8; }  // 16-byte units of one (page, kv head): K and V
 
 template <bool WRITTEN> struct PoolPtr { typedef const u32x4_t* __restrict__ type; };
 template <> struct PoolPtr<true> { typedef const u32x4_t* type; };
@@ -80,6 +83,61 @@ __device__ __forceinline__ void load_pair(PagePair& pp, const u32x4_t* kbase, co
     pp.v[0][s] = __builtin_nontemporal_load(vbase + oa + s * 64);
     pp.v[1][s] = __builtin_nontemporal_load(vbase + ob + s * 64);
   }
+}
+
+// The same 32 keys from fp8 pages, as loaded: half the registers; widened to a PagePair when the step consumes them.
+struct PagePair8 {
+  u32x4_t k[2][2];  // [page a|b][c]: this lane's key, dims 64c + 16g .. +15 (two matrix-core steps of 8 dims)
+  u32x4_t v[2][2];  // [page a|b][J]: word 2*(jj&1) + par = this lane's 4 keys of dim 32jj + 16par + dl, jj = 2J + (jj&1)
+};
+
+__device__ __forceinline__ void load_pair(PagePair8& pp, const u32x4_t* kbase, const u32x4_t* vbase, int64_t page_a,
+                                          int64_t page_b, int n_kv, int lane) {
+  const size_t oa = (size_t)page_a * n_kv * kPairU4(true) + lane;
+  const size_t ob = (size_t)page_b * n_kv * kPairU4(true) + lane;
+#pragma unroll
+  for (int c = 0; c < 2; ++c) {
+    pp.k[0][c] = __builtin_nontemporal_load(kbase + oa + c * 64);
+    pp.k[1][c] = __builtin_nontemporal_load(kbase + ob + c * 64);
+  }
+#pragma unroll
+  for (int c = 0; c < 2; ++c) {
+    pp.v[0][c] = __builtin_nontemporal_load(vbase + oa + c * 64);
+    pp.v[1][c] = __builtin_nontemporal_load(vbase + ob + c * 64);
+  }
+}
+
+// Four fp8 (one word) -> four bf16 (two words); exact, every e4m3 value is a bf16 value.
+__device__ __forceinline__ void fp8x4_to_bf16x4(uint32_t w, uint32_t& lo, uint32_t& hi) {
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
+  lo = (__float_as_uint(a[0]) >> 16) | (__float_as_uint(a[1]) & 0xffff0000u);
+  hi = (__float_as_uint(b[0]) >> 16) | (__float_as_uint(b[1]) & 0xffff0000u);
+}
+
+__device__ __forceinline__ void widen(PagePair& out, const PagePair8& in) {
+#pragma unroll
+  for (int p = 0; p < 2; ++p)
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {  // matrix-core step s = 2c + h: dims 64c + 16g + 8h .. +7
+        uint32_t w0, w1, w2, w3;
+        fp8x4_to_bf16x4(in.k[p][c][2 * h], w0, w1);
+        fp8x4_to_bf16x4(in.k[p][c][2 * h + 1], w2, w3);
+        out.k[p][2 * c + h] = (u32x4_t){w0, w1, w2, w3};
+      }
+#pragma unroll
+  for (int p = 0; p < 2; ++p)
+#pragma unroll
+    for (int J = 0; J < 2; ++J)
+#pragma unroll
+      for (int j2 = 0; j2 < 2; ++j2) {  // jj = 2J + j2: words (par 0: two, par 1: two) as in the bf16 page
+        uint32_t w0, w1, w2, w3;
+        fp8x4_to_bf16x4(in.v[p][J][2 * j2], w0, w1);
+        fp8x4_to_bf16x4(in.v[p][J][2 * j2 + 1], w2, w3);
+        out.v[p][2 * J + j2] = (u32x4_t){w0, w1, w2, w3};
+      }
 }
 
 __host__ __device__ inline int attn_num_splits(int n_seg) { return n_seg <= kLdsSegs ? 1 : (n_seg + kLdsSegs - 1) / kLdsSegs; }
@@ -144,7 +202,8 @@ struct AppendArgs {
 // APPEND: q is not read; every block forms the queries of its columns from the split sums, and the last wave of the
 // row block that holds a row's last segment forms the row's new key and value, uses them in its last step and then
 // writes them into their page.  The pools are therefore not declared read-only in that variant.
-template <bool APPEND>
+// KV8: the pages hold fp8 keys and values (widened to bf16 in registers; scores, softmax and products as for bf16 pages).
+template <bool APPEND, bool KV8>
 __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* __restrict__ q, const RowMeta* __restrict__ rows,
                                                                const int32_t* __restrict__ block_table, int max_blocks,
                                                                typename PoolPtr<APPEND>::type k_pool,
@@ -200,8 +259,8 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
   int seg = lo + (wave * (hi - lo)) / 4;  // contiguous, balanced share of the block's segments
   const int seg_end = lo + ((wave + 1) * (hi - lo)) / 4;
   const int it_begin = seg_begin(seg), it_end = seg_begin(seg_end);
-  const u32x4_t* kb = k_pool + (size_t)hk * (2 * kPageElems / 8);
-  const u32x4_t* vb = v_pool + (size_t)hk * (2 * kPageElems / 8);
+  const u32x4_t* kb = k_pool + (size_t)hk * kPairU4(KV8);
+  const u32x4_t* vb = v_pool + (size_t)hk * kPairU4(KV8);
   if (!APPEND) {
     for (int i = threadIdx.x; i <= n_blk; i += 256)  // entry n_blk duplicates the last page (odd page counts)
       pages[i] = block_table[(size_t)rm.seq * max_blocks + (i < n_blk ? i : n_blk - 1)];
@@ -290,10 +349,18 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
     if (appends) {  // the new key and value, rounded, wait in LDS for this wave's last step
       HeadPair hv;
       head_pair_sum(hv, lv, ap.S);
-      lds_new[lane] = (uint16_t)f2bf(hp[4].v0);
-      lds_new[lane + kD / 2] = (uint16_t)f2bf(hp[4].v1);
-      lds_new[kD + lane] = (uint16_t)f2bf(hv.v0);
-      lds_new[kD + lane + kD / 2] = (uint16_t)f2bf(hv.v1);
+      if (KV8) {  // as the bytes the page will hold: key [128], then value [128]
+        uint8_t* n8 = (uint8_t*)lds_new;
+        n8[lane] = (uint8_t)f2fp8(hp[4].v0);
+        n8[lane + kD / 2] = (uint8_t)f2fp8(hp[4].v1);
+        n8[kD + lane] = (uint8_t)f2fp8(hv.v0);
+        n8[kD + lane + kD / 2] = (uint8_t)f2fp8(hv.v1);
+      } else {
+        lds_new[lane] = (uint16_t)f2bf(hp[4].v0);
+        lds_new[lane + kD / 2] = (uint16_t)f2bf(hp[4].v1);
+        lds_new[kD + lane] = (uint16_t)f2bf(hv.v0);
+        lds_new[kD + lane + kD / 2] = (uint16_t)f2bf(hv.v1);
+      }
     }
     __syncthreads();  // pages[] and the queries are in LDS
   }
@@ -308,7 +375,9 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
 #pragma unroll
       for (int e = 0; e < 8; e += 2) {
         float x0 = 0.f, x1 = 0.f;
-        if (col_valid) { x0 = qh[32 * s + 8 * g + e]; x1 = qh[32 * s + 8 * g + e + 1]; }
+        // dims of matrix-core step s held by lane group g: as the K operand of the page layout has them
+        const int d0 = KV8 ? 64 * (s >> 1) + 16 * g + 8 * (s & 1) + e : 32 * s + 8 * g + e;
+        if (col_valid) { x0 = qh[d0]; x1 = qh[d0 + 1]; }
         const uint32_t h0 = f2bf(x0), h1 = f2bf(x1);
         hi16[e >> 1] = h0 | (h1 << 16);
         lo16[e >> 1] = pack2bf(x0 - bf2f(h0), x1 - bf2f(h1));
@@ -399,14 +468,54 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
       boundary = seg < seg_end ? seg_begin(seg + 1) : it_end;
     }
   };
-  auto fetch = [&](PagePair& pp, int it) __attribute__((always_inline)) {
+  typedef typename std::conditional<KV8, PagePair8, PagePair>::type Buf;  // registers of a step as loaded
+  auto fetch = [&](Buf& pp, int it) __attribute__((always_inline)) {
     load_pair(pp, kb, vb, pages[2 * it], pages[2 * it + 1], n_kv, lane);
+  };
+  auto consume = [&](const Buf& pp, int it) __attribute__((always_inline)) {
+    if constexpr (KV8) {
+      PagePair w;
+      widen(w, pp);
+      step(w, it);
+    } else {
+      step(pp, it);
+    }
   };
 
   // The appending wave's last step: the entries of the new token (key pos & 15 of page (pos >> 4) & 1 of the pair)
   // are replaced by the rounded new key and value; what memory holds there is stale.
-  auto patch_new = [&](PagePair& pp) __attribute__((always_inline)) {
+  auto patch_new = [&](Buf& buf) __attribute__((always_inline)) {
     const int t = rm.pos & 15, pg = (rm.pos >> 4) & 1;
+    if constexpr (KV8) {
+      const uint8_t* n8 = (const uint8_t*)lds_new;
+      // K: the lane whose key is t holds, per load c, the key's dims 64c + 16g .. +15: one 16-byte piece of the new key
+      const bool k_lane = (lane & 15) == t;
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const u32x4_t kn = *(const u32x4_t*)(n8 + 64 * c + 16 * g);
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) buf.k[p][c][e] = (k_lane && pg == p) ? kn[e] : buf.k[p][c][e];
+      }
+      // V: lanes of key group t >> 2 hold byte t & 3 of word 2*(jj&1) + par = dim 32jj + 16par + dl (dl = lane & 15)
+      const bool v_lane = g == (t >> 2);
+      const int sh = (t & 3) * 8;
+      const uint32_t keep = ~(0xffu << sh);
+#pragma unroll
+      for (int J = 0; J < 2; ++J)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const uint32_t vn = (uint32_t)n8[kD + 64 * J + 32 * (w >> 1) + 16 * (w & 1) + j] << sh;
+#pragma unroll
+          for (int p = 0; p < 2; ++p) {
+            const uint32_t old = buf.v[p][J][w];
+            buf.v[p][J][w] = (v_lane && pg == p) ? ((old & keep) | vn) : old;
+          }
+        }
+      return;
+    } else {
+    PagePair& pp = buf;
     // K operand: the lane whose row is key t holds 8 dims per step, one 16-byte piece of the new key
     const bool k_lane = (lane & 15) == t;
 #pragma unroll
@@ -436,10 +545,19 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
         }
       }
     }
+    }
   };
   // ... and its stores, once nothing of the wave's work is behind them
   auto store_new = [&]() __attribute__((always_inline)) {
     const int t = rm.pos & 15;
+    if constexpr (KV8) {
+      const uint8_t* n8 = (const uint8_t*)lds_new;
+      kv_store_fp8_bits((void*)k_pool, rm.page, hk, n_kv, t, lane, n8[lane], false);
+      kv_store_fp8_bits((void*)k_pool, rm.page, hk, n_kv, t, lane + kD / 2, n8[lane + kD / 2], false);
+      kv_store_fp8_bits((void*)v_pool, rm.page, hk, n_kv, t, lane, n8[kD + lane], true);
+      kv_store_fp8_bits((void*)v_pool, rm.page, hk, n_kv, t, lane + kD / 2, n8[kD + lane + kD / 2], true);
+      return;
+    }
     kv_store_bf16_bits((void*)k_pool, rm.page, hk, n_kv, t, lane, lds_new[lane], false);
     kv_store_bf16_bits((void*)k_pool, rm.page, hk, n_kv, t, lane + kD / 2, lds_new[lane + kD / 2], false);
     kv_store_bf16_bits((void*)v_pool, rm.page, hk, n_kv, t, lane, lds_new[kD + lane], true);
@@ -449,28 +567,28 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
   // Two register buffers, refilled unconditionally inside the loop so that the compiler's wait counts let the
   // other buffer's 16 loads stay in flight while one is consumed; the ragged end is peeled off below.
   if (it_begin < it_end) {
-    PagePair pa, pb;
+    Buf pa, pb;
     fetch(pa, it_begin);
     int it = it_begin;
     for (; it + 2 < it_end; it += 2) {
       fetch(pb, it + 1);
       __builtin_amdgcn_sched_barrier(0);
-      step(pa, it);
+      consume(pa, it);
       __builtin_amdgcn_sched_barrier(0);
       fetch(pa, it + 2);
       __builtin_amdgcn_sched_barrier(0);
-      step(pb, it + 1);
+      consume(pb, it + 1);
       __builtin_amdgcn_sched_barrier(0);
     }
     if (it + 1 < it_end) {  // two steps left
       fetch(pb, it + 1);
       __builtin_amdgcn_sched_barrier(0);
-      step(pa, it);
+      consume(pa, it);
       if (APPEND && appends) patch_new(pb);
-      step(pb, it + 1);
+      consume(pb, it + 1);
     } else {  // one step left
       if (APPEND && appends) patch_new(pa);
-      step(pa, it);
+      consume(pa, it);
     }
   }
 
@@ -573,14 +691,18 @@ void launch_attn_decode_bf16(hipStream_t s, const Geometry& g, const float* q, c
     ap.qkv_part = append->qkv_part; ap.S = append->S;
     ap.split_stride = (size_t)M * (g.n_q + 2 * g.n_kv) * g.head_dim;
     ap.q_gain = append->q_gain; ap.k_gain = append->k_gain; ap.rope = append->rope_table; ap.eps = g.rms_eps;
-    attn_decode_bf16_kernel<true><<<grid, 256, lds, s>>>(q, rows, block_table, g.max_blocks, (const u32x4_t*)k_pool_layer,
-                                                         (const u32x4_t*)v_pool_layer, part, max_segs_alloc, g.n_q, g.n_kv,
-                                                         scale, (uint16_t*)o_out, page_ints, page_ints + part_floats, M, skip_segs, shared, ap);
-  } else {
-    attn_decode_bf16_kernel<false><<<grid, 256, lds, s>>>(q, rows, block_table, g.max_blocks, (const u32x4_t*)k_pool_layer,
-                                                          (const u32x4_t*)v_pool_layer, part, max_segs_alloc, g.n_q, g.n_kv,
-                                                          scale, (uint16_t*)o_out, page_ints, page_ints + part_floats, M, skip_segs, shared, ap);
   }
+#define RL_ATTN_LAUNCH(APP, K8)                                                                                          \
+  attn_decode_bf16_kernel<APP, K8><<<grid, 256, lds, s>>>(q, rows, block_table, g.max_blocks, (const u32x4_t*)k_pool_layer, \
+                                                          (const u32x4_t*)v_pool_layer, part, max_segs_alloc, g.n_q, g.n_kv, \
+                                                          scale, (uint16_t*)o_out, page_ints, page_ints + part_floats, M,  \
+                                                          skip_segs, shared, ap)
+  if (append) {
+    if (g.kv_fp8) RL_ATTN_LAUNCH(true, true); else RL_ATTN_LAUNCH(true, false);
+  } else {
+    if (g.kv_fp8) RL_ATTN_LAUNCH(false, true); else RL_ATTN_LAUNCH(false, false);
+  }
+#undef RL_ATTN_LAUNCH
   if (n_seg_max > kLdsSegs || n_shared > 0)
     attn_merge_bf16_kernel<<<dim3(g.n_q, M), 64, 0, s>>>(part, rows, max_segs_alloc, (uint16_t*)o_out, g.n_q, skip_segs);
 }

@@ -30,6 +30,7 @@ struct Geometry {
   int dtype;
   int max_blocks;   // block-table row length = max_ctx / 16
   int64_t n_pages;  // pages in the pool
+  int kv_fp8;       // bf16 models: keys and values are cached as fp8 (e4m3), one byte per element
 };
 
 // "Fragment-major" order of a [rows x K] bf16 operand of the MFMA GEMM: 32-row blocks, 64-wide k

@@ -58,11 +58,15 @@ struct Layout {
 };
 
 size_t elem_size(uint32_t dtype) { return dtype == RL_BF16 ? 2 : 4; }
+size_t kv_elem_size(const rl_model_config& c) { return c.kv_dtype == RL_KV_FP8 ? 1 : elem_size(c.dtype); }
 
 rl_status check_config(const rl_model_config* c) {
   if (!c) return fail(RL_ERR_INVALID_ARG, "config is NULL");
   if (c->struct_size != sizeof(rl_model_config)) return fail(RL_ERR_INVALID_ARG, "struct_size mismatch");
   if (c->dtype != RL_F32 && c->dtype != RL_BF16) return fail(RL_ERR_INVALID_ARG, "unknown dtype");
+  if (c->kv_dtype != RL_KV_SAME && c->kv_dtype != RL_KV_FP8) return fail(RL_ERR_INVALID_ARG, "unknown kv_dtype");
+  if (c->kv_dtype == RL_KV_FP8 && c->dtype != RL_BF16) return fail(RL_ERR_UNSUPPORTED, "fp8 keys and values need a bf16 model");
+  if (c->reserved != 0) return fail(RL_ERR_INVALID_ARG, "reserved must be 0");
   if (c->kv_block != 16) return fail(RL_ERR_UNSUPPORTED, "kv_block must be 16");
   if (!c->n_layers || !c->hidden || !c->n_q_heads || !c->n_kv_heads || !c->head_dim || !c->ffn)
     return fail(RL_ERR_INVALID_ARG, "zero dimension");
@@ -434,7 +438,7 @@ const char* rl_last_error(void) { return g_err.c_str(); }
 
 uint64_t rl_kv_page_bytes(const rl_model_config* c) {
   if (check_config(c) != RL_OK) return 0;
-  return (uint64_t)c->n_layers * 2 * c->n_kv_heads * 16 * c->head_dim * elem_size(c->dtype);
+  return (uint64_t)c->n_layers * 2 * c->n_kv_heads * 16 * c->head_dim * kv_elem_size(*c);
 }
 
 rl_status rl_query_workspace(const rl_model_config* c, uint64_t* bytes_out) {
@@ -466,7 +470,8 @@ rl_status rl_init_model(const rl_model_config* c, const rl_weights* w, rl_model*
   m->cfg = *c;
   m->lay = L;
   m->geo = Geometry{(int)c->n_layers, (int)c->hidden, (int)c->n_q_heads, (int)c->n_kv_heads, (int)c->head_dim, (int)c->ffn,
-                    (int)c->vocab, (int)c->qk_norm, c->rms_eps, (int)c->dtype, (int)(c->max_ctx / 16), n_pages};
+                    (int)c->vocab, (int)c->qk_norm, c->rms_eps, (int)c->dtype, (int)(c->max_ctx / 16), n_pages,
+                    c->kv_dtype == RL_KV_FP8 ? 1 : 0};
   m->embed = w->embed; m->lm_head = w->lm_head; m->final_norm = w->final_norm;
   auto copy = [&](std::vector<const void*>& dst, const void* const* src) {
     dst.assign(c->n_layers, nullptr);
@@ -482,7 +487,7 @@ rl_status rl_init_model(const rl_model_config* c, const rl_weights* w, rl_model*
     }
   m->kv_pool = (char*)w->kv_pool;
   m->ws = (char*)w->workspace;
-  m->kv_block_bytes = (size_t)16 * c->head_dim * elem_size(c->dtype);
+  m->kv_block_bytes = (size_t)16 * c->head_dim * kv_elem_size(*c);
   m->layer_kv_bytes = (size_t)n_pages * c->n_kv_heads * 2 * m->kv_block_bytes;
   m->table = new SeqTable((int)c->max_seqs, (int)c->max_ctx, n_pages);
   for (int i = 0; i < K_COUNT; ++i) { m->prof_ms[i] = 0; m->prof_n[i] = 0; }

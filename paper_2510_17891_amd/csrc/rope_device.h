@@ -25,10 +25,37 @@ __device__ __forceinline__ void kv_store_bf16_bits(void* pool_layer, int64_t pag
   ((uint16_t*)pool_layer)[base + (is_v ? v_page_offset_bf16(t, dd) : k_page_offset_bf16(t, dd))] = bits;
 }
 
-template <bool BF16>
+// fp8 pages (e4m3 in the matrix cores' own encoding, no scales, d = 128): one byte per element, 2 KiB per (page, kv
+// head) for K and as much for V.  K as [d/16][16 tokens][16] -- a lane's 16-byte load is one key's 16 consecutive
+// dims, i.e. two matrix-core steps of 8 -- and V as [d/64][4 key groups][16 dims][2 x 2 x 4 keys]: a lane's 16 bytes
+// are four keys of the four dims {dl, dl+16, dl+32, dl+48} of a 64-dim block.  After widening to bf16 in registers
+// these are exactly the operands of the bf16 pages.
+__device__ __forceinline__ int k_page_offset_fp8(int t, int dd) { return ((dd >> 4) * 16 + t) * 16 + (dd & 15); }
+__device__ __forceinline__ int v_page_offset_fp8(int t, int dd) {
+  const int jj = dd >> 5, par = (dd >> 4) & 1, dl = dd & 15, g = t >> 2;
+  return (((jj >> 1) * 4 + g) * 16 + dl) * 16 + ((jj & 1) * 2 + par) * 4 + (t & 3);
+}
+// fp32 -> fp8 bits: nearest even in the hardware's conversion, magnitudes beyond the format's largest finite value
+// (448) end there.
+__device__ __forceinline__ uint32_t f2fp8(float x) {
+  x = x > 448.0f ? 448.0f : (x < -448.0f ? -448.0f : x);
+  return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(x, 0.0f, 0, false) & 0xffu;
+}
+__device__ __forceinline__ float fp8_to_f(uint32_t b) { return __builtin_amdgcn_cvt_f32_fp8((int)b, 0); }
+__device__ __forceinline__ void kv_store_fp8_bits(void* pool_layer, int64_t page, int hk, int n_kv, int t, int dd,
+                                                  uint8_t bits, bool is_v) {
+  const size_t page_bytes = (size_t)kPageTokens * 128;
+  const size_t base = ((size_t)page * n_kv + hk) * 2 * page_bytes;  // [page][kv head][K | V]; V's base pointer is one block in
+  ((uint8_t*)pool_layer)[base + (is_v ? v_page_offset_fp8(t, dd) : k_page_offset_fp8(t, dd))] = bits;
+}
+
+// KVT: 0 = fp32 pages, 1 = bf16 pages, 2 = fp8 pages (bf16 models only).
+template <int KVT>
 __device__ __forceinline__ void kv_store(void* pool_layer, int64_t page, int hk, int n_kv, int d, int t, int dd,
                                          float val, bool is_v) {
-  if (BF16) {
+  if (KVT == 2) {
+    kv_store_fp8_bits(pool_layer, page, hk, n_kv, t, dd, (uint8_t)f2fp8(val), is_v);
+  } else if (KVT == 1) {
     kv_store_bf16_bits(pool_layer, page, hk, n_kv, t, dd, (uint16_t)f2bf(val), is_v);
   } else {
     const size_t page_elems = (size_t)kPageTokens * d;

@@ -121,7 +121,7 @@ void launch_residual_norm(hipStream_t s, int dtype, float* x, const float* part,
 }
 
 // One wave per (row, head), four heads per block.  Lane i < d/2 owns the rotary pair (i, i + d/2).
-template <bool BF16>
+template <bool BF16, int KVT>
 __global__ __launch_bounds__(256) void qk_rope_append_kernel(const float* __restrict__ part, int S, size_t split_stride,
                                                             const void* __restrict__ q_gain,
                                                             const void* __restrict__ k_gain,
@@ -154,8 +154,8 @@ __global__ __launch_bounds__(256) void qk_rope_append_kernel(const float* __rest
     } else {
       const int hk = is_k ? hh - n_q : hh - n_q - n_kv;
       const int t = rm.pos & 15;
-      kv_store<BF16>(is_k ? k_pool : v_pool, page, hk, n_kv, d, t, i, hp.v0, !is_k);
-      kv_store<BF16>(is_k ? k_pool : v_pool, page, hk, n_kv, d, t, i + half, hp.v1, !is_k);
+      kv_store<KVT>(is_k ? k_pool : v_pool, page, hk, n_kv, d, t, i, hp.v0, !is_k);
+      kv_store<KVT>(is_k ? k_pool : v_pool, page, hk, n_kv, d, t, i + half, hp.v1, !is_k);
     }
   }
 }
@@ -165,20 +165,24 @@ void launch_qk_rope_append(hipStream_t s, const Geometry& g, const float* qkv_pa
                            void* v_pool_layer, float* q_out, int M) {
   dim3 grid((g.n_q + 2 * g.n_kv + 3) / 4, M);
   size_t stride = (size_t)M * (g.n_q + 2 * g.n_kv) * g.head_dim;
-  if (g.dtype == kBF16)
-    qk_rope_append_kernel<true><<<grid, 256, 0, s>>>(qkv_part, S, stride, q_gain, k_gain, rope_table, rows,
-                                                    k_pool_layer, v_pool_layer, q_out, g.n_q, g.n_kv,
-                                                    g.head_dim, g.qk_norm, g.rms_eps);
+  if (g.dtype == kBF16 && g.kv_fp8)
+    qk_rope_append_kernel<true, 2><<<grid, 256, 0, s>>>(qkv_part, S, stride, q_gain, k_gain, rope_table, rows,
+                                                       k_pool_layer, v_pool_layer, q_out, g.n_q, g.n_kv,
+                                                       g.head_dim, g.qk_norm, g.rms_eps);
+  else if (g.dtype == kBF16)
+    qk_rope_append_kernel<true, 1><<<grid, 256, 0, s>>>(qkv_part, S, stride, q_gain, k_gain, rope_table, rows,
+                                                       k_pool_layer, v_pool_layer, q_out, g.n_q, g.n_kv,
+                                                       g.head_dim, g.qk_norm, g.rms_eps);
   else
-    qk_rope_append_kernel<false><<<grid, 256, 0, s>>>(qkv_part, S, stride, q_gain, k_gain, rope_table, rows,
-                                                     k_pool_layer, v_pool_layer, q_out, g.n_q, g.n_kv,
-                                                     g.head_dim, g.qk_norm, g.rms_eps);
+    qk_rope_append_kernel<false, 0><<<grid, 256, 0, s>>>(qkv_part, S, stride, q_gain, k_gain, rope_table, rows,
+                                                        k_pool_layer, v_pool_layer, q_out, g.n_q, g.n_kv,
+                                                        g.head_dim, g.qk_norm, g.rms_eps);
 }
 
 // ------------------------------------------------------------------------------------------------
 // KV import: contiguous [n_tokens][n_kv][d] -> positions first_pos .. first_pos + n_tokens - 1 of one sequence.
 // ------------------------------------------------------------------------------------------------
-template <typename T, bool BF16>
+template <typename T, int KVT>
 __global__ __launch_bounds__(256) void kv_import_kernel(const T* __restrict__ k_src, const T* __restrict__ v_src,
                                                         int first_pos, const int32_t* __restrict__ bt_row,
                                                         void* __restrict__ k_pool, void* __restrict__ v_pool, int n_kv,
@@ -189,20 +193,24 @@ __global__ __launch_bounds__(256) void kv_import_kernel(const T* __restrict__ k_
   for (int i = threadIdx.x; i < n_kv * d; i += 256) {
     int hk = i / d, dd = i - hk * d;
     size_t src = (size_t)blockIdx.x * n_kv * d + i;
-    kv_store<BF16>(k_pool, page, hk, n_kv, d, t, dd, load_as_float(k_src, src), false);
-    kv_store<BF16>(v_pool, page, hk, n_kv, d, t, dd, load_as_float(v_src, src), true);
+    kv_store<KVT>(k_pool, page, hk, n_kv, d, t, dd, load_as_float(k_src, src), false);
+    kv_store<KVT>(v_pool, page, hk, n_kv, d, t, dd, load_as_float(v_src, src), true);
   }
 }
 
 void launch_kv_import(hipStream_t s, const Geometry& g, const void* k_src, const void* v_src, int first_pos, int n_tokens,
                       const int32_t* block_table_row, void* k_pool_layer, void* v_pool_layer) {
   if (n_tokens <= 0) return;
-  if (g.dtype == kBF16)
-    kv_import_kernel<uint16_t, true><<<n_tokens, 256, 0, s>>>((const uint16_t*)k_src, (const uint16_t*)v_src, first_pos,
-                                                              block_table_row, k_pool_layer, v_pool_layer, g.n_kv,
-                                                              g.head_dim);
+  if (g.dtype == kBF16 && g.kv_fp8)
+    kv_import_kernel<uint16_t, 2><<<n_tokens, 256, 0, s>>>((const uint16_t*)k_src, (const uint16_t*)v_src, first_pos,
+                                                           block_table_row, k_pool_layer, v_pool_layer, g.n_kv,
+                                                           g.head_dim);
+  else if (g.dtype == kBF16)
+    kv_import_kernel<uint16_t, 1><<<n_tokens, 256, 0, s>>>((const uint16_t*)k_src, (const uint16_t*)v_src, first_pos,
+                                                           block_table_row, k_pool_layer, v_pool_layer, g.n_kv,
+                                                           g.head_dim);
   else
-    kv_import_kernel<float, false><<<n_tokens, 256, 0, s>>>((const float*)k_src, (const float*)v_src, first_pos,
+    kv_import_kernel<float, 0><<<n_tokens, 256, 0, s>>>((const float*)k_src, (const float*)v_src, first_pos,
                                                             block_table_row, k_pool_layer, v_pool_layer, g.n_kv,
                                                             g.head_dim);
 }

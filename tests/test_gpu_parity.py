@@ -1105,6 +1105,125 @@ def test_rescored_rollout_gives_ratio_one(amd, kind):
     ro.close()
 
 
+# ------------------------------------------------------------------------------- fp8 keys and values (opt-in)
+def _e4m3_exact(shape_, seed, tid):
+    """Random values that every fp8 e4m3 variant represents exactly: multiples of 0.25 in [-2, 2]."""
+    return (ri.lengths(int(np.prod(shape_)), -8, 8, seed, tid).float() * 0.25).reshape(shape_).to(torch.bfloat16)
+
+
+def test_fp8_kv_layer_with_exactly_representable_cache_matches_oracle(amd):
+    """fp8 pages pin their layout: imported keys and values that e4m3 represents exactly lose nothing in the cache, so
+    the layer must match the oracle to the bf16 bound (only each row's own new key and value are rounded to fp8: one
+    key among >= 100).  Contexts on page, step and merge boundaries, a forked group (shared pages, set blocks), and
+    bit equality with the shared-prompt treatment switched off."""
+    shape = ri.SHAPES["layer8b"]
+    w, wn = make_both(shape, 38)
+    wd = to_device(w)
+    nkv, d, H = shape["n_kv"], shape["head_dim"], shape["hidden"]
+    ctxs = [100, 255, 256, 257, 700, 1023, 1024, 4095, 5000]
+    G = 4                                                   # the last context is continued as four samples
+    ks = [_e4m3_exact((c, nkv, d), 38, 2000 + 2 * b) for b, c in enumerate(ctxs)]
+    vs = [_e4m3_exact((c, nkv, d), 38, 2001 + 2 * b) for b, c in enumerate(ctxs)]
+    n = len(ctxs) + G - 1
+    x = ri.normal((n, H), 1.0, 38, 1999).to(torch.bfloat16).float()
+    pages = sum((c + 16) // 16 + 1 for c in ctxs) + 2 * G + 8
+    outs = []
+    for share in (True, False):
+        ro = amd.Rollout(shape, wd, max_seqs=n, max_ctx=5056, max_rows=n, kv_pages=pages, kv_fp8=True)
+        assert ro.cfg.kv_pool_bytes == pages * 16 * nkv * d * 2          # one byte per element, K and V
+        ro.rl_debug_shuffle_free_pages(13)
+        ro.rl_debug_share_attention(share)
+        for b in range(len(ctxs)):
+            ro.rl_seq_import_kv(b, [ks[b].to(DEV)], [vs[b].to(DEV)])
+        last = len(ctxs) - 1
+        ro.rl_seq_fork(last, list(range(len(ctxs), n)))
+        outs.append(ro.rl_decode_hidden(list(range(n)), x.to(DEV)).cpu())
+        ro.close()
+    assert torch.equal(outs[0], outs[1])
+    out = outs[0].numpy()
+    for r in range(n):
+        b = min(r, len(ctxs) - 1)
+        ref = _oracle_layer_row(shape, wn, ks[b], vs[b], x[r], ctxs[b])
+        err = rel_inf(out[r] - x[r].numpy(), ref - x[r].numpy())
+        assert err < 3e-2, (r, ctxs[b], err)
+
+
+def test_fp8_kv_layer_random_cache_within_the_fp8_tolerance(amd):
+    """N(0,1) keys and values cached as fp8 against the oracle, which never rounds them.  e4m3 keeps 4 significant
+    bits: each cached element is within 2^-4 relative (about 2.6e-2 rms), the scores and the value average inherit
+    that, and the layer's output moves by a few per cent of its change to the residual stream: bound 1e-1."""
+    ctxs = [0, 1, 15, 16, 17, 255, 256, 257, 700, 2048, 4500]
+    shape = ri.SHAPES["layer8b"]
+    w, wn = make_both(shape, 31)
+    nkv, d, H = shape["n_kv"], shape["head_dim"], shape["hidden"]
+    n = len(ctxs)
+    ro = amd.Rollout(shape, to_device(w), max_seqs=n, max_ctx=4544, max_rows=n,
+                     kv_pages=sum((c + 16) // 16 + 1 for c in ctxs) + 4, kv_fp8=True)
+    ro.rl_debug_shuffle_free_pages(9)
+    ks = [ri.normal((c, nkv, d), 1.0, 31, 2000 + 2 * b, dtype=torch.bfloat16) for b, c in enumerate(ctxs)]
+    vs = [ri.normal((c, nkv, d), 1.0, 31, 2001 + 2 * b, dtype=torch.bfloat16) for b, c in enumerate(ctxs)]
+    for b in range(n):
+        ro.rl_seq_import_kv(b, [ks[b].to(DEV)], [vs[b].to(DEV)])
+    x = ri.normal((n, H), 1.0, 31, 1999).to(torch.bfloat16).float()
+    out = ro.rl_decode_hidden(list(range(n)), x.to(DEV)).cpu().numpy()
+    worst = 0.0
+    for b, c in enumerate(ctxs):
+        ref = _oracle_layer_row(shape, wn, ks[b], vs[b], x[b], c)
+        err = float(rel_inf(out[b] - x[b].numpy(), ref - x[b].numpy()))
+        worst = max(worst, err)
+        assert err < 1e-1, (b, c, err)
+    print(f"[fp8 kv] worst layer error with N(0,1) keys and values: {worst:.2e}")
+    ro.close()
+
+
+def test_fp8_kv_small_model_rollout_fused_and_separate_append_agree(amd):
+    """A 2-layer bf16 model with fp8 pages: grouped prefill + 36 sampled steps.  The attention kernel's own rotation
+    and append (new key and value patched into its operands, bytes written afterwards) give the bits of the separate
+    append kernel, with shared-prompt sets on and off; logits stay within the fp8 bound of the oracle's (one layer's
+    bound 1e-1, errors of independent roundings add in squares over the two layers: 1.41e-1), and the sampled ids are
+    the oracle sampler's on the GPU's logits."""
+    shape = dict(ri.SHAPES["layer8b"], n_layers=2, hidden=512, n_q=8, n_kv=2, ffn=768, vocab=8192)
+    w, wn = make_both(shape, 64, std=0.05)
+    wd = to_device(w)
+    G, seed = 4, 5
+    lens = [300, 40, 5]
+    prompts = [ri.tokens((n,), shape["vocab"], 64, 940 + i).tolist() for i, n in enumerate(lens)]
+    ids = list(range(len(lens) * G))
+    kw = dict(max_seqs=16, max_ctx=352, max_rows=64, kv_pages=120, kv_fp8=True)
+    ra, rb, rc = (amd.Rollout(shape, wd, **kw) for _ in range(3))
+    rb.rl_debug_attention_appends(False)
+    rc.rl_debug_share_attention(False)
+    every = (ra, rb, rc)
+    toks = [r.rl_prefill_groups(ids, G, prompts, 1.0, seed) for r in every]
+    torch.cuda.synchronize()
+    for t_, l_ in toks[1:]:
+        assert torch.equal(toks[0][0], t_) and torch.equal(toks[0][1], l_)
+    oms = {}
+    for i in ids:
+        oms[i] = orc.OracleModel(dims_of(shape), wn, max_ctx=352)
+        oms[i].prefill(0, prompts[i // G])
+    V = shape["vocab"]
+    tok = toks[0][0]
+    worst = 0.0
+    for step in range(36):
+        zs = [torch.empty(len(ids), V, device=DEV) for _ in every]
+        outs = [r.rl_decode_step(ids, tok, 1.0, seed, debug_logits=z) for r, z in zip(every, zs)]
+        torch.cuda.synchronize()
+        for z, (t_, l_) in zip(zs[1:], outs[1:]):
+            assert torch.equal(zs[0], z) and torch.equal(outs[0][0], t_) and torch.equal(outs[0][1], l_), step
+        zg = zs[0].cpu().numpy()
+        for k, i in enumerate(ids):
+            z = oms[i].forward_token(0, int(tok[k]))
+            worst = max(worst, float(rel_inf(zg[k], z)))
+            t_ref, lp_ref = orc.sample(zg[k], 1.0, seed, i, lens[i // G] + step + 1)
+            assert int(outs[0][0][k]) == t_ref and abs(float(outs[0][1][k]) - lp_ref) < 1e-4
+        tok = outs[0][0]
+    assert worst < 1e-1 * 2 ** 0.5, worst
+    print(f"[fp8 kv] 2-layer model, worst logit error over 36 steps: {worst:.2e}")
+    for r in every:
+        r.close()
+
+
 def test_bf16_sampled_step_bits_do_not_depend_on_batch_size_class(amd):
     """The output projection with the sampling epilogue also changes kernels with the batch.  A 1-layer model wide
     enough for every variant (hidden 1024, vocabulary 24576): three sequences decoded alone, among 40, 100 and 150
