@@ -70,6 +70,8 @@ def parse():
     ap.add_argument("--wave-prompts", type=int, default=16, help="wave workload: resident prompts (x 8 samples each)")
     ap.add_argument("--kv-fp8", action="store_true",
                     help="wave / full workloads: cache keys and values as fp8 (opt-in performance variant, not the headline)")
+    ap.add_argument("--graph", action="store_true",
+                    help="wave workload: launch every decode step as a HIP graph (rl_decode_graph_step)")
     ap.add_argument("--no-small-batch", action="store_true",
                     help="wave workload: skip the 32-sequence comparison run")
     ap.add_argument("--length-scale", type=float, default=1.0,
@@ -195,7 +197,7 @@ def run_wave(args):
     B = n_prompts * G
     ctx_mid = max(P, args.ctx_mid)
     private = ctx_mid - P
-    n_steps = args.warmup + args.steps
+    n_steps = args.warmup + args.steps + 4 + args.profile_steps
     max_ctx = (max(ctx_mid + n_steps, 1024 + 64 + n_steps) + 1 + 15) // 16 * 16
     pages = n_prompts * (P // 16 + G * ((ctx_mid + n_steps + 15) // 16 - P // 16)) + 64
     t_setup = time.perf_counter()
@@ -225,27 +227,40 @@ def run_wave(args):
             for _ in range(2)]
     state = {"cur": tok, "i": 0}
 
+    graphs = {}
+
     def step(id_arr=ids, n=B):
+        if args.graph:
+            if n not in graphs:
+                graphs[n] = ro.decode_graph(list(id_arr), 1.0, seed)
+            graphs[n].step()
+            return
         ot, ol = bufs[state["i"] & 1]
         ro.rl_decode_step(id_arr, state["cur"], 1.0, seed, out_tokens=ot[:n], out_logprobs=ol[:n])
         state["cur"] = ot[:n]
         state["i"] += 1
 
+    if args.graph:   # a graph cannot be captured on the null stream: everything from here on runs on a stream of its own
+        torch.cuda.synchronize()
+        torch.cuda.set_stream(torch.cuda.Stream())
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # HIP events bracket every launch of every stride-th timed step (about 2 us per launch on those steps, inside `value`)
-    stride = 0 if args.no_profile else max(1, args.steps // 5)
     t0 = time.perf_counter()
     for k in range(args.steps):
-        on = stride and k % stride == 0
-        if on:
-            ro.rl_profile_enable(True)
         step()
-        if on:
-            ro.rl_profile_enable(False)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    # Per-kernel durations: HIP events bracket every launch of the steps that directly follow the timed region (events
+    # on every launch cost about 8 % of a step, so they stay out of `value`; the contexts are args.steps tokens longer,
+    # 0.2 % at this length).  A graph launch has no per-kernel events.
+    n_prof = 0 if (args.no_profile or args.graph) else max(1, min(args.profile_steps, 4))
+    if n_prof:
+        ro.rl_profile_enable(True)
+        for _ in range(n_prof):
+            step()
+        torch.cuda.synchronize()
+        ro.rl_profile_enable(False)
     ms_per_step = elapsed / args.steps * 1e3
     ctx_first = ctx_mid + args.warmup + 1            # keys the first timed step attends to (its own token included)
     ctx_last = ctx_first + args.steps - 1
@@ -278,9 +293,12 @@ def run_wave(args):
         "step_hbm_fraction_shared_pages_once": step_bytes_of(shape, kb_once) / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9),
         "prefill_s": prefill_s, "prefill_prompt_tokens_per_s": n_prompts * P / prefill_s, "setup_s": setup_s,
     }
-    if stride:
+    if n_prof:
         prof = ro.rl_profile_read()
-        out["config"]["kernel_timing"] = f"HIP events on every {stride}th step of the timed region"
+        out["config"]["kernel_timing"] = f"HIP events on the {n_prof} steps that follow the timed region"
+        ctx_p = ctx_last + 0.5 * (n_prof + 1)
+        kb_once = kernel_bytes(shape, B, ctx_sum(ctx_p, True), kv_bytes=kvb)
+        kb_each = kernel_bytes(shape, B, ctx_sum(ctx_p, False), kv_bytes=kvb)
         kernels = kernel_table(prof, kb_once)
         out["kernels"] = kernels
         dom = max((n for n in kernels if n in kb_once), key=lambda n: kernels[n]["avg_us"] * kernels[n]["launches"])
@@ -291,6 +309,9 @@ def run_wave(args):
                            "achieved_per_sequence_formula": kb_each[dom] / (kernels[dom]["avg_us"] * 1e-6) / 1e9}
 
     # ---- the 32-sequence workload on the same model: 4 prompts x 8 samples, prompts of 1024 tokens ---------------
+    for gr in graphs.values():
+        gr.close()
+    graphs.clear()
     if not args.no_small_batch:
         ro.rl_free_seqs(seq_ids)
         n2, P2 = 4, 1024
@@ -320,7 +341,7 @@ def run_wave(args):
         kb2_each = kernel_bytes(shape, B2, int(B2 * c2), kv_bytes=kvb)
         small["step_hbm_fraction"] = step_bytes_of(shape, kb2_each) / (el2 / args.steps) / (HBM_PEAK_GBS * 1e9)
         small["step_hbm_fraction_shared_pages_once"] = step_bytes_of(shape, kb2) / (el2 / args.steps) / (HBM_PEAK_GBS * 1e9)
-        if not args.no_profile:
+        if not args.no_profile and not args.graph:
             ro.rl_profile_enable(True)
             for _ in range(args.profile_steps):
                 step(ids2, B2)
@@ -328,6 +349,10 @@ def run_wave(args):
             ro.rl_profile_enable(False)
             small["kernels"] = kernel_table(ro.rl_profile_read(), kb2)
         out["batch32"] = small
+    for gr in graphs.values():
+        gr.close()
+    if args.graph:
+        out["config"]["launch"] = "one HIP graph launch per decode step"
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline_full(shape, int(ctx_avg))
     ro.close()

@@ -223,6 +223,24 @@ rl_status rl_decode_step(rl_model* m, void* stream, int32_t n_seqs, const int32_
                          const int32_t* in_tokens, const int32_t* forced_next, const rl_sampling* sp,
                          int32_t* out_tokens, float* out_logprobs, float* debug_logits);
 
+/*
+ * The decode step of a batch that stays the same from step to step, launched as a HIP graph: one graph launch per
+ * step instead of several hundred kernel launches.  Every step is rl_decode_step(m, stream, n_seqs, seq_ids, NULL,
+ * NULL, sp, out_tokens, out_logprobs, NULL) -- each sequence is fed the token it sampled last -- and gives the same
+ * bits.  The step is captured on first use and again whenever a launch shape changes (the longest context crosses
+ * a multiple of 1024 tokens, or the sets of samples that share prompt pages change); *captures_out (may be NULL)
+ * counts the captures so far.  Every step reads the sequences' state afresh, so other calls (also rl_decode_step on
+ * the same sequences) may come between two steps.  One graph per model at a time; destroy it before the model;
+ * out_tokens / out_logprobs must stay valid until then.  rl_decode_graph_step captures on `stream` itself: it must
+ * not be the null stream (RL_ERR_INVALID_ARG), and no other thread may enqueue on it during the call.
+ * Errors of rl_decode_graph_step: as rl_decode_step.
+ */
+typedef struct rl_decode_graph rl_decode_graph;
+rl_status rl_decode_graph_create(rl_model* m, int32_t n_seqs, const int32_t* seq_ids, const rl_sampling* sp,
+                                 int32_t* out_tokens, float* out_logprobs, rl_decode_graph** out);
+rl_status rl_decode_graph_step(rl_decode_graph* g, void* stream, int64_t* captures_out);
+void rl_decode_graph_destroy(rl_decode_graph* g);
+
 /* Retire sequences and return their pages to the pool.  Errors: INVALID_ARG, BAD_SEQ. */
 rl_status rl_free_seqs(rl_model* m, int32_t n_seqs, const int32_t* seq_ids);
 

@@ -20,7 +20,7 @@ RL_KV_SAME, RL_KV_FP8 = 0, 2
 
 EXPORTS = [
     "rl_kv_page_bytes", "rl_query_workspace", "rl_init_model", "rl_destroy_model", "rl_prefill", "rl_prefill_groups", "rl_score", "rl_hrd_objective",
-    "rl_decode_step", "rl_free_seqs", "rl_last_error", "rl_kv_stats", "rl_seq_len", "rl_sample_logits", "rl_sample_logits_static",
+    "rl_decode_step", "rl_decode_graph_create", "rl_decode_graph_step", "rl_decode_graph_destroy", "rl_free_seqs", "rl_last_error", "rl_kv_stats", "rl_seq_len", "rl_sample_logits", "rl_sample_logits_static",
     "rl_seq_import_kv", "rl_seq_append_kv", "rl_decode_hidden", "rl_set_capture", "rl_pack_weight",
     "rl_debug_shuffle_free_pages", "rl_debug_share_attention", "rl_debug_attention_appends", "rl_seq_fork", "rl_profile_enable", "rl_profile_read", "rl_profile_host_read",
 ]
@@ -88,6 +88,11 @@ def lib():
             [C.c_void_p] * 4 + [C.POINTER(rl_objective_params)] + [C.c_void_p] * 3
         L.rl_decode_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, _i32p, C.c_void_p, C.c_void_p,
                                      C.POINTER(rl_sampling), C.c_void_p, C.c_void_p, C.c_void_p]
+        L.rl_decode_graph_create.argtypes = [C.c_void_p, C.c_int32, _i32p, C.POINTER(rl_sampling), C.c_void_p, C.c_void_p,
+                                             C.POINTER(C.c_void_p)]
+        L.rl_decode_graph_step.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int64)]
+        L.rl_decode_graph_destroy.restype = None
+        L.rl_decode_graph_destroy.argtypes = [C.c_void_p]
         L.rl_free_seqs.argtypes = [C.c_void_p, C.c_int32, _i32p]
         L.rl_kv_stats.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
         L.rl_seq_len.argtypes = [C.c_void_p, C.c_int32, _i32p]
@@ -317,6 +322,11 @@ class Rollout:
                                    _ptr(out_t), _ptr(out_lp), _ptr(debug_logits)))
         return out_t, out_lp
 
+    def decode_graph(self, seq_ids, temperature, seed):
+        """DecodeGraph over a fixed batch: .step() runs one decode step (fed the last sampled tokens) as a graph launch
+        and returns (out_tokens, out_logprobs), the same two device tensors every step."""
+        return DecodeGraph(self, seq_ids, temperature, seed)
+
     def rl_free_seqs(self, seq_ids):
         check(lib().rl_free_seqs(self.h, len(seq_ids), _i32(seq_ids)))
 
@@ -403,3 +413,37 @@ class Rollout:
         n = C.c_int32()
         check(lib().rl_profile_read(self.h, n_max, names, ms, cnt, C.byref(n)))
         return {names[i].decode(): (cnt[i], ms[i]) for i in range(n.value)}
+
+
+class DecodeGraph:
+    """rl_decode_graph_create / _step / _destroy for a fixed batch of sequences of one Rollout."""
+
+    def __init__(self, ro, seq_ids, temperature, seed):
+        n = len(seq_ids)
+        self.ro = ro
+        self.out_tokens = torch.empty(n, dtype=torch.int32, device=ro.device)
+        self.out_logprobs = torch.empty(n, dtype=torch.float32, device=ro.device)
+        self.captures = 0
+        sp = rl_sampling(temperature, 0, seed, 0.0, 0)
+        h = C.c_void_p()
+        check(lib().rl_decode_graph_create(ro.h, n, _i32(seq_ids), C.byref(sp), _ptr(self.out_tokens),
+                                           _ptr(self.out_logprobs), C.byref(h)))
+        self.h = h
+
+    def step(self):
+        c = C.c_int64()
+        check(lib().rl_decode_graph_step(self.h, _stream(), C.byref(c)))
+        self.captures = c.value
+        return self.out_tokens, self.out_logprobs
+
+    def close(self):
+        if self.h:
+            torch.cuda.synchronize(self.ro.device)
+            lib().rl_decode_graph_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

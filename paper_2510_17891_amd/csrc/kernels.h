@@ -17,7 +17,7 @@ struct RowMeta {
   int32_t seq;   // sequence id (row of the block table, RNG stream)
   int32_t pos;   // absolute position of the token fed in this row
   int32_t page;  // KV page that holds position pos (the host knows it; saves the append kernel a dependent load)
-  int32_t pad;
+  int32_t pad;   // row 0 of a decode call: number of page grants uploaded with the rows; otherwise 0
 };
 
 enum Dtype : int { kF32 = 0, kBF16 = 1 };
@@ -153,5 +153,8 @@ void launch_scatter_f32(hipStream_t s, const float* src, const int32_t* idx, flo
 
 // block_table[upd[3i]][upd[3i+1]] = upd[3i+2] for i < n (device-side mirror update of newly granted pages).
 void launch_table_update(hipStream_t s, int32_t* block_table, int max_blocks, const int32_t* upd, int n);
+// The same for at most n_max entries, of which the first rows[0].pad (read on the device) are applied.
+void launch_table_update_counted(hipStream_t s, int32_t* block_table, int max_blocks, const int32_t* upd,
+                                 const RowMeta* rows, int n_max);
 
 }  // namespace rl

@@ -46,7 +46,8 @@ namespace {
     if (e_ != hipSuccess) return fail(RL_ERR_DEVICE, "%s: %s", #expr, hipGetErrorString(e_)); \
   } while (0)
 
-constexpr int kRing = 64;  // per-call metadata slots in flight
+constexpr int kRing = 64;  // per-call metadata slots in the workspace
+constexpr int kRingCalls = kRing - 2;  // slots that ordinary calls cycle through; the last two belong to a decode graph
 constexpr int T_MAX_SCORE = 4096;  // sequences per scoring call
 
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
@@ -159,6 +160,7 @@ struct rl_model {
   bool ring_used[kRing];
   int ring_next = 0;
   float* capture = nullptr;
+  bool graph_alive = false;     // a decode graph owns the last two metadata slots
   bool share_attention = true;  // compute segments inside shared prompt pages once per set of rows
   bool attention_appends = true;  // decode steps: the attention kernel forms q and appends k, v itself
   // profiling
@@ -209,7 +211,7 @@ struct Timer {
 // Reserve a metadata slot: wait (practically never) until its previous upload has been consumed.
 rl_status ring_acquire(rl_model* m, int* slot_out) {
   int s = m->ring_next;
-  m->ring_next = (s + 1) % kRing;
+  m->ring_next = (s + 1) % kRingCalls;
   if (m->ring_used[s]) HIP_TRY(hipEventSynchronize(m->ring_ev[s]));
   *slot_out = s;
   return RL_OK;
@@ -368,15 +370,10 @@ rl_status upload_window_plan(rl_model* m, hipStream_t st, char* hs, char* ds, in
   return upload_attn_plan(m, st, hs, ds, n, plan, sa);
 }
 
-// Build and upload the rows (and page grants) of one decode call; returns device pointers into the slot.
-rl_status upload_decode_meta(rl_model* m, hipStream_t st, int32_t n, const int32_t* seq_ids,
-                             const std::vector<PageGrant>& grants, const RowMeta** rows_dev, int* max_ctx_out,
-                             SharedAttn* sa) {
-  int slot;
-  rl_status rs = ring_acquire(m, &slot);
-  if (rs != RL_OK) return rs;
-  char* hs = m->host_ring + (size_t)slot * m->lay.slot_bytes;
-  char* ds = m->ws + m->lay.ring + (size_t)slot * m->lay.slot_bytes;
+// Write the rows, page grants and shared-attention plan of one decode call into the host slot hs and describe them
+// (device pointers relative to the device slot ds).  Returns the bytes of the slot in use.
+size_t build_decode_meta(rl_model* m, int32_t n, const int32_t* seq_ids, const std::vector<PageGrant>& grants, char* hs,
+                         char* ds, int* max_ctx_out, SharedAttn* sa) {
   RowMeta* hr = (RowMeta*)hs;
   int max_ctx = 0;
   for (int i = 0; i < n; ++i) {
@@ -406,7 +403,7 @@ rl_status upload_decode_meta(rl_model* m, hipStream_t st, int32_t n, const int32
       plan_shared_attention(n, fam.data(), fam_blocks.data(), pos.data(), std::min(4, 16 / group), &plan);
     }
   }
-  Timer t(m, st, K_META);
+  hr[0].pad = (int32_t)grants.size();
   // One upload for everything the step needs: the slot's regions lie at fixed offsets, so the copy runs from the rows
   // to the end of the last region in use (a few KB; what lies between is not read).
   size_t used = (size_t)n * sizeof(RowMeta);
@@ -420,17 +417,63 @@ rl_status upload_decode_meta(rl_model* m, hipStream_t st, int32_t n, const int32
     sa->n_sets = (int)plan.sets.size();
     sa->max_segs = plan.max_shared_segs;
   }
+  *max_ctx_out = max_ctx;
+  return used;
+}
+
+// Build and upload the rows (and page grants) of one decode call; returns device pointers into the slot.
+rl_status upload_decode_meta(rl_model* m, hipStream_t st, int32_t n, const int32_t* seq_ids,
+                             const std::vector<PageGrant>& grants, const RowMeta** rows_dev, int* max_ctx_out,
+                             SharedAttn* sa) {
+  int slot;
+  rl_status rs = ring_acquire(m, &slot);
+  if (rs != RL_OK) return rs;
+  char* hs = m->host_ring + (size_t)slot * m->lay.slot_bytes;
+  char* ds = m->ws + m->lay.ring + (size_t)slot * m->lay.slot_bytes;
+  const size_t used = build_decode_meta(m, n, seq_ids, grants, hs, ds, max_ctx_out, sa);
+  Timer t(m, st, K_META);
   HIP_TRY(hipMemcpyAsync(ds, hs, used, hipMemcpyHostToDevice, st));
   if (!grants.empty())
     launch_table_update(st, m->wsp<int32_t>(m->lay.block_table), m->geo.max_blocks, (const int32_t*)(ds + m->lay.slot_upd), (int)grants.size());
   HIP_TRY(hipEventRecord(m->ring_ev[slot], st));
   m->ring_used[slot] = true;
   *rows_dev = (const RowMeta*)ds;
-  *max_ctx_out = max_ctx;
   return RL_OK;
 }
 
+// The kernels of one decode step for n rows whose metadata is on the device: embedding, layers, head.
+void decode_enqueue(rl_model* m, hipStream_t st, int n, const RowMeta* rows, int max_ctx_in_batch, const SharedAttn& sa,
+                    const int32_t* in_tokens, const int32_t* forced_next, const rl_sampling* sp, int32_t* out_tokens,
+                    float* out_logprobs, float* debug_logits) {
+  float* x = m->wsp<float>(m->lay.x);
+  { Timer t(m, st, K_EMBED);
+    launch_embed(st, m->geo.dtype, m->embed, in_tokens, x, n, m->geo.hidden, m->geo.vocab, rows, m->wsp<int32_t>(m->lay.last_tok)); }
+  int pend = run_layers(m, st, n, rows, max_ctx_in_batch, sa, true);
+  run_head(m, st, n, x, pend, rows, 1, forced_next, sp, out_tokens, out_logprobs, debug_logits);
+}
+
 }  // namespace
+
+// A decode step of a fixed batch as a HIP graph.  What changes from step to step is data (rows, page grants, the
+// shared-attention plan: one upload from a pinned buffer that the graph's copy node reads at every launch) except for
+// three launch shapes, which form the key of the captured graph: the 1024-key bracket of the longest context (block
+// count and shared-memory size of the attention launch), the number of row sets, and the blocks the sets need.  When
+// the key changes -- once per 1024 steps for a batch in lock step -- the step is captured again.  Two buffers and two
+// graphs alternate, so the host may prepare step k + 1 while step k runs.
+struct rl_decode_graph {
+  rl_model* m = nullptr;
+  std::vector<int32_t> ids;
+  rl_sampling sp;
+  int32_t* out_tokens = nullptr;
+  float* out_logprobs = nullptr;
+  char* host[2] = {nullptr, nullptr};  // pinned copies of the metadata slot
+  hipEvent_t ev[2] = {nullptr, nullptr};
+  bool ev_used[2] = {false, false};
+  hipGraphExec_t exec[2] = {nullptr, nullptr};
+  struct Key { int ctx_bracket, n_sets, set_blocks; } key[2] = {{-1, -1, -1}, {-1, -1, -1}};
+  int next = 0;
+  int64_t captures = 0;
+};
 
 extern "C" {
 
@@ -600,11 +643,7 @@ rl_status rl_decode_step(rl_model* m, void* stream, int32_t n, const int32_t* se
   rs = upload_decode_meta(m, st, n, seq_ids, grants, &rows, &max_ctx_in_batch, &sa);
   if (rs != RL_OK) return rs;
   const auto t2 = std::chrono::steady_clock::now();
-  float* x = m->wsp<float>(m->lay.x);
-  { Timer t(m, st, K_EMBED);
-    launch_embed(st, m->geo.dtype, m->embed, in_tokens, x, n, m->geo.hidden, m->geo.vocab, rows, m->wsp<int32_t>(m->lay.last_tok)); }
-  int pend = run_layers(m, st, n, rows, max_ctx_in_batch, sa, true);
-  run_head(m, st, n, x, pend, rows, 1, forced_next, sp, out_tokens, out_logprobs, debug_logits);
+  decode_enqueue(m, st, n, rows, max_ctx_in_batch, sa, in_tokens, forced_next, sp, out_tokens, out_logprobs, debug_logits);
   HIP_TRY(hipGetLastError());
   for (int i = 0; i < n; ++i) m->table->set_len(seq_ids[i], m->table->len(seq_ids[i]) + 1);
   const auto t3 = std::chrono::steady_clock::now();
@@ -620,6 +659,94 @@ rl_status rl_profile_host_read(rl_model* m, double* admit_us, double* meta_us, d
   *admit_us = m->host_us[0]; *meta_us = m->host_us[1]; *launch_us = m->host_us[2]; *calls = m->host_calls;
   m->host_us[0] = m->host_us[1] = m->host_us[2] = 0.0;
   m->host_calls = 0;
+  return RL_OK;
+}
+
+rl_status rl_decode_graph_create(rl_model* m, int32_t n, const int32_t* seq_ids, const rl_sampling* sp,
+                                 int32_t* out_tokens, float* out_logprobs, rl_decode_graph** out) {
+  if (!m || !seq_ids || !sp || !out_tokens || !out_logprobs || !out) return fail(RL_ERR_INVALID_ARG, "NULL argument");
+  if (m->geo.vocab == 0) return fail(RL_ERR_UNSUPPORTED, "model has no vocabulary");
+  if (n < 1 || n > (int32_t)m->cfg.max_rows) return fail(RL_ERR_INVALID_ARG, "n_seqs %d outside [1, max_rows=%u]", n, m->cfg.max_rows);
+  if (m->graph_alive) return fail(RL_ERR_UNSUPPORTED, "one decode graph per model at a time");
+  rl_decode_graph* g = new rl_decode_graph();
+  g->m = m;
+  g->ids.assign(seq_ids, seq_ids + n);
+  g->sp = *sp;
+  g->out_tokens = out_tokens;
+  g->out_logprobs = out_logprobs;
+  for (int b = 0; b < 2; ++b) {
+    hipError_t e = hipHostMalloc((void**)&g->host[b], m->lay.slot_bytes, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&g->ev[b], hipEventDisableTiming);
+    if (e != hipSuccess) {
+      rl_decode_graph_destroy(g);
+      return fail(RL_ERR_DEVICE, "rl_decode_graph_create: %s", hipGetErrorString(e));
+    }
+    memset(g->host[b], 0, m->lay.slot_bytes);
+  }
+  m->graph_alive = true;
+  *out = g;
+  return RL_OK;
+}
+
+void rl_decode_graph_destroy(rl_decode_graph* g) {
+  if (!g) return;
+  for (int b = 0; b < 2; ++b) {
+    if (g->ev[b]) { if (g->ev_used[b]) (void)hipEventSynchronize(g->ev[b]); (void)hipEventDestroy(g->ev[b]); }
+    if (g->exec[b]) (void)hipGraphExecDestroy(g->exec[b]);
+    if (g->host[b]) (void)hipHostFree(g->host[b]);
+  }
+  if (g->m) g->m->graph_alive = false;
+  delete g;
+}
+
+rl_status rl_decode_graph_step(rl_decode_graph* g, void* stream, int64_t* captures_out) {
+  if (!g) return fail(RL_ERR_INVALID_ARG, "graph is NULL");
+  if (!stream) return fail(RL_ERR_INVALID_ARG, "the null stream cannot be captured: pass a stream created by the caller");
+  rl_model* m = g->m;
+  hipStream_t st = (hipStream_t)stream;
+  const int n = (int)g->ids.size();
+  std::vector<PageGrant> grants;
+  rl_status rs = admit_decode(m, n, g->ids.data(), &grants);
+  if (rs != RL_OK) return rs;
+  const int b = g->next;
+  if (g->ev_used[b]) HIP_TRY(hipEventSynchronize(g->ev[b]));  // the launch that read this buffer last has finished
+  char* hs = g->host[b];
+  char* ds = m->ws + m->lay.ring + (size_t)(kRingCalls + b) * m->lay.slot_bytes;
+  int max_ctx = 0;
+  SharedAttn sa;
+  build_decode_meta(m, n, g->ids.data(), grants, hs, ds, &max_ctx, &sa);
+  const rl_decode_graph::Key key = {(max_ctx + 1023) / 1024, sa.n_sets, (sa.max_segs + 3) / 4};
+  if (!g->exec[b] || key.ctx_bracket != g->key[b].ctx_bracket || key.n_sets != g->key[b].n_sets ||
+      key.set_blocks != g->key[b].set_blocks) {
+    if (g->exec[b]) { (void)hipGraphExecDestroy(g->exec[b]); g->exec[b] = nullptr; }
+    const bool prof = m->prof_on;
+    m->prof_on = false;  // no event pairs inside a captured step
+    hipGraph_t graph = nullptr;
+    hipError_t e = hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal);
+    if (e == hipSuccess) {
+      e = hipMemcpyAsync(ds, hs, m->lay.slot_bytes, hipMemcpyHostToDevice, st);
+      launch_table_update_counted(st, m->wsp<int32_t>(m->lay.block_table), m->geo.max_blocks,
+                                  (const int32_t*)(ds + m->lay.slot_upd), (const RowMeta*)ds, n);
+      SharedAttn sa_cap = sa;
+      sa_cap.max_segs = key.set_blocks * 4;  // the attention grid only takes its block count from it
+      decode_enqueue(m, st, n, (const RowMeta*)ds, key.ctx_bracket * 1024, sa_cap, nullptr, nullptr, &g->sp, g->out_tokens,
+                     g->out_logprobs, nullptr);
+      const hipError_t e_end = hipStreamEndCapture(st, &graph);  // always ends the capture
+      if (e == hipSuccess) e = e_end;
+    }
+    if (e == hipSuccess) e = hipGraphInstantiate(&g->exec[b], graph, nullptr, nullptr, 0);
+    if (graph) (void)hipGraphDestroy(graph);
+    m->prof_on = prof;
+    if (e != hipSuccess) { g->exec[b] = nullptr; return fail(RL_ERR_DEVICE, "rl_decode_graph_step: capture: %s", hipGetErrorString(e)); }
+    g->key[b] = key;
+    g->captures += 1;
+  }
+  HIP_TRY(hipGraphLaunch(g->exec[b], st));
+  HIP_TRY(hipEventRecord(g->ev[b], st));
+  g->ev_used[b] = true;
+  for (int i = 0; i < n; ++i) m->table->set_len(g->ids[i], m->table->len(g->ids[i]) + 1);
+  g->next = b ^ 1;
+  if (captures_out) *captures_out = g->captures;
   return RL_OK;
 }
 

@@ -246,6 +246,19 @@ void launch_table_update(hipStream_t s, int32_t* block_table, int max_blocks, co
   table_update_kernel<<<(n + 63) / 64, 64, 0, s>>>(block_table, max_blocks, upd, n);
 }
 
+// The same with the number of entries read on the device (rows[0].pad), for launches whose shape must not depend
+// on it: a grid for n_max entries, of which the first rows[0].pad are applied.
+__global__ void table_update_counted_kernel(int32_t* __restrict__ bt, int max_blocks, const int32_t* __restrict__ upd,
+                                            const RowMeta* __restrict__ rows) {
+  const int i = blockIdx.x * 64 + threadIdx.x;
+  if (i < rows[0].pad) bt[(size_t)upd[3 * i] * max_blocks + upd[3 * i + 1]] = upd[3 * i + 2];
+}
+
+void launch_table_update_counted(hipStream_t s, int32_t* block_table, int max_blocks, const int32_t* upd,
+                                 const RowMeta* rows, int n_max) {
+  table_update_counted_kernel<<<(n_max + 63) / 64, 64, 0, s>>>(block_table, max_blocks, upd, rows);
+}
+
 }  // namespace rl
 
 namespace rl {

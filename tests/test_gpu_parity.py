@@ -1105,6 +1105,49 @@ def test_rescored_rollout_gives_ratio_one(amd, kind):
     ro.close()
 
 
+# ----------------------------------------------------------------------------------- decode step as a HIP graph
+@pytest.mark.parametrize("kv_fp8", [False, True])
+def test_decode_graph_steps_equal_eager_steps(amd, kv_fp8):
+    """rl_decode_graph_step against rl_decode_step on a second instance: same tokens and log-probabilities, bit for
+    bit, on every one of 40 steps (compared after each launch, with eager work and synchronisations in between).  The
+    batch holds two groups of four samples (shared prompt pages: set blocks in the attention launch) and a single
+    sequence whose context crosses 1024 tokens on the way, which changes a launch shape and forces a new capture; page
+    grants arrive every 16 steps through the device-counted table update.  An eager step in the middle of the graph
+    steps keeps both instances in agreement too."""
+    shape = dict(ri.SHAPES["layer8b"], n_layers=2, hidden=512, n_q=8, n_kv=2, ffn=768, vocab=8192)
+    w, _ = make_both(shape, 65, std=0.05)
+    wd = to_device(w)
+    G, seed = 4, 9
+    lens = [1003, 70, 33]
+    prompts = [ri.tokens((n,), shape["vocab"], 65, 940 + i).tolist() for i, n in enumerate(lens)]
+    ids = list(range(2 * G + 1))
+    kw = dict(max_seqs=16, max_ctx=1088, max_rows=64, kv_pages=160, kv_fp8=kv_fp8)
+    ra, rb = amd.Rollout(shape, wd, **kw), amd.Rollout(shape, wd, **kw)
+    for r in (ra, rb):
+        r.rl_prefill_groups(ids[:2 * G], G, prompts[1:], 1.0, seed)
+        r.rl_prefill([2 * G], [prompts[0]], 1.0, seed)
+    g = ra.decode_graph(ids, 1.0, seed)
+    with pytest.raises(amd.binding.RLError) as e:         # the null stream cannot be captured
+        g.step()
+    assert e.value.status == amd.binding.RL_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        for step in range(40):
+            if step == 20:                                # an eager step between graph steps, on both instances
+                ta, la = ra.rl_decode_step(ids, None, 1.0, seed)
+            else:
+                ta, la = g.step()
+            tb, lb = rb.rl_decode_step(ids, None, 1.0, seed)
+            torch.cuda.synchronize()
+            assert torch.equal(ta, tb) and torch.equal(la, lb), step
+    assert [ra.rl_seq_len(i) for i in ids] == [rb.rl_seq_len(i) for i in ids] == [110] * G + [73] * G + [1043]
+    assert 2 <= g.captures <= 6, g.captures               # two buffers, one change of shape
+    g.close()
+    ra.close()
+    rb.close()
+
+
 # ------------------------------------------------------------------------------- fp8 keys and values (opt-in)
 def _e4m3_exact(shape_, seed, tid):
     """Random values that every fp8 e4m3 variant represents exactly: multiples of 0.25 in [-2, 2]."""
