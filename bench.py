@@ -70,6 +70,8 @@ def parse():
     ap.add_argument("--wave-prompts", type=int, default=16, help="wave workload: resident prompts (x 8 samples each)")
     ap.add_argument("--kv-fp8", action="store_true",
                     help="wave / full workloads: cache keys and values as fp8 (opt-in performance variant, not the headline)")
+    ap.add_argument("--attn-split", type=int, default=0,
+                    help="wave workload: segments per attention block beyond 4096 keys (0: the library's default)")
     ap.add_argument("--graph", action="store_true",
                     help="wave workload: launch every decode step as a HIP graph (rl_decode_graph_step)")
     ap.add_argument("--no-small-batch", action="store_true",
@@ -206,6 +208,8 @@ def run_wave(args):
                  kv_fp8=args.kv_fp8)
     del w
     torch.cuda.empty_cache()
+    if args.attn_split:
+        ro.rl_debug_attention_split(args.attn_split)
     prompts = ri.tokens((n_prompts, P), shape["vocab"], seed, 960)
     seq_ids = list(range(B))
     torch.cuda.synchronize()
@@ -751,6 +755,8 @@ def main():
         pages = B * (max_ctx // 16)
         w = ri.make_weights(shape, seed, device=dev, dtype=torch.bfloat16)
         ro = Rollout(shape, w, max_seqs=B, max_ctx=max_ctx, max_rows=B, kv_pages=pages)
+        if args.attn_split:
+            ro.rl_debug_attention_split(args.attn_split)
         if not args.contiguous_pages:
             ro.rl_debug_shuffle_free_pages(seed)  # block tables are a random permutation of the pool
         if args.no_share_attention:

@@ -34,7 +34,10 @@
  *   embed, lm_head  vocab x hidden               (not tied)
  *   wqkv            (n_q+2*n_kv)*head_dim x hidden, rows ordered q heads, k heads, v heads
  *   wo              hidden x n_q*head_dim
- *   w_gate_up       2*ffn x hidden, the ffn gate rows followed by the ffn up rows
+ *   w_gate_up       2*ffn x hidden.  RL_F32: the ffn gate rows followed by the ffn up rows.  RL_BF16: gate and up rows
+ *                   alternate in groups of 16 -- rows 32j .. 32j+15 are gate rows 16j .. 16j+15, rows 32j+16 .. 32j+31
+ *                   the up rows of the same outputs -- so that one 32-row block of the streamed matrix holds both
+ *                   factors of 16 outputs (then packed like the other matrices)
  *   w_down          hidden x ffn
  *   *_norm          RMSNorm gains: hidden (attn_norm, mlp_norm, final_norm), head_dim (q_norm, k_norm)
  *   kv_pool         opaque; n_pages = kv_pool_bytes / rl_kv_page_bytes(cfg); one page holds
@@ -389,6 +392,13 @@ rl_status rl_debug_share_attention(rl_model* m, int32_t on);
  * fp32 models and on calls that feed several positions of one sequence (prefill, scoring).
  */
 rl_status rl_debug_attention_appends(rl_model* m, int32_t on);
+
+/*
+ * Test and tuning aid: how many 256-key segments one attention block takes of a context beyond 4096 keys (1..16).
+ * Smaller blocks balance better at the end of a launch, larger ones amortise their prologue.  Results of every
+ * other call must not change by a single bit.  Not to be changed while a decode graph exists.
+ */
+rl_status rl_debug_attention_split(rl_model* m, int32_t segs_per_block);
 
 /*
  * Per-kernel timing.  While enabled, every kernel launch of decode/prefill calls is bracketed by

@@ -22,7 +22,7 @@ EXPORTS = [
     "rl_kv_page_bytes", "rl_query_workspace", "rl_init_model", "rl_destroy_model", "rl_prefill", "rl_prefill_groups", "rl_score", "rl_hrd_objective",
     "rl_decode_step", "rl_decode_graph_create", "rl_decode_graph_step", "rl_decode_graph_destroy", "rl_free_seqs", "rl_last_error", "rl_kv_stats", "rl_seq_len", "rl_sample_logits", "rl_sample_logits_static",
     "rl_seq_import_kv", "rl_seq_append_kv", "rl_decode_hidden", "rl_set_capture", "rl_pack_weight",
-    "rl_debug_shuffle_free_pages", "rl_debug_share_attention", "rl_debug_attention_appends", "rl_seq_fork", "rl_profile_enable", "rl_profile_read", "rl_profile_host_read",
+    "rl_debug_shuffle_free_pages", "rl_debug_share_attention", "rl_debug_attention_appends", "rl_debug_attention_split", "rl_seq_fork", "rl_profile_enable", "rl_profile_read", "rl_profile_host_read",
 ]
 
 
@@ -108,6 +108,7 @@ def lib():
         L.rl_debug_shuffle_free_pages.argtypes = [C.c_void_p, C.c_uint64]
         L.rl_debug_share_attention.argtypes = [C.c_void_p, C.c_int32]
         L.rl_debug_attention_appends.argtypes = [C.c_void_p, C.c_int32]
+        L.rl_debug_attention_split.argtypes = [C.c_void_p, C.c_int32]
         L.rl_seq_fork.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, _i32p]
         L.rl_profile_enable.argtypes = [C.c_void_p, C.c_int32]
         L.rl_profile_read.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
@@ -232,6 +233,18 @@ class Rollout:
             del src
             return out
 
+        def packed_gate_up(d):
+            g, u = take(d, "w_gate"), take(d, "w_up")
+            if self.dtype == RL_BF16:   # rl.h: gate and up rows alternate in groups of 16
+                F, H = g.shape
+                src = torch.stack([g.view(F // 16, 16, H), u.view(F // 16, 16, H)], 1).reshape(2 * F, H)
+            else:
+                src = torch.cat([g, u], 0)
+            del g, u
+            out = rl_pack_weight(src)
+            del src
+            return out
+
         lay = weights["layers"]
         w = rl_weights()
         if shape["vocab"] > 0:
@@ -246,7 +259,7 @@ class Rollout:
         w.k_norm = arr([take(l, "k_norm").contiguous() for l in lay])
         w.wqkv = arr([packed(l, ["wq", "wk", "wv"]) for l in lay])
         w.wo = arr([packed(l, ["wo"]) for l in lay])
-        w.w_gate_up = arr([packed(l, ["w_gate", "w_up"]) for l in lay])
+        w.w_gate_up = arr([packed_gate_up(l) for l in lay])
         w.w_down = arr([packed(l, ["w_down"]) for l in lay])
         if kv_pages is None:
             torch.cuda.synchronize(self.device)
@@ -391,6 +404,9 @@ class Rollout:
 
     def rl_debug_share_attention(self, on):
         check(lib().rl_debug_share_attention(self.h, int(on)))
+
+    def rl_debug_attention_split(self, segs_per_block):
+        check(lib().rl_debug_attention_split(self.h, int(segs_per_block)))
 
     def rl_debug_attention_appends(self, on):
         check(lib().rl_debug_attention_appends(self.h, int(on)))

@@ -140,7 +140,10 @@ __device__ __forceinline__ void widen(PagePair& out, const PagePair8& in) {
       }
 }
 
-__host__ __device__ inline int attn_num_splits(int n_seg) { return n_seg <= kLdsSegs ? 1 : (n_seg + kLdsSegs - 1) / kLdsSegs; }
+// Blocks per (row, kv head): contexts of up to kLdsSegs segments take one block (partials merged in LDS), longer ones
+// one block per spb segments (spb <= kLdsSegs, a launch parameter: smaller blocks balance better at the end of a
+// launch; the partials and their merge do not depend on it).
+__host__ __device__ inline int attn_num_splits(int n_seg, int spb) { return n_seg <= kLdsSegs ? 1 : (n_seg + spb - 1) / spb; }
 
 // Flat merge of the (at most kLdsSegs) segments of one head: running maximum, weights exp(m_c - M), sums in index
 // order; the lane owns dims 2*lane, 2*lane+1.  seg_ptr(c) -> [O(128), max, sum] of segment c (LDS or workspace);
@@ -211,7 +214,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
                                                                int max_segs, int n_q, int n_kv, float scale,
                                                                uint16_t* __restrict__ o_out, int lds_part_offset,
                                                                int lds_q_offset, int n_rows, const int32_t* __restrict__ skip_segs,
-                                                               const AttnShared* __restrict__ shared, AppendArgs ap) {
+                                                               const AttnShared* __restrict__ shared, AppendArgs ap, int spb) {
   extern __shared__ int32_t pages[];  // block-table slice of this row: ceil(ctx/16) entries (+1 pad), then partials
   const int hk = blockIdx.x;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -248,9 +251,10 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
     lo = blockIdx.z * 4;
     hi = min(lo + 4, shared_segs);
   } else {
-    if ((int)blockIdx.z >= attn_num_splits(n_seg)) return;  // block-uniform
-    lo = max((int)blockIdx.z * kLdsSegs, skip);
-    hi = min((int)blockIdx.z * kLdsSegs + kLdsSegs, n_seg);
+    if ((int)blockIdx.z >= attn_num_splits(n_seg, spb)) return;  // block-uniform
+    const int per = n_seg <= kLdsSegs ? kLdsSegs : spb;
+    lo = max((int)blockIdx.z * per, skip);
+    hi = min((int)blockIdx.z * per + per, n_seg);
   }
   if (lo >= hi) return;  // block-uniform: nothing left for this block
   const int n_blk = (ctx + 15) >> 4;
@@ -675,11 +679,13 @@ int attn_bf16_max_segments(int max_ctx) { return attn_num_segments(max_ctx); }
 void launch_attn_decode_bf16(hipStream_t s, const Geometry& g, const float* q, const RowMeta* rows,
                              const int32_t* block_table, void* k_pool_layer, void* v_pool_layer, float* part,
                              int max_segs_alloc, int max_ctx_in_batch, void* o_out, int M, const int32_t* skip_segs,
-                             const AttnShared* shared, int n_shared, int max_shared_segs, const AttnAppend* append) {
+                             const AttnShared* shared, int n_shared, int max_shared_segs, const AttnAppend* append,
+                             int segs_per_block) {
   const int n_seg_max = attn_num_segments(max_ctx_in_batch);
+  const int spb = std::min(std::max(segs_per_block, 1), kLdsSegs);
   const int page_ints = ((max_ctx_in_batch + 15) / 16 + 1 + 3) & ~3;  // keeps the partials 16-byte aligned
   if (n_shared <= 0) { skip_segs = nullptr; n_shared = 0; max_shared_segs = 0; }
-  const int z = std::max(attn_num_splits(n_seg_max), (max_shared_segs + 3) / 4);
+  const int z = std::max(attn_num_splits(n_seg_max, spb), (max_shared_segs + 3) / 4);
   dim3 grid(g.n_kv, M + n_shared, z);
   const int segs = n_seg_max > kLdsSegs ? kLdsSegs : n_seg_max;
   const int part_floats = (g.n_q / g.n_kv) * segs * kPartStride;  // even
@@ -696,7 +702,7 @@ void launch_attn_decode_bf16(hipStream_t s, const Geometry& g, const float* q, c
   attn_decode_bf16_kernel<APP, K8><<<grid, 256, lds, s>>>(q, rows, block_table, g.max_blocks, (const u32x4_t*)k_pool_layer, \
                                                           (const u32x4_t*)v_pool_layer, part, max_segs_alloc, g.n_q, g.n_kv, \
                                                           scale, (uint16_t*)o_out, page_ints, page_ints + part_floats, M,  \
-                                                          skip_segs, shared, ap)
+                                                          skip_segs, shared, ap, spb)
   if (append) {
     if (g.kv_fp8) RL_ATTN_LAUNCH(true, true); else RL_ATTN_LAUNCH(true, false);
   } else {

@@ -26,26 +26,23 @@ __device__ __forceinline__ f32x16_t mfma_f16(u32x4_t a, u32x4_t b, f32x16_t c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
 }
 
-template <int MB>
+template <int MB, int RB = 2>
 struct Frags {
-  u32x4_t a[2][4];
+  u32x4_t a[RB][4];  // RB 32-row blocks of the weight matrix
   u32x4_t b[MB][4];
 };
 
-template <int MB, bool NT = true>
-__device__ __forceinline__ void load_frags(Frags<MB>& f, const u32x4_t* __restrict__ w0, const u32x4_t* __restrict__ w1,
+// wr[nb]: row block nb of the tile; NT: weights pass through once (non-temporal), otherwise the block's other waves
+// read the same tile and it may live in L1/L2.
+template <int MB, int RB, bool NT = true>
+__device__ __forceinline__ void load_frags(Frags<MB, RB>& f, const u32x4_t* const (&wr)[RB],
                                            const u32x4_t* const* __restrict__ xb, int kb, int lane) {
   // block (rb, kb) = 256 uint4; sub-load t is [t*64 + lane]
   const int o = kb * 256 + lane;
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
-    if (NT) {  // weights pass through once
-      f.a[0][t] = __builtin_nontemporal_load(w0 + o + t * 64);
-      f.a[1][t] = __builtin_nontemporal_load(w1 + o + t * 64);
-    } else {   // the block's other waves read the same tile: let it live in L1/L2
-      f.a[0][t] = w0[o + t * 64];
-      f.a[1][t] = w1[o + t * 64];
-    }
+#pragma unroll
+    for (int nb = 0; nb < RB; ++nb) f.a[nb][t] = NT ? __builtin_nontemporal_load(wr[nb] + o + t * 64) : wr[nb][o + t * 64];
   }
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb)
@@ -53,16 +50,43 @@ __device__ __forceinline__ void load_frags(Frags<MB>& f, const u32x4_t* __restri
     for (int t = 0; t < 4; ++t) f.b[mb][t] = xb[mb][o + t * 64];
 }
 
-template <int MB>
-__device__ __forceinline__ void mma_frags(const Frags<MB>& f, f32x16_t (&acc)[2][MB]) {
+template <int MB, int RB>
+__device__ __forceinline__ void mma_frags(const Frags<MB, RB>& f, f32x16_t (&acc)[RB][MB]) {
 #pragma unroll
   for (int t = 0; t < 4; ++t)
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
+    for (int nb = 0; nb < RB; ++nb) {
       const u32x4_t a = w_to_f16(f.a[nb][t]);
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = mfma_f16(a, f.b[mb][t], acc[nb][mb]);
     }
+}
+
+// One finished 32-row block held in MFMA accumulator order -- lane (col, hb) has outputs 8q + 4hb + e (q, e = 0..3)
+// of batch row m -- for the epilogues that work per row block.
+template <int EPI>
+__device__ __forceinline__ void store_rowblock(const float (&sum)[16], int m, int hb, int rb, int split, int M, int N,
+                                               void* __restrict__ out) {
+  if (EPI == kEpiPartial) {
+    float* o = (float*)out + ((size_t)split * M + m) * N;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      *(float4*)(o + rb * 32 + 8 * q + 4 * hb) = make_float4(sum[4 * q], sum[4 * q + 1], sum[4 * q + 2], sum[4 * q + 3]);
+  } else {
+    // SwiGLU: a 32-row block of the interleaved gate/up matrix holds the gate rows (0..15) and the up rows (16..31)
+    // of the 16 outputs 16 rb .. 16 rb + 15: a lane finds both factors of its outputs in its own registers.
+    uint16_t* o = (uint16_t*)out;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      float a[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float gte = sum[4 * q + e], up = sum[4 * (q + 2) + e];
+        a[e] = gte / (1.0f + __expf(-gte)) * up;
+      }
+      *(uint2*)(o + frag_offset(m, rb * 16 + 8 * q + 4 * hb, N >> 6)) = make_uint2(pack2h(a[0], a[1]), pack2h(a[2], a[3]));
+    }
+  }
 }
 
 // Write one finished 64 x 32 output block held in MFMA accumulator order: lane (col, hb) has, for both row blocks,
@@ -70,28 +94,9 @@ __device__ __forceinline__ void mma_frags(const Frags<MB>& f, f32x16_t (&acc)[2]
 template <int EPI>
 __device__ __forceinline__ void store_block(const float (&sum)[2][16], int m, int hb, int rb0, int rb1, int split, int M,
                                           int N, void* __restrict__ out, const SampleEpilogue& se, int tile) {
-  if (EPI == kEpiPartial) {
-    float* o = (float*)out + ((size_t)split * M + m) * N;
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = (nb ? rb1 : rb0) * 32 + 8 * q + 4 * hb;
-        *(float4*)(o + n) = make_float4(sum[nb][4 * q], sum[nb][4 * q + 1], sum[nb][4 * q + 2], sum[nb][4 * q + 3]);
-      }
-  } else if (EPI == kEpiSwiGLU) {
-    uint16_t* o = (uint16_t*)out;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      float a[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float gte = sum[0][4 * q + e], up = sum[1][4 * q + e];
-        a[e] = gte / (1.0f + __expf(-gte)) * up;
-      }
-      const int n = rb0 * 32 + 8 * q + 4 * hb;
-      *(uint2*)(o + frag_offset(m, n, N >> 6)) = make_uint2(pack2h(a[0], a[1]), pack2h(a[2], a[3]));
-    }
+  if (EPI == kEpiPartial || EPI == kEpiSwiGLU) {
+    store_rowblock<EPI>(sum[0], m, hb, rb0, split, M, N, out);
+    store_rowblock<EPI>(sum[1], m, hb, rb1, split, M, N, out);
   } else {
     // lane (col, hb) holds 32 logits of row m: vocabulary ids (rb*32 + 8q + 4hb + e), in aligned groups of four,
     // i.e. one Philox block per group.
@@ -136,28 +141,29 @@ __device__ __forceinline__ void store_block(const float (&sum)[2][16], int m, in
 
 // grid: x = N tile, y = K split, z = M tile of 32*MB rows.
 //   EPI == kEpiPartial: tile = 64 output columns (row blocks 2x, 2x+1 of W); out fp32 [S][M][N].
-//   EPI == kEpiSwiGLU : tile = 32 output columns (gate block x, up block x + N/32); out bf16 fragment-major [M x N].
+//   EPI == kEpiSwiGLU : tile = 32 output columns (row blocks 2x, 2x+1 of the interleaved gate/up matrix, each 16 gate
+//                       rows and the 16 up rows of the same outputs); out f16 fragment-major [M x N].
 //   EPI == kEpiSample : tile = 64 vocabulary entries; the logits stay in registers: temperature, Gumbel noise, running
 //                       arg-max and log-sum-exp are taken per (row, tile) and only those partials are written
 //                       (plus the logits themselves when the caller asked for them).
 // ST = k blocks a wave keeps in flight.  HBM latency is ~10x the MFMA time of a block, so the loop is a ring of
 // ST register buffers: compute block i, immediately re-issue its buffer for block i + ST.  The scheduling
 // barriers keep the compiler from sinking the loads below the next block's MFMAs.
-template <int MB, int EPI, int ST>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ W,
-                                                        void* __restrict__ out, int M, int N, int K, int kb_per_wave,
-                                                        SampleEpilogue se) {
-  __shared__ float red[4][16][64];
+// One tile of RB 32-row blocks (rb_first .. rb_first + RB - 1) over the K range of `split`, for batch tile m_tile:
+// the body of the K-split kernels.  `tile` is the index of the 64-entry vocabulary tile (sampling epilogue, RB == 2).
+template <int MB, int EPI, int ST, int RB>
+__device__ __forceinline__ void kslice_tile(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ W,
+                                            void* __restrict__ out, int M, int N, int K, int kb_per_wave,
+                                            const SampleEpilogue& se, int rb_first, int split, int m_tile, int tile,
+                                            float (&red)[4][16][64]) {
+  static_assert(EPI != kEpiSample || RB == 2, "the sampling epilogue works on 64-entry tiles");
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int KB = K >> 6;
-  const int m_blk0 = blockIdx.z * MB;
+  const int m_blk0 = m_tile * MB;
   const int n_blocks_m = (M + 31) >> 5;
-
-  int rb0, rb1;
-  if (EPI == kEpiSwiGLU) { rb0 = blockIdx.x; rb1 = blockIdx.x + (N >> 5); }
-  else                   { rb0 = blockIdx.x * 2; rb1 = rb0 + 1; }
-  const u32x4_t* w0 = W + (size_t)rb0 * KB * 256;
-  const u32x4_t* w1 = W + (size_t)rb1 * KB * 256;
+  const u32x4_t* wr[RB];
+#pragma unroll
+  for (int nb = 0; nb < RB; ++nb) wr[nb] = W + (size_t)(rb_first + nb) * KB * 256;
   const u32x4_t* xb[MB];
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
@@ -166,27 +172,27 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const u32x4_t* __restric
     xb[mb] = X + (size_t)b * KB * 256;
   }
 
-  f32x16_t acc[2][MB];
+  f32x16_t acc[RB][MB];
 #pragma unroll
-  for (int nb = 0; nb < 2; ++nb)
+  for (int nb = 0; nb < RB; ++nb)
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[nb][mb][r] = 0.f;
 
-  const int kb0 = (blockIdx.y * 4 + wave) * kb_per_wave;
+  const int kb0 = (split * 4 + wave) * kb_per_wave;
   const int n = kb_per_wave;
-  Frags<MB> f[ST];
+  Frags<MB, RB> f[ST];
 #pragma unroll
-  for (int s = 0; s < ST; ++s) load_frags<MB>(f[s], w0, w1, xb, kb0 + s, lane);  // the launcher guarantees ST <= n
+  for (int s = 0; s < ST; ++s) load_frags<MB, RB>(f[s], wr, xb, kb0 + s, lane);  // the launcher guarantees ST <= n
   const int full = n / ST, rem = n - full * ST;
   int b = 0;
   for (int r = 0; r + 1 < full; ++r) {  // steady state: every buffer is refilled
 #pragma unroll
     for (int s = 0; s < ST; ++s) {
-      mma_frags<MB>(f[s], acc);
+      mma_frags<MB, RB>(f[s], acc);
       __builtin_amdgcn_sched_barrier(0);
-      load_frags<MB>(f[s], w0, w1, xb, kb0 + b + s + ST, lane);
+      load_frags<MB, RB>(f[s], wr, xb, kb0 + b + s + ST, lane);
       __builtin_amdgcn_sched_barrier(0);
     }
     b += ST;
@@ -194,24 +200,23 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const u32x4_t* __restric
   if (full > 0) {  // last full round: refill only what the remainder round will use
 #pragma unroll
     for (int s = 0; s < ST; ++s) {
-      mma_frags<MB>(f[s], acc);
+      mma_frags<MB, RB>(f[s], acc);
       __builtin_amdgcn_sched_barrier(0);
-      if (s < rem) load_frags<MB>(f[s], w0, w1, xb, kb0 + b + s + ST, lane);
+      if (s < rem) load_frags<MB, RB>(f[s], wr, xb, kb0 + b + s + ST, lane);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
 #pragma unroll
   for (int s = 0; s < ST; ++s)
-    if (s < rem) mma_frags<MB>(f[s], acc);
+    if (s < rem) mma_frags<MB, RB>(f[s], acc);
 
-  // ---- add the four waves' accumulators (fixed order) and write --------------------------------
-  // Output block mb is finished by wave mb % 4, which takes both row blocks (needed by SwiGLU).
+  // ---- add the four waves' accumulators (fixed order) and write: column block mb is finished by wave mb % 4 ----
   const int col = lane & 31, hb = lane >> 5;
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
-    float sum[2][16];
+    float sum[RB][16];
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
+    for (int nb = 0; nb < RB; ++nb) {
       __syncthreads();
 #pragma unroll
       for (int r = 0; r < 16; ++r) red[wave][r][lane] = acc[nb][mb][r];
@@ -225,7 +230,43 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const u32x4_t* __restric
     if (wave != (mb & 3)) continue;
     const int m = (m_blk0 + mb) * 32 + col;
     if (m >= M) continue;
-    store_block<EPI>(sum, m, hb, rb0, rb1, blockIdx.y, M, N, out, se, blockIdx.x);
+    if constexpr (EPI == kEpiSample) {
+      store_block<EPI>(sum, m, hb, rb_first, rb_first + 1, split, M, N, out, se, tile);
+    } else {
+#pragma unroll
+      for (int nb = 0; nb < RB; ++nb) store_rowblock<EPI>(sum[nb], m, hb, rb_first + nb, split, M, N, out);
+    }
+  }
+}
+
+template <int MB, int EPI, int ST>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ W,
+                                                        void* __restrict__ out, int M, int N, int K, int kb_per_wave,
+                                                        SampleEpilogue se) {
+  __shared__ float red[4][16][64];
+  kslice_tile<MB, EPI, ST, 2>(X, W, out, M, N, K, kb_per_wave, se, blockIdx.x * 2, blockIdx.y, blockIdx.z, blockIdx.x, red);
+}
+
+// The same with tiles of two sizes in one launch, for matrices whose row blocks times K splits are three per compute
+// unit (768 on this chip): n_big tiles of two row blocks per split come first in the grid, then n_small tiles of one.
+// Two blocks fit a compute unit, and blocks are handed out in grid order to whatever unit has room: the first 256 land
+// one per unit, the second 256 fill the remaining place of each, so every unit streams three row blocks -- the same
+// bytes everywhere -- with two blocks resident, each hiding the other's start and end.  (Tiles of one size leave either
+// 384 blocks, i.e. half of the units with twice the bytes of the rest, or 256 with nothing to overlap.)  Same K
+// ranges, same order: same bits as every other variant.
+// grid: x = splits * (n_big + n_small), z = M tile of 32*MB rows.
+template <int MB, int EPI, int ST>
+__global__ __launch_bounds__(256) void gemm_bf16_mixed_kernel(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ W,
+                                                              void* __restrict__ out, int M, int N, int K, int kb_per_wave,
+                                                              int n_big, int n_small, int splits, SampleEpilogue se) {
+  static_assert(EPI != kEpiSample, "per-row-block epilogues only");
+  __shared__ float red[4][16][64];
+  const int id = blockIdx.x, all_big = splits * n_big;  // block-uniform
+  if (id < all_big) {
+    kslice_tile<MB, EPI, ST, 2>(X, W, out, M, N, K, kb_per_wave, se, (id % n_big) * 2, id / n_big, blockIdx.z, 0, red);
+  } else {
+    const int j = id - all_big;
+    kslice_tile<MB, EPI, ST, 1>(X, W, out, M, N, K, kb_per_wave, se, 2 * n_big + j % n_small, j / n_small, blockIdx.z, 0, red);
   }
 }
 
@@ -253,8 +294,8 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_wide_kernel(const u32x4_t* _
 #pragma unroll
   for (int p = 0; p < 2; ++p) {
     tile[p] = min((int)blockIdx.x * 2 + p, n_tiles - 1);  // an odd tile count: the last block's second pair shadows its first
-    if (EPI == kEpiSwiGLU) { rb[2 * p] = tile[p]; rb[2 * p + 1] = tile[p] + (N >> 5); }
-    else                   { rb[2 * p] = tile[p] * 2; rb[2 * p + 1] = tile[p] * 2 + 1; }
+    rb[2 * p] = tile[p] * 2;
+    rb[2 * p + 1] = tile[p] * 2 + 1;
   }
   const bool second_valid = (int)blockIdx.x * 2 + 1 < n_tiles;
   const u32x4_t* wp[4];
@@ -375,10 +416,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_cols_kernel(const u32x4_t* __re
   if (m_blk0 >= n_blocks_m) return;  // this wave has no rows (no barriers below)
 
   int rb0, rb1;
-  if (EPI == kEpiSwiGLU) { rb0 = blockIdx.x; rb1 = blockIdx.x + (N >> 5); }
-  else                   { rb0 = blockIdx.x * 2; rb1 = rb0 + 1; }
-  const u32x4_t* w0 = W + (size_t)rb0 * KB * 256;
-  const u32x4_t* w1 = W + (size_t)rb1 * KB * 256;
+  rb0 = blockIdx.x * 2;  // SwiGLU: the gate/up matrix is interleaved in 16-row groups, so this holds for it too
+  rb1 = rb0 + 1;
+  const u32x4_t* const wr[2] = {W + (size_t)rb0 * KB * 256, W + (size_t)rb1 * KB * 256};
   const u32x4_t* xb[MBW];
 #pragma unroll
   for (int mb = 0; mb < MBW; ++mb) {
@@ -390,7 +430,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_cols_kernel(const u32x4_t* __re
   const int rounds = kb_per_quarter / ST;  // the launcher picks ST so that it divides kb_per_quarter
   Frags<MBW> f[ST];
 #pragma unroll
-  for (int s = 0; s < ST; ++s) load_frags<MBW, false>(f[s], w0, w1, xb, kb0 + s, lane);
+  for (int s = 0; s < ST; ++s) load_frags<MBW, 2, false>(f[s], wr, xb, kb0 + s, lane);
   // One K quarter into a fresh accumulator.  The register ring keeps running across quarters: every block but the
   // last ST of the whole range re-issues its buffer for the block ST ahead.
   auto quarter = [&](f32x16_t (&a)[2][MBW], int q, bool last) __attribute__((always_inline)) {
@@ -405,15 +445,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_cols_kernel(const u32x4_t* __re
     for (int r = 0; r < refill_rounds; ++r) {
 #pragma unroll
       for (int s = 0; s < ST; ++s) {
-        mma_frags<MBW>(f[s], a);
+        mma_frags<MBW, 2>(f[s], a);
         __builtin_amdgcn_sched_barrier(0);
-        load_frags<MBW, false>(f[s], w0, w1, xb, base + r * ST + s + ST, lane);
+        load_frags<MBW, 2, false>(f[s], wr, xb, base + r * ST + s + ST, lane);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
     if (last) {
 #pragma unroll
-      for (int s = 0; s < ST; ++s) mma_frags<MBW>(f[s], a);
+      for (int s = 0; s < ST; ++s) mma_frags<MBW, 2>(f[s], a);
     }
   };
   f32x16_t acc[2][MBW], other[2][MBW];
@@ -460,8 +500,8 @@ __global__ __launch_bounds__(256, MBW == 1 ? 2 : 1) void gemm_bf16_lds_kernel(co
   if (!has_rows) m_blk0 = n_blocks_m - 1;  // idle waves shadow a valid block (they still carry tiles and barriers)
 
   int rb0, rb1;
-  if (EPI == kEpiSwiGLU) { rb0 = blockIdx.x; rb1 = blockIdx.x + (N >> 5); }
-  else                   { rb0 = blockIdx.x * 2; rb1 = rb0 + 1; }
+  rb0 = blockIdx.x * 2;  // SwiGLU: the gate/up matrix is interleaved in 16-row groups, so this holds for it too
+  rb1 = rb0 + 1;
   const u32x4_t* w0 = W + (size_t)rb0 * KB * 256 + tid;
   const u32x4_t* w1 = W + (size_t)rb1 * KB * 256 + tid;
   const u32x4_t* xb[MBW];
@@ -589,8 +629,8 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_lds4_kernel(const u32x4_t* _
 #pragma unroll
   for (int p = 0; p < 2; ++p) {
     tile[p] = min(tile_x * 2 + p, n_tiles - 1);
-    if (EPI == kEpiSwiGLU) { rb[2 * p] = tile[p]; rb[2 * p + 1] = tile[p] + (N >> 5); }
-    else                   { rb[2 * p] = tile[p] * 2; rb[2 * p + 1] = tile[p] * 2 + 1; }
+    rb[2 * p] = tile[p] * 2;
+    rb[2 * p + 1] = tile[p] * 2 + 1;
   }
   const bool second_valid = tile_x * 2 + 1 < n_tiles;
   const u32x4_t* wp[4];
@@ -717,8 +757,8 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_lds8_kernel(const u32x4_t* _
 #pragma unroll
   for (int p = 0; p < 2; ++p) {
     tile[p] = min(tile_x * 2 + p, n_tiles - 1);
-    if (EPI == kEpiSwiGLU) { rb[2 * p] = tile[p]; rb[2 * p + 1] = tile[p] + (N >> 5); }
-    else                   { rb[2 * p] = tile[p] * 2; rb[2 * p + 1] = tile[p] * 2 + 1; }
+    rb[2 * p] = tile[p] * 2;
+    rb[2 * p + 1] = tile[p] * 2 + 1;
   }
   const bool second_valid = tile_x * 2 + 1 < n_tiles;
   const u32x4_t* wp[2];
@@ -867,6 +907,31 @@ void launch_wide(hipStream_t s, const void* X, const void* W, void* out, int M, 
     gemm_bf16_wide_kernel<MB, kEpiPartial, ST><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, se);
 }
 
+// Tiles of two sizes (see gemm_bf16_mixed_kernel): used when the matrix has exactly three (row block, K split) units
+// per compute unit.
+constexpr int kComputeUnits = 256;
+bool mixed_fits(int N, int K, int epi, bool allow_split) {
+  if (epi == kEpiSample) return false;
+  const Plan p = make_plan(N, K, epi, allow_split);
+  const int row_blocks = (epi == kEpiSwiGLU ? 2 * N : N) >> 5;
+  return row_blocks % 3 == 0 && row_blocks * p.splits == 3 * kComputeUnits;
+}
+
+template <int MB, int ST>
+void launch_mixed(hipStream_t s, const void* X, const void* W, void* out, int M, int N, int K, int epi, bool allow_split,
+                  const SampleEpilogue& se) {
+  const Plan p = make_plan(N, K, epi, allow_split);  // same K split as the other variants: bit-identical results
+  const int row_blocks = (epi == kEpiSwiGLU ? 2 * N : N) >> 5, third = row_blocks / 3;
+  const int m_tiles = (M + 32 * MB - 1) / (32 * MB);
+  dim3 grid(p.splits * 2 * third, 1, m_tiles);
+  if (epi == kEpiSwiGLU)
+    gemm_bf16_mixed_kernel<MB, kEpiSwiGLU, ST><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K,
+                                                                    p.kb_per_wave, third, third, p.splits, se);
+  else
+    gemm_bf16_mixed_kernel<MB, kEpiPartial, ST><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K,
+                                                                     p.kb_per_wave, third, third, p.splits, se);
+}
+
 // Blocks of the 128-row tiling for (N, K): it is used where they still fill the chip.
 int wide_blocks(int N, int K, int epi, bool allow_split) {
   const Plan p = make_plan(N, K, epi, allow_split);
@@ -987,7 +1052,11 @@ void launch_gemm_bf16(hipStream_t s, const void* X, const void* W, void* out, in
   // at 32 rows, 20.5 -> 17.8 us at 64); measured a loss for gate/up and the output projection, which keep 64-row tiles.
   const bool wide = epi == kEpiPartial && make_plan(N, K, epi, allow_split).splits > 1 &&
                     wide_blocks(N, K, epi, allow_split) >= 192 && make_plan(N, K, epi, allow_split).kb_per_wave >= 2;
-  if (M <= 32 && wide) launch_wide<1, 2>(s, X, W, out, M, N, K, epi, allow_split, e);
+  const bool mixed = mixed_fits(N, K, epi, allow_split);
+  const int kbw = make_plan(N, K, epi, allow_split).kb_per_wave;
+  if (M <= 32 && mixed && kbw >= 4) launch_mixed<1, 4>(s, X, W, out, M, N, K, epi, allow_split, e);
+  else if (M <= 64 && M > 32 && mixed && kbw >= 2) launch_mixed<2, 2>(s, X, W, out, M, N, K, epi, allow_split, e);
+  else if (M <= 32 && wide) launch_wide<1, 2>(s, X, W, out, M, N, K, epi, allow_split, e);
   else if (M <= 32) launch_st<1>(s, X, W, out, M, N, K, epi, allow_split, 4, e);
   else if (M <= 64 && wide) launch_wide<2, 2>(s, X, W, out, M, N, K, epi, allow_split, e);
   else if (M <= 64) launch_st<2>(s, X, W, out, M, N, K, epi, allow_split, 2, e);

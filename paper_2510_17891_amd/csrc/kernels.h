@@ -80,6 +80,8 @@ int attn_bf16_max_segments(int max_ctx);
 // launch_qk_rope_append is not called.  Only for batches with one row per sequence: the block of a row is then the
 // only one that needs the row's new key, and it takes it from registers, not from the page.  The arithmetic is the
 // one of launch_qk_rope_append, bit for bit.
+// segs_per_block (1..16): segments one block takes of a context of more than 16 segments (> 4096 keys); results do
+// not depend on it.
 constexpr int kAttnAppendMaxSplits = 4;
 struct AttnAppend {
   const float* qkv_part;  // [S][M][(n_q + 2 n_kv) * d]
@@ -92,7 +94,7 @@ void launch_attn_decode_bf16(hipStream_t s, const Geometry& g, const float* q, c
                              const int32_t* block_table, void* k_pool_layer, void* v_pool_layer,
                              float* part, int max_segs_alloc, int max_ctx_in_batch, void* o_out, int M,
                              const int32_t* skip_segs = nullptr, const AttnShared* shared = nullptr, int n_shared = 0,
-                             int max_shared_segs = 0, const AttnAppend* append = nullptr);
+                             int max_shared_segs = 0, const AttnAppend* append = nullptr, int segs_per_block = 16);
 // fp32, any head_dim <= 256: one wave per (row, q head), whole context, output fp32 row-major [M][n_q*d].
 void launch_attn_f32(hipStream_t s, const Geometry& g, const float* q, const RowMeta* rows,
                      const int32_t* block_table, const void* k_pool_layer, const void* v_pool_layer,

@@ -161,6 +161,7 @@ struct rl_model {
   int ring_next = 0;
   float* capture = nullptr;
   bool graph_alive = false;     // a decode graph owns the last two metadata slots
+  int attn_segs_per_block = 4;  // segments per attention block of contexts beyond 4096 keys (one per wave)
   bool share_attention = true;  // compute segments inside shared prompt pages once per set of rows
   bool attention_appends = true;  // decode steps: the attention kernel forms q and appends k, v itself
   // profiling
@@ -261,7 +262,7 @@ int run_layers(rl_model* m, hipStream_t st, int M, const RowMeta* rows, int max_
       Timer t(m, st, K_ATTN);
       const AttnAppend ap = {part, s_qkv, q_gain, k_gain, rope};
       launch_attn_decode_bf16(st, g, q, rows, bt, m->k_pool(l), m->v_pool(l), apart, m->lay.max_segs, max_ctx_in_batch, o, M,
-                              sa.skip, sa.sets, sa.n_sets, sa.max_segs, fused ? &ap : nullptr);
+                              sa.skip, sa.sets, sa.n_sets, sa.max_segs, fused ? &ap : nullptr, m->attn_segs_per_block);
     } else {
       Timer t(m, st, K_ATTN);
       launch_attn_f32(st, g, q, rows, bt, m->k_pool(l), m->v_pool(l), (float*)o, M);
@@ -611,6 +612,13 @@ rl_status rl_debug_shuffle_free_pages(rl_model* m, uint64_t seed) {
 rl_status rl_debug_share_attention(rl_model* m, int32_t on) {
   if (!m) return fail(RL_ERR_INVALID_ARG, "model is NULL");
   m->share_attention = on != 0;
+  return RL_OK;
+}
+
+rl_status rl_debug_attention_split(rl_model* m, int32_t segs_per_block) {
+  if (!m) return fail(RL_ERR_INVALID_ARG, "model is NULL");
+  if (segs_per_block < 1 || segs_per_block > 16) return fail(RL_ERR_INVALID_ARG, "segs_per_block %d outside [1, 16]", segs_per_block);
+  m->attn_segs_per_block = segs_per_block;
   return RL_OK;
 }
 

@@ -239,14 +239,14 @@ def test_fork_errors_and_long_run_of_steps(amd):
 
 
 # ------------------------------------------------------------------------- bf16, one layer at 8B dimensions
-def _layer_case(amd, ctxs, seed, max_rows=None, shuffle=None, extra_pages=0, **shape_over):
+def _layer_case(amd, ctxs, seed, max_rows=None, shuffle=None, extra_pages=0, max_seqs=None, **shape_over):
     """Import random N(0,1) bf16 KV of the given lengths, run one decode step on N(0,1) hidden rows."""
     shape = dict(ri.SHAPES["layer8b"], **shape_over)
     w, wn = make_both(shape, seed)
     B = len(ctxs)
     max_ctx = (max(ctxs) + 1 + 15) // 16 * 16 + 16
     pages = sum((c + 1 + 15) // 16 for c in ctxs) + 4 + extra_pages
-    ro = amd.Rollout(shape, to_device(w), max_seqs=B, max_ctx=max_ctx, max_rows=max_rows or B, kv_pages=pages)
+    ro = amd.Rollout(shape, to_device(w), max_seqs=max_seqs or B, max_ctx=max_ctx, max_rows=max_rows or B, kv_pages=pages)
     if shuffle is not None:
         ro.rl_debug_shuffle_free_pages(shuffle)
     nkv, d, H = shape["n_kv"], shape["head_dim"], shape["hidden"]
@@ -290,6 +290,24 @@ def test_bf16_layer_decode_matches_oracle(amd, ctxs):
         assert err < 3e-2, (b, c, err)
         assert ro.rl_seq_len(b) == c + 1
     ro.close()
+
+
+def test_bf16_layer_bits_do_not_depend_on_attention_block_size(amd):
+    """Contexts beyond 4096 keys are cut over several attention blocks per (row, kv head); how many segments a block
+    takes is a launch parameter.  Outputs are bit-equal for every choice (also one that leaves a block a single
+    segment), with rows on both sides of the switch and a forked pair that shares its prompt pages."""
+    ctxs = [16383, 5000, 4097, 4096, 300, 9000]
+    outs = []
+    for spb in (16, 8, 5, 4, 1):
+        shape, wn, ro, ks, vs, x = _layer_case(amd, ctxs, seed=40, shuffle=5, max_rows=8, extra_pages=8, max_seqs=8)
+        ro.rl_debug_attention_split(spb)
+        ro.rl_seq_fork(5, [6])
+        xin = torch.cat([x, x[5:6]])
+        outs.append(ro.rl_decode_hidden(list(range(7)), xin.to(DEV)).cpu())
+        ro.close()
+    for o in outs[1:]:
+        assert torch.equal(o, outs[0])
+    assert torch.equal(outs[0][5], outs[0][6])
 
 
 def test_bf16_layer_pages_far_into_a_large_pool(amd):
