@@ -48,6 +48,9 @@ def lib():
                                     C.c_int32, _f32p, _f64p]
         L.orc_layer_forward.argtypes = [C.POINTER(_Dims), C.POINTER(_Layer), _f32p, C.c_int32,
                                         _f32p, _f32p]
+        L.orc_model_forward_token.restype = None
+        L.orc_model_forward_token.argtypes = [C.POINTER(_Dims), C.c_int32, C.POINTER(_Layer), _f32p, _f32p, _f32p, C.c_int32,
+                                              C.c_int32, C.c_int32, C.POINTER(_f32p), C.POINTER(_f32p), _f32p, _f32p]
         L.orc_philox4x32_10.argtypes = [C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
                                         C.POINTER(C.c_uint32)]
         L.orc_token_bits.restype = C.c_uint32
@@ -233,7 +236,8 @@ def layer_forward(dims, layer, x, pos, kcache, vcache):
 
 
 class OracleModel:
-    """Whole decoder with per-sequence contiguous KV histories.
+    """Whole decoder with per-sequence contiguous KV histories; the arithmetic is orc_model_forward_token (C++), this
+    class only keeps the arrays and the per-sequence positions.
 
     weights: dict with 'embed' [V,H], 'lm_head' [V,H], 'final_norm' [H] and
     'layers' = list of per-layer dicts (LAYER_KEYS), all fp32 numpy arrays that
@@ -246,41 +250,41 @@ class OracleModel:
         self.max_ctx = max_ctx
         self.n_layers = len(weights["layers"])
         self.seqs = {}
+        self._dm = _Dims(dims["hidden"], dims["n_q"], dims["n_kv"], dims["head_dim"], dims["ffn"],
+                         int(dims["qk_norm"]), dims["rms_eps"], dims["rope_base"])
+        for l in weights["layers"]:
+            for k in LAYER_KEYS:
+                assert l[k].dtype == np.float32 and l[k].flags["C_CONTIGUOUS"]
+        self._layers = (_Layer * max(1, self.n_layers))(*[_Layer(*[_p(l[k]) for k in LAYER_KEYS])
+                                                          for l in weights["layers"]])
+        for k in ("embed", "lm_head", "final_norm"):
+            assert weights[k].dtype == np.float32 and weights[k].flags["C_CONTIGUOUS"]
+        self.vocab = weights["lm_head"].shape[0]
 
     def _cache(self, seq):
         if seq not in self.seqs:
             shape = (self.max_ctx, self.dims["n_kv"], self.dims["head_dim"])
-            self.seqs[seq] = dict(
-                len=0,
-                k=[np.zeros(shape, np.float32) for _ in range(self.n_layers)],
-                v=[np.zeros(shape, np.float32) for _ in range(self.n_layers)])
+            k = [np.zeros(shape, np.float32) for _ in range(self.n_layers)]
+            v = [np.zeros(shape, np.float32) for _ in range(self.n_layers)]
+            fpp = C.POINTER(C.c_float) * max(1, self.n_layers)
+            self.seqs[seq] = dict(len=0, k=k, v=v, kp=fpp(*[_p(a) for a in k]), vp=fpp(*[_p(a) for a in v]))
         return self.seqs[seq]
 
     def free(self, seq):
         self.seqs.pop(seq, None)
 
-    def hidden_forward(self, seq, x, capture=None):
-        """Run all layers on residual `x` at the sequence's next position."""
+    def forward_token(self, seq, tok, want_hidden=False):
+        """Feed one token, extend the history, return the next-token logits [V] (and the last residual stream)."""
         st = self._cache(seq)
         pos = st["len"]
-        x = f32(x).copy()
-        for l in range(self.n_layers):
-            if capture is not None:
-                capture.append(x.copy())
-            layer_forward(self.dims, self.w["layers"][l], x, pos, st["k"][l], st["v"][l])
-        if capture is not None:
-            capture.append(x.copy())
+        assert pos < self.max_ctx and 0 <= int(tok) < self.w["embed"].shape[0]
+        logits = np.empty(self.vocab, np.float32)
+        hidden = np.empty(self.dims["hidden"], np.float32)
+        lib().orc_model_forward_token(C.byref(self._dm), self.n_layers, self._layers, _p(self.w["embed"]),
+                                      _p(self.w["lm_head"]), _p(self.w["final_norm"]), self.vocab, int(tok), pos,
+                                      st["kp"], st["vp"], _p(logits), _p(hidden))
         st["len"] = pos + 1
-        return x
-
-    def logits_from_hidden(self, x):
-        h = rmsnorm(x, self.w["final_norm"], self.dims["rms_eps"])
-        return matvec(self.w["lm_head"], h)
-
-    def forward_token(self, seq, tok):
-        """Feed one token, extend the history, return the next-token logits [V]."""
-        x = self.w["embed"][tok]
-        return self.logits_from_hidden(self.hidden_forward(seq, x))
+        return (logits, hidden) if want_hidden else logits
 
     def prefill(self, seq, tokens):
         z = None

@@ -21,7 +21,7 @@
 // Parity pins (tests/test_oracle_*.py): softmax rows sum to one, one-key
 // attention returns V, RoPE keeps norms and is relative, RMSNorm scale
 // invariance, SiLU identities, brute-force matvec, prefill-vs-decode
-// consistency, zero-layer model = one matvec, published known-answer vectors
+// consistency, zero-layer model = one matvec, the whole-model step against its own composition from the pinned parts, published known-answer vectors
 // of the counter generator, log accuracy against libm, Gumbel-max frequencies
 // against softmax on a tiny vocabulary; for the objective: ratio-one closed form, zero-sum advantages, clip
 // cases worked by hand, class weights, both printed forms of the clipped term.  No function here is
@@ -241,6 +241,22 @@ void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t ou
   }
   out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
+
+// The whole decoder for one token of one sequence: x = E[token]; the n_layers blocks in order, each appending its
+// key and value at `pos` of its own contiguous cache (kcaches[l], vcaches[l]: [max_ctx][n_kv][head_dim]); logits =
+// W_lm rmsnorm(x, g_final) over the untied output matrix.  hidden_out (may be null) receives the residual stream
+// that leaves the last block.  This is the function a rollout iterates: feed a token, read the next-token logits.
+void orc_model_forward_token(const orc_dims* dm, int32_t n_layers, const orc_layer* layers, const float* embed,
+                             const float* lm_head, const float* final_norm, int32_t vocab, int32_t token, int32_t pos,
+                             float* const* kcaches, float* const* vcaches, float* logits, float* hidden_out) {
+  const int32_t H = dm->hidden;
+  std::vector<float> x(embed + (int64_t)token * H, embed + (int64_t)(token + 1) * H), h(H);
+  for (int32_t l = 0; l < n_layers; ++l) orc_layer_forward(dm, &layers[l], x.data(), pos, kcaches[l], vcaches[l]);
+  if (hidden_out) std::memcpy(hidden_out, x.data(), sizeof(float) * (size_t)H);
+  orc_rmsnorm(x.data(), final_norm, H, dm->rms_eps, h.data());
+  orc_matvec(lm_head, h.data(), vocab, H, logits);
+}
+
 
 // Random word for vocabulary index i of the token generated at absolute
 // position `pos` of sequence `seq`: counter (i >> 2, pos, seq, 0), key = the

@@ -365,3 +365,26 @@ def test_model_zero_layers_is_one_matvec_and_batch_invariance():
     # prefill() is the same chain
     mc = orc.OracleModel(dims, wn, max_ctx=8)
     assert np.array_equal(mc.prefill(0, toks[0]), za[-1])
+
+
+def test_model_step_is_the_composition_of_its_pinned_parts():
+    """orc_model_forward_token (embedding row, the layers in order with their own caches, final norm, output matrix)
+    against the same chain assembled here from the separately pinned functions: equal bits, logits and last residual
+    stream, over several positions of two interleaved sequences; a wrong layer order, cache or position would show."""
+    s, dims, w, wn = _tiny()
+    m = orc.OracleModel(dims, wn, max_ctx=8)
+    toks = ri.tokens((2, 6), s["vocab"], 9, 61).numpy()
+    caches = {q: ([np.zeros((8, s["n_kv"], s["head_dim"]), np.float32) for _ in wn["layers"]],
+                  [np.zeros((8, s["n_kv"], s["head_dim"]), np.float32) for _ in wn["layers"]]) for q in (0, 1)}
+    for pos in range(6):
+        for q in (1, 0):
+            tok = int(toks[q, pos])
+            z, hid = m.forward_token(q, tok, want_hidden=True)
+            x = wn["embed"][tok].copy()
+            for l, lw in enumerate(wn["layers"]):
+                orc.layer_forward(dims, lw, x, pos, caches[q][0][l], caches[q][1][l])
+            assert np.array_equal(hid, x)
+            assert np.array_equal(z, orc.matvec(wn["lm_head"], orc.rmsnorm(x, wn["final_norm"], s["rms_eps"])))
+    # swapping two layers changes the result (the order is observable)
+    swapped = orc.OracleModel(dims, dict(wn, layers=wn["layers"][::-1]), max_ctx=8)
+    assert not np.array_equal(swapped.forward_token(0, int(toks[0, 0])), orc.OracleModel(dims, wn, max_ctx=8).forward_token(0, int(toks[0, 0])))
