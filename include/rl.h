@@ -355,10 +355,15 @@ rl_status rl_hrd_objective(void* stream, int32_t n_prompts, int32_t group_size, 
 /*
  * Reorder a row-major [rows x cols] matrix (device) into the order the projection kernels stream
  * (device, same size, must not overlap src).  RL_BF16: 32-row x 64-column tiles, each stored so that a
- * wavefront reads it as four contiguous 1 KiB pieces in matrix-core operand order; needs rows % 32 == 0
- * and cols % 64 == 0.  RL_F32: plain copy.  No model is needed.
+ * wavefront reads it as four contiguous 1 KiB pieces in matrix-core operand order, the tiles of a 32-row block
+ * ordered so that what the four wavefronts of a block read together is contiguous; needs rows % 64 == 0 and
+ * cols % 256 == 0.  That order depends on how the product is cut along the columns, hence `kind`:
+ * RL_W_SPLIT_K for wqkv, wo and w_down, RL_W_WHOLE_K for w_gate_up and lm_head.  RL_F32: plain copy.  No model
+ * is needed.
  */
-rl_status rl_pack_weight(void* stream, uint32_t dtype, const void* src, void* dst, int64_t rows, int64_t cols);
+typedef enum { RL_W_SPLIT_K = 0, RL_W_WHOLE_K = 1 } rl_weight_kind;
+rl_status rl_pack_weight(void* stream, uint32_t dtype, uint32_t kind, const void* src, void* dst, int64_t rows,
+                         int64_t cols);
 
 /*
  * Continue one sequence as several (the G outputs sampled for one prompt, Section 2.3, from a state that is

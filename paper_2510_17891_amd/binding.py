@@ -17,6 +17,7 @@ RL_ERR_INVALID_ARG, RL_ERR_KV_FULL, RL_ERR_BAD_SEQ = -1, -2, -3
 RL_ERR_CTX_OVERFLOW, RL_ERR_DEVICE, RL_ERR_UNSUPPORTED = -4, -5, -6
 RL_F32, RL_BF16 = 0, 1
 RL_KV_SAME, RL_KV_FP8 = 0, 2
+RL_W_SPLIT_K, RL_W_WHOLE_K = 0, 1
 
 EXPORTS = [
     "rl_kv_page_bytes", "rl_query_workspace", "rl_init_model", "rl_destroy_model", "rl_prefill", "rl_prefill_groups", "rl_score", "rl_hrd_objective",
@@ -104,7 +105,7 @@ def lib():
         L.rl_seq_append_kv.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, _pp, _pp]
         L.rl_decode_hidden.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, _i32p, C.c_void_p, C.c_void_p]
         L.rl_set_capture.argtypes = [C.c_void_p, C.c_void_p]
-        L.rl_pack_weight.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64]
+        L.rl_pack_weight.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64]
         L.rl_debug_shuffle_free_pages.argtypes = [C.c_void_p, C.c_uint64]
         L.rl_debug_share_attention.argtypes = [C.c_void_p, C.c_int32]
         L.rl_debug_attention_appends.argtypes = [C.c_void_p, C.c_int32]
@@ -151,12 +152,13 @@ def make_config(shape, dtype, max_seqs, max_ctx, max_rows, kv_pool_bytes=0, work
     return c
 
 
-def rl_pack_weight(w):
-    """Row-major device matrix -> the order the projection kernels stream (new tensor, same shape)."""
+def rl_pack_weight(w, kind):
+    """Row-major device matrix -> the order the projection kernels stream (new tensor, same shape).
+    kind: RL_W_SPLIT_K for wqkv, wo, w_down; RL_W_WHOLE_K for w_gate_up, lm_head."""
     assert w.is_cuda and w.is_contiguous() and w.dim() == 2
     dt = RL_BF16 if w.dtype == torch.bfloat16 else RL_F32
     out = torch.empty_like(w)
-    check(lib().rl_pack_weight(_stream(), dt, _ptr(w), _ptr(out), w.shape[0], w.shape[1]))
+    check(lib().rl_pack_weight(_stream(), dt, kind, _ptr(w), _ptr(out), w.shape[0], w.shape[1]))
     return out
 
 
@@ -225,11 +227,11 @@ class Rollout:
         def take(d, k):
             return d.pop(k) if consume_weights else d[k]
 
-        def packed(d, keys):
+        def packed(d, keys, kind=RL_W_SPLIT_K):
             parts = [take(d, k) for k in keys]
             src = parts[0].contiguous() if len(parts) == 1 else torch.cat(parts, 0)
             del parts
-            out = rl_pack_weight(src)
+            out = rl_pack_weight(src, kind)
             del src
             return out
 
@@ -241,7 +243,7 @@ class Rollout:
             else:
                 src = torch.cat([g, u], 0)
             del g, u
-            out = rl_pack_weight(src)
+            out = rl_pack_weight(src, RL_W_WHOLE_K)
             del src
             return out
 
@@ -249,7 +251,7 @@ class Rollout:
         w = rl_weights()
         if shape["vocab"] > 0:
             self.embed = take(weights, "embed").contiguous()
-            self.lm_head = packed(weights, ["lm_head"])
+            self.lm_head = packed(weights, ["lm_head"], RL_W_WHOLE_K)
             w.embed, w.lm_head = self.embed.data_ptr(), self.lm_head.data_ptr()
         self.final_norm = take(weights, "final_norm").contiguous()
         w.final_norm = self.final_norm.data_ptr()

@@ -34,15 +34,16 @@ struct Frags {
 
 // wr[nb]: row block nb of the tile; NT: weights pass through once (non-temporal), otherwise the block's other waves
 // read the same tile and it may live in L1/L2.
+// kb: the k block (activations are stored in that order); kw: where the weights keep it (weight_kb_slot).
 template <int MB, int RB, bool NT = true>
 __device__ __forceinline__ void load_frags(Frags<MB, RB>& f, const u32x4_t* const (&wr)[RB],
-                                           const u32x4_t* const* __restrict__ xb, int kb, int lane) {
-  // block (rb, kb) = 256 uint4; sub-load t is [t*64 + lane]
-  const int o = kb * 256 + lane;
+                                           const u32x4_t* const* __restrict__ xb, int kb, int kw, int lane) {
+  // block (rb, slot) = 256 uint4; sub-load t is [t*64 + lane]
+  const int o = kb * 256 + lane, ow = kw * 256 + lane;
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
 #pragma unroll
-    for (int nb = 0; nb < RB; ++nb) f.a[nb][t] = NT ? __builtin_nontemporal_load(wr[nb] + o + t * 64) : wr[nb][o + t * 64];
+    for (int nb = 0; nb < RB; ++nb) f.a[nb][t] = NT ? __builtin_nontemporal_load(wr[nb] + ow + t * 64) : wr[nb][ow + t * 64];
   }
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb)
@@ -181,10 +182,11 @@ __device__ __forceinline__ void kslice_tile(const u32x4_t* __restrict__ X, const
       for (int r = 0; r < 16; ++r) acc[nb][mb][r] = 0.f;
 
   const int kb0 = (split * 4 + wave) * kb_per_wave;
+  const int kw0 = split * 4 * kb_per_wave + wave;  // slot of k block kb0; this wave's later blocks follow at stride 4
   const int n = kb_per_wave;
   Frags<MB, RB> f[ST];
 #pragma unroll
-  for (int s = 0; s < ST; ++s) load_frags<MB, RB>(f[s], wr, xb, kb0 + s, lane);  // the launcher guarantees ST <= n
+  for (int s = 0; s < ST; ++s) load_frags<MB, RB>(f[s], wr, xb, kb0 + s, kw0 + 4 * s, lane);  // the launcher guarantees ST <= n
   const int full = n / ST, rem = n - full * ST;
   int b = 0;
   for (int r = 0; r + 1 < full; ++r) {  // steady state: every buffer is refilled
@@ -192,7 +194,7 @@ __device__ __forceinline__ void kslice_tile(const u32x4_t* __restrict__ X, const
     for (int s = 0; s < ST; ++s) {
       mma_frags<MB, RB>(f[s], acc);
       __builtin_amdgcn_sched_barrier(0);
-      load_frags<MB, RB>(f[s], wr, xb, kb0 + b + s + ST, lane);
+      load_frags<MB, RB>(f[s], wr, xb, kb0 + b + s + ST, kw0 + 4 * (b + s + ST), lane);
       __builtin_amdgcn_sched_barrier(0);
     }
     b += ST;
@@ -202,7 +204,7 @@ __device__ __forceinline__ void kslice_tile(const u32x4_t* __restrict__ X, const
     for (int s = 0; s < ST; ++s) {
       mma_frags<MB, RB>(f[s], acc);
       __builtin_amdgcn_sched_barrier(0);
-      if (s < rem) load_frags<MB, RB>(f[s], wr, xb, kb0 + b + s + ST, lane);
+      if (s < rem) load_frags<MB, RB>(f[s], wr, xb, kb0 + b + s + ST, kw0 + 4 * (b + s + ST), lane);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
@@ -316,12 +318,13 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_wide_kernel(const u32x4_t* _
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[b][mb][r] = 0.f;
 
+  const int kw0 = blockIdx.y * 4 * kb_per_wave + wave - 4 * ((blockIdx.y * 4 + wave) * kb_per_wave);  // slot = kw0 + 4 kb
   auto load = [&](FragsW<MB>& f, int kb) __attribute__((always_inline)) {
-    const int o = kb * 256;
+    const int o = kb * 256, ow = (kw0 + 4 * kb) * 256;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
 #pragma unroll
-      for (int b = 0; b < 4; ++b) f.a[b][t] = __builtin_nontemporal_load(wp[b] + o + t * 64);
+      for (int b = 0; b < 4; ++b) f.a[b][t] = __builtin_nontemporal_load(wp[b] + ow + t * 64);
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) f.b[mb][t] = xb[mb][o + t * 64];
     }
@@ -429,8 +432,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_cols_kernel(const u32x4_t* __re
   const int kb0 = blockIdx.y * 4 * kb_per_quarter;
   const int rounds = kb_per_quarter / ST;  // the launcher picks ST so that it divides kb_per_quarter
   Frags<MBW> f[ST];
+  auto slot = [&](int kb) { return weight_kb_slot(kb, kb_per_quarter); };
 #pragma unroll
-  for (int s = 0; s < ST; ++s) load_frags<MBW, 2, false>(f[s], wr, xb, kb0 + s, lane);
+  for (int s = 0; s < ST; ++s) load_frags<MBW, 2, false>(f[s], wr, xb, kb0 + s, slot(kb0 + s), lane);
   // One K quarter into a fresh accumulator.  The register ring keeps running across quarters: every block but the
   // last ST of the whole range re-issues its buffer for the block ST ahead.
   auto quarter = [&](f32x16_t (&a)[2][MBW], int q, bool last) __attribute__((always_inline)) {
@@ -447,7 +451,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_cols_kernel(const u32x4_t* __re
       for (int s = 0; s < ST; ++s) {
         mma_frags<MBW, 2>(f[s], a);
         __builtin_amdgcn_sched_barrier(0);
-        load_frags<MBW, 2, false>(f[s], wr, xb, base + r * ST + s + ST, lane);
+        load_frags<MBW, 2, false>(f[s], wr, xb, base + r * ST + s + ST, slot(base + r * ST + s + ST), lane);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -514,13 +518,23 @@ __global__ __launch_bounds__(256, MBW == 1 ? 2 : 1) void gemm_bf16_lds_kernel(co
   const int n = 4 * kb_per_quarter;
   const int kb0 = blockIdx.y * n;
   auto kb_of = [&](int i) { return kb0 + (i < n ? i : n - 1); };  // clamped: no conditional loads in the pipeline
+  // Weight k blocks are loaded strictly in order (0, 1, 2, ...; the last one again once the range is exhausted), so
+  // the slot of the next one is kept as (block within its quarter, quarter) and stepped, without a division.
+  int w_r = 0, w_q = 0;
+  auto next_wslot = [&]() {
+    const int off = (((int)blockIdx.y * kb_per_quarter + w_r) * 4 + w_q) * 256;
+    if (w_r + 1 < kb_per_quarter) ++w_r;
+    else if (w_q < 3) { w_r = 0; ++w_q; }
+    return off;
+  };
 
   u32x4_t wr[4][2];          // weight registers: slot s holds a block with index = s (mod 4)
   u32x4_t xr[XS][MBW][4];    // activation fragments: slot s holds a block with index = s (mod XS)
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
-    wr[s][0] = __builtin_nontemporal_load(w0 + (size_t)kb_of(s) * 256);
-    wr[s][1] = __builtin_nontemporal_load(w1 + (size_t)kb_of(s) * 256);
+    const int ow = next_wslot();
+    wr[s][0] = __builtin_nontemporal_load(w0 + ow);
+    wr[s][1] = __builtin_nontemporal_load(w1 + ow);
   }
 #pragma unroll
   for (int s = 0; s < XS; ++s)
@@ -530,16 +544,20 @@ __global__ __launch_bounds__(256, MBW == 1 ? 2 : 1) void gemm_bf16_lds_kernel(co
       for (int t = 0; t < 4; ++t) xr[s][mb][t] = xb[mb][(size_t)kb_of(s) * 256 + t * 64];
   wlds[0][0][tid] = w_to_f16(wr[0][0]);
   wlds[0][1][tid] = w_to_f16(wr[0][1]);
-  wr[0][0] = __builtin_nontemporal_load(w0 + (size_t)kb_of(4) * 256);
-  wr[0][1] = __builtin_nontemporal_load(w1 + (size_t)kb_of(4) * 256);
+  {
+    const int ow = next_wslot();
+    wr[0][0] = __builtin_nontemporal_load(w0 + ow);
+    wr[0][1] = __builtin_nontemporal_load(w1 + ow);
+  }
 
   // One k block: publish the next tile, barrier, multiply this one.  j = i mod 4 at compile time.
   auto iter = [&](f32x16_t (&a)[2][MBW], int i, auto jc) __attribute__((always_inline)) {
     constexpr int j = decltype(jc)::value, jn = (j + 1) & 3, jx = j % XS;
     wlds[jn][0][tid] = w_to_f16(wr[jn][0]);
     wlds[jn][1][tid] = w_to_f16(wr[jn][1]);
-    wr[jn][0] = __builtin_nontemporal_load(w0 + (size_t)kb_of(i + 5) * 256);
-    wr[jn][1] = __builtin_nontemporal_load(w1 + (size_t)kb_of(i + 5) * 256);
+    const int ow = next_wslot();  // k block i + 5
+    wr[jn][0] = __builtin_nontemporal_load(w0 + ow);
+    wr[jn][1] = __builtin_nontemporal_load(w1 + ow);
     // Barrier that orders LDS traffic only: __syncthreads() would also drain every global load in flight
     // (loads and stores share one counter on this ISA), i.e. the whole prefetch pipeline, once per k block.
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -646,31 +664,46 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_lds4_kernel(const u32x4_t* _
   const int n = 4 * kb_per_quarter;
   const int kb0 = blockIdx.y * n;
   auto kb_of = [&](int i) { return kb0 + (i < n ? i : n - 1); };  // clamped: no conditional loads in the pipeline
+  // Weight k blocks are loaded strictly in order (0, 1, 2, ...; the last one again once the range is exhausted), so
+  // the slot of the next one is kept as (block within its quarter, quarter) and stepped, without a division.
+  int w_r = 0, w_q = 0;
+  auto next_wslot = [&]() {
+    const int off = (((int)blockIdx.y * kb_per_quarter + w_r) * 4 + w_q) * 256;
+    if (w_r + 1 < kb_per_quarter) ++w_r;
+    else if (w_q < 3) { w_r = 0; ++w_q; }
+    return off;
+  };
 
   u32x4_t wr[4][4];          // weight registers: slot s holds a k block with index = s (mod 4)
   u32x4_t xr[XS][MBW][4];    // activation fragments: slot s holds a k block with index = s (mod XS)
 #pragma unroll
-  for (int s = 0; s < 4; ++s)
+  for (int s = 0; s < 4; ++s) {
+    const int ow = next_wslot();
 #pragma unroll
-    for (int b = 0; b < 4; ++b) wr[s][b] = __builtin_nontemporal_load(wp[b] + (size_t)kb_of(s) * 256);
+    for (int b = 0; b < 4; ++b) wr[s][b] = __builtin_nontemporal_load(wp[b] + ow);
+  }
 #pragma unroll
   for (int s = 0; s < XS; ++s)
 #pragma unroll
     for (int mb = 0; mb < MBW; ++mb)
 #pragma unroll
       for (int t = 0; t < 4; ++t) xr[s][mb][t] = xb[mb][(size_t)kb_of(s) * 256 + t * 64];
+  {
+    const int ow = next_wslot();
 #pragma unroll
-  for (int b = 0; b < 4; ++b) {
-    wlds[0][b][tid] = w_to_f16(wr[0][b]);
-    wr[0][b] = __builtin_nontemporal_load(wp[b] + (size_t)kb_of(4) * 256);
+    for (int b = 0; b < 4; ++b) {
+      wlds[0][b][tid] = w_to_f16(wr[0][b]);
+      wr[0][b] = __builtin_nontemporal_load(wp[b] + ow);
+    }
   }
 
   auto iter = [&](f32x16_t (&a)[4][MBW], int i, auto jc) __attribute__((always_inline)) {
     constexpr int j = decltype(jc)::value, jn = (j + 1) & 3, jx = j % XS;
+    const int ow = next_wslot();  // k block i + 5
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
       wlds[jn][b][tid] = w_to_f16(wr[jn][b]);
-      wr[jn][b] = __builtin_nontemporal_load(wp[b] + (size_t)kb_of(i + 5) * 256);
+      wr[jn][b] = __builtin_nontemporal_load(wp[b] + ow);
     }
     // barrier that orders LDS traffic only (a full one would drain the global loads in flight)
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -774,31 +807,46 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_lds8_kernel(const u32x4_t* _
   const int n = 4 * kb_per_quarter;
   const int kb0 = blockIdx.y * n;
   auto kb_of = [&](int i) { return kb0 + (i < n ? i : n - 1); };  // clamped: no conditional loads in the pipeline
+  // Weight k blocks are loaded strictly in order (0, 1, 2, ...; the last one again once the range is exhausted), so
+  // the slot of the next one is kept as (block within its quarter, quarter) and stepped, without a division.
+  int w_r = 0, w_q = 0;
+  auto next_wslot = [&]() {
+    const int off = (((int)blockIdx.y * kb_per_quarter + w_r) * 4 + w_q) * 256;
+    if (w_r + 1 < kb_per_quarter) ++w_r;
+    else if (w_q < 3) { w_r = 0; ++w_q; }
+    return off;
+  };
 
   u32x4_t wr[4][2];          // weight registers: slot s holds a k block with index = s (mod 4)
   u32x4_t xr[XS][MBW][4];    // activation fragments: slot s holds a k block with index = s (mod XS)
 #pragma unroll
-  for (int s = 0; s < 4; ++s)
+  for (int s = 0; s < 4; ++s) {
+    const int ow = next_wslot();
 #pragma unroll
-    for (int b = 0; b < 2; ++b) wr[s][b] = __builtin_nontemporal_load(wp[b] + (size_t)kb_of(s) * 256);
+    for (int b = 0; b < 2; ++b) wr[s][b] = __builtin_nontemporal_load(wp[b] + ow);
+  }
 #pragma unroll
   for (int s = 0; s < XS; ++s)
 #pragma unroll
     for (int mb = 0; mb < MBW; ++mb)
 #pragma unroll
       for (int t = 0; t < 4; ++t) xr[s][mb][t] = xb[mb][(size_t)kb_of(s) * 256 + t * 64];
+  {
+    const int ow = next_wslot();
 #pragma unroll
-  for (int b = 0; b < 2; ++b) {
-    wlds[0][2 * half + b][t256] = w_to_f16(wr[0][b]);
-    wr[0][b] = __builtin_nontemporal_load(wp[b] + (size_t)kb_of(4) * 256);
+    for (int b = 0; b < 2; ++b) {
+      wlds[0][2 * half + b][t256] = w_to_f16(wr[0][b]);
+      wr[0][b] = __builtin_nontemporal_load(wp[b] + ow);
+    }
   }
 
   auto iter = [&](f32x16_t (&a)[4][MBW], int i, auto jc) __attribute__((always_inline)) {
     constexpr int j = decltype(jc)::value, jn = (j + 1) & 3, jx = j % XS;
+    const int ow = next_wslot();  // k block i + 5
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
       wlds[jn][2 * half + b][t256] = w_to_f16(wr[jn][b]);
-      wr[jn][b] = __builtin_nontemporal_load(wp[b] + (size_t)kb_of(i + 5) * 256);
+      wr[jn][b] = __builtin_nontemporal_load(wp[b] + ow);
     }
     // barrier that orders LDS traffic only (a full one would drain the global loads in flight)
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -942,6 +990,7 @@ int wide_blocks(int N, int K, int epi, bool allow_split) {
 }  // namespace
 
 int gemm_bf16_splits(int N, int K, int epi) { return make_plan(N, K, epi, true).splits; }
+int gemm_bf16_weight_segment(int N, int K, bool split_k) { return make_plan(N, K, kEpiPartial, split_k).kb_per_wave; }
 
 template <int MB>
 void launch_st(hipStream_t s, const void* X, const void* W, void* out, int M, int N, int K, int epi, bool allow_split,

@@ -1164,16 +1164,17 @@ rl_status rl_sample_logits(rl_model* m, void* stream, int32_t n, const float* lo
   return RL_OK;
 }
 
-rl_status rl_pack_weight(void* stream, uint32_t dtype, const void* src, void* dst, int64_t rows, int64_t cols) {
+rl_status rl_pack_weight(void* stream, uint32_t dtype, uint32_t kind, const void* src, void* dst, int64_t rows, int64_t cols) {
   if (!src || !dst || rows < 1 || cols < 1) return fail(RL_ERR_INVALID_ARG, "bad arguments");
+  if (kind != RL_W_SPLIT_K && kind != RL_W_WHOLE_K) return fail(RL_ERR_INVALID_ARG, "unknown weight kind %u", kind);
   hipStream_t st = (hipStream_t)stream;
   if (dtype == RL_F32) {
     HIP_TRY(hipMemcpyAsync(dst, src, (size_t)rows * cols * 4, hipMemcpyDeviceToDevice, st));
     return RL_OK;
   }
   if (dtype != RL_BF16) return fail(RL_ERR_INVALID_ARG, "unknown dtype");
-  if (rows % 32 || cols % 64 || rows > 0x7fffffff || cols > 0x7fffffff) return fail(RL_ERR_UNSUPPORTED, "bf16 packing needs rows %% 32 == 0 and cols %% 64 == 0");
-  launch_pack_weight_bf16(st, src, dst, (int)rows, (int)cols);
+  if (rows % 64 || cols % 256 || rows > 0x7fffffff || cols > 0x7fffffff) return fail(RL_ERR_UNSUPPORTED, "bf16 packing needs rows %% 64 == 0 and cols %% 256 == 0");
+  launch_pack_weight_bf16(st, src, dst, (int)rows, (int)cols, gemm_bf16_weight_segment((int)rows, (int)cols, kind == RL_W_SPLIT_K));
   HIP_TRY(hipGetLastError());
   return RL_OK;
 }

@@ -219,17 +219,17 @@ void launch_kv_import(hipStream_t s, const Geometry& g, const void* k_src, const
 // Weight packing: row-major [N][K] bf16 -> fragment-major.  One thread per 8 consecutive k.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void pack_weight_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int N,
-                                                          int K) {
+                                                          int K, int seg) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;  // over N * K/8
   const int kg = K >> 3;
   if (idx >= (size_t)N * kg) return;
   const int n = (int)(idx / kg), k = (int)(idx - (size_t)n * kg) * 8;
-  dst[frag_offset(n, k, K >> 6) >> 3] = src[idx];
+  dst[weight_offset(n, k, K >> 6, seg) >> 3] = src[idx];
 }
 
-void launch_pack_weight_bf16(hipStream_t s, const void* src, void* dst, int N, int K) {
+void launch_pack_weight_bf16(hipStream_t s, const void* src, void* dst, int N, int K, int seg) {
   size_t total = (size_t)N * (K >> 3);
-  pack_weight_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const uint4*)src, (uint4*)dst, N, K);
+  pack_weight_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const uint4*)src, (uint4*)dst, N, K, seg);
 }
 
 }  // namespace rl
