@@ -33,10 +33,11 @@ HBM_PEAK_GBS = 8000.0
 # 1 GiB device copy (FETCH_SIZE x 2.0000, WRITE_SIZE x 1.0000).  An entry is used only while the kernel's source
 # file still has the hash it had when the counters were taken; otherwise "traffic" is null.
 TRAFFIC_RATIO = {
-    ("layer", "attn_decode"): (1.016, "attn_bf16.hip", "d7afd3d1a7c9087e"),
-    ("layer", "gemm_gate_up_swiglu"): (1.019, "gemm_bf16.hip", "1a0576369b1c34ea"),
-    ("full", "attn_decode"): (1.035, "attn_bf16.hip", "d7afd3d1a7c9087e"),
-    ("full", "gemm_gate_up_swiglu"): (1.010, "gemm_bf16.hip", "1a0576369b1c34ea"),
+    # one layer at the launch shape of the 128-sequence wave (16 groups x 8 samples, 2048 shared + 7168 private tokens)
+    ("wave", "attn_decode"): (1.054, "attn_bf16.hip", "8769ebfa2ed28cd9"),
+    ("layer", "attn_decode"): (1.054, "attn_bf16.hip", "8769ebfa2ed28cd9"),
+    ("full", "attn_decode"): (1.040, "attn_bf16.hip", "8769ebfa2ed28cd9"),
+    ("full", "gemm_gate_up_swiglu"): (1.011, "gemm_bf16.hip", "548f2fa1caf035c7"),
 }
 
 
@@ -94,6 +95,8 @@ def parse():
     ap.add_argument("--grow", type=int, default=0,
                     help="layer workload: untimed decode steps after the import (the members of a group get private "
                          "tokens on top of the shared context)")
+    ap.add_argument("--grow-append", action="store_true",
+                    help="layer workload: --grow tokens are appended as random keys and values instead of decoded")
     ap.add_argument("--n-prompts", type=int, default=4, help="full workload: prompts (x 8 samples each); 4 is the headline")
     ap.add_argument("--temperature", type=float, default=1.0, help="full workload: sampling temperature")
     ap.add_argument("--top-k", type=int, default=0, help="full workload: top-k cut (0: none)")
@@ -214,7 +217,17 @@ def run_wave(args):
     seq_ids = list(range(B))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    tok, lp = ro.rl_prefill_groups(seq_ids, G, [prompts[i].tolist() for i in range(n_prompts)], 1.0, seed)
+    if args.prefill == "real":
+        tok, lp = ro.rl_prefill_groups(seq_ids, G, [prompts[i].tolist() for i in range(n_prompts)], 1.0, seed)
+    else:
+        # counter runs that should only see decode steps: the prompt's keys and values are imported (N(0,1)) for the
+        # first sample of a group and the others are forked from it, which shares the prompt pages like the prefill does
+        for g in range(n_prompts):
+            kv = [ri.normal((P, nkv, d), 1.0, seed, 6000 + g * L + l, device=dev, dtype=torch.bfloat16) for l in range(L)]
+            ro.rl_seq_import_kv(g * G, kv, kv[::-1])
+            ro.rl_seq_fork(g * G, list(range(g * G + 1, (g + 1) * G)))
+            del kv
+        tok = ri.tokens((B,), shape["vocab"], seed, 961).to(dev)
     torch.cuda.synchronize()
     prefill_s = time.perf_counter() - t0
     if private > 0:
@@ -286,7 +299,8 @@ def run_wave(args):
                    "batch": B, "groups": n_prompts,
                    "group_size": G, "context_first_timed_step": ctx_first, "context_last_timed_step": ctx_last,
                    "kv_block": 16, "temperature": 1.0, "logprob_per_token": True, "shared_prompt_tokens": shared_tok,
-                   "prefill": f"{n_prompts} prompts x {P} tokens run once each, pages shared by the {G} samples of a prompt",
+                   "prefill": (f"{n_prompts} prompts x {P} tokens run once each, pages shared by the {G} samples of a prompt"
+                               if args.prefill == "real" else "prompt keys and values imported, samples forked"),
                    "private_context": f"{private} tokens per sequence of appended N(0,1) keys and values",
                    "kv_pool_GB": pages * rl_page_bytes(shape) * kvb / 2 / 1e9},
         # step-level fractions: per-sequence byte formula (weights once + 4096 B per cached token, layer and sequence),
@@ -797,8 +811,15 @@ def main():
             ro.rl_decode_hidden(ids, x_in, x_out)
 
     if args.workload == "layer":
-        for _ in range(args.grow):
-            step()
+        if args.grow_append and args.grow:
+            # the grown part as appended N(0,1) keys and values, one private stretch per sequence, instead of decode steps
+            for b in seq_ids:
+                k = ri.normal((args.grow, shape["n_kv"], shape["head_dim"]), 1.0, seed, 5000 + b, device=dev,
+                              dtype=torch.bfloat16)
+                ro.rl_seq_append_kv(b, [k], [k])
+        else:
+            for _ in range(args.grow):
+                step()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
