@@ -414,8 +414,11 @@ rl_status rl_debug_attention_split(rl_model* m, int32_t segs_per_block);
  */
 rl_status rl_profile_enable(rl_model* m, int32_t on);
 /* Host microseconds that rl_decode_step spent since the last read (always collected): admission checks (ids, pages),
- * building and uploading the rows / page grants / shared-attention plan, and enqueueing the kernels; and the calls. */
-rl_status rl_profile_host_read(rl_model* m, double* admit_us, double* meta_us, double* launch_us, int64_t* calls);
+ * building and uploading the rows / page grants / shared-attention plan, enqueueing the kernels, and -- apart from
+ * those -- waiting for a metadata slot that the device has not consumed yet (the device is then 62 calls behind the
+ * host; calls of other entry points that take a slot add to this figure too); and the number of calls. */
+rl_status rl_profile_host_read(rl_model* m, double* admit_us, double* meta_us, double* launch_us, double* wait_us,
+                               int64_t* calls);
 rl_status rl_profile_read(rl_model* m, int32_t n_max, const char** names_out, double* ms_out,
                           int64_t* counts_out, int32_t* n_out);
 

@@ -114,7 +114,7 @@ def lib():
         L.rl_profile_enable.argtypes = [C.c_void_p, C.c_int32]
         L.rl_profile_read.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                       C.POINTER(C.c_int64), _i32p]
-        L.rl_profile_host_read.argtypes = [C.c_void_p] + [C.POINTER(C.c_double)] * 3 + [C.POINTER(C.c_int64)]
+        L.rl_profile_host_read.argtypes = [C.c_void_p] + [C.POINTER(C.c_double)] * 4 + [C.POINTER(C.c_int64)]
         _lib = L
     return _lib
 
@@ -417,10 +417,10 @@ class Rollout:
         check(lib().rl_profile_enable(self.h, 1 if on else 0))
 
     def rl_profile_host_read(self):
-        """Host microseconds inside rl_decode_step since the last read: dict(admit, meta, launch, calls)."""
-        a, b, c, n = C.c_double(), C.c_double(), C.c_double(), C.c_int64()
-        check(lib().rl_profile_host_read(self.h, C.byref(a), C.byref(b), C.byref(c), C.byref(n)))
-        return {"admit_us": a.value, "meta_us": b.value, "launch_us": c.value, "calls": n.value}
+        """Host microseconds inside rl_decode_step since the last read: dict(admit, meta, launch, wait, calls)."""
+        a, b, c, w, n = C.c_double(), C.c_double(), C.c_double(), C.c_double(), C.c_int64()
+        check(lib().rl_profile_host_read(self.h, C.byref(a), C.byref(b), C.byref(c), C.byref(w), C.byref(n)))
+        return {"admit_us": a.value, "meta_us": b.value, "launch_us": c.value, "wait_us": w.value, "calls": n.value}
 
     def rl_profile_read(self):
         """{kernel class: (launches, total ms)} since the last read."""

@@ -172,7 +172,7 @@ struct rl_model {
   double prof_ms[K_COUNT];
   int64_t prof_n[K_COUNT];
   // host time of rl_decode_step since the last read: admission checks, metadata build + upload, kernel launches
-  double host_us[3] = {0.0, 0.0, 0.0};
+  double host_us[4] = {0.0, 0.0, 0.0, 0.0};  // admission, metadata, enqueue, wait for a metadata slot
   int64_t host_calls = 0;
 
   template <typename T> T* wsp(size_t off) const { return reinterpret_cast<T*>(ws + off); }
@@ -213,7 +213,11 @@ struct Timer {
 rl_status ring_acquire(rl_model* m, int* slot_out) {
   int s = m->ring_next;
   m->ring_next = (s + 1) % kRingCalls;
-  if (m->ring_used[s]) HIP_TRY(hipEventSynchronize(m->ring_ev[s]));
+  if (m->ring_used[s]) {  // the device is kRingCalls calls behind: the host has nothing better to do than wait
+    const auto t0 = std::chrono::steady_clock::now();
+    HIP_TRY(hipEventSynchronize(m->ring_ev[s]));
+    m->host_us[3] += std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
+  }
   *slot_out = s;
   return RL_OK;
 }
@@ -645,6 +649,7 @@ rl_status rl_decode_step(rl_model* m, void* stream, int32_t n, const int32_t* se
   rl_status rs = admit_decode(m, n, seq_ids, &grants);
   if (rs != RL_OK) return rs;
   const auto t1 = std::chrono::steady_clock::now();
+  const double waited = m->host_us[3];
   const RowMeta* rows;
   int max_ctx_in_batch;
   SharedAttn sa;
@@ -656,16 +661,18 @@ rl_status rl_decode_step(rl_model* m, void* stream, int32_t n, const int32_t* se
   for (int i = 0; i < n; ++i) m->table->set_len(seq_ids[i], m->table->len(seq_ids[i]) + 1);
   const auto t3 = std::chrono::steady_clock::now();
   m->host_us[0] += std::chrono::duration<double, std::micro>(t1 - t0).count();
-  m->host_us[1] += std::chrono::duration<double, std::micro>(t2 - t1).count();
+  m->host_us[1] += std::chrono::duration<double, std::micro>(t2 - t1).count() - (m->host_us[3] - waited);
   m->host_us[2] += std::chrono::duration<double, std::micro>(t3 - t2).count();
   m->host_calls += 1;
   return RL_OK;
 }
 
-rl_status rl_profile_host_read(rl_model* m, double* admit_us, double* meta_us, double* launch_us, int64_t* calls) {
-  if (!m || !admit_us || !meta_us || !launch_us || !calls) return fail(RL_ERR_INVALID_ARG, "NULL argument");
-  *admit_us = m->host_us[0]; *meta_us = m->host_us[1]; *launch_us = m->host_us[2]; *calls = m->host_calls;
-  m->host_us[0] = m->host_us[1] = m->host_us[2] = 0.0;
+rl_status rl_profile_host_read(rl_model* m, double* admit_us, double* meta_us, double* launch_us, double* wait_us,
+                               int64_t* calls) {
+  if (!m || !admit_us || !meta_us || !launch_us || !wait_us || !calls) return fail(RL_ERR_INVALID_ARG, "NULL argument");
+  *admit_us = m->host_us[0]; *meta_us = m->host_us[1]; *launch_us = m->host_us[2]; *wait_us = m->host_us[3];
+  *calls = m->host_calls;
+  m->host_us[0] = m->host_us[1] = m->host_us[2] = m->host_us[3] = 0.0;
   m->host_calls = 0;
   return RL_OK;
 }
