@@ -642,7 +642,8 @@ def main():
         pages = sum(group_page_need(p_len[i], limits[i * G:(i + 1) * G]) for i in range(n_prompts))
         max_ctx = (max(p_len[k // G] + limits[k] for k in range(n_prompts * G)) + 15) // 16 * 16
         w = ri.make_weights(shape, seed, device=dev, dtype=torch.bfloat16)
-        ro = Rollout(shape, w, max_seqs=n_prompts * G, max_ctx=max_ctx, max_rows=256, kv_pages=pages)
+        kvb = 1 if args.kv_fp8 else 2
+        ro = Rollout(shape, w, max_seqs=n_prompts * G, max_ctx=max_ctx, max_rows=256, kv_pages=pages, kv_fp8=args.kv_fp8)
         del w
         torch.cuda.empty_cache()
         torch.cuda.synchronize()
@@ -659,13 +660,13 @@ def main():
         wbytes = 2 * (shape["n_layers"] * (shape["hidden"] * (shape["n_q"] + 2 * shape["n_kv"]) * shape["head_dim"]
                                           + shape["n_q"] * shape["head_dim"] * shape["hidden"]
                                           + 3 * shape["ffn"] * shape["hidden"]) + shape["vocab"] * shape["hidden"])
-        total_bytes = steps * wbytes + kv_tokens * shape["n_layers"] * shape["n_kv"] * 2 * shape["head_dim"] * 2
+        total_bytes = steps * wbytes + kv_tokens * shape["n_layers"] * shape["n_kv"] * 2 * shape["head_dim"] * kvb
         print(json.dumps({
             "metric": "generated tokens/s (8B-shaped bf16 decode) + % peak HBM GB/s, 1 MI355X",
             "value": n_tok / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": 0,
             "ms_per_step": elapsed / max(1, steps) * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
             "dtype": "bf16", "data": "synthetic",
-            "config": {"workload": f"full8b_ragged_{n_prompts}x{G}_scale{sc}", "prompts": "U[256,1024] per prompt",
+            "config": {"workload": f"full8b_ragged_{n_prompts}x{G}_scale{sc}" + ("_kvfp8" if args.kv_fp8 else ""), "prompts": "U[256,1024] per prompt",
                        "final_lengths": "U[1024,8192] per sequence", "generated_tokens": n_tok, "kv_pages": pages,
                        "prefill": "inside the timed region, prompts run once per group", "temperature": 1.0},
             "whole_run_s": elapsed, "hbm_fraction_per_sequence_formula": total_bytes / elapsed / (HBM_PEAK_GBS * 1e9),
@@ -686,10 +687,11 @@ def main():
         prompts = [ri.tokens((P,), shape["vocab"], seed, 960 + i).tolist() for i in range(n_prompts)]
         need_group = group_page_need(P, limits[:G])
         w = ri.make_weights(shape, seed, device=dev, dtype=torch.bfloat16)
-        page_bytes = 16 * shape["n_layers"] * shape["n_kv"] * shape["head_dim"] * 2 * 2
+        kvb = 1 if args.kv_fp8 else 2
+        page_bytes = 16 * shape["n_layers"] * shape["n_kv"] * shape["head_dim"] * 2 * kvb
         # kv_pages=None: the pool takes what the card holds once the packed weights and the workspace are placed
         ro = Rollout(shape, w, max_seqs=n_prompts * G, max_ctx=(total + 15) // 16 * 16, max_rows=256, kv_pages=None,
-                     consume_weights=True, kv_slack_bytes=4 << 30)
+                     consume_weights=True, kv_slack_bytes=4 << 30, kv_fp8=args.kv_fp8)
         del w
         pages = ro.rl_kv_stats()[1]
         torch.cuda.synchronize()
@@ -710,13 +712,14 @@ def main():
         wbytes = 2 * (shape["n_layers"] * (shape["hidden"] * (shape["n_q"] + 2 * shape["n_kv"]) * shape["head_dim"]
                                           + shape["n_q"] * shape["head_dim"] * shape["hidden"]
                                           + 3 * shape["ffn"] * shape["hidden"]) + shape["vocab"] * shape["hidden"])
-        total_bytes = steps * wbytes + kv_tokens * shape["n_layers"] * shape["n_kv"] * 2 * shape["head_dim"] * 2
+        total_bytes = steps * wbytes + kv_tokens * shape["n_layers"] * shape["n_kv"] * 2 * shape["head_dim"] * kvb
         print(json.dumps({
             "metric": "generated tokens/s (8B-shaped bf16 decode) + % peak HBM GB/s, 1 MI355X",
             "value": n_tok / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": 0,
             "ms_per_step": elapsed / max(1, steps) * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
             "dtype": "bf16", "data": "synthetic",
-            "config": {"workload": f"full8b_max_{n_prompts}x{G}_prompt{P}_to{total}", "generated_tokens": n_tok,
+            "config": {"workload": f"full8b_max_{n_prompts}x{G}_prompt{P}_to{total}" + ("_kvfp8" if args.kv_fp8 else ""),
+                       "generated_tokens": n_tok,
                        "kv_pages": pages, "kv_pool_GB": pages * page_bytes / 1e9, "pages_per_group": need_group,
                        "groups_resident_at_once": pages // need_group,
                        "prefill": "inside the timed region, prompts run once per group", "temperature": 1.0,

@@ -86,7 +86,8 @@ typedef enum { RL_F32 = 0, RL_BF16 = 1 } rl_dtype;
  * element, e4m3 as the matrix cores of the device encode it (nearest even, no scales, magnitudes above 448 end at
  * 448): half the bytes per cached token, which is what a decode step at long contexts mostly reads.  A performance
  * option outside the default path: the cached values then carry 4 significant bits, and results agree with the
- * unrounded definition only to about that (see the design notes for the tolerance).  rl_seq_import_kv still takes
+ * unrounded definition only to about that (a layer's output to a few per cent of its change to the residual
+ * stream on unit-variance keys and values; the tests bound it by 1e-1 per layer).  rl_seq_import_kv still takes
  * bf16 arrays and rounds them.
  */
 typedef enum { RL_KV_SAME = 0, RL_KV_FP8 = 2 } rl_kv_dtype;
