@@ -213,6 +213,8 @@ def run_wave(args):
     torch.cuda.empty_cache()
     if args.attn_split:
         ro.rl_debug_attention_split(args.attn_split)
+    if args.separate_append:
+        ro.rl_debug_attention_appends(False)
     prompts = ri.tokens((n_prompts, P), shape["vocab"], seed, 960)
     seq_ids = list(range(B))
     torch.cuda.synchronize()

@@ -617,16 +617,20 @@ __global__ __launch_bounds__(256, MBW == 1 ? 2 : 1) void gemm_bf16_lds_kernel(co
   }
 }
 
-// Wide tile for batches of 65..256 rows: the block owns two 64-row weight tiles (four 32-row blocks) and the four waves
-// split the batch columns, 32*MBW each.  What every block must pull through L2 per k block is its weight tile plus the
-// whole activation panel, and with 64-row tiles the panel re-reads (one per block) are 2-4x the weight stream: the
-// projection is then bound by what the L2 can deliver, not by HBM.  Doubling the tile halves the number of blocks and
-// with it the panel traffic.  Same K quarters, same order inside a quarter, quarters added in order: same bits.
-template <int MBW, int EPI, int XS>
+// Wide tile for batches of 65..256 rows: the block owns RBN 32-row blocks of the weight matrix (128 rows, or 96 where
+// that makes the tiles as many as the compute units) and the four waves split the batch columns, 32*MBW each.  What
+// every block must pull through L2 per k block is its weight tile plus the whole activation panel, and with 64-row
+// tiles the panel re-reads (one per block) are 2-4x the weight stream: the projection is then bound by what the L2 can
+// deliver, not by HBM.  A larger tile means fewer blocks and with them less panel traffic.  A block runs one wave per
+// SIMD and its steps (stage, barrier, multiply) do not overlap, so the time of a launch follows the steps of its
+// longest-running compute unit: 256 tiles of 96 rows finish sooner than 192 tiles of 128 rows that leave 64 units idle.
+// Same K quarters, same order inside a quarter, quarters added in order: same bits.
+template <int MBW, int EPI, int XS, int RBN>
 __global__ __launch_bounds__(256, 2) void gemm_bf16_lds4_kernel(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ W,
                                                               void* __restrict__ out, int M, int N, int K,
                                                               int kb_per_quarter, int tiles_x, SampleEpilogue se) {
-  __shared__ u32x4_t wlds[4][4][256];  // four stages x four row blocks x 4 KiB
+  static_assert(RBN == 4 || (RBN == 3 && EPI != kEpiSample), "the sampling epilogue works on pairs of row blocks");
+  __shared__ u32x4_t wlds[4][RBN][256];  // four stages x RBN row blocks x 4 KiB
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int KB = K >> 6;
   const int n_blocks_m = (M + 31) >> 5;
@@ -641,19 +645,14 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_lds4_kernel(const u32x4_t* _
   const int m_blk0 = (m_tile * 4 + wave) * MBW;
   const bool has_rows = m_blk0 < n_blocks_m;
 
-  // row blocks: pair p = 64-row tile 2x + p (the second pair shadows the first when the tile count is odd)
-  const int n_tiles = EPI == kEpiSwiGLU ? (N >> 5) : (N >> 6);
-  int tile[2], rb[4];
+  // row blocks of the tile; those past the end of the matrix shadow its last one (computed, never stored)
+  const int n_rb = EPI == kEpiSwiGLU ? (N >> 4) : (N >> 5);
+  int rb[RBN];
 #pragma unroll
-  for (int p = 0; p < 2; ++p) {
-    tile[p] = min(tile_x * 2 + p, n_tiles - 1);
-    rb[2 * p] = tile[p] * 2;
-    rb[2 * p + 1] = tile[p] * 2 + 1;
-  }
-  const bool second_valid = tile_x * 2 + 1 < n_tiles;
-  const u32x4_t* wp[4];
+  for (int b = 0; b < RBN; ++b) rb[b] = min(tile_x * RBN + b, n_rb - 1);
+  const u32x4_t* wp[RBN];
 #pragma unroll
-  for (int b = 0; b < 4; ++b) wp[b] = W + (size_t)rb[b] * KB * 256 + tid;
+  for (int b = 0; b < RBN; ++b) wp[b] = W + (size_t)rb[b] * KB * 256 + tid;
   const u32x4_t* xb[MBW];
 #pragma unroll
   for (int mb = 0; mb < MBW; ++mb) {
@@ -674,13 +673,13 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_lds4_kernel(const u32x4_t* _
     return off;
   };
 
-  u32x4_t wr[4][4];          // weight registers: slot s holds a k block with index = s (mod 4)
+  u32x4_t wr[4][RBN];        // weight registers: slot s holds a k block with index = s (mod 4)
   u32x4_t xr[XS][MBW][4];    // activation fragments: slot s holds a k block with index = s (mod XS)
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
     const int ow = next_wslot();
 #pragma unroll
-    for (int b = 0; b < 4; ++b) wr[s][b] = __builtin_nontemporal_load(wp[b] + ow);
+    for (int b = 0; b < RBN; ++b) wr[s][b] = __builtin_nontemporal_load(wp[b] + ow);
   }
 #pragma unroll
   for (int s = 0; s < XS; ++s)
@@ -691,17 +690,17 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_lds4_kernel(const u32x4_t* _
   {
     const int ow = next_wslot();
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
+    for (int b = 0; b < RBN; ++b) {
       wlds[0][b][tid] = w_to_f16(wr[0][b]);
       wr[0][b] = __builtin_nontemporal_load(wp[b] + ow);
     }
   }
 
-  auto iter = [&](f32x16_t (&a)[4][MBW], int i, auto jc) __attribute__((always_inline)) {
+  auto iter = [&](f32x16_t (&a)[RBN][MBW], int i, auto jc) __attribute__((always_inline)) {
     constexpr int j = decltype(jc)::value, jn = (j + 1) & 3, jx = j % XS;
     const int ow = next_wslot();  // k block i + 5
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
+    for (int b = 0; b < RBN; ++b) {
       wlds[jn][b][tid] = w_to_f16(wr[jn][b]);
       wr[jn][b] = __builtin_nontemporal_load(wp[b] + ow);
     }
@@ -712,7 +711,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_lds4_kernel(const u32x4_t* _
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
 #pragma unroll
-      for (int b = 0; b < 4; ++b) {
+      for (int b = 0; b < RBN; ++b) {
         const u32x4_t afrag = wlds[j][b][t * 64 + lane];
 #pragma unroll
         for (int mb = 0; mb < MBW; ++mb) a[b][mb] = mfma_f16(afrag, xr[jx][mb][t], a[b][mb]);
@@ -723,9 +722,9 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_lds4_kernel(const u32x4_t* _
 #pragma unroll
       for (int t = 0; t < 4; ++t) xr[jx][mb][t] = xb[mb][(size_t)kb_of(i + XS) * 256 + t * 64];
   };
-  auto quarter = [&](f32x16_t (&a)[4][MBW], int q) __attribute__((always_inline)) {
+  auto quarter = [&](f32x16_t (&a)[RBN][MBW], int q) __attribute__((always_inline)) {
 #pragma unroll
-    for (int b = 0; b < 4; ++b)
+    for (int b = 0; b < RBN; ++b)
 #pragma unroll
       for (int mb = 0; mb < MBW; ++mb)
 #pragma unroll
@@ -737,12 +736,12 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_lds4_kernel(const u32x4_t* _
       iter(a, i + 3, std::integral_constant<int, 3>{});
     }
   };
-  f32x16_t acc[4][MBW], other[4][MBW];
+  f32x16_t acc[RBN][MBW], other[RBN][MBW];
   quarter(acc, 0);
   for (int q = 1; q < 4; ++q) {
     quarter(other, q);
 #pragma unroll
-    for (int b = 0; b < 4; ++b)
+    for (int b = 0; b < RBN; ++b)
 #pragma unroll
       for (int mb = 0; mb < MBW; ++mb) acc[b][mb] += other[b][mb];
   }
@@ -753,15 +752,26 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_lds4_kernel(const u32x4_t* _
   for (int mb = 0; mb < MBW; ++mb) {
     const int m = (m_blk0 + mb) * 32 + col;
     if (m >= M) continue;
+    if constexpr (RBN == 4) {  // as two 64-row tiles (the sampling epilogue works per tile)
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      if (p == 1 && !second_valid) break;
-      float sum[2][16];
+      for (int p = 0; p < 2; ++p) {
+        if (tile_x * 4 + 2 * p >= n_rb) break;
+        float sum[2][16];
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
+        for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sum[nb][r] = acc[2 * p + nb][mb][r];
-      store_block<EPI>(sum, m, hb, rb[2 * p], rb[2 * p + 1], blockIdx.y, M, N, out, se, tile[p]);
+          for (int r = 0; r < 16; ++r) sum[nb][r] = acc[2 * p + nb][mb][r];
+        store_block<EPI>(sum, m, hb, rb[2 * p], rb[2 * p + 1], blockIdx.y, M, N, out, se, tile_x * 2 + p);
+      }
+    } else {
+#pragma unroll
+      for (int b = 0; b < RBN; ++b) {
+        if (tile_x * RBN + b >= n_rb) break;
+        float sum[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum[r] = acc[b][mb][r];
+        store_rowblock<EPI>(sum, m, hb, rb[b], blockIdx.y, M, N, out);
+      }
     }
   }
 }
@@ -1039,22 +1049,23 @@ void launch_lds(hipStream_t s, const void* X, const void* W, void* out, int M, i
   }
 }
 
-template <int MBW, int XS>
+template <int MBW, int XS, int RBN = 4>
 void launch_lds4(hipStream_t s, const void* X, const void* W, void* out, int M, int N, int K, int epi, bool allow_split,
                  const SampleEpilogue& se) {
   Plan p = make_plan(N, K, epi, allow_split);  // same K split as the other variants: bit-identical results
   const int m_tiles = (M + 128 * MBW - 1) / (128 * MBW);
-  const int tiles = epi == kEpiSwiGLU ? (N >> 5) : (N >> 6);
-  const int tx = (tiles + 1) / 2;
+  const int n_rb = epi == kEpiSwiGLU ? (N >> 4) : (N >> 5);
+  const int tx = (n_rb + RBN - 1) / RBN;
   const bool fold = m_tiles == 2 && (tx & 7) == 0;  // pair the two batch tiles of a weight tile on one die
   dim3 grid(fold ? 2 * tx : tx, epi == kEpiPartial ? p.splits : 1, fold ? 1 : m_tiles);
   const int tiles_x = fold ? tx : 0;
   if (epi == kEpiSwiGLU)
-    gemm_bf16_lds4_kernel<MBW, kEpiSwiGLU, XS><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, tiles_x, se);
-  else if (epi == kEpiSample)
-    gemm_bf16_lds4_kernel<MBW, kEpiSample, XS><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, tiles_x, se);
-  else
-    gemm_bf16_lds4_kernel<MBW, kEpiPartial, XS><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, tiles_x, se);
+    gemm_bf16_lds4_kernel<MBW, kEpiSwiGLU, XS, RBN><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, tiles_x, se);
+  else if (epi == kEpiSample) {
+    if constexpr (RBN == 4)
+      gemm_bf16_lds4_kernel<MBW, kEpiSample, XS, 4><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, tiles_x, se);
+  } else
+    gemm_bf16_lds4_kernel<MBW, kEpiPartial, XS, RBN><<<grid, 256, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave, tiles_x, se);
 }
 
 void launch_lds8(hipStream_t s, const void* X, const void* W, void* out, int M, int N, int K, int epi, bool allow_split,
@@ -1082,7 +1093,18 @@ void launch_cols(hipStream_t s, const void* X, const void* W, void* out, int M, 
     // QKV 33 -> 29, output projection 538 -> 420 at 256 rows); the O and down projections would be left with 128 blocks
     // (measured 21 -> 26 and 42 -> 50 us) and run as two batch tiles of 128 whose blocks are paired on one die.
     if (M > 128 && wide_blocks >= 192) { launch_lds8(s, X, W, out, M, N, K, epi, allow_split, se); return; }
-    if (wide_blocks * ((M + 127) / 128) >= 192) { launch_lds4<1, 2>(s, X, W, out, M, N, K, epi, allow_split, se); return; }
+    if (wide_blocks * ((M + 127) / 128) >= 192) {
+      // up to 128 rows: 96-row tiles where 128-row tiles would leave a quarter of the compute units without a block
+      // and 96-row tiles give every unit one (gate/up 55 -> 41 us, QKV 21 -> 16 us at 128 rows)
+      const int n_rb = epi == kEpiSwiGLU ? (N >> 4) : (N >> 5);
+      const int splits = epi == kEpiPartial ? p.splits : 1;
+      if (M <= 128 && epi != kEpiSample && n_rb % 3 == 0 && wide_blocks < kComputeUnits && (n_rb / 3) * splits <= kComputeUnits) {
+        launch_lds4<1, 2, 3>(s, X, W, out, M, N, K, epi, allow_split, se);
+        return;
+      }
+      launch_lds4<1, 2>(s, X, W, out, M, N, K, epi, allow_split, se);
+      return;
+    }
     launch_lds<MBW, MBW == 1 ? 4 : 2>(s, X, W, out, M, N, K, epi, allow_split, se);
     return;
   }
