@@ -11,7 +11,7 @@ the pool size, admission order or batch composition.
 """
 import torch
 
-from .binding import RLError, RL_ERR_KV_FULL
+from .binding import RLError, RL_ERR_KV_FULL, _i32
 
 KV_BLOCK = 16
 
@@ -58,7 +58,9 @@ def generate_groups(ro, prompts, group_size, max_new_tokens, temperature=1.0, se
     next_group = 0
     members_left = {}                  # group -> sequences still running
     active = []                        # sequence ids in batch order
-    count = [0] * n_seq                # tokens generated so far
+    dead = [0] * n_seq                 # decode step after which a sequence has reached its length limit
+    next_dead = [1 << 62]              # the earliest of them among the active sequences
+    calls = []                         # the decode calls of a step: (ids, ids as a C array); rebuilt when `active` changes
     rows_t, rows_lp, rows_ids = [], [], []   # per call: device outputs and the ids they belong to
     # End-token checks run one call behind: the tokens of a call are copied to pinned host memory without waiting, and
     # read when the next call has been enqueued.  A sequence that drew the end token therefore takes one step more than
@@ -83,18 +85,20 @@ def generate_groups(ro, prompts, group_size, max_new_tokens, temperature=1.0, se
             record(ids, tok, lp)
             members_left[g] = G
             active.extend(ids)
+            calls.clear()
+            for k in ids:                # the prefill gave token 1; decode step `step + n` gives token n + 1
+                dead[k] = step + limits[k] - 1
+            next_dead[0] = min(next_dead[0], min(dead[k] for k in ids))
 
     def record(ids, tok, lp):
         rows_t.append(tok)
         rows_lp.append(lp)
-        rows_ids.append(list(ids))
-        for s in ids:
-            count[s] += 1
+        rows_ids.append(ids)           # lists are never changed once they are in a call
         if eos_id is not None:
             buf, ev = spare.pop() if spare else (torch.empty(max_rows, dtype=torch.int32, pin_memory=True), torch.cuda.Event())
             buf[:len(ids)].copy_(tok, non_blocking=True)
             ev.record()
-            pending.append((list(ids), buf, ev))
+            pending.append((ids, buf, ev))
 
     def retire(finished):
         nonlocal reserved
@@ -105,6 +109,8 @@ def generate_groups(ro, prompts, group_size, max_new_tokens, temperature=1.0, se
         gone = set(finished)
         running.difference_update(gone)
         active[:] = [s for s in active if s not in gone]
+        calls.clear()
+        next_dead[0] = min((dead[s] for s in active), default=1 << 62)
         for s in finished:
             g = s // G
             members_left[g] -= 1
@@ -113,7 +119,9 @@ def generate_groups(ro, prompts, group_size, max_new_tokens, temperature=1.0, se
                 del members_left[g]
 
     def at_limit(ids):
-        return [s for s in ids if count[s] >= limits[s]]
+        if step < next_dead[0]:
+            return []
+        return [s for s in ids if step >= dead[s]]
 
     def drew_end_token(keep_last):
         """Sequences whose end token has arrived on the host; the newest `keep_last` copies stay in flight."""
@@ -134,17 +142,20 @@ def generate_groups(ro, prompts, group_size, max_new_tokens, temperature=1.0, se
         if not active:
             retire(drew_end_token(0))
             continue
-        for b0 in range(0, len(active), max_rows):
-            ids = active[b0:b0 + max_rows]
+        if not calls:
+            for b0 in range(0, len(active), max_rows):
+                ids = active[b0:b0 + max_rows]
+                calls.append((ids, _i32(ids)))
+        for ids, ids_c in calls:
             # in_tokens = None: the library feeds every sequence the token it returned for it last
-            tok, lp = ro.rl_decode_step(ids, None, temperature, seed, top_k=top_k, top_p=top_p)
+            tok, lp = ro.rl_decode_step(ids_c, None, temperature, seed, top_k=top_k, top_p=top_p)
             record(ids, tok, lp)
-        n_calls = (len(active) + max_rows - 1) // max_rows
+        step += 1
+        n_calls = len(calls)
         finished = at_limit(active)
         if eos_id is not None:
             finished += drew_end_token(n_calls)   # everything but the calls just enqueued
         retire(finished)
-        step += 1
         if on_step is not None:
             on_step(step, len(active))
 
