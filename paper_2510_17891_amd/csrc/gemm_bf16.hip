@@ -626,7 +626,7 @@ __global__ __launch_bounds__(256, MBW == 1 ? 2 : 1) void gemm_bf16_lds_kernel(co
 // longest-running compute unit: 256 tiles of 96 rows finish sooner than 192 tiles of 128 rows that leave 64 units idle.
 // Same K quarters, same order inside a quarter, quarters added in order: same bits.
 template <int MBW, int EPI, int XS, int RBN>
-__global__ __launch_bounds__(256, 2) void gemm_bf16_lds4_kernel(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ W,
+__global__ __launch_bounds__(256, RBN == 3 ? 1 : 2) void gemm_bf16_lds4_kernel(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ W,
                                                               void* __restrict__ out, int M, int N, int K,
                                                               int kb_per_quarter, int tiles_x, SampleEpilogue se) {
   static_assert(RBN == 4 || (RBN == 3 && EPI != kEpiSample), "the sampling epilogue works on pairs of row blocks");
