@@ -12,10 +12,11 @@
 //
 // The context is cut into segments whose number and bounds depend on the context length alone
 // (4*ceil(ctx/1024) equal runs of 32-key steps), each leaving (max, sum, unnormalised O) per head.  One block of
-// four waves handles up to 16 segments of one (row, kv head), each wave a contiguous quarter.
+// four waves handles up to 16 segments of one (row, kv head), each wave a contiguous quarter; beyond 4096 keys a block
+// takes `spb` segments (a launch parameter, 4 by default: shorter blocks fill the end of a long launch better).
 //   ctx <= 4096: one block per (row, kv head); partials stay in LDS and after a block barrier the four waves
 //                merge the segments of one head each, flat and in index order.
-//   ctx  > 4096: ceil(segments/16) blocks per (row, kv head), so that long contexts become many short blocks
+//   ctx  > 4096: ceil(segments/spb) blocks per (row, kv head), so that long contexts become many short blocks
 //                that the dispatcher can balance; partials go to the workspace and a second small kernel does the
 //                same flat merge.
 // Which path runs is a function of the row's context only, and nothing synchronises across blocks inside a

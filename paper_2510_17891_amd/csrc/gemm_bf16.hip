@@ -2,8 +2,8 @@
 //
 // At M <= 256 the projection is bound by reading W once from HBM (M flop per weight byte), so the kernel is
 // organised around that stream: both operands are stored fragment-major (see frag_offset), which makes every
-// global load a fully coalesced 1 KiB wave access that lands directly in MFMA 32x32x16 operand registers -- no
-// LDS staging, no shuffles.  A wave owns a 64 x (32*MB) output tile over a slice of K; the four waves of a
+// global load a fully coalesced 1 KiB wave access that lands directly in MFMA 32x32x16 operand registers (the bf16
+// weights are widened to f16 there, exactly; the activations arrive as f16) -- no LDS staging, no shuffles.  A wave owns a 64 x (32*MB) output tile over a slice of K; the four waves of a
 // block take four K slices and add their accumulators through LDS in a fixed order; further K splits across
 // blocks (to put >= 256 blocks on the chip for the small matrices) leave fp32 partials that the consumer sums.
 #include <type_traits>

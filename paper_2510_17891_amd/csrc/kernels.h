@@ -64,7 +64,7 @@ void launch_embed(hipStream_t s, int dtype, const void* embed, const int32_t* to
                   const RowMeta* rows = nullptr, const int32_t* last_tok = nullptr);
 
 // x[r] += sum_{s<S} part[s][r][:] (part may be null);  capture (may be null) gets x;  if gain != null,
-// h = x * rsqrt(mean(x^2)+eps) * gain written as fp32 row-major (kF32) or bf16 fragment-major (kBF16).
+// h = x * rsqrt(mean(x^2)+eps) * gain written as fp32 row-major (kF32) or f16 fragment-major (kBF16 models).
 void launch_residual_norm(hipStream_t s, int dtype, float* x, const float* part, int S, const void* gain,
                           void* h_out, float* capture, int M, int H, float eps);
 
@@ -86,7 +86,7 @@ void launch_page_copy(hipStream_t s, void* kv_pool, size_t layer_bytes, size_t p
 
 // ---- attention -----------------------------------------------------------------------------------
 // bf16, head_dim 128: decode attention over paged KV (MFMA), one block per (row, kv head), context cut into
-// segments that depend on the context length only and merged in index order; writes bf16 fragment-major
+// segments that depend on the context length only and merged in index order; writes f16 fragment-major
 // [M x n_q*d].  part: fp32 [M][n_q][max_segs][d+2] with max_segs = attn_bf16_max_segments(max_ctx).
 int attn_bf16_max_segments(int max_ctx);
 // skip_segs (per row, may be null): leading segments of the row that a set in `shared` covers; every row with a
@@ -134,8 +134,9 @@ struct SampleEpilogue {
 
 // Number of K splits the bf16 GEMM uses for (N, K); partial outputs are [S][M][N] fp32.
 int gemm_bf16_splits(int N, int K, int epi);
-// bf16 MFMA GEMM: X fragment-major [M x K], W fragment-major [N x K] (2N rows for SwiGLU: gate then up).
-// kEpiPartial: out = fp32 [S][M][N];  kEpiSwiGLU: out = bf16 fragment-major [M x N] = silu(gate)*up;
+// MFMA GEMM of the bf16 models: X f16 fragment-major [M x K], W bf16 fragment-major [N x K] (2N rows for SwiGLU: gate
+// and up rows interleaved in groups of 16).
+// kEpiPartial: out = fp32 [S][M][N];  kEpiSwiGLU: out = f16 fragment-major [M x N] = silu(gate)*up;
 // kEpiSample: out unused, results go through *se.  allow_split = false forces S = 1 (finished [M][N] product).
 void launch_gemm_bf16(hipStream_t s, const void* X, const void* W, void* out, int M, int N, int K, int epi,
                       bool allow_split = true, const SampleEpilogue* se = nullptr);
