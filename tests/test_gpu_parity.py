@@ -586,6 +586,54 @@ def test_layer8b_full_size_batch64_ctx2048_sampled_rows(amd):
     ro.close()
 
 
+def test_layer8b_wave_shape_128_rows_shared_prompt_context_9k_sampled_rows(amd):
+    """The launch configuration that the benchmark times, on one layer at full width: 128 rows = 16 prompts x 8 samples,
+    a prompt of 2048 tokens whose pages the samples of a group share (imported once, forked), 7168 + j private tokens
+    appended per sequence (so that the members of a group stand at different positions within a few steps, as after
+    ragged retirements), one decode step.  Rows are sampled (two per group pattern: first and last member of some
+    groups) and compared with the oracle, which gets each row's own keys and values as one contiguous history."""
+    shape = dict(ri.SHAPES["layer8b"])
+    seed, G, n_groups, P, private = 41, 8, 16, 2048, 7168
+    w, wn = make_both(shape, seed)
+    B = G * n_groups
+    nkv, d, H = shape["n_kv"], shape["head_dim"], shape["hidden"]
+    extra = [0 if g % 2 == 0 else (j % 3) for g in range(n_groups) for j in range(G)]   # odd groups: members out of step
+    max_ctx = (P + private + 3 + 1 + 15) // 16 * 16 + 16
+    pages = n_groups * (P // 16) + sum((private + e + 1 + 15) // 16 + 1 for e in extra) + 8
+    ro = amd.Rollout(shape, to_device(w), max_seqs=B, max_ctx=max_ctx, max_rows=B, kv_pages=pages)
+    sampled = {0, 7, 8 + 1, 8 + 2, 8 + 7, 5 * 8 + 3, 15 * 8, 15 * 8 + 5, 15 * 8 + 7}
+    hist = {}
+    for g in range(n_groups):
+        kp = ri.normal((P, nkv, d), 1.0, seed, 3000 + 2 * g, dtype=torch.bfloat16)
+        vp = ri.normal((P, nkv, d), 1.0, seed, 3001 + 2 * g, dtype=torch.bfloat16)
+        ro.rl_seq_import_kv(g * G, [kp.to(DEV)], [vp.to(DEV)])
+        ro.rl_seq_fork(g * G, list(range(g * G + 1, (g + 1) * G)))
+        for j in range(G):
+            b = g * G + j
+            n = private + extra[b]
+            ka = ri.normal((n, nkv, d), 1.0, seed, 4000 + 2 * b, device=DEV, dtype=torch.bfloat16)
+            va = ri.normal((n, nkv, d), 1.0, seed, 4001 + 2 * b, device=DEV, dtype=torch.bfloat16)
+            ro.rl_seq_append_kv(b, [ka], [va])
+            if b in sampled:
+                hist[b] = (torch.cat([kp, ka.cpu()]), torch.cat([vp, va.cpu()]))
+    assert [ro.rl_seq_len(b) for b in range(B)] == [P + private + e for e in extra]
+    x = ri.normal((B, H), 1.0, seed, 1999).to(torch.bfloat16).float()
+    out = ro.rl_decode_hidden(list(range(B)), x.to(DEV))
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    assert np.isfinite(out).all()
+    worst = 0.0
+    for b in sorted(sampled):
+        k, v = hist[b]
+        ctx = P + private + extra[b]
+        ref = _oracle_layer_row(shape, wn, k, v, x[b], ctx)
+        err = float(rel_inf(out[b] - x[b].numpy(), ref - x[b].numpy()))
+        worst = max(worst, err)
+        assert err < 3e-2, (b, err)
+    print(f"[wave shape] worst layer error over {len(sampled)} sampled rows at context {P + private}: {worst:.2e}")
+    ro.close()
+
+
 def test_bf16_layer_many_rows_uses_wide_tiles(amd):
     """70 and 130 rows (the 128-column tile, one and two passes) with short histories."""
     for n in (70, 130):
