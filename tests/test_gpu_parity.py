@@ -543,6 +543,14 @@ def test_error_paths_leave_state_untouched(amd):
     with pytest.raises(B.RLError) as e:
         ro.rl_prefill([0], [[shape["vocab"]]], 0.0, 0)
     assert e.value.status == B.RL_ERR_INVALID_ARG
+    with pytest.raises(B.RLError) as e:
+        ro.rl_prefill([0], [[]], 0.0, 0)              # an empty prompt
+    assert e.value.status == B.RL_ERR_INVALID_ARG
+    with pytest.raises(B.RLError) as e:
+        ro.rl_decode_step([], torch.empty(0, dtype=torch.int32, device=DEV), 0.0, 0)   # an empty batch
+    assert e.value.status == B.RL_ERR_INVALID_ARG
+    ro.rl_free_seqs([])                               # freeing nothing is allowed
+    assert ro.rl_kv_stats() == (3, 3)
     tok, _ = ro.rl_prefill([0], [p], 0.0, 0)
     assert ro.rl_kv_stats() == (1, 3)
     with pytest.raises(B.RLError) as e:
