@@ -34,9 +34,9 @@ HBM_PEAK_GBS = 8000.0
 # file still has the hash it had when the counters were taken; otherwise "traffic" is null.
 TRAFFIC_RATIO = {
     # one layer at the launch shape of the 128-sequence wave (16 groups x 8 samples, 2048 shared + 7168 private tokens)
-    ("wave", "attn_decode"): (1.054, "attn_bf16.hip", "040b6e6172a57634"),
-    ("layer", "attn_decode"): (1.054, "attn_bf16.hip", "040b6e6172a57634"),
-    ("full", "attn_decode"): (1.040, "attn_bf16.hip", "040b6e6172a57634"),
+    ("wave", "attn_decode"): (1.054, "attn_bf16.hip", "f3ba5d4ed014e901"),
+    ("layer", "attn_decode"): (1.054, "attn_bf16.hip", "f3ba5d4ed014e901"),
+    ("full", "attn_decode"): (1.040, "attn_bf16.hip", "f3ba5d4ed014e901"),
     ("full", "gemm_gate_up_swiglu"): (1.011, "gemm_bf16.hip", "304e69ce061a6808"),
 }
 

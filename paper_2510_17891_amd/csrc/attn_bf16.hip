@@ -677,7 +677,7 @@ __global__ __launch_bounds__(64) void attn_merge_bf16_kernel(const float* __rest
 
 int attn_bf16_max_segments(int max_ctx) { return attn_num_segments(max_ctx); }
 
-void launch_attn_decode_bf16(hipStream_t s, const Geometry& g, const float* q, const RowMeta* rows,
+bool launch_attn_decode_bf16(hipStream_t s, const Geometry& g, const float* q, const RowMeta* rows,
                              const int32_t* block_table, void* k_pool_layer, void* v_pool_layer, float* part,
                              int max_segs_alloc, int max_ctx_in_batch, void* o_out, int M, const int32_t* skip_segs,
                              const AttnShared* shared, int n_shared, int max_shared_segs, const AttnAppend* append,
@@ -710,8 +710,13 @@ void launch_attn_decode_bf16(hipStream_t s, const Geometry& g, const float* q, c
     if (g.kv_fp8) RL_ATTN_LAUNCH(false, true); else RL_ATTN_LAUNCH(false, false);
   }
 #undef RL_ATTN_LAUNCH
-  if (n_seg_max > kLdsSegs || n_shared > 0)
-    attn_merge_bf16_kernel<<<dim3(g.n_q, M), 64, 0, s>>>(part, rows, max_segs_alloc, (uint16_t*)o_out, g.n_q, skip_segs);
+  return n_seg_max > kLdsSegs || n_shared > 0;
+}
+
+void launch_attn_merge_bf16(hipStream_t s, const Geometry& g, const RowMeta* rows, float* part, int max_segs_alloc,
+                            void* o_out, int M, const int32_t* skip_segs, int n_shared) {
+  if (n_shared <= 0) skip_segs = nullptr;
+  attn_merge_bf16_kernel<<<dim3(g.n_q, M), 64, 0, s>>>(part, rows, max_segs_alloc, (uint16_t*)o_out, g.n_q, skip_segs);
 }
 
 }  // namespace rl

@@ -106,11 +106,15 @@ struct AttnAppend {
   const void* k_gain;
   const float2* rope_table;
 };
-void launch_attn_decode_bf16(hipStream_t s, const Geometry& g, const float* q, const RowMeta* rows,
+// Returns true when the partials of some rows were left in the workspace, i.e. launch_attn_merge_bf16 (same arguments)
+// has to follow; the two launches are separate calls so that a caller can time them separately.
+bool launch_attn_decode_bf16(hipStream_t s, const Geometry& g, const float* q, const RowMeta* rows,
                              const int32_t* block_table, void* k_pool_layer, void* v_pool_layer,
                              float* part, int max_segs_alloc, int max_ctx_in_batch, void* o_out, int M,
                              const int32_t* skip_segs = nullptr, const AttnShared* shared = nullptr, int n_shared = 0,
                              int max_shared_segs = 0, const AttnAppend* append = nullptr, int segs_per_block = 16);
+void launch_attn_merge_bf16(hipStream_t s, const Geometry& g, const RowMeta* rows, float* part, int max_segs_alloc,
+                            void* o_out, int M, const int32_t* skip_segs, int n_shared);
 // fp32, any head_dim <= 256: one wave per (row, q head), whole context, output fp32 row-major [M][n_q*d].
 void launch_attn_f32(hipStream_t s, const Geometry& g, const float* q, const RowMeta* rows,
                      const int32_t* block_table, const void* k_pool_layer, const void* v_pool_layer,

@@ -137,8 +137,8 @@ void compute_layout(const rl_model_config& c, Layout* L) {
   L->total = off;
 }
 
-enum Kind { K_META, K_EMBED, K_NORM, K_QKV, K_ROPE_APPEND, K_ATTN, K_OPROJ, K_GATEUP, K_DOWN, K_LMHEAD, K_SAMPLE, K_COUNT };
-const char* const kKindNames[K_COUNT] = {"meta", "embed", "residual_norm", "gemm_qkv", "qk_rope_append", "attn_decode",
+enum Kind { K_META, K_EMBED, K_NORM, K_QKV, K_ROPE_APPEND, K_ATTN, K_ATTN_MERGE, K_OPROJ, K_GATEUP, K_DOWN, K_LMHEAD, K_SAMPLE, K_COUNT };
+const char* const kKindNames[K_COUNT] = {"meta", "embed", "residual_norm", "gemm_qkv", "qk_rope_append", "attn_decode", "attn_merge",
                                         "gemm_o", "gemm_gate_up_swiglu", "gemm_down", "gemm_lm_head", "sample"};
 
 }  // namespace
@@ -263,10 +263,16 @@ int run_layers(rl_model* m, hipStream_t st, int M, const RowMeta* rows, int max_
       launch_qk_rope_append(st, g, part, s_qkv, q_gain, k_gain, rope, rows, m->k_pool(l), m->v_pool(l), q, M);
     }
     if (bf) {
-      Timer t(m, st, K_ATTN);
-      const AttnAppend ap = {part, s_qkv, q_gain, k_gain, rope};
-      launch_attn_decode_bf16(st, g, q, rows, bt, m->k_pool(l), m->v_pool(l), apart, m->lay.max_segs, max_ctx_in_batch, o, M,
-                              sa.skip, sa.sets, sa.n_sets, sa.max_segs, fused ? &ap : nullptr, m->attn_segs_per_block);
+      bool merge;
+      { Timer t(m, st, K_ATTN);
+        const AttnAppend ap = {part, s_qkv, q_gain, k_gain, rope};
+        merge = launch_attn_decode_bf16(st, g, q, rows, bt, m->k_pool(l), m->v_pool(l), apart, m->lay.max_segs, max_ctx_in_batch,
+                                        o, M, sa.skip, sa.sets, sa.n_sets, sa.max_segs, fused ? &ap : nullptr,
+                                        m->attn_segs_per_block); }
+      if (merge) {
+        Timer t(m, st, K_ATTN_MERGE);
+        launch_attn_merge_bf16(st, g, rows, apart, m->lay.max_segs, o, M, sa.skip, sa.n_sets);
+      }
     } else {
       Timer t(m, st, K_ATTN);
       launch_attn_f32(st, g, q, rows, bt, m->k_pool(l), m->v_pool(l), (float*)o, M);
