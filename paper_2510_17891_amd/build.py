@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librl_rollout.so")
 SOURCES = ["small_kernels.hip", "gemm_bf16.hip", "attn_bf16.hip", "generic_f32.hip", "sampler.hip", "objective.hip", "model.hip"]
-HEADERS = ["device_utils.h", "kernels.h", "seq_table.h", "sampler_device.h", "attn_plan.h", "rope_device.h", os.path.join("..", "..", "include", "rl.h")]
+HEADERS = ["device_utils.h", "kernels.h", "seq_table.h", "sampler_device.h", "attn_plan.h", "rope_device.h", "weight_order.h", os.path.join("..", "..", "include", "rl.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

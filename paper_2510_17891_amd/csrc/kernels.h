@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "attn_plan.h"
+#include "weight_order.h"
 
 namespace rl {
 
@@ -39,16 +40,6 @@ struct Geometry {
 __host__ __device__ inline size_t frag_offset(int r, int k, int k_blocks) {
   int rb = r >> 5, row = r & 31, kb = k >> 6, hb = (k >> 5) & 1, t = (k >> 3) & 3, e = k & 7;
   return ((((size_t)(rb * (size_t)k_blocks + kb) * 4 + t) * 2 + hb) * 32 + row) * 8 + e;
-}
-
-// Order of the k blocks of a weight row block in memory.  The K range of a product is cut into segments of `seg` k
-// blocks, four consecutive segments per K split, one per wave of a block.  Memory holds the k blocks of the four
-// segments of a split interleaved -- block i of segment 0, of 1, of 2, of 3, then block i + 1 of each -- so that what
-// the four waves of a block read at about the same time is one contiguous 16 KiB piece per row block instead of four
-// pieces a quarter of the split apart (measured: 7 us of 42 on the gate/up stream at 32 rows).
-__host__ __device__ inline int weight_kb_slot(int kb, int seg) {
-  const int s = kb / seg, i = kb - s * seg;
-  return ((s >> 2) * seg + i) * 4 + (s & 3);
 }
 
 // Offset of weight element (r, k) in the packed matrix: frag_offset with the k block moved to its slot.

@@ -2,6 +2,7 @@
 // Built with g++ into its own small library by the CPU tests; not part of the product library.
 #include "attn_plan.h"
 #include "seq_table.h"
+#include "weight_order.h"
 
 extern "C" {
 
@@ -34,6 +35,7 @@ int st_reserve(void* t, int s, int tokens, int* grants_out, int max_grants) {
 
 long long st_prefix_id(void* t, int s) { return ((rl::SeqTable*)t)->prefix_id(s); }
 int st_prefix_blocks(void* t, int s) { return ((rl::SeqTable*)t)->prefix_blocks(s); }
+int st_weight_kb_slot(int kb, int seg) { return rl::weight_kb_slot(kb, seg); }
 int st_attn_num_segments(int ctx) { return rl::attn_num_segments(ctx); }
 int st_attn_seg_begin(int sgm, int ctx) { return rl::attn_seg_begin(sgm, (ctx + 31) >> 5, rl::attn_num_segments(ctx)); }
 // plan of one decode batch: skip_out[n]; sets_out gets (rows[4], n_rows, n_segs) per set; returns the number of sets

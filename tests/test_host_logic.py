@@ -268,6 +268,25 @@ def test_window_sets_of_prefill_rows(st):
     assert [sorted(set(s[:4])) for s in sets] == [[0, 1], [2, 3]] and [s[5] for s in sets] == [4, 8]
 
 
+def test_weight_k_block_order_is_a_permutation_that_interleaves_four_segments(st):
+    """Order of the k blocks of a packed weight row block: for every (number of k blocks, segment length) the 8B shape
+    uses and a few others, the slots are a permutation, the four segments of a K split are interleaved block by
+    block (what four waves read at the same moment is adjacent), and splits follow one another."""
+    for n_kb, seg in [(64, 4), (64, 16), (192, 12), (192, 48), (8, 1), (8, 2), (16, 4), (48, 3)]:
+        assert n_kb % (4 * seg) == 0
+        slots = [st.st_weight_kb_slot(kb, seg) for kb in range(n_kb)]
+        assert sorted(slots) == list(range(n_kb)), (n_kb, seg)
+        for kb in range(n_kb):
+            s, i = divmod(kb, seg)                 # segment (wave range) and block inside it
+            split, wave = divmod(s, 4)
+            assert slots[kb] == (split * seg + i) * 4 + wave
+        # the blocks that the four waves of a split read at step i are one run of four slots
+        for split in range(n_kb // (4 * seg)):
+            for i in range(seg):
+                run = [slots[(4 * split + w) * seg + i] for w in range(4)]
+                assert run == list(range(run[0], run[0] + 4)) and run[0] % 4 == 0
+
+
 def test_group_page_need_matches_the_allocator(st):
     """The rollout loop admits a group when the pool can hold it up to its length limits; its estimate must equal what
     the allocator really hands out when the group is prefilled (shared full pages, one partial-page copy per member)
