@@ -357,7 +357,9 @@ rl_status rl_hrd_objective(void* stream, int32_t n_prompts, int32_t group_size, 
  * Reorder a row-major [rows x cols] matrix (device) into the order the projection kernels stream
  * (device, same size, must not overlap src).  RL_BF16: 32-row x 64-column tiles, each stored so that a
  * wavefront reads it as four contiguous 1 KiB pieces in matrix-core operand order, the tiles of a 32-row block
- * ordered so that what the four wavefronts of a block read together is contiguous; needs rows % 64 == 0 and
+ * ordered so that what the four wavefronts of a block read together is contiguous, and every weight stored as its
+ * f16 image, the grid on which the matrix cores multiply (exact for 2^-14 <= |w| <= 65504; smaller magnitudes are cut
+ * toward zero on the f16 subnormal grid, absolute error < 2^-24; same two bytes per weight); needs rows % 64 == 0 and
  * cols % 256 == 0.  That order depends on how the product is cut along the columns, hence `kind`:
  * RL_W_SPLIT_K for wqkv, wo and w_down, RL_W_WHOLE_K for w_gate_up and lm_head.  RL_F32: plain copy.  No model
  * is needed.

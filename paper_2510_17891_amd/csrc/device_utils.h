@@ -22,8 +22,8 @@ __device__ __forceinline__ uint32_t f2bf(float x) {
 __device__ __forceinline__ float bf2f(uint32_t b) { return __uint_as_float(b << 16); }
 __device__ __forceinline__ uint32_t pack2bf(float lo, float hi) { return f2bf(lo) | (f2bf(hi) << 16); }
 
-// The projections multiply on the f16 grid: weights stay bf16 in memory and are widened in registers, activations
-// are written as f16 by their producers.  f16 keeps 11 significant bits against bf16's 8, so the rounding of an
+// The projections multiply on the f16 grid: the packed weights hold the f16 image of the model's bf16 weights (made
+// once, when they are packed), activations are written as f16 by their producers.  f16 keeps 11 significant bits against bf16's 8, so the rounding of an
 // activation entering a projection is 8 times smaller, at the same bytes and the same matrix-core rate.
 //
 // Two bf16 (one 32-bit word) -> two f16.  Exact for 2^-14 <= |w| <= 65504 (a bf16 significand fits an f16 one);

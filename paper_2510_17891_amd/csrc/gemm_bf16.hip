@@ -2,8 +2,8 @@
 //
 // At M <= 256 the projection is bound by reading W once from HBM (M flop per weight byte), so the kernel is
 // organised around that stream: both operands are stored fragment-major (see frag_offset), which makes every
-// global load a fully coalesced 1 KiB wave access that lands directly in MFMA 32x32x16 operand registers (the bf16
-// weights are widened to f16 there, exactly; the activations arrive as f16) -- no LDS staging, no shuffles.  A wave owns a 64 x (32*MB) output tile over a slice of K; the four waves of a
+// global load a fully coalesced 1 KiB wave access that lands directly in MFMA 32x32x16 operand registers (the packed
+// weights hold the f16 image of the model's bf16 weights; the activations arrive as f16) -- no LDS staging, no shuffles.  A wave owns a 64 x (32*MB) output tile over a slice of K; the four waves of a
 // block take four K slices and add their accumulators through LDS in a fixed order; further K splits across
 // blocks (to put >= 256 blocks on the chip for the small matrices) leave fp32 partials that the consumer sums.
 #include <type_traits>
@@ -18,10 +18,6 @@ namespace {
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-// A weight fragment as loaded (eight bf16) -> the f16 operand of the matrix core (exact, see bf2_to_h2).
-__device__ __forceinline__ u32x4_t w_to_f16(u32x4_t w) {
-  return (u32x4_t){bf2_to_h2(w[0]), bf2_to_h2(w[1]), bf2_to_h2(w[2]), bf2_to_h2(w[3])};
-}
 __device__ __forceinline__ f32x16_t mfma_f16(u32x4_t a, u32x4_t b, f32x16_t c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
 }
@@ -57,7 +53,7 @@ __device__ __forceinline__ void mma_frags(const Frags<MB, RB>& f, f32x16_t (&acc
   for (int t = 0; t < 4; ++t)
 #pragma unroll
     for (int nb = 0; nb < RB; ++nb) {
-      const u32x4_t a = w_to_f16(f.a[nb][t]);
+      const u32x4_t a = f.a[nb][t];
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = mfma_f16(a, f.b[mb][t], acc[nb][mb]);
     }
@@ -334,7 +330,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_wide_kernel(const u32x4_t* _
     for (int t = 0; t < 4; ++t)
 #pragma unroll
       for (int b = 0; b < 4; ++b) {
-        const u32x4_t a = w_to_f16(f.a[b][t]);
+        const u32x4_t a = f.a[b][t];
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) acc[b][mb] = mfma_f16(a, f.b[mb][t], acc[b][mb]);
       }
@@ -542,8 +538,8 @@ __global__ __launch_bounds__(256, MBW == 1 ? 2 : 1) void gemm_bf16_lds_kernel(co
     for (int mb = 0; mb < MBW; ++mb)
 #pragma unroll
       for (int t = 0; t < 4; ++t) xr[s][mb][t] = xb[mb][(size_t)kb_of(s) * 256 + t * 64];
-  wlds[0][0][tid] = w_to_f16(wr[0][0]);
-  wlds[0][1][tid] = w_to_f16(wr[0][1]);
+  wlds[0][0][tid] = wr[0][0];
+  wlds[0][1][tid] = wr[0][1];
   {
     const int ow = next_wslot();
     wr[0][0] = __builtin_nontemporal_load(w0 + ow);
@@ -553,8 +549,8 @@ __global__ __launch_bounds__(256, MBW == 1 ? 2 : 1) void gemm_bf16_lds_kernel(co
   // One k block: publish the next tile, barrier, multiply this one.  j = i mod 4 at compile time.
   auto iter = [&](f32x16_t (&a)[2][MBW], int i, auto jc) __attribute__((always_inline)) {
     constexpr int j = decltype(jc)::value, jn = (j + 1) & 3, jx = j % XS;
-    wlds[jn][0][tid] = w_to_f16(wr[jn][0]);
-    wlds[jn][1][tid] = w_to_f16(wr[jn][1]);
+    wlds[jn][0][tid] = wr[jn][0];
+    wlds[jn][1][tid] = wr[jn][1];
     const int ow = next_wslot();  // k block i + 5
     wr[jn][0] = __builtin_nontemporal_load(w0 + ow);
     wr[jn][1] = __builtin_nontemporal_load(w1 + ow);
@@ -691,7 +687,7 @@ __global__ __launch_bounds__(256, RBN == 3 ? 1 : 2) void gemm_bf16_lds4_kernel(c
     const int ow = next_wslot();
 #pragma unroll
     for (int b = 0; b < RBN; ++b) {
-      wlds[0][b][tid] = w_to_f16(wr[0][b]);
+      wlds[0][b][tid] = wr[0][b];
       wr[0][b] = __builtin_nontemporal_load(wp[b] + ow);
     }
   }
@@ -701,7 +697,7 @@ __global__ __launch_bounds__(256, RBN == 3 ? 1 : 2) void gemm_bf16_lds4_kernel(c
     const int ow = next_wslot();  // k block i + 5
 #pragma unroll
     for (int b = 0; b < RBN; ++b) {
-      wlds[jn][b][tid] = w_to_f16(wr[jn][b]);
+      wlds[jn][b][tid] = wr[jn][b];
       wr[jn][b] = __builtin_nontemporal_load(wp[b] + ow);
     }
     // barrier that orders LDS traffic only (a full one would drain the global loads in flight)
@@ -845,7 +841,7 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_lds8_kernel(const u32x4_t* _
     const int ow = next_wslot();
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
-      wlds[0][2 * half + b][t256] = w_to_f16(wr[0][b]);
+      wlds[0][2 * half + b][t256] = wr[0][b];
       wr[0][b] = __builtin_nontemporal_load(wp[b] + ow);
     }
   }
@@ -855,7 +851,7 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_lds8_kernel(const u32x4_t* _
     const int ow = next_wslot();  // k block i + 5
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
-      wlds[jn][2 * half + b][t256] = w_to_f16(wr[jn][b]);
+      wlds[jn][2 * half + b][t256] = wr[jn][b];
       wr[jn][b] = __builtin_nontemporal_load(wp[b] + ow);
     }
     // barrier that orders LDS traffic only (a full one would drain the global loads in flight)

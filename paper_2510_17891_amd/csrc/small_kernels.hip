@@ -216,7 +216,9 @@ void launch_kv_import(hipStream_t s, const Geometry& g, const void* k_src, const
 }
 
 // ------------------------------------------------------------------------------------------------
-// Weight packing: row-major [N][K] bf16 -> fragment-major.  One thread per 8 consecutive k.
+// Weight packing: row-major [N][K] bf16 -> fragment-major, each weight as its f16 image (the grid the matrix cores
+// multiply on; see bf2_to_h2: exact from 2^-14 up, smaller magnitudes cut toward zero, same bytes per weight), so
+// that no kernel spends an instruction on it.  One thread per 8 consecutive k.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void pack_weight_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int N,
                                                           int K, int seg) {
@@ -224,7 +226,8 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const uint4* __restric
   const int kg = K >> 3;
   if (idx >= (size_t)N * kg) return;
   const int n = (int)(idx / kg), k = (int)(idx - (size_t)n * kg) * 8;
-  dst[weight_offset(n, k, K >> 6, seg) >> 3] = src[idx];
+  const uint4 w = src[idx];
+  dst[weight_offset(n, k, K >> 6, seg) >> 3] = make_uint4(bf2_to_h2(w.x), bf2_to_h2(w.y), bf2_to_h2(w.z), bf2_to_h2(w.w));
 }
 
 void launch_pack_weight_bf16(hipStream_t s, const void* src, void* dst, int N, int K, int seg) {
