@@ -37,7 +37,7 @@ TRAFFIC_RATIO = {
     ("wave", "attn_decode"): (1.054, "attn_bf16.hip", "f3ba5d4ed014e901"),
     ("layer", "attn_decode"): (1.054, "attn_bf16.hip", "f3ba5d4ed014e901"),
     ("full", "attn_decode"): (1.040, "attn_bf16.hip", "f3ba5d4ed014e901"),
-    ("full", "gemm_gate_up_swiglu"): (1.011, "gemm_bf16.hip", "304e69ce061a6808"),
+    ("full", "gemm_gate_up_swiglu"): (1.011, "gemm_bf16.hip", "0acffe086d9cc71f"),
 }
 
 
