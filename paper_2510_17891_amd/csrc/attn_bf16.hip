@@ -108,12 +108,11 @@ __device__ __forceinline__ void load_pair(PagePair8& pp, const u32x4_t* kbase, c
   }
 }
 
-// Four fp8 (one word) -> four bf16 (two words); exact, every e4m3 value is a bf16 value.
+// Four fp8 (one word) -> four bf16 (two words), two values per instruction (the packed conversion with a scale
+// operand, scale one); exact, every e4m3 value is a bf16 value.
 __device__ __forceinline__ void fp8x4_to_bf16x4(uint32_t w, uint32_t& lo, uint32_t& hi) {
-  typedef float f32x2_t __attribute__((ext_vector_type(2)));
-  const f32x2_t a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
-  lo = (__float_as_uint(a[0]) >> 16) | (__float_as_uint(a[1]) & 0xffff0000u);
-  hi = (__float_as_uint(b[0]) >> 16) | (__float_as_uint(b[1]) & 0xffff0000u);
+  lo = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false));
+  hi = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true));
 }
 
 __device__ __forceinline__ void widen(PagePair& out, const PagePair8& in) {
@@ -207,8 +206,9 @@ struct AppendArgs {
 // row block that holds a row's last segment forms the row's new key and value, uses them in its last step and then
 // writes them into their page.  The pools are therefore not declared read-only in that variant.
 // KV8: the pages hold fp8 keys and values (widened to bf16 in registers; scores, softmax and products as for bf16 pages).
+// Its step buffers are half as large, and with the q operand in LDS the variant fits three blocks per compute unit.
 template <bool APPEND, bool KV8>
-__global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* __restrict__ q, const RowMeta* __restrict__ rows,
+__global__ __launch_bounds__(256, KV8 ? 3 : 2) void attn_decode_bf16_kernel(const float* __restrict__ q, const RowMeta* __restrict__ rows,
                                                                const int32_t* __restrict__ block_table, int max_blocks,
                                                                typename PoolPtr<APPEND>::type k_pool,
                                                                typename PoolPtr<APPEND>::type v_pool, float* __restrict__ part,
@@ -276,6 +276,9 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
   float* const lds_part = (float*)(pages + lds_part_offset);
   float* const lds_q = (float*)(pages + lds_q_offset);  // [16 columns][128], APPEND only
   uint16_t* const lds_new = (uint16_t*)(lds_q + 16 * kD);  // the row's new key [128] and value [128] as bf16, APPEND only
+  // KV8: the q operand lives in LDS ([hi | lo][matrix-core step][lane], 8 KiB) instead of 32 registers per lane, which
+  // lets three blocks share a compute unit.  It takes the place of the fp32 queries once those have been read.
+  u32x4_t* const lds_qop = (u32x4_t*)lds_q;
   if (APPEND) {
     // Tasks of a wave: the query heads of columns w, w+4, ...; the last wave of the row block that holds the
     // row's last segment also takes the new key and value.  That wave is the only reader of the page entries they
@@ -371,11 +374,12 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
   }
 
   // ---- q operand: hi/lo bf16 split; columns beyond the set are zero -------------------------------
-  u32x4_t q_hi[4], q_lo[4];
+  u32x4_t q_hi[KV8 ? 1 : 4], q_lo[KV8 ? 1 : 4];  // KV8: the step this wave builds for the block
   {
     const float* qh = APPEND ? lds_q + j * kD : q + ((size_t)col_row * n_q + col_head) * kD;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
+      if (KV8 && s != wave) continue;  // one step per wave, shared through LDS
       uint32_t hi16[4], lo16[4];
 #pragma unroll
       for (int e = 0; e < 8; e += 2) {
@@ -387,11 +391,16 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
         hi16[e >> 1] = h0 | (h1 << 16);
         lo16[e >> 1] = pack2bf(x0 - bf2f(h0), x1 - bf2f(h1));
       }
-      q_hi[s] = (u32x4_t){hi16[0], hi16[1], hi16[2], hi16[3]};
-      q_lo[s] = (u32x4_t){lo16[0], lo16[1], lo16[2], lo16[3]};
+      q_hi[KV8 ? 0 : s] = (u32x4_t){hi16[0], hi16[1], hi16[2], hi16[3]};
+      q_lo[KV8 ? 0 : s] = (u32x4_t){lo16[0], lo16[1], lo16[2], lo16[3]};
     }
   }
-  if (!APPEND) __syncthreads();  // pages[] is filled
+  if constexpr (KV8) {
+    if (APPEND) __syncthreads();  // every wave has read the fp32 queries that the operand overwrites
+    lds_qop[wave * 64 + lane] = q_hi[0];
+    lds_qop[256 + wave * 64 + lane] = q_lo[0];
+  }
+  if (!APPEND || KV8) __syncthreads();  // pages[] is filled; KV8: the q operand is in LDS
 
   // Segment partials of short contexts (<= kLdsSegs segments) stay in LDS; longer ones and the shared ones go
   // through the workspace.  pcol: this lane's column, indexed by the absolute segment number.
@@ -414,7 +423,8 @@ __global__ __launch_bounds__(256, 2) void attn_decode_bf16_kernel(const float* _
     f32x4_t sa = (f32x4_t){0.f, 0.f, 0.f, 0.f}, sb = sa;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      const bf16x8_t qa = __builtin_bit_cast(bf16x8_t, q_hi[s]), ql = __builtin_bit_cast(bf16x8_t, q_lo[s]);
+      const bf16x8_t qa = __builtin_bit_cast(bf16x8_t, KV8 ? lds_qop[s * 64 + lane] : q_hi[KV8 ? 0 : s]);
+      const bf16x8_t ql = __builtin_bit_cast(bf16x8_t, KV8 ? lds_qop[256 + s * 64 + lane] : q_lo[KV8 ? 0 : s]);
       sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pp.k[0][s]), qa, sa, 0, 0, 0);
       sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pp.k[0][s]), ql, sa, 0, 0, 0);
       sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pp.k[1][s]), qa, sb, 0, 0, 0);
@@ -690,7 +700,8 @@ bool launch_attn_decode_bf16(hipStream_t s, const Geometry& g, const float* q, c
   dim3 grid(g.n_kv, M + n_shared, z);
   const int segs = n_seg_max > kLdsSegs ? kLdsSegs : n_seg_max;
   const int part_floats = (g.n_q / g.n_kv) * segs * kPartStride;  // even
-  const int q_ints = append ? 16 * kD + kD : 0;  // the queries of up to 16 columns, the new key and value (bf16)
+  // the queries of up to 16 columns, the new key and value (bf16); fp8 pages: the q operand (in the queries' place)
+  const int q_ints = append ? 16 * kD + kD : g.kv_fp8 ? 16 * kD : 0;
   const size_t lds = (size_t)(page_ints + part_floats + q_ints) * 4;
   const float scale = 1.0f / sqrtf((float)g.head_dim);
   AppendArgs ap = {};
