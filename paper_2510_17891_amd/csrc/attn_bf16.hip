@@ -24,9 +24,11 @@
 // depend on the batch.
 //
 // Shared prompt pages (the samples of one prompt, Section 2.3): rows of equal context length whose first pages are
-// the same physical pages form sets of up to 16 / group rows.  The same launch holds one more kind of block: a
-// "set" block computes up to four of the segments that lie inside the shared pages once for the whole set, the
-// set's (row, head) pairs side by side in the columns of the matrix operand.  The rows of a set start after those
+// the same physical pages form sets of up to 16 / group rows, or 32 / group when the launch is large enough to be
+// bound by memory traffic.  The same launch holds one more kind of block: a "set" block computes up to four of
+// the segments that lie inside the shared pages once for the whole set, the set's (row, head) pairs side by side
+// in the columns of the matrix operand (two operands of 16 columns, fed from the same key and value registers,
+// for the larger sets).  The rows of a set start after those
 // segments; both kinds leave their partials in the workspace and the merge kernel combines them with the
 // arithmetic of the in-block merge.  A column of the matrix product does not depend on its neighbours and the
 // segment bounds are the same, so a row's bits equal those of the row computed alone.
@@ -222,28 +224,34 @@ __global__ __launch_bounds__(256, KV8 ? 3 : 2) void attn_decode_bf16_kernel(cons
   const int group = n_q / n_kv;  // <= 8
   const int j = lane & 15, g = lane >> 4;
   const bool is_set = (int)blockIdx.y >= n_rows;  // block-uniform
-  // column j of the matrix operand: member j / group of the set (the row itself in a row block), head j % group
+  // column c of the matrix operand: member c / group of the set (the row itself in a row block), head c % group.
+  // Lane (j, g) holds column j and, in a set of more than 16 columns, column j + 16 of a second operand as well.
   int r, n_members = 1, skip = 0, shared_segs = 0;
-  int col_row;
+  int col_row[2];
   if (is_set) {
     const AttnShared* sh = shared + (blockIdx.y - n_rows);
     n_members = sh->n_rows;
     shared_segs = sh->n_segs;
     r = sh->rows[0];
-    const int mj = j / group;
-    col_row = sh->rows[mj < n_members ? mj : 0];
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      const int mj = (j + 16 * c) / group;
+      col_row[c] = sh->rows[mj < n_members ? mj : 0];
+    }
   } else {
     r = blockIdx.y;
-    col_row = r;
+    col_row[0] = col_row[1] = r;
     if (skip_segs) skip = skip_segs[r];
   }
-  const bool col_valid = j < n_members * group;
-  const int col_head = hk * group + j % group;
+  const int n_cols = n_members * group;   // <= 32 (fp8 pages: <= 16)
+  const bool wide = !KV8 && n_cols > 16;  // block-uniform: the set fills a second group of 16 columns
+  const bool col_valid[2] = {j < n_cols, j + 16 < n_cols};
+  const int col_head[2] = {hk * group + j % group, hk * group + (j + 16) % group};
   const RowMeta rm = rows[r];
   const int ctx = rm.pos + 1;  // keys 0..pos; the row's own key is in its page already, or (APPEND) formed here
   // A set's members may stand at different positions of one 32-key window (rows of one sequence): same steps and
   // segments, and each column is masked at its own length.  r is the member with the longest context.
-  const int ctx_col = is_set ? rows[col_row].pos + 1 : ctx;
+  const int ctx_col[2] = {is_set ? rows[col_row[0]].pos + 1 : ctx, is_set ? rows[col_row[1]].pos + 1 : ctx};
   const int n_seg = attn_num_segments(ctx);
   const bool in_lds = !is_set && skip == 0 && n_seg <= kLdsSegs;  // merged by this block
   // this block's segments [lo, hi)
@@ -275,6 +283,11 @@ __global__ __launch_bounds__(256, KV8 ? 3 : 2) void attn_decode_bf16_kernel(cons
   bool appends = false;  // wave-uniform: this wave owns the row's last step and with it the new key and value
   float* const lds_part = (float*)(pages + lds_part_offset);
   float* const lds_q = (float*)(pages + lds_q_offset);  // [16 columns][128], APPEND only
+  // A set block keeps no partials in LDS; in a wide one that area holds the queries of columns 16.. ([16][128],
+  // APPEND only) and behind them the q operands of both column groups ([group][hi | lo][matrix-core step][lane]):
+  // with two accumulators per lane there are no registers left for them.
+  float* const lds_q1 = lds_part;
+  u32x4_t* const lds_qopw = (u32x4_t*)(lds_part + 16 * kD);
   uint16_t* const lds_new = (uint16_t*)(lds_q + 16 * kD);  // the row's new key [128] and value [128] as bf16, APPEND only
   // KV8: the q operand lives in LDS ([hi | lo][matrix-core step][lane], 8 KiB) instead of 32 registers per lane, which
   // lets three blocks share a compute unit.  It takes the place of the fp32 queries once those have been read.
@@ -285,13 +298,17 @@ __global__ __launch_bounds__(256, KV8 ? 3 : 2) void attn_decode_bf16_kernel(cons
     // belong to (the block's last 32-key step): it puts them into the operands of that step from LDS, and writes
     // them to the page after its last step, when nothing waits for the stores any more.
     // All loads (split sums, rotation, gains, block table) are issued before anything is consumed.
-    const int n_cols = n_members * group;  // <= 16
-    int set_rows[4] = {0, 0, 0, 0};         // fetched together, ahead of the loads that need them
+    int set_rows[8] = {0, 0, 0, 0, 0, 0, 0, 0};  // fetched together, ahead of the loads that need them
     if (is_set) {
       const AttnShared* sh = shared + (blockIdx.y - n_rows);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) set_rows[e] = sh->rows[e];
+      for (int e = 0; e < 8; ++e) set_rows[e] = sh->rows[e];
     }
+    auto member_row = [&](int m) {  // m is the same for the whole wave
+      const int a = m & 1 ? set_rows[1] : set_rows[0], b = m & 1 ? set_rows[3] : set_rows[2];
+      const int c = m & 1 ? set_rows[5] : set_rows[4], d = m & 1 ? set_rows[7] : set_rows[6];
+      return m & 4 ? (m & 2 ? d : c) : (m & 2 ? b : a);
+    };
     const int uw = __builtin_amdgcn_readfirstlane(wave);  // lets the compiler see that the task choice is per wave
     appends = !is_set && hi == n_seg && uw == 3;
     const int n_tot = (n_q + 2 * n_kv) * kD;
@@ -304,7 +321,7 @@ __global__ __launch_bounds__(256, KV8 ? 3 : 2) void attn_decode_bf16_kernel(cons
       const int t = uw + 4 * u;
       if (t < n_cols) {
         const int m = t / group;  // member of the set
-        const int trow = is_set ? (m == 0 ? set_rows[0] : m == 1 ? set_rows[1] : m == 2 ? set_rows[2] : set_rows[3]) : r;
+        const int trow = is_set ? member_row(m) : r;
         head_pair_issue(lq[u], ap.qkv_part + (size_t)trow * n_tot + (size_t)(hk * group + t % group) * kD, ap.S, ap.split_stride,
                         kD, lane);
       }
@@ -370,29 +387,60 @@ __global__ __launch_bounds__(256, KV8 ? 3 : 2) void attn_decode_bf16_kernel(cons
         lds_new[kD + lane + kD / 2] = (uint16_t)f2bf(hv.v1);
       }
     }
+    if (wide) {  // block-uniform: the same for the columns 16.. of a wide set, in the same arithmetic
+      HeadPairLoads lw[4] = {};
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int t = 16 + uw + 4 * u;
+        if (t < n_cols)
+          head_pair_issue(lw[u], ap.qkv_part + (size_t)member_row(t / group) * n_tot + (size_t)(hk * group + t % group) * kD, ap.S,
+                          ap.split_stride, kD, lane);
+      }
+      HeadPair hw[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        hold(lw[u]);
+        hw[u].cs = cs; hw[u].g0 = bf2f(gq0); hw[u].g1 = bf2f(gq1);
+        head_pair_sum(hw[u], lw[u], ap.S);
+      }
+      head_pairs_finish<4>(hw, kD, normalise, ap.eps);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int t = uw + 4 * u;  // column 16 + t
+        if (16 + t < n_cols) {
+          lds_q1[t * kD + lane] = hw[u].v0;
+          lds_q1[t * kD + kD / 2 + lane] = hw[u].v1;
+        }
+      }
+    }
     __syncthreads();  // pages[] and the queries are in LDS
   }
 
   // ---- q operand: hi/lo bf16 split; columns beyond the set are zero -------------------------------
+  // matrix-core step s of the column whose query is qh: the dims held by lane group g, as the K operand of the page
+  // layout has them
+  auto split_q = [&](const float* qh, bool valid, int s, u32x4_t& hi, u32x4_t& lo) __attribute__((always_inline)) {
+    uint32_t hi16[4], lo16[4];
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+      float x0 = 0.f, x1 = 0.f;
+      const int d0 = KV8 ? 64 * (s >> 1) + 16 * g + 8 * (s & 1) + e : 32 * s + 8 * g + e;
+      if (valid) { x0 = qh[d0]; x1 = qh[d0 + 1]; }
+      const uint32_t h0 = f2bf(x0), h1 = f2bf(x1);
+      hi16[e >> 1] = h0 | (h1 << 16);
+      lo16[e >> 1] = pack2bf(x0 - bf2f(h0), x1 - bf2f(h1));
+    }
+    hi = (u32x4_t){hi16[0], hi16[1], hi16[2], hi16[3]};
+    lo = (u32x4_t){lo16[0], lo16[1], lo16[2], lo16[3]};
+  };
   u32x4_t q_hi[KV8 ? 1 : 4], q_lo[KV8 ? 1 : 4];  // KV8: the step this wave builds for the block
   {
-    const float* qh = APPEND ? lds_q + j * kD : q + ((size_t)col_row * n_q + col_head) * kD;
+    const float* qh = APPEND ? lds_q + j * kD : q + ((size_t)col_row[0] * n_q + col_head[0]) * kD;
+    if constexpr (KV8) {
+      split_q(qh, col_valid[0], wave, q_hi[0], q_lo[0]);  // one step per wave, shared through LDS
+    } else {
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      if (KV8 && s != wave) continue;  // one step per wave, shared through LDS
-      uint32_t hi16[4], lo16[4];
-#pragma unroll
-      for (int e = 0; e < 8; e += 2) {
-        float x0 = 0.f, x1 = 0.f;
-        // dims of matrix-core step s held by lane group g: as the K operand of the page layout has them
-        const int d0 = KV8 ? 64 * (s >> 1) + 16 * g + 8 * (s & 1) + e : 32 * s + 8 * g + e;
-        if (col_valid) { x0 = qh[d0]; x1 = qh[d0 + 1]; }
-        const uint32_t h0 = f2bf(x0), h1 = f2bf(x1);
-        hi16[e >> 1] = h0 | (h1 << 16);
-        lo16[e >> 1] = pack2bf(x0 - bf2f(h0), x1 - bf2f(h1));
-      }
-      q_hi[KV8 ? 0 : s] = (u32x4_t){hi16[0], hi16[1], hi16[2], hi16[3]};
-      q_lo[KV8 ? 0 : s] = (u32x4_t){lo16[0], lo16[1], lo16[2], lo16[3]};
+      for (int s = 0; s < 4; ++s) split_q(qh, col_valid[0], s, q_hi[s], q_lo[s]);
     }
   }
   if constexpr (KV8) {
@@ -400,60 +448,97 @@ __global__ __launch_bounds__(256, KV8 ? 3 : 2) void attn_decode_bf16_kernel(cons
     lds_qop[wave * 64 + lane] = q_hi[0];
     lds_qop[256 + wave * 64 + lane] = q_lo[0];
   }
-  if (!APPEND || KV8) __syncthreads();  // pages[] is filled; KV8: the q operand is in LDS
+  if constexpr (!KV8) {
+    if (wide) {  // both groups' operands go through LDS, wave w storing step w
+      const float* qh = APPEND ? lds_q1 + j * kD : q + ((size_t)col_row[1] * n_q + col_head[1]) * kD;
+      u32x4_t w_hi, w_lo;
+      split_q(qh, col_valid[1], wave, w_hi, w_lo);
+      const u32x4_t h0 = wave == 0 ? q_hi[0] : wave == 1 ? q_hi[1] : wave == 2 ? q_hi[2] : q_hi[3];
+      const u32x4_t l0 = wave == 0 ? q_lo[0] : wave == 1 ? q_lo[1] : wave == 2 ? q_lo[2] : q_lo[3];
+      lds_qopw[wave * 64 + lane] = h0;
+      lds_qopw[256 + wave * 64 + lane] = l0;
+      lds_qopw[512 + wave * 64 + lane] = w_hi;
+      lds_qopw[768 + wave * 64 + lane] = w_lo;
+    }
+  }
+  if (!APPEND || KV8 || wide) __syncthreads();  // pages[] is filled; the q operands kept in LDS are complete
 
   // Segment partials of short contexts (<= kLdsSegs segments) stay in LDS; longer ones and the shared ones go
   // through the workspace.  pcol: this lane's column, indexed by the absolute segment number.
-  float* const gcol = part + ((size_t)col_row * n_q + col_head) * max_segs * kPartStride;
-  float* const pcol = in_lds ? lds_part + (size_t)j * n_seg * kPartStride : gcol;
-  f32x4_t o_acc[8];
-  float m_run, l_run;
-  auto reset = [&]() {
+  float* const gcol = part + ((size_t)col_row[0] * n_q + col_head[0]) * max_segs * kPartStride;
+  float* const pcol[2] = {in_lds ? lds_part + (size_t)j * n_seg * kPartStride : gcol,
+                          part + ((size_t)col_row[1] * n_q + col_head[1]) * max_segs * kPartStride};
+  // per column group (the second one only in a wide set)
+  f32x4_t o_acc[2][8];
+  float m_run[2], l_run[2];
+  auto reset = [&](auto ng) __attribute__((always_inline)) {
 #pragma unroll
-    for (int b = 0; b < 8; ++b) o_acc[b] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-    m_run = -INFINITY;
-    l_run = 0.f;
+    for (int c = 0; c < decltype(ng)::value; ++c) {
+#pragma unroll
+      for (int b = 0; b < 8; ++b) o_acc[c][b] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+      m_run[c] = -INFINITY;
+      l_run[c] = 0.f;
+    }
   };
-  reset();
+  reset(std::integral_constant<int, 2>{});
   while (seg < seg_end && seg_begin(seg + 1) == seg_begin(seg)) ++seg;  // skip leading empty segments
   int boundary = seg < seg_end ? seg_begin(seg + 1) : it_end;
 
   // One step = 32 keys (two pages): scores, online softmax, P*V; at a segment end the partial is written.
-  auto step = [&](const PagePair& pp, int it) __attribute__((always_inline)) {
-    f32x4_t sa = (f32x4_t){0.f, 0.f, 0.f, 0.f}, sb = sa;
+  // NG = 2: the same for both column groups of a wide set, from the same key and value registers.
+  auto step = [&](const PagePair& pp, int it, auto ng) __attribute__((always_inline)) {
+    constexpr int NG = decltype(ng)::value;
+    f32x4_t sa[NG], sb[NG];
+#pragma unroll
+    for (int c = 0; c < NG; ++c) sa[c] = sb[c] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      const bf16x8_t qa = __builtin_bit_cast(bf16x8_t, KV8 ? lds_qop[s * 64 + lane] : q_hi[KV8 ? 0 : s]);
-      const bf16x8_t ql = __builtin_bit_cast(bf16x8_t, KV8 ? lds_qop[256 + s * 64 + lane] : q_lo[KV8 ? 0 : s]);
-      sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pp.k[0][s]), qa, sa, 0, 0, 0);
-      sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pp.k[0][s]), ql, sa, 0, 0, 0);
-      sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pp.k[1][s]), qa, sb, 0, 0, 0);
-      sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pp.k[1][s]), ql, sb, 0, 0, 0);
+      const bool q_in_lds = KV8 || NG == 2;
+      const u32x4_t* const qop = KV8 ? lds_qop : lds_qopw;
+      const bf16x8_t qa = __builtin_bit_cast(bf16x8_t, q_in_lds ? qop[s * 64 + lane] : q_hi[KV8 ? 0 : s]);
+      const bf16x8_t ql = __builtin_bit_cast(bf16x8_t, q_in_lds ? qop[256 + s * 64 + lane] : q_lo[KV8 ? 0 : s]);
+      sa[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pp.k[0][s]), qa, sa[0], 0, 0, 0);
+      sa[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pp.k[0][s]), ql, sa[0], 0, 0, 0);
+      sb[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pp.k[1][s]), qa, sb[0], 0, 0, 0);
+      sb[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pp.k[1][s]), ql, sb[0], 0, 0, 0);
+      if constexpr (NG == 2) {
+        const bf16x8_t wa = __builtin_bit_cast(bf16x8_t, lds_qopw[512 + s * 64 + lane]);
+        const bf16x8_t wl = __builtin_bit_cast(bf16x8_t, lds_qopw[768 + s * 64 + lane]);
+        sa[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pp.k[0][s]), wa, sa[1], 0, 0, 0);
+        sa[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pp.k[0][s]), wl, sa[1], 0, 0, 0);
+        sb[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pp.k[1][s]), wa, sb[1], 0, 0, 0);
+        sb[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pp.k[1][s]), wl, sb[1], 0, 0, 0);
+      }
     }
     const int kbase = it * 32 + 4 * g;
-    float sc[8];
-    float mx = -INFINITY;
+    bf16x8_t p_op[NG];
+    float alpha[NG];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      sc[e] = (kbase + e < ctx_col) ? sa[e] * scale : -INFINITY;
-      sc[4 + e] = (kbase + 16 + e < ctx_col) ? sb[e] * scale : -INFINITY;
-      mx = fmaxf(mx, fmaxf(sc[e], sc[4 + e]));
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-    const float m_new = fmaxf(m_run, mx);  // finite: key it*32 is inside every column's context
-    const float alpha = __expf(m_run - m_new);
-    m_run = m_new;
-    uint32_t pw[4];
-    float psum = 0.f;
+    for (int c = 0; c < NG; ++c) {
+      float sc[8];
+      float mx = -INFINITY;
 #pragma unroll
-    for (int e = 0; e < 8; e += 2) {
-      const uint32_t b0 = f2bf(__expf(sc[e] - m_new)), b1 = f2bf(__expf(sc[e + 1] - m_new));
-      psum += bf2f(b0) + bf2f(b1);  // the sum uses the rounded weights the product uses
-      pw[e >> 1] = b0 | (b1 << 16);
+      for (int e = 0; e < 4; ++e) {
+        sc[e] = (kbase + e < ctx_col[c]) ? sa[c][e] * scale : -INFINITY;
+        sc[4 + e] = (kbase + 16 + e < ctx_col[c]) ? sb[c][e] * scale : -INFINITY;
+        mx = fmaxf(mx, fmaxf(sc[e], sc[4 + e]));
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+      const float m_new = fmaxf(m_run[c], mx);  // finite: key it*32 is inside every column's context
+      alpha[c] = __expf(m_run[c] - m_new);
+      m_run[c] = m_new;
+      uint32_t pw[4];
+      float psum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; e += 2) {
+        const uint32_t b0 = f2bf(__expf(sc[e] - m_new)), b1 = f2bf(__expf(sc[e + 1] - m_new));
+        psum += bf2f(b0) + bf2f(b1);  // the sum uses the rounded weights the product uses
+        pw[e >> 1] = b0 | (b1 << 16);
+      }
+      l_run[c] = l_run[c] * alpha[c] + psum;
+      p_op[c] = __builtin_bit_cast(bf16x8_t, (u32x4_t){pw[0], pw[1], pw[2], pw[3]});
     }
-    l_run = l_run * alpha + psum;
-    const bf16x8_t p_op = __builtin_bit_cast(bf16x8_t, (u32x4_t){pw[0], pw[1], pw[2], pw[3]});
 #pragma unroll
     for (int b = 0; b < 8; ++b) {
       const int jj = b >> 1, par = b & 1;
@@ -462,22 +547,28 @@ __global__ __launch_bounds__(256, KV8 ? 3 : 2) void attn_decode_bf16_kernel(cons
       vop[1] = pp.v[0][jj][2 * par + 1];
       vop[2] = pp.v[1][jj][2 * par];
       vop[3] = pp.v[1][jj][2 * par + 1];
-      o_acc[b] *= alpha;
-      o_acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vop), p_op, o_acc[b], 0, 0, 0);
+#pragma unroll
+      for (int c = 0; c < NG; ++c) {
+        o_acc[c][b] *= alpha[c];
+        o_acc[c][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vop), p_op[c], o_acc[c][b], 0, 0, 0);
+      }
     }
     if (it + 1 == boundary) {  // wave-uniform
-      float l_tot = l_run + __shfl_xor(l_run, 16, kWave);
-      l_tot += __shfl_xor(l_tot, 32, kWave);
-      if (col_valid) {
-        float* p = pcol + (size_t)seg * kPartStride;
 #pragma unroll
-        for (int b = 0; b < 8; ++b) {
-          p[16 * b + 4 * g] = o_acc[b][0]; p[16 * b + 4 * g + 1] = o_acc[b][1];
-          p[16 * b + 4 * g + 2] = o_acc[b][2]; p[16 * b + 4 * g + 3] = o_acc[b][3];
+      for (int c = 0; c < NG; ++c) {
+        float l_tot = l_run[c] + __shfl_xor(l_run[c], 16, kWave);
+        l_tot += __shfl_xor(l_tot, 32, kWave);
+        if (col_valid[c]) {
+          float* p = pcol[c] + (size_t)seg * kPartStride;
+#pragma unroll
+          for (int b = 0; b < 8; ++b) {
+            p[16 * b + 4 * g] = o_acc[c][b][0]; p[16 * b + 4 * g + 1] = o_acc[c][b][1];
+            p[16 * b + 4 * g + 2] = o_acc[c][b][2]; p[16 * b + 4 * g + 3] = o_acc[c][b][3];
+          }
+          if (g == 0) { p[kD] = m_run[c]; p[kD + 1] = l_tot; }
         }
-        if (g == 0) { p[kD] = m_run; p[kD + 1] = l_tot; }
       }
-      reset();
+      reset(ng);
       ++seg;
       while (seg < seg_end && seg_begin(seg + 1) == seg_begin(seg)) ++seg;
       boundary = seg < seg_end ? seg_begin(seg + 1) : it_end;
@@ -487,13 +578,13 @@ __global__ __launch_bounds__(256, KV8 ? 3 : 2) void attn_decode_bf16_kernel(cons
   auto fetch = [&](Buf& pp, int it) __attribute__((always_inline)) {
     load_pair(pp, kb, vb, pages[2 * it], pages[2 * it + 1], n_kv, lane);
   };
-  auto consume = [&](const Buf& pp, int it) __attribute__((always_inline)) {
+  auto consume = [&](const Buf& pp, int it, auto ng) __attribute__((always_inline)) {
     if constexpr (KV8) {
       PagePair w;
       widen(w, pp);
-      step(w, it);
+      step(w, it, ng);
     } else {
-      step(pp, it);
+      step(pp, it, ng);
     }
   };
 
@@ -581,30 +672,38 @@ __global__ __launch_bounds__(256, KV8 ? 3 : 2) void attn_decode_bf16_kernel(cons
 
   // Two register buffers, refilled unconditionally inside the loop so that the compiler's wait counts let the
   // other buffer's 16 loads stay in flight while one is consumed; the ragged end is peeled off below.
-  if (it_begin < it_end) {
-    Buf pa, pb;
-    fetch(pa, it_begin);
-    int it = it_begin;
-    for (; it + 2 < it_end; it += 2) {
-      fetch(pb, it + 1);
-      __builtin_amdgcn_sched_barrier(0);
-      consume(pa, it);
-      __builtin_amdgcn_sched_barrier(0);
-      fetch(pa, it + 2);
-      __builtin_amdgcn_sched_barrier(0);
-      consume(pb, it + 1);
-      __builtin_amdgcn_sched_barrier(0);
+  auto run = [&](auto ng) __attribute__((always_inline)) {
+    constexpr bool kRow = decltype(ng)::value == 1;  // only a row block appends
+    if (it_begin < it_end) {
+      Buf pa, pb;
+      fetch(pa, it_begin);
+      int it = it_begin;
+      for (; it + 2 < it_end; it += 2) {
+        fetch(pb, it + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(pa, it, ng);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(pa, it + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(pb, it + 1, ng);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (it + 1 < it_end) {  // two steps left
+        fetch(pb, it + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(pa, it, ng);
+        if (APPEND && kRow && appends) patch_new(pb);
+        consume(pb, it + 1, ng);
+      } else {  // one step left
+        if (APPEND && kRow && appends) patch_new(pa);
+        consume(pa, it, ng);
+      }
     }
-    if (it + 1 < it_end) {  // two steps left
-      fetch(pb, it + 1);
-      __builtin_amdgcn_sched_barrier(0);
-      consume(pa, it);
-      if (APPEND && appends) patch_new(pb);
-      consume(pb, it + 1);
-    } else {  // one step left
-      if (APPEND && appends) patch_new(pa);
-      consume(pa, it);
-    }
+  };
+  if (wide) {
+    if constexpr (!KV8) run(std::integral_constant<int, 2>{});
+  } else {
+    run(std::integral_constant<int, 1>{});
   }
 
   if (!in_lds) {  // the merge kernel combines the partials in the workspace
@@ -699,7 +798,9 @@ bool launch_attn_decode_bf16(hipStream_t s, const Geometry& g, const float* q, c
   const int z = std::max(attn_num_splits(n_seg_max, spb), (max_shared_segs + 3) / 4);
   dim3 grid(g.n_kv, M + n_shared, z);
   const int segs = n_seg_max > kLdsSegs ? kLdsSegs : n_seg_max;
-  const int part_floats = (g.n_q / g.n_kv) * segs * kPartStride;  // even
+  int part_floats = (g.n_q / g.n_kv) * segs * kPartStride;  // a multiple of 4
+  // a set of more than 16 columns keeps the queries of its columns 16.. and the two q operands there
+  if (n_shared > 0 && !g.kv_fp8) part_floats = std::max(part_floats, 3 * 16 * kD);
   // the queries of up to 16 columns, the new key and value (bf16); fp8 pages: the q operand (in the queries' place)
   const int q_ints = append ? 16 * kD + kD : g.kv_fp8 ? 16 * kD : 0;
   const size_t lds = (size_t)(page_ints + part_floats + q_ints) * 4;

@@ -27,11 +27,23 @@ RL_HOST_DEVICE inline int attn_seg_begin(int sgm, int n_it, int n_seg) {
 
 // Rows of equal context length whose leading pages are the same physical pages: their first n_segs segments are
 // computed once for the set.
+constexpr int kAttnSetRows = 8;
 struct AttnShared {
-  int32_t rows[4];
+  int32_t rows[kAttnSetRows];  // entries beyond n_rows repeat rows[0]
   int32_t n_rows;
   int32_t n_segs;
 };
+
+// Rows a set may hold: the matrix operand has 16 columns of (row, query head of the kv head) pairs, and the kernel
+// for bf16 pages can run two such operands side by side (the one for fp8 pages has the registers for one).  Two
+// operands halve the reads of the common keys once more but make the set's blocks longer, which pays only when
+// the launch is bound by memory traffic: with at least two row blocks per compute unit (512 (row, kv head) pairs).
+// The choice changes no bit of any result.
+inline int attn_rows_per_set(int group, bool kv_fp8, int n_rows, int n_kv) {
+  const int one_operand = std::min(4, 16 / group);
+  if (kv_fp8 || n_rows * n_kv < 512) return one_operand;
+  return std::min(kAttnSetRows, 32 / group);
+}
 
 // Leading segments of a context of ctx keys that end inside the first shared_keys keys.
 inline int attn_shared_segments(int ctx, int shared_keys) {
@@ -48,7 +60,7 @@ struct AttnPlan {
 };
 
 // prefix_id[i] != 0 names the page-sharing family of row i (equal ids: the first prefix_blocks[i] pages are the
-// same physical pages), pos[i] is the row's position.  rows_per_set <= 4.
+// same physical pages), pos[i] is the row's position.  rows_per_set <= kAttnSetRows.
 inline void plan_shared_attention(int n, const int64_t* prefix_id, const int32_t* prefix_blocks, const int32_t* pos,
                                   int rows_per_set, AttnPlan* plan) {
   plan->skip.assign(n, 0);
@@ -74,7 +86,7 @@ inline void plan_shared_attention(int n, const int64_t* prefix_id, const int32_t
         AttnShared s;
         s.n_rows = (int)std::min<size_t>(rows_per_set, e - b);
         s.n_segs = segs;
-        for (int k = 0; k < 4; ++k) s.rows[k] = order[b + (k < s.n_rows ? k : 0)];
+        for (int k = 0; k < kAttnSetRows; ++k) s.rows[k] = order[b + (k < s.n_rows ? k : 0)];
         for (int k = 0; k < s.n_rows; ++k) plan->skip[order[b + k]] = segs;
         plan->sets.push_back(s);
         plan->max_shared_segs = std::max(plan->max_shared_segs, segs);
@@ -86,7 +98,7 @@ inline void plan_shared_attention(int n, const int64_t* prefix_id, const int32_t
 
 // Rows that feed consecutive positions of one sequence (prefill, scoring).  Positions inside one aligned window of
 // 32 have the same number of 32-key steps and hence the same segments, and every row's keys are a prefix of the
-// keys of the row after it: up to rows_per_set (<= 4) neighbouring rows of a window form a set that computes ALL their
+// keys of the row after it: up to rows_per_set (<= kAttnSetRows) neighbouring rows of a window form a set that computes ALL their
 // segments side by side (n_segs = every segment, each column masked at its own context length), so the window's
 // keys are read once per set instead of once per row.  rows[0] of a set is its highest position (the block takes
 // its page list and step count from it).  seq[i], pos[i]: sequence and position of row i; rows of a sequence must
@@ -103,7 +115,7 @@ inline void plan_window_sets(int n, const int32_t* seq, const int32_t* pos, int 
       AttnShared s;
       s.n_rows = e - i;
       s.n_segs = attn_num_segments(pos[e - 1] + 1);  // the same for every member
-      for (int k = 0; k < 4; ++k) s.rows[k] = e - 1 - (k < s.n_rows ? k : 0);
+      for (int k = 0; k < kAttnSetRows; ++k) s.rows[k] = e - 1 - (k < s.n_rows ? k : 0);
       for (int k = i; k < e; ++k) plan->skip[k] = s.n_segs;
       plan->sets.push_back(s);
       plan->max_shared_segs = std::max(plan->max_shared_segs, s.n_segs);

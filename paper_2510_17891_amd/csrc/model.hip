@@ -162,7 +162,7 @@ struct rl_model {
   float* capture = nullptr;
   bool graph_alive = false;     // a decode graph owns the last two metadata slots
   int attn_segs_per_block = 4;  // segments per attention block of contexts beyond 4096 keys (one per wave)
-  bool share_attention = true;  // compute segments inside shared prompt pages once per set of rows
+  int share_attention = 1;  // compute segments inside shared prompt pages once per set of rows (0: off, 2: widest sets always)
   bool attention_appends = true;  // decode steps: the attention kernel forms q and appends k, v itself
   // profiling
   bool prof_on = false;
@@ -369,6 +369,11 @@ rl_status upload_attn_plan(rl_model* m, hipStream_t st, char* hs, char* ds, int 
   return RL_OK;
 }
 
+// Rows per set for a call of n rows (the test switch can ask for the widest sets whatever the size of the call).
+int rows_per_set(const rl_model* m, int n) {
+  return attn_rows_per_set(m->geo.n_q / m->geo.n_kv, m->geo.kv_fp8, m->share_attention == 2 ? (1 << 20) : n, m->geo.n_kv);
+}
+
 // Sets of neighbouring rows of one sequence for a chunk of prefill or scoring rows (bf16 only).
 rl_status upload_window_plan(rl_model* m, hipStream_t st, char* hs, char* ds, int n, const RowMeta* hr, SharedAttn* sa) {
   *sa = SharedAttn();
@@ -376,8 +381,7 @@ rl_status upload_window_plan(rl_model* m, hipStream_t st, char* hs, char* ds, in
   std::vector<int32_t> seq(n), pos(n);
   for (int i = 0; i < n; ++i) { seq[i] = hr[i].seq; pos[i] = hr[i].pos; }
   AttnPlan plan;
-  const int group = m->geo.n_q / m->geo.n_kv;
-  plan_window_sets(n, seq.data(), pos.data(), std::min(4, 16 / group), &plan);
+  plan_window_sets(n, seq.data(), pos.data(), rows_per_set(m, n), &plan);
   return upload_attn_plan(m, st, hs, ds, n, plan, sa);
 }
 
@@ -409,10 +413,7 @@ size_t build_decode_meta(rl_model* m, int32_t n, const int32_t* seq_ids, const s
       pos[i] = hr[i].pos;
       any |= fam[i] != 0;
     }
-    if (any) {
-      const int group = m->geo.n_q / m->geo.n_kv;
-      plan_shared_attention(n, fam.data(), fam_blocks.data(), pos.data(), std::min(4, 16 / group), &plan);
-    }
+    if (any) plan_shared_attention(n, fam.data(), fam_blocks.data(), pos.data(), rows_per_set(m, n), &plan);
   }
   hr[0].pad = (int32_t)grants.size();
   // One upload for everything the step needs: the slot's regions lie at fixed offsets, so the copy runs from the rows
@@ -621,7 +622,7 @@ rl_status rl_debug_shuffle_free_pages(rl_model* m, uint64_t seed) {
 
 rl_status rl_debug_share_attention(rl_model* m, int32_t on) {
   if (!m) return fail(RL_ERR_INVALID_ARG, "model is NULL");
-  m->share_attention = on != 0;
+  m->share_attention = on == 2 ? 2 : on != 0;
   return RL_OK;
 }
 

@@ -36,9 +36,12 @@ int st_reserve(void* t, int s, int tokens, int* grants_out, int max_grants) {
 long long st_prefix_id(void* t, int s) { return ((rl::SeqTable*)t)->prefix_id(s); }
 int st_prefix_blocks(void* t, int s) { return ((rl::SeqTable*)t)->prefix_blocks(s); }
 int st_weight_kb_slot(int kb, int seg) { return rl::weight_kb_slot(kb, seg); }
+int st_attn_rows_per_set(int group, int kv_fp8, int n_rows, int n_kv) {
+  return rl::attn_rows_per_set(group, kv_fp8 != 0, n_rows, n_kv);
+}
 int st_attn_num_segments(int ctx) { return rl::attn_num_segments(ctx); }
 int st_attn_seg_begin(int sgm, int ctx) { return rl::attn_seg_begin(sgm, (ctx + 31) >> 5, rl::attn_num_segments(ctx)); }
-// plan of one decode batch: skip_out[n]; sets_out gets (rows[4], n_rows, n_segs) per set; returns the number of sets
+// plan of one decode batch: skip_out[n]; sets_out gets (rows[8], n_rows, n_segs) per set; returns the number of sets
 int st_plan_shared(void* t, int n, const int* seq_ids, const int* pos, int rows_per_set, int* skip_out, int* sets_out,
                    int max_sets) {
   auto* T = (rl::SeqTable*)t;
@@ -49,9 +52,9 @@ int st_plan_shared(void* t, int n, const int* seq_ids, const int* pos, int rows_
   rl::plan_shared_attention(n, fam.data(), blocks.data(), pos, rows_per_set, &plan);
   for (int i = 0; i < n; ++i) skip_out[i] = plan.skip[i];
   for (size_t k = 0; k < plan.sets.size() && (int)k < max_sets; ++k) {
-    for (int e = 0; e < 4; ++e) sets_out[6 * k + e] = plan.sets[k].rows[e];
-    sets_out[6 * k + 4] = plan.sets[k].n_rows;
-    sets_out[6 * k + 5] = plan.sets[k].n_segs;
+    for (int e = 0; e < rl::kAttnSetRows; ++e) sets_out[10 * k + e] = plan.sets[k].rows[e];
+    sets_out[10 * k + 8] = plan.sets[k].n_rows;
+    sets_out[10 * k + 9] = plan.sets[k].n_segs;
   }
   return (int)plan.sets.size();
 }
@@ -61,9 +64,9 @@ int st_plan_windows(int n, const int* seq, const int* pos, int rows_per_set, int
   rl::plan_window_sets(n, seq, pos, rows_per_set, &plan);
   for (int i = 0; i < n; ++i) skip_out[i] = plan.skip[i];
   for (size_t k = 0; k < plan.sets.size() && (int)k < max_sets; ++k) {
-    for (int e = 0; e < 4; ++e) sets_out[6 * k + e] = plan.sets[k].rows[e];
-    sets_out[6 * k + 4] = plan.sets[k].n_rows;
-    sets_out[6 * k + 5] = plan.sets[k].n_segs;
+    for (int e = 0; e < rl::kAttnSetRows; ++e) sets_out[10 * k + e] = plan.sets[k].rows[e];
+    sets_out[10 * k + 8] = plan.sets[k].n_rows;
+    sets_out[10 * k + 9] = plan.sets[k].n_segs;
   }
   return (int)plan.sets.size();
 }

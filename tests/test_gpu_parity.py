@@ -341,8 +341,9 @@ def test_bf16_layer_eight_query_heads_per_kv_head_long_contexts(amd):
 def test_bf16_layer_forked_rows_share_prompt_attention_and_match_oracle(amd, ctxs, G):
     """8B-dimension layer: cached contexts are each continued as G sequences (shared full pages, copied partial
     page).  The step computes the attention over the common pages once per set of rows; every row still matches
-    the oracle run on that row alone, and the bits equal those with the sharing switched off.  The second case is
-    the launch shape of the 32-sequence rollout workload: 4 prompts of 1024 tokens x 8 samples, 32 rows."""
+    the oracle run on that row alone, and the bits equal those with the sharing switched off and those with the
+    widest sets (two 16-column operands side by side, which calls of this size do not choose by themselves).  The
+    second case is the launch shape of the 32-sequence rollout workload: 4 prompts of 1024 tokens x 8 samples."""
     shape = ri.SHAPES["layer8b"]
     w, wn = make_both(shape, 34)
     wd = to_device(w)
@@ -353,7 +354,7 @@ def test_bf16_layer_forked_rows_share_prompt_attention_and_match_oracle(amd, ctx
     vs = [ri.normal((c, nkv, d), 1.0, 34, 2001 + 2 * b, dtype=torch.bfloat16) for b, c in enumerate(ctxs)]
     x = ri.normal((B, H), 1.0, 34, 1999).to(torch.bfloat16).float()
     outs = []
-    for share in (True, False):
+    for share in (1, 0, 2):
         ro = amd.Rollout(shape, wd, max_seqs=B, max_ctx=5040, max_rows=B, kv_pages=pages)
         ro.rl_debug_shuffle_free_pages(5)
         ro.rl_debug_share_attention(share)
@@ -370,6 +371,7 @@ def test_bf16_layer_forked_rows_share_prompt_attention_and_match_oracle(amd, ctx
         assert all(ro.rl_seq_len(i) == ctxs[i // G] + 2 for i in range(B))
         ro.close()
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    assert torch.equal(outs[0][0], outs[2][0]) and torch.equal(outs[0][1], outs[2][1])
     out = outs[0][0].numpy()
     for i in range(B):
         b = i // G
@@ -1038,7 +1040,8 @@ def test_shared_prompt_attention_is_bit_identical_to_per_row(amd):
     beyond 4096 keys (partials through the workspace) and a short one; with sets of four and of two, a left-over
     row, members that retire, and members that fall out of step.  A fourth instance runs the rotation and the KV
     append as a kernel of their own instead of inside the attention kernel: same bits again, step after step (so
-    the keys and values it leaves in the pages are the same too)."""
+    the keys and values it leaves in the pages are the same too).  A fifth uses the widest sets (all seven samples
+    of a prompt in one set, 28 columns in two operands) in the decode steps and in the prefill's window sets."""
     shape = dict(ri.SHAPES["layer8b"], n_layers=2, hidden=512, n_q=8, n_kv=2, ffn=768, vocab=8192)
     w, _ = make_both(shape, 63, std=0.05)
     wd = to_device(w)
@@ -1051,17 +1054,20 @@ def test_shared_prompt_attention_is_bit_identical_to_per_row(amd):
     rb = amd.Rollout(shape, wd, **kw)       # shared pages, every row on its own
     rc = amd.Rollout(shape, wd, **kw)       # nothing shared
     rd = amd.Rollout(shape, wd, **kw)       # shared pages and attention, separate rotation + append kernel
+    re = amd.Rollout(shape, wd, **kw)       # shared pages and attention, widest sets
     rb.rl_debug_share_attention(False)
     rd.rl_debug_attention_appends(False)
+    re.rl_debug_share_attention(2)
     ta, la = ra.rl_prefill_groups(ids, G, prompts, 1.0, seed)
     tb, lb = rb.rl_prefill_groups(ids, G, prompts, 1.0, seed)
     tc, lc = rc.rl_prefill(ids, [prompts[i // G] for i in ids], 1.0, seed)
     td, ld = rd.rl_prefill_groups(ids, G, prompts, 1.0, seed)
+    te, le = re.rl_prefill_groups(ids, G, prompts, 1.0, seed)
     torch.cuda.synchronize()
     assert torch.equal(ta, tb) and torch.equal(la, lb) and torch.equal(ta, tc) and torch.equal(la, lc)
-    assert torch.equal(ta, td) and torch.equal(la, ld)
+    assert torch.equal(ta, td) and torch.equal(la, ld) and torch.equal(ta, te) and torch.equal(la, le)
     V = shape["vocab"]
-    every = (ra, rb, rc, rd)
+    every = (ra, rb, rc, rd, re)
 
     def step(active, tok):
         zs = [torch.empty(len(active), V, device=DEV) for _ in every]

@@ -172,9 +172,11 @@ def test_lockstep_growth_keeps_sequences_physically_contiguous(st):
 def _plan(L, t, seqs, pos, rows_per_set):
     n = len(seqs)
     skip = (C.c_int * n)()
-    sets = (C.c_int * (6 * n))()
+    sets = (C.c_int * (10 * n))()                  # per set: rows[8], n_rows, n_segs
     k = L.st_plan_shared(t, n, (C.c_int * n)(*seqs), (C.c_int * n)(*pos), rows_per_set, skip, sets, n)
-    return list(skip), [(list(sets[6 * i:6 * i + sets[6 * i + 4]]), sets[6 * i + 5]) for i in range(k)]
+    for i in range(k):                             # the unused row slots repeat the first row
+        assert all(sets[10 * i + e] == sets[10 * i] for e in range(sets[10 * i + 8], 8))
+    return list(skip), [(list(sets[10 * i:10 * i + sets[10 * i + 8]]), sets[10 * i + 9]) for i in range(k)]
 
 
 def test_attention_segments_partition_every_context(st):
@@ -221,6 +223,13 @@ def test_shared_attention_plan(st):
     # five rows with sets of four: the fifth computes everything itself
     skip, sets = _plan(st, t, [0, 1, 2, 3, 4], [1150] * 5, 4)
     assert sets == [([0, 1, 2, 3], sA)] and skip == [sA] * 4 + [0]
+    # sets of eight (two 16-column operands at four query heads per kv head): all seven rows of the family in one set
+    skip, sets = _plan(st, t, [0, 1, 2, 3, 4, 5, 6], [1150] * 7, 8)
+    assert sets == [([0, 1, 2, 3, 4, 5, 6], sA)] and skip == [sA] * 7
+    # ... which the model asks for only with bf16 pages and at least 512 (row, kv head) pairs in the call
+    assert [st.st_attn_rows_per_set(g, 0, 128, 8) for g in (1, 2, 4, 8)] == [8, 8, 8, 4]
+    assert [st.st_attn_rows_per_set(g, 1, 128, 8) for g in (1, 2, 4, 8)] == [4, 4, 4, 2]
+    assert [st.st_attn_rows_per_set(4, 0, n, 8) for n in (1, 32, 63, 64, 256)] == [4, 4, 4, 8, 8]
     # right after the prompt the last shared page may hold the row's own position: never shared
     skip, sets = _plan(st, t, [0, 1], [1088, 1088], 2)
     assert sets and sets[0][1] == covered(1089, 1088) and st.st_attn_seg_begin(sets[0][1], 1089) * 32 <= 1088
@@ -241,9 +250,11 @@ def test_window_sets_of_prefill_rows(st):
     def plan(seq, pos, per_set):
         n = len(seq)
         skip = (C.c_int * n)()
-        sets = (C.c_int * (6 * n))()
+        sets = (C.c_int * (10 * n))()
         k = st.st_plan_windows(n, (C.c_int * n)(*seq), (C.c_int * n)(*pos), per_set, skip, sets, n)
-        return list(skip), [tuple(sets[6 * i:6 * i + 6]) for i in range(k)]
+        # per set: rows[8], n_rows, n_segs; returned as (the four first rows, n_rows, n_segs, all eight rows)
+        return list(skip), [tuple(sets[10 * i:10 * i + 4]) + (sets[10 * i + 8], sets[10 * i + 9], tuple(sets[10 * i:10 * i + 8]))
+                            for i in range(k)]
 
     # one sequence, positions 28..37: the window boundary at 32 cuts the sets; sets of four
     seq, pos = [5] * 10, list(range(28, 38))
@@ -266,6 +277,11 @@ def test_window_sets_of_prefill_rows(st):
     seq, pos = [0] * 4, [1022, 1023, 1024, 1025]
     skip, sets = plan(seq, pos, 4)
     assert [sorted(set(s[:4])) for s in sets] == [[0, 1], [2, 3]] and [s[5] for s in sets] == [4, 8]
+    # sets of eight: a whole window of 32 positions gives four sets, each led by its highest position
+    seq, pos = [3] * 32, list(range(64, 96))
+    skip, sets = plan(seq, pos, 8)
+    assert [s[4] for s in sets] == [8, 8, 8, 8]
+    assert [list(s[6]) for s in sets] == [list(range(b + 7, b - 1, -1)) for b in (0, 8, 16, 24)]
 
 
 def test_weight_k_block_order_is_a_permutation_that_interleaves_four_segments(st):
