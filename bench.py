@@ -34,9 +34,9 @@ HBM_PEAK_GBS = 8000.0
 # file still has the hash it had when the counters were taken; otherwise "traffic" is null.
 TRAFFIC_RATIO = {
     # one layer at the launch shape of the 128-sequence wave (16 groups x 8 samples, 2048 shared + 7168 private tokens)
-    ("wave", "attn_decode"): (1.054, "attn_bf16.hip", "f3ba5d4ed014e901"),
-    ("layer", "attn_decode"): (1.054, "attn_bf16.hip", "f3ba5d4ed014e901"),
-    ("full", "attn_decode"): (1.040, "attn_bf16.hip", "f3ba5d4ed014e901"),
+    ("wave", "attn_decode"): (1.043, "attn_bf16.hip", "754511b8bf6d831c"),
+    ("layer", "attn_decode"): (1.043, "attn_bf16.hip", "754511b8bf6d831c"),
+    ("full", "attn_decode"): (1.040, "attn_bf16.hip", "754511b8bf6d831c"),
     ("full", "gemm_gate_up_swiglu"): (1.011, "gemm_bf16.hip", "0acffe086d9cc71f"),
 }
 
@@ -103,6 +103,9 @@ def parse():
     ap.add_argument("--top-p", type=float, default=0.0, help="full workload: top-p cut (0: none)")
     ap.add_argument("--no-share-attention", action="store_true",
                     help="full workload: attention over the prompt pages once per row instead of once per set of samples")
+    ap.add_argument("--set-width", type=int, choices=[1, 2, 3], default=1,
+                    help="full and layer workloads: rows per set of samples; 1: the library's rule, 2: always the wide "
+                         "sets (two operands), 3: never")
     ap.add_argument("--separate-append", action="store_true",
                     help="rotation and KV append as a kernel of their own instead of inside the decode attention kernel")
     args = ap.parse_args()
@@ -744,6 +747,8 @@ def main():
         torch.cuda.empty_cache()
         if args.no_share_attention:
             ro.rl_debug_share_attention(False)
+        elif args.set_width != 1:
+            ro.rl_debug_share_attention(args.set_width)
         if args.separate_append:
             ro.rl_debug_attention_appends(False)
         prompts = ri.tokens((n_prompts, P), shape["vocab"], seed, 900)
@@ -781,6 +786,8 @@ def main():
             ro.rl_debug_shuffle_free_pages(seed)  # block tables are a random permutation of the pool
         if args.no_share_attention:
             ro.rl_debug_share_attention(False)
+        elif args.set_width != 1:
+            ro.rl_debug_share_attention(args.set_width)
         if args.separate_append:
             ro.rl_debug_attention_appends(False)
         for b in range(0, B, args.group):

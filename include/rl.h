@@ -393,8 +393,8 @@ rl_status rl_debug_shuffle_free_pages(rl_model* m, uint64_t seed);
  */
 rl_status rl_debug_share_attention(rl_model* m, int32_t on);
 /* on = 2: as on = 1, and the sets are as large as the kernel allows (bf16 pages: two 16-column operands side by
- * side, i.e. up to 32 / (query heads per kv head) rows) in every call; by default only calls with at least 512
- * (row, kv head) pairs use those, smaller ones a single operand.  No bit of any result depends on the choice. */
+ * side, i.e. up to 32 / (query heads per kv head) rows) in every call; on = 3: a single operand in every call.
+ * By default the size of the call decides.  No bit of any result depends on the choice. */
 
 /*
  * Test aid: switch off (on = 0) or on again (the default) the fused form of a bf16 decode step in which the

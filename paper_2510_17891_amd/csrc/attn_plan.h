@@ -36,12 +36,13 @@ struct AttnShared {
 
 // Rows a set may hold: the matrix operand has 16 columns of (row, query head of the kv head) pairs, and the kernel
 // for bf16 pages can run two such operands side by side (the one for fp8 pages has the registers for one).  Two
-// operands halve the reads of the common keys once more but make the set's blocks longer, which pays only when
-// the launch is bound by memory traffic: with at least two row blocks per compute unit (512 (row, kv head) pairs).
+// operands halve the reads of the common keys once more but make the set's blocks the longest of the launch, which
+// pays only when the launch is large and bound by memory traffic: from 1024 (row, kv head) pairs on, four row blocks
+// per compute unit (measured: a loss at 64 rows, even at 96 to 128 rows, a gain from 128 rows with long prompts on).
 // The choice changes no bit of any result.
 inline int attn_rows_per_set(int group, bool kv_fp8, int n_rows, int n_kv) {
   const int one_operand = std::min(4, 16 / group);
-  if (kv_fp8 || n_rows * n_kv < 512) return one_operand;
+  if (kv_fp8 || n_rows * n_kv < 1024) return one_operand;
   return std::min(kAttnSetRows, 32 / group);
 }
 

@@ -162,7 +162,7 @@ struct rl_model {
   float* capture = nullptr;
   bool graph_alive = false;     // a decode graph owns the last two metadata slots
   int attn_segs_per_block = 4;  // segments per attention block of contexts beyond 4096 keys (one per wave)
-  int share_attention = 1;  // compute segments inside shared prompt pages once per set of rows (0: off, 2: widest sets always)
+  int share_attention = 1;  // compute segments inside shared prompt pages once per set of rows (0: off, 2 / 3: wide sets always / never)
   bool attention_appends = true;  // decode steps: the attention kernel forms q and appends k, v itself
   // profiling
   bool prof_on = false;
@@ -369,9 +369,11 @@ rl_status upload_attn_plan(rl_model* m, hipStream_t st, char* hs, char* ds, int 
   return RL_OK;
 }
 
-// Rows per set for a call of n rows (the test switch can ask for the widest sets whatever the size of the call).
+// Rows per set for a call of n rows (the test switch can ask for the wide sets always or never, whatever the size).
 int rows_per_set(const rl_model* m, int n) {
-  return attn_rows_per_set(m->geo.n_q / m->geo.n_kv, m->geo.kv_fp8, m->share_attention == 2 ? (1 << 20) : n, m->geo.n_kv);
+  if (m->share_attention == 2) n = 1 << 20;
+  if (m->share_attention == 3) n = 0;
+  return attn_rows_per_set(m->geo.n_q / m->geo.n_kv, m->geo.kv_fp8, n, m->geo.n_kv);
 }
 
 // Sets of neighbouring rows of one sequence for a chunk of prefill or scoring rows (bf16 only).
@@ -622,7 +624,7 @@ rl_status rl_debug_shuffle_free_pages(rl_model* m, uint64_t seed) {
 
 rl_status rl_debug_share_attention(rl_model* m, int32_t on) {
   if (!m) return fail(RL_ERR_INVALID_ARG, "model is NULL");
-  m->share_attention = on == 2 ? 2 : on != 0;
+  m->share_attention = (on == 2 || on == 3) ? on : on != 0;
   return RL_OK;
 }
 

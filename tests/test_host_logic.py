@@ -226,10 +226,10 @@ def test_shared_attention_plan(st):
     # sets of eight (two 16-column operands at four query heads per kv head): all seven rows of the family in one set
     skip, sets = _plan(st, t, [0, 1, 2, 3, 4, 5, 6], [1150] * 7, 8)
     assert sets == [([0, 1, 2, 3, 4, 5, 6], sA)] and skip == [sA] * 7
-    # ... which the model asks for only with bf16 pages and at least 512 (row, kv head) pairs in the call
+    # ... which the model asks for only with bf16 pages and at least 1024 (row, kv head) pairs in the call
     assert [st.st_attn_rows_per_set(g, 0, 128, 8) for g in (1, 2, 4, 8)] == [8, 8, 8, 4]
     assert [st.st_attn_rows_per_set(g, 1, 128, 8) for g in (1, 2, 4, 8)] == [4, 4, 4, 2]
-    assert [st.st_attn_rows_per_set(4, 0, n, 8) for n in (1, 32, 63, 64, 256)] == [4, 4, 4, 8, 8]
+    assert [st.st_attn_rows_per_set(4, 0, n, 8) for n in (1, 32, 64, 127, 128, 256)] == [4, 4, 4, 4, 8, 8]
     # right after the prompt the last shared page may hold the row's own position: never shared
     skip, sets = _plan(st, t, [0, 1], [1088, 1088], 2)
     assert sets and sets[0][1] == covered(1089, 1088) and st.st_attn_seg_begin(sets[0][1], 1089) * 32 <= 1088
