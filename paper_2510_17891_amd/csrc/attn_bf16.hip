@@ -568,6 +568,11 @@ __global__ __launch_bounds__(256, KV8 ? 3 : 2) void attn_decode_bf16_kernel(cons
           if (g == 0) { p[kD] = m_run[c]; p[kD + 1] = l_tot; }
         }
       }
+      // Stores and loads share one counter and may finish out of order, so a store that may be pending makes the
+      // compiler turn every later wait for a load into a wait for everything, the other buffer's loads included.
+      // Draining the counter here, once per segment, keeps the steps after this branch free of that: they wait
+      // only for the loads they consume, and the other buffer stays in flight.
+      __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0); expcnt and lgkmcnt at their maxima, i.e. not waited for
       reset(ng);
       ++seg;
       while (seg < seg_end && seg_begin(seg + 1) == seg_begin(seg)) ++seg;
