@@ -34,9 +34,9 @@ HBM_PEAK_GBS = 8000.0
 # file still has the hash it had when the counters were taken; otherwise "traffic" is null.
 TRAFFIC_RATIO = {
     # one layer at the launch shape of the 128-sequence wave (16 groups x 8 samples, 2048 shared + 7168 private tokens)
-    ("wave", "attn_decode"): (1.044, "attn_bf16.hip", "8c6e7db88b866054"),
-    ("layer", "attn_decode"): (1.044, "attn_bf16.hip", "8c6e7db88b866054"),
-    ("full", "attn_decode"): (1.040, "attn_bf16.hip", "8c6e7db88b866054"),
+    ("wave", "attn_decode"): (1.044, "attn_bf16.hip", "bf9a68219783273c"),
+    ("layer", "attn_decode"): (1.044, "attn_bf16.hip", "bf9a68219783273c"),
+    ("full", "attn_decode"): (1.040, "attn_bf16.hip", "bf9a68219783273c"),
     ("full", "gemm_gate_up_swiglu"): (1.011, "gemm_bf16.hip", "0acffe086d9cc71f"),
 }
 

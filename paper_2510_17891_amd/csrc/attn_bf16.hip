@@ -59,6 +59,12 @@ typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 constexpr int kD = 128;
 constexpr int kPageElems = kPageTokens * kD;  // 2048 bf16 = 4 KiB per (page, kv head), K or V
 constexpr int kPartStride = kD + 2;           // floats per (row, head, segment): O[128], max, sum
+// In LDS a segment's record is those 130 floats in a row.  In the workspace the max_segs records of a (row, head) are
+// split into the O rows (128 floats each, so that every row is whole cache lines: max_segs is a multiple of 16 and
+// with it the 520 * max_segs bytes of a (row, head)) followed by the (max, sum) pairs, which the merge then finds
+// side by side.
+__device__ __forceinline__ size_t part_o(int max_segs, int seg) { return (size_t)seg * kD; }
+__device__ __forceinline__ size_t part_ml(int max_segs, int seg) { return (size_t)max_segs * kD + 2 * (size_t)seg; }
 constexpr int kLdsSegs = 16;                  // contexts up to 4096 keep their segment partials in LDS
 
 constexpr int kPairU4(bool kv8) { return kv8 ? 2 * kPageElems / 16 : 2 * kPageElems / 8; }  // 16-byte units of one (page, kv head): K and V
@@ -148,11 +154,11 @@ __device__ __forceinline__ void widen(PagePair& out, const PagePair8& in) {
 __host__ __device__ inline int attn_num_splits(int n_seg, int spb) { return n_seg <= kLdsSegs ? 1 : (n_seg + spb - 1) / spb; }
 
 // Flat merge of the (at most kLdsSegs) segments of one head: running maximum, weights exp(m_c - M), sums in index
-// order; the lane owns dims 2*lane, 2*lane+1.  seg_ptr(c) -> [O(128), max, sum] of segment c (LDS or workspace);
-// all loads are issued before the arithmetic.  Returns the two normalised outputs packed as f16 (the operand type
+// order; the lane owns dims 2*lane, 2*lane+1.  o_ptr(c) -> O(128), ml_ptr(c) -> (max, sum) of segment c (LDS or
+// workspace); all loads are issued before the arithmetic.  Returns the two normalised outputs packed as f16 (the operand type
 // of the output projection).
-template <typename F>
-__device__ __forceinline__ uint32_t merge_short(F seg_ptr, int n_seg, int n_it, int lane) {
+template <typename F, typename G>
+__device__ __forceinline__ uint32_t merge_short(F o_ptr, G ml_ptr, int n_seg, int n_it, int lane) {
   float mx[kLdsSegs], lx[kLdsSegs];
   float2 vx[kLdsSegs];
 #pragma unroll
@@ -161,10 +167,10 @@ __device__ __forceinline__ uint32_t merge_short(F seg_ptr, int n_seg, int n_it, 
     lx[c] = 0.f;
     vx[c] = make_float2(0.f, 0.f);
     if (c < n_seg && attn_seg_begin(c + 1, n_it, n_seg) != attn_seg_begin(c, n_it, n_seg)) {
-      const float* pc = seg_ptr(c);
-      mx[c] = pc[kD];
-      lx[c] = pc[kD + 1];
-      vx[c] = *(const float2*)(pc + 2 * lane);
+      const float* pm = ml_ptr(c);
+      mx[c] = pm[0];
+      lx[c] = pm[1];
+      vx[c] = *(const float2*)(o_ptr(c) + 2 * lane);
     }
   }
   float M = -INFINITY;
@@ -559,13 +565,15 @@ __global__ __launch_bounds__(256, KV8 ? 3 : 2) void attn_decode_bf16_kernel(cons
         float l_tot = l_run[c] + __shfl_xor(l_run[c], 16, kWave);
         l_tot += __shfl_xor(l_tot, 32, kWave);
         if (col_valid[c]) {
-          float* p = pcol[c] + (size_t)seg * kPartStride;
+          const bool lds_rec = c == 0 && in_lds;  // block-uniform
+          float* p = pcol[c] + (lds_rec ? (size_t)seg * kPartStride : part_o(max_segs, seg));
+          float* pm = lds_rec ? p + kD : pcol[c] + part_ml(max_segs, seg);
 #pragma unroll
           for (int b = 0; b < 8; ++b) {
             p[16 * b + 4 * g] = o_acc[c][b][0]; p[16 * b + 4 * g + 1] = o_acc[c][b][1];
             p[16 * b + 4 * g + 2] = o_acc[c][b][2]; p[16 * b + 4 * g + 3] = o_acc[c][b][3];
           }
-          if (g == 0) { p[kD] = m_run[c]; p[kD + 1] = l_tot; }
+          if (g == 0) { pm[0] = m_run[c]; pm[1] = l_tot; }
         }
       }
       // Stores and loads share one counter and may finish out of order, so a store that may be pending makes the
@@ -721,7 +729,8 @@ __global__ __launch_bounds__(256, KV8 ? 3 : 2) void attn_decode_bf16_kernel(cons
   for (int hh = wave; hh < group; hh += 4) {
     const int head = hk * group + hh;
     const float* p = lds_part + (size_t)hh * n_seg * kPartStride;
-    const uint32_t o2 = merge_short([&](int c) { return p + (size_t)c * kPartStride; }, n_seg, n_it, lane);
+    const uint32_t o2 = merge_short([&](int c) { return p + (size_t)c * kPartStride; },
+                                    [&](int c) { return p + (size_t)c * kPartStride + kD; }, n_seg, n_it, lane);
     *(uint32_t*)(o_out + frag_offset(r, head * kD + 2 * lane, (n_q * kD) >> 6)) = o2;
   }
   if (APPEND && appends) store_new();
@@ -741,7 +750,8 @@ __global__ __launch_bounds__(64) void attn_merge_bf16_kernel(const float* __rest
   const float* p = part + ((size_t)r * n_q + head) * max_segs * kPartStride;
   if (n_seg <= kLdsSegs) {
     if (!skip_segs || skip_segs[r] == 0) return;  // finished by its own block
-    const uint32_t o2 = merge_short([&](int c) { return p + (size_t)c * kPartStride; }, n_seg, (ctx + 31) >> 5, lane);
+    const uint32_t o2 = merge_short([&](int c) { return p + part_o(max_segs, c); }, [&](int c) { return p + part_ml(max_segs, c); },
+                                    n_seg, (ctx + 31) >> 5, lane);
     *(uint32_t*)(o_out + frag_offset(r, head * kD + 2 * lane, (n_q * kD) >> 6)) = o2;
     return;
   }
@@ -753,7 +763,11 @@ __global__ __launch_bounds__(64) void attn_merge_bf16_kernel(const float* __rest
     const int c = lane + 64 * u;
     mc[u] = -INFINITY;
     lc[u] = 0.f;
-    if (c < n_seg) { mc[u] = p[(size_t)c * kPartStride + kD]; lc[u] = p[(size_t)c * kPartStride + kD + 1]; }
+    if (c < n_seg) {
+      const float2 ml = *(const float2*)(p + part_ml(max_segs, c));
+      mc[u] = ml.x;
+      lc[u] = ml.y;
+    }
     M = fmaxf(M, mc[u]);
   }
   M = wave_max(M);
@@ -773,7 +787,7 @@ __global__ __launch_bounds__(64) void attn_merge_bf16_kernel(const float* __rest
       float w[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        v[e] = *(const float2*)(p + (size_t)(64 * u + cl + e) * kPartStride + 2 * lane);
+        v[e] = *(const float2*)(p + part_o(max_segs, 64 * u + cl + e) + 2 * lane);
         w[e] = __shfl(mc[u], cl + e, kWave);
       }
 #pragma unroll
@@ -789,7 +803,9 @@ __global__ __launch_bounds__(64) void attn_merge_bf16_kernel(const float* __rest
 
 }  // namespace
 
-int attn_bf16_max_segments(int max_ctx) { return attn_num_segments(max_ctx); }
+// Segment records to allocate per (row, head): a multiple of 16, which keeps every O row of the workspace on whole
+// cache lines.
+int attn_bf16_max_segments(int max_ctx) { return (attn_num_segments(max_ctx) + 15) & ~15; }
 
 bool launch_attn_decode_bf16(hipStream_t s, const Geometry& g, const float* q, const RowMeta* rows,
                              const int32_t* block_table, void* k_pool_layer, void* v_pool_layer, float* part,

@@ -78,7 +78,8 @@ void launch_page_copy(hipStream_t s, void* kv_pool, size_t layer_bytes, size_t p
 // ---- attention -----------------------------------------------------------------------------------
 // bf16, head_dim 128: decode attention over paged KV (MFMA), one block per (row, kv head), context cut into
 // segments that depend on the context length only and merged in index order; writes f16 fragment-major
-// [M x n_q*d].  part: fp32 [M][n_q][max_segs][d+2] with max_segs = attn_bf16_max_segments(max_ctx).
+// [M x n_q*d].  part: fp32, per (row, head) max_segs rows of d floats followed by max_segs (max, sum) pairs, with
+// max_segs = attn_bf16_max_segments(max_ctx).
 int attn_bf16_max_segments(int max_ctx);
 // skip_segs (per row, may be null): leading segments of the row that a set in `shared` covers; every row with a
 // non-zero entry must belong to exactly one set with that n_segs.  max_shared_segs = largest n_segs.
