@@ -1099,6 +1099,47 @@ def test_shared_prompt_attention_is_bit_identical_to_per_row(amd):
         r.close()
 
 
+@pytest.mark.parametrize("n_q,n_kv", [(8, 1), (4, 2), (2, 2), (6, 2)])
+def test_shared_attention_set_widths_agree_for_other_head_groupings(amd, n_q, n_kv):
+    """Query heads per kv head other than the 8B model's four: eight (a set of four rows fills both 16-column
+    operands), two (eight rows in one operand), one, and three (a row's heads straddle the two operands).  Logits,
+    tokens and log-probs with the wide sets, with the narrow ones and with the sharing switched off are the same
+    bits, for a prompt inside one block's segments and one beyond 4096 keys, with a retired member."""
+    shape = dict(ri.SHAPES["layer8b"], n_layers=2, hidden=512, n_q=n_q, n_kv=n_kv, ffn=768, vocab=8192)
+    w, _ = make_both(shape, 64, std=0.05)
+    wd = to_device(w)
+    G, seed = 8, 9
+    lens = [700, 4400]
+    prompts = [ri.tokens((n,), shape["vocab"], 64, 950 + i).tolist() for i, n in enumerate(lens)]
+    ids = list(range(len(lens) * G))
+    kw = dict(max_seqs=16, max_ctx=4480, max_rows=32, kv_pages=700)
+    every = [amd.Rollout(shape, wd, **kw) for _ in range(3)]
+    for r, mode in zip(every, (0, 2, 3)):           # off, wide sets, narrow sets
+        r.rl_debug_share_attention(mode)
+    first = [r.rl_prefill_groups(ids, G, prompts, 1.0, seed) for r in every]
+    torch.cuda.synchronize()
+    for t_, l_ in first[1:]:
+        assert torch.equal(first[0][0], t_) and torch.equal(first[0][1], l_)
+    V = shape["vocab"]
+    tok = {i: int(first[0][0][k]) for k, i in enumerate(ids)}
+    active = list(ids)
+    for it in range(6):
+        if it == 3:                                  # seven and eight members from here on
+            for r in every:
+                r.rl_free_seqs([5])
+            active.remove(5)
+        t_in = torch.tensor([tok[i] for i in active], dtype=torch.int32, device=DEV)
+        zs = [torch.empty(len(active), V, device=DEV) for _ in every]
+        outs = [r.rl_decode_step(active, t_in, 1.0, seed, debug_logits=z) for r, z in zip(every, zs)]
+        torch.cuda.synchronize()
+        for z, (t_, l_) in zip(zs[1:], outs[1:]):
+            assert torch.equal(zs[0], z) and torch.equal(outs[0][0], t_) and torch.equal(outs[0][1], l_), (it, n_q, n_kv)
+        for k, i in enumerate(active):
+            tok[i] = int(outs[0][0][k])
+    for r in every:
+        r.close()
+
+
 # ------------------------------------------------------------------------------ teacher-forced scoring call
 def test_score_matches_oracle_log_softmax(amd):
     shape = ri.SHAPES["tiny"]
