@@ -37,7 +37,7 @@ TRAFFIC_RATIO = {
     ("wave", "attn_decode"): (1.044, "attn_bf16.hip", "bf9a68219783273c"),
     ("layer", "attn_decode"): (1.044, "attn_bf16.hip", "bf9a68219783273c"),
     ("full", "attn_decode"): (1.040, "attn_bf16.hip", "bf9a68219783273c"),
-    ("full", "gemm_gate_up_swiglu"): (1.011, "gemm_bf16.hip", "0acffe086d9cc71f"),
+    ("full", "gemm_gate_up_swiglu"): (1.011, "gemm_bf16.hip", "4edefcaac5772181"),
 }
 
 

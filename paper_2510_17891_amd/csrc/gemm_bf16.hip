@@ -915,6 +915,148 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_lds8_kernel(const u32x4_t* _
   }
 }
 
+// The eight-wave block with a 96-row weight tile (three row blocks), for matrices whose 128-row tiles would leave a
+// quarter of the compute units without a block while 96-row tiles give every unit one.  The first four waves stage
+// row blocks 0 and 2, the other four row block 1; each half runs its own copy of the loop (same steps, one barrier
+// per k block in both), so that no load in the pipeline is conditional.  Same K quarters, same order: same bits.
+template <int EPI, int XS>
+__global__ __launch_bounds__(512, 1) void gemm_bf16_lds8r3_kernel(const u32x4_t* __restrict__ X, const u32x4_t* __restrict__ W,
+                                                                void* __restrict__ out, int M, int N, int K,
+                                                                int kb_per_quarter) {
+  static_assert(EPI != kEpiSample, "per-row-block epilogues only");
+  constexpr int MBW = 1, RBN = 3;
+  __shared__ u32x4_t wlds[4][RBN][256];  // four stages x three row blocks x 4 KiB
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int KB = K >> 6;
+  const int n_blocks_m = (M + 31) >> 5;
+  const int t256 = tid & 255;
+  const int tile_x = blockIdx.x;
+  const int m_blk0 = blockIdx.z * 8 + wave;
+  const bool has_rows = m_blk0 < n_blocks_m;
+  const int n_rb = EPI == kEpiSwiGLU ? (N >> 4) : (N >> 5);
+  int rb[RBN];
+#pragma unroll
+  for (int b = 0; b < RBN; ++b) rb[b] = min(tile_x * RBN + b, n_rb - 1);  // past the end: shadows the last one, never stored
+  const u32x4_t* xb[MBW];
+#pragma unroll
+  for (int mb = 0; mb < MBW; ++mb) {
+    int blk = m_blk0 + mb;
+    if (blk >= n_blocks_m) blk = n_blocks_m - 1;  // idle waves shadow a valid block (never stored)
+    xb[mb] = X + (size_t)blk * KB * 256 + lane;
+  }
+  const int n = 4 * kb_per_quarter;
+  const int kb0 = blockIdx.y * n;
+  auto kb_of = [&](int i) { return kb0 + (i < n ? i : n - 1); };  // clamped: no conditional loads in the pipeline
+  f32x16_t acc[RBN][MBW];
+
+  // NS = row blocks this half of the block stages: srb[0 .. NS-1]
+  auto run = [&](auto ns_c, int srb0, int srb1) __attribute__((always_inline)) {
+    constexpr int NS = decltype(ns_c)::value;
+    const int srb[2] = {srb0, srb1};
+    const u32x4_t* wp[NS];
+#pragma unroll
+    for (int b = 0; b < NS; ++b) wp[b] = W + (size_t)rb[srb[b]] * KB * 256 + t256;
+    // Weight k blocks are loaded strictly in order (the last one again once the range is exhausted); the slot of the
+    // next one is kept as (block within its quarter, quarter) and stepped, without a division.
+    int w_r = 0, w_q = 0;
+    auto next_wslot = [&]() {
+      const int off = (((int)blockIdx.y * kb_per_quarter + w_r) * 4 + w_q) * 256;
+      if (w_r + 1 < kb_per_quarter) ++w_r;
+      else if (w_q < 3) { w_r = 0; ++w_q; }
+      return off;
+    };
+    u32x4_t wr[4][NS];        // weight registers: slot s holds a k block with index = s (mod 4)
+    u32x4_t xr[XS][MBW][4];   // activation fragments: slot s holds a k block with index = s (mod XS)
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int ow = next_wslot();
+#pragma unroll
+      for (int b = 0; b < NS; ++b) wr[s][b] = __builtin_nontemporal_load(wp[b] + ow);
+    }
+#pragma unroll
+    for (int s = 0; s < XS; ++s)
+#pragma unroll
+      for (int mb = 0; mb < MBW; ++mb)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) xr[s][mb][t] = xb[mb][(size_t)kb_of(s) * 256 + t * 64];
+    {
+      const int ow = next_wslot();
+#pragma unroll
+      for (int b = 0; b < NS; ++b) {
+        wlds[0][srb[b]][t256] = wr[0][b];
+        wr[0][b] = __builtin_nontemporal_load(wp[b] + ow);
+      }
+    }
+    auto iter = [&](f32x16_t (&a)[RBN][MBW], int i, auto jc) __attribute__((always_inline)) {
+      constexpr int j = decltype(jc)::value, jn = (j + 1) & 3, jx = j % XS;
+      const int ow = next_wslot();  // k block i + 5
+#pragma unroll
+      for (int b = 0; b < NS; ++b) {
+        wlds[jn][srb[b]][t256] = wr[jn][b];
+        wr[jn][b] = __builtin_nontemporal_load(wp[b] + ow);
+      }
+      // barrier that orders LDS traffic only (a full one would drain the global loads in flight)
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+#pragma unroll
+        for (int b = 0; b < RBN; ++b) {
+          const u32x4_t afrag = wlds[j][b][t * 64 + lane];
+#pragma unroll
+          for (int mb = 0; mb < MBW; ++mb) a[b][mb] = mfma_f16(afrag, xr[jx][mb][t], a[b][mb]);
+        }
+      }
+#pragma unroll
+      for (int mb = 0; mb < MBW; ++mb)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) xr[jx][mb][t] = xb[mb][(size_t)kb_of(i + XS) * 256 + t * 64];
+    };
+    auto quarter = [&](f32x16_t (&a)[RBN][MBW], int q) __attribute__((always_inline)) {
+#pragma unroll
+      for (int b = 0; b < RBN; ++b)
+#pragma unroll
+        for (int mb = 0; mb < MBW; ++mb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) a[b][mb][r] = 0.f;
+      for (int i = q * kb_per_quarter; i < (q + 1) * kb_per_quarter; i += 4) {
+        iter(a, i, std::integral_constant<int, 0>{});
+        iter(a, i + 1, std::integral_constant<int, 1>{});
+        iter(a, i + 2, std::integral_constant<int, 2>{});
+        iter(a, i + 3, std::integral_constant<int, 3>{});
+      }
+    };
+    f32x16_t other[RBN][MBW];
+    quarter(acc, 0);
+    for (int q = 1; q < 4; ++q) {
+      quarter(other, q);
+#pragma unroll
+      for (int b = 0; b < RBN; ++b)
+#pragma unroll
+        for (int mb = 0; mb < MBW; ++mb) acc[b][mb] += other[b][mb];
+    }
+  };
+  if (__builtin_amdgcn_readfirstlane(wave) < 4) run(std::integral_constant<int, 2>{}, 0, 2);
+  else run(std::integral_constant<int, 1>{}, 1, 1);
+
+  if (!has_rows) return;
+  const int col = lane & 31, hb = lane >> 5;
+#pragma unroll
+  for (int mb = 0; mb < MBW; ++mb) {
+    const int m = (m_blk0 + mb) * 32 + col;
+    if (m >= M) continue;
+#pragma unroll
+    for (int b = 0; b < RBN; ++b) {
+      if (tile_x * RBN + b >= n_rb) break;
+      float sum[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sum[r] = acc[b][mb][r];
+      store_rowblock<EPI>(sum, m, hb, rb[b], blockIdx.y, M, N, out);
+    }
+  }
+}
+
 struct Plan {
   int splits;       // K splits across blocks
   int kb_per_wave;  // 64-wide k blocks per wave
@@ -1088,7 +1230,22 @@ void launch_cols(hipStream_t s, const void* X, const void* W, void* out, int M, 
     // 129..256 rows: one block of eight waves per weight tile where that still gives >= 192 blocks (gate/up 82 -> 65 us,
     // QKV 33 -> 29, output projection 538 -> 420 at 256 rows); the O and down projections would be left with 128 blocks
     // (measured 21 -> 26 and 42 -> 50 us) and run as two batch tiles of 128 whose blocks are paired on one die.
-    if (M > 128 && wide_blocks >= 192) { launch_lds8(s, X, W, out, M, N, K, epi, allow_split, se); return; }
+    if (M > 128 && wide_blocks >= 192) {
+      // ... and 96-row tiles where those give every compute unit a block and 128-row tiles do not (M <= 256: one
+      // batch tile per weight tile; gate/up and QKV of the 8B shape)
+      const int n_rb = epi == kEpiSwiGLU ? (N >> 4) : (N >> 5);
+      const int splits = epi == kEpiPartial ? p.splits : 1;
+      if (M <= 256 && epi != kEpiSample && n_rb % 3 == 0 && wide_blocks < kComputeUnits && (n_rb / 3) * splits <= kComputeUnits) {
+        dim3 grid(n_rb / 3, splits, 1);
+        if (epi == kEpiSwiGLU)
+          gemm_bf16_lds8r3_kernel<kEpiSwiGLU, 2><<<grid, 512, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave);
+        else
+          gemm_bf16_lds8r3_kernel<kEpiPartial, 2><<<grid, 512, 0, s>>>((const u32x4_t*)X, (const u32x4_t*)W, out, M, N, K, p.kb_per_wave);
+        return;
+      }
+      launch_lds8(s, X, W, out, M, N, K, epi, allow_split, se);
+      return;
+    }
     if (wide_blocks * ((M + 127) / 128) >= 192) {
       // up to 128 rows: 96-row tiles where 128-row tiles would leave a quarter of the compute units without a block
       // and 96-row tiles give every unit one (gate/up 55 -> 41 us, QKV 21 -> 16 us at 128 rows)
