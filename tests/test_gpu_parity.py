@@ -1227,23 +1227,26 @@ def test_rescored_rollout_gives_ratio_one(amd, kind):
 
 
 # ----------------------------------------------------------------------------------- decode step as a HIP graph
-@pytest.mark.parametrize("kv_fp8", [False, True])
-def test_decode_graph_steps_equal_eager_steps(amd, kv_fp8):
+@pytest.mark.parametrize("kv_fp8,G,wide", [(False, 4, False), (True, 4, False), (False, 8, True)])
+def test_decode_graph_steps_equal_eager_steps(amd, kv_fp8, G, wide):
     """rl_decode_graph_step against rl_decode_step on a second instance: same tokens and log-probabilities, bit for
     bit, on every one of 40 steps (compared after each launch, with eager work and synchronisations in between).  The
     batch holds two groups of four samples (shared prompt pages: set blocks in the attention launch) and a single
     sequence whose context crosses 1024 tokens on the way, which changes a launch shape and forces a new capture; page
     grants arrive every 16 steps through the device-counted table update.  An eager step in the middle of the graph
-    steps keeps both instances in agreement too."""
+    steps keeps both instances in agreement too.  In the third case the groups have eight samples and the graph
+    instance uses the wide sets (two operands) while the eager one keeps sets of four."""
     shape = dict(ri.SHAPES["layer8b"], n_layers=2, hidden=512, n_q=8, n_kv=2, ffn=768, vocab=8192)
     w, _ = make_both(shape, 65, std=0.05)
     wd = to_device(w)
-    G, seed = 4, 9
+    seed = 9
     lens = [1003, 70, 33]
     prompts = [ri.tokens((n,), shape["vocab"], 65, 940 + i).tolist() for i, n in enumerate(lens)]
     ids = list(range(2 * G + 1))
-    kw = dict(max_seqs=16, max_ctx=1088, max_rows=64, kv_pages=160, kv_fp8=kv_fp8)
+    kw = dict(max_seqs=24, max_ctx=1088, max_rows=64, kv_pages=280, kv_fp8=kv_fp8)
     ra, rb = amd.Rollout(shape, wd, **kw), amd.Rollout(shape, wd, **kw)
+    if wide:
+        ra.rl_debug_share_attention(2)
     for r in (ra, rb):
         r.rl_prefill_groups(ids[:2 * G], G, prompts[1:], 1.0, seed)
         r.rl_prefill([2 * G], [prompts[0]], 1.0, seed)
