@@ -37,7 +37,7 @@ TRAFFIC_RATIO = {
     ("wave", "attn_decode"): (1.044, "attn_bf16.hip", "bf9a68219783273c"),
     ("layer", "attn_decode"): (1.044, "attn_bf16.hip", "bf9a68219783273c"),
     ("full", "attn_decode"): (1.040, "attn_bf16.hip", "bf9a68219783273c"),
-    ("full", "gemm_gate_up_swiglu"): (1.011, "gemm_bf16.hip", "4edefcaac5772181"),
+    ("full", "gemm_gate_up_swiglu"): (1.011, "gemm_bf16.hip", "c85762f8c6f26887"),
 }
 
 
@@ -66,6 +66,8 @@ def parse():
                     default="wave")
     ap.add_argument("--score-len", type=int, default=1024, help="score workload: tokens per sequence (32 x 8 sequences)")
     ap.add_argument("--prefill-len", type=int, default=2048, help="prefill workload: tokens per prompt (32 prompts)")
+    ap.add_argument("--chunk-rows", type=int, default=1024,
+                    help="prefill and score workloads: rows (tokens) pushed through the layers per launch (max_rows)")
     ap.add_argument("--ctx-mid", type=int, default=9216,
                     help="wave workload: tokens of context per sequence when the timed region starts")
     ap.add_argument("--wave-prompts", type=int, default=16, help="wave workload: resident prompts (x 8 samples each)")
@@ -498,7 +500,7 @@ def run_score_or_prefill(args):
     n_seq, T = (256, args.score_len) if score else (32, args.prefill_len)
     max_ctx = (T + 16 + 15) // 16 * 16
     w = ri.make_weights(shape, seed, device=dev, dtype=torch.bfloat16)
-    ro = Rollout(shape, w, max_seqs=n_seq, max_ctx=max_ctx, max_rows=256, kv_pages=n_seq * (max_ctx // 16) + 16,
+    ro = Rollout(shape, w, max_seqs=n_seq, max_ctx=max_ctx, max_rows=args.chunk_rows, kv_pages=n_seq * (max_ctx // 16) + 16,
                  consume_weights=True)
     del w
     torch.cuda.empty_cache()
@@ -526,7 +528,7 @@ def run_score_or_prefill(args):
     el = time.perf_counter() - t0
     out = {"metric": "teacher-forced scoring tokens/s" if score else "prefill prompt tokens/s", "value": n_seq * T / el,
            "unit": "tokens/s", "n_gpus": 1, "steps": 1, "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
-           "config": {"workload": f"full8b_{'score' if score else 'prefill'}_{n_seq}x{T}", "rows_per_chunk": 256},
+           "config": {"workload": f"full8b_{'score' if score else 'prefill'}_{n_seq}x{T}", "rows_per_chunk": args.chunk_rows},
            "seconds": el, "model_TFLOPs": flops / el / 1e12,
            "roofline": {"bound": "mfma", "achieved": flops / el / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
                         "frac": flops / el / 1e12 / 2500.0, "traffic": None}}

@@ -101,7 +101,8 @@ typedef struct {
   uint32_t kv_block; /* tokens per page; must be 16 */
   uint32_t max_seqs; /* ids are in [0, max_seqs) */
   uint32_t max_ctx;  /* longest prompt + response, multiple of kv_block; bf16: at most 65536 */
-  uint32_t max_rows; /* most sequences per decode call (<= 256); prefill is chunked to this internally */
+  uint32_t max_rows; /* most sequences per decode call (<= 1024); prefill and scoring push their tokens through
+                        the layers in chunks of this many rows (workspace grows with it) */
   uint32_t kv_dtype; /* rl_kv_dtype */
   uint32_t reserved; /* 0 */
   uint64_t kv_pool_bytes;   /* size of rl_weights.kv_pool */

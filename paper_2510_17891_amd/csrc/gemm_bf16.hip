@@ -1230,7 +1230,8 @@ void launch_cols(hipStream_t s, const void* X, const void* W, void* out, int M, 
     // 129..256 rows: one block of eight waves per weight tile where that still gives >= 192 blocks (gate/up 82 -> 65 us,
     // QKV 33 -> 29, output projection 538 -> 420 at 256 rows); the O and down projections would be left with 128 blocks
     // (measured 21 -> 26 and 42 -> 50 us) and run as two batch tiles of 128 whose blocks are paired on one die.
-    if (M > 128 && wide_blocks >= 192) {
+    // (more than 256 rows: the batch tiles of 256 count as blocks too, which brings the O and down projections in)
+    if (M > 128 && wide_blocks * ((M + 255) / 256) >= 192) {
       // ... and 96-row tiles where those give every compute unit a block and 128-row tiles do not (M <= 256: one
       // batch tile per weight tile; gate/up and QKV of the 8B shape)
       const int n_rb = epi == kEpiSwiGLU ? (N >> 4) : (N >> 5);

@@ -72,7 +72,7 @@ rl_status check_config(const rl_model_config* c) {
   if (!c->n_layers || !c->hidden || !c->n_q_heads || !c->n_kv_heads || !c->head_dim || !c->ffn)
     return fail(RL_ERR_INVALID_ARG, "zero dimension");
   if (c->n_q_heads % c->n_kv_heads) return fail(RL_ERR_INVALID_ARG, "n_q_heads %% n_kv_heads != 0");
-  if (c->max_seqs == 0 || c->max_rows == 0 || c->max_rows > 256) return fail(RL_ERR_INVALID_ARG, "max_rows must be in [1,256]");
+  if (c->max_seqs == 0 || c->max_rows == 0 || c->max_rows > 1024) return fail(RL_ERR_INVALID_ARG, "max_rows must be in [1,1024]");
   if (c->max_ctx == 0 || c->max_ctx % 16) return fail(RL_ERR_INVALID_ARG, "max_ctx must be a positive multiple of 16");
   if (c->hidden % 8 || c->hidden > 8192 || c->head_dim % 2 || c->head_dim > 128 || c->ffn % 8 || c->vocab % 4)
     return fail(RL_ERR_UNSUPPORTED, "need hidden %% 8 == 0, hidden <= 8192, even head_dim <= 128, ffn %% 8 == 0, vocab %% 4 == 0");

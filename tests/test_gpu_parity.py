@@ -1140,6 +1140,29 @@ def test_shared_attention_set_widths_agree_for_other_head_groupings(amd, n_q, n_
         r.close()
 
 
+def test_prefill_and_score_bits_do_not_depend_on_the_row_chunk(amd):
+    """Prompts pushed through the layers 1024, 320 or 48 rows at a time (max_rows): the first tokens, their
+    log-probabilities, the teacher-forced scores and the decode steps that follow are the same bits."""
+    shape = dict(ri.SHAPES["layer8b"], n_layers=2, hidden=512, n_q=8, n_kv=2, ffn=768, vocab=8192)
+    w, _ = make_both(shape, 66, std=0.05)
+    wd = to_device(w)
+    lens = [1500, 700, 33]
+    prompts = [ri.tokens((n,), shape["vocab"], 66, 960 + i).tolist() for i, n in enumerate(lens)]
+    ids = [0, 1, 2]
+    res = []
+    for rows in (1024, 320, 48):
+        ro = amd.Rollout(shape, wd, max_seqs=8, max_ctx=1536, max_rows=rows, kv_pages=300)
+        t, lp = ro.rl_prefill(ids, prompts, 1.0, 3)
+        sc = ro.rl_score([5, 6], [prompts[0][:1200], prompts[1]], 1.0)
+        steps = [ro.rl_decode_step(ids, None, 1.0, 3) for _ in range(3)]
+        torch.cuda.synchronize()
+        res.append([t.cpu(), lp.cpu(), sc.cpu()] + [x.cpu() for st in steps for x in st])
+        ro.close()
+    for other in res[1:]:
+        for a, b in zip(res[0], other):
+            assert torch.equal(a, b)
+
+
 # ------------------------------------------------------------------------------ teacher-forced scoring call
 def test_score_matches_oracle_log_softmax(amd):
     shape = ri.SHAPES["tiny"]

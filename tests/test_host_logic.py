@@ -37,7 +37,7 @@ def test_config_validation_needs_no_gpu():
     assert b"head_dim" in L.rl_last_error()
     bad = B.make_config(ri.SHAPES["tiny"], B.RL_F32, 4, 60, 4)                 # max_ctx not a multiple of 16
     assert L.rl_query_workspace(C.byref(bad), C.byref(need)) == B.RL_ERR_INVALID_ARG
-    bad = B.make_config(ri.SHAPES["tiny"], B.RL_F32, 4, 64, 300)
+    bad = B.make_config(ri.SHAPES["tiny"], B.RL_F32, 4, 64, 1025)              # max_rows beyond 1024
     assert L.rl_query_workspace(C.byref(bad), C.byref(need)) == B.RL_ERR_INVALID_ARG
     cfg = B.make_config(ri.SHAPES["tiny"], B.RL_F32, 4, 64, 4)
     cfg.struct_size = 8
