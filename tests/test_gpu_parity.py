@@ -1416,17 +1416,18 @@ def test_fp8_kv_small_model_rollout_fused_and_separate_append_agree(amd):
 
 def test_bf16_sampled_step_bits_do_not_depend_on_batch_size_class(amd):
     """The output projection with the sampling epilogue also changes kernels with the batch.  A 1-layer model wide
-    enough for every variant (hidden 1024, vocabulary 24576): three sequences decoded alone, among 40, 100 and 150
-    rows give the same logits, tokens and log-probabilities, bit for bit, sampled and greedy."""
+    enough for every variant (hidden 1024, vocabulary 24576): three sequences decoded alone, among 40, 100, 150,
+    300 and 600 rows (more than one batch tile of 256) give the same logits, tokens and log-probabilities, bit for
+    bit, sampled and greedy."""
     shape = dict(ri.SHAPES["layer8b"], n_layers=1, hidden=1024, n_q=8, n_kv=2, ffn=1024, vocab=24576)
     w, _ = make_both(shape, 43, std=0.05)
     wd = to_device(w)
-    n_max = 150
+    n_max = 600
     prompts = [ri.tokens((3 + i % 5,), shape["vocab"], 43, 3000 + i).tolist() for i in range(n_max)]
     V = shape["vocab"]
     res = []
-    for n in (3, 40, 100, 150):
-        ro = amd.Rollout(shape, wd, max_seqs=n_max, max_ctx=32, max_rows=256, kv_pages=2 * n_max)
+    for n in (3, 40, 100, 150, 300, 600):
+        ro = amd.Rollout(shape, wd, max_seqs=n_max, max_ctx=32, max_rows=256 if n <= 256 else 1024, kv_pages=2 * n_max)
         ids = list(range(n))
         tok, lp = ro.rl_prefill(ids, prompts[:n], 1.0, 9)
         outs = [(tok[:3].clone(), lp[:3].clone())]
