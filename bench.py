@@ -744,7 +744,7 @@ def main():
         max_ctx = (P + total_steps + 1 + 15) // 16 * 16
         pages = B * (max_ctx // 16)
         w = ri.make_weights(shape, seed, device=dev, dtype=torch.bfloat16)
-        ro = Rollout(shape, w, max_seqs=B, max_ctx=max_ctx, max_rows=256, kv_pages=pages)
+        ro = Rollout(shape, w, max_seqs=B, max_ctx=max_ctx, max_rows=max(256, B), kv_pages=pages)
         del w
         torch.cuda.empty_cache()
         if args.no_share_attention:
